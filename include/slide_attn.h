@@ -1,0 +1,117 @@
+/*
+ * slide_attn.h -- C ABI of the MI355X (gfx950) Slide Attention library.
+ *
+ * The operator is per-pixel local self-attention over a k x k neighbourhood whose
+ * keys and values come from a "deformed shift": k*k depthwise convolutions per
+ * channel, each the sum of a fixed one-hot shift kernel and a learned kernel.
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Activations are contiguous NCHW [B, C, H, W]; `dtype` gives their element
+ *     type (SLIDE_F32 or SLIDE_BF16).  Kernels, bias and all parameter gradients
+ *     are always float32.  Arithmetic accumulates in float32.
+ *   - S = ksize*ksize.  Shift index s = (u+r)*ksize + (v+r) for u,v in [-r, r],
+ *     r = ksize/2, reads the neighbour at offset (u, v) (row, column).  Tap index
+ *     t = p*ksize + q reads offset (p-r, q-r): depthwise cross-correlation, no
+ *     kernel flip.  Outside the map the input is zero; padded neighbours are not
+ *     masked out of the softmax.
+ *   - Head m owns channels [m*d, (m+1)*d), d = C/heads; logits are scaled by
+ *     1/sqrt(d) inside the library.
+ *   - Return value: SLIDE_OK or an error code.  Argument errors are detected on
+ *     the host before any HIP call and leave all outputs untouched.
+ */
+#ifndef SLIDE_ATTN_H
+#define SLIDE_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SLIDE_OK = 0,
+    SLIDE_ERR_NULL = 1,       /* a required pointer is NULL */
+    SLIDE_ERR_SHAPE = 2,      /* a dimension < 1, C % heads != 0, ksize even or not in {1,3,5,7},
+                                 or a size product that overflows 31 bits per plane */
+    SLIDE_ERR_DTYPE = 3,      /* dtype is not SLIDE_F32 / SLIDE_BF16 */
+    SLIDE_ERR_WORKSPACE = 4,  /* workspace NULL or smaller than slide_attn_workspace_bytes() */
+    SLIDE_ERR_HIP = 5,        /* a kernel launch failed (hipGetLastError) */
+    SLIDE_ERR_ALIGN = 6       /* an activation pointer is not aligned to its element size */
+} slide_status;
+
+typedef enum { SLIDE_F32 = 0, SLIDE_BF16 = 1 } slide_dtype;
+
+/*
+ * Re-parameterisation (Sec. 4.3, Fig. 4(2)): merge the fixed shift path and the
+ * learned path of the deformed shifting module into one depthwise kernel,
+ *     w_merged[c, s, t] = w_learned[c, s, t] + (t == s ? 1 : 0)
+ * (the one-hot kernel of Eq. 11 generalised to every shift direction).
+ * Both arrays are float32 [C, S, ksize, ksize] on the device; they may alias.
+ */
+int slide_reparam(const float* w_learned, float* w_merged, int C, int ksize, void* stream);
+
+/*
+ * Bytes of device scratch that slide_attn_fwd (backward == 0) or slide_attn_bwd
+ * (backward != 0) needs for this problem.  Returns 0 if the arguments are
+ * invalid or no scratch is needed.  Host-only; makes no HIP call.
+ */
+size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int heads, int ksize,
+                                  int dtype, int backward);
+
+/*
+ * Forward (Sec. 3.1 Eq. 2 restricted to the local window; Sec. 4.1-4.3):
+ *     Ks[c,s] = sum_t wk[c,s,t] * k[c, pixel + offset(t)]        (deformed shift of K)
+ *     l[m,s]  = (1/sqrt(d)) * sum_{c in head m} q[c] * Ks[c,s] + bias[m,s]
+ *     a       = softmax over s of l
+ *     out[c]  = sum_s a[m(c),s] * Vs[c,s],  Vs as Ks with wv and v.
+ * q, k, v, out: [B,C,H,W] of `dtype`.  wk, wv: MERGED kernels (output of
+ * slide_reparam), float32 [C,S,ksize,ksize].  bias: float32 [heads,S] or NULL
+ * (= zero).  out is overwritten and must not alias an input.  The k*k-fold
+ * shifted tensors are never written to memory.
+ * workspace: device scratch of at least slide_attn_workspace_bytes(..., 0) bytes
+ * (may be NULL when that is 0); contents are undefined afterwards.
+ */
+int slide_attn_fwd(const void* q, const void* k, const void* v,
+                   const float* wk, const float* wv, const float* bias,
+                   void* out,
+                   int B, int H, int W, int C, int heads, int ksize, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of slide_attn_fwd (chain rule through the definition above; the
+ * attention weights are recomputed, nothing is saved by the forward):
+ *     dq, dk, dv : [B,C,H,W] of `dtype`   (overwritten)
+ *     dwk, dwv   : float32 [C,S,ksize,ksize] (overwritten; gradient with respect
+ *                  to the merged kernel, which equals the gradient with respect
+ *                  to the learned kernel)
+ *     dbias      : float32 [heads,S] (overwritten; may be NULL if bias is NULL)
+ * dout is the gradient of the loss with respect to `out`, same layout and dtype.
+ * Parameter gradients are accumulated in float32 in a fixed order (results are
+ * reproducible run to run).
+ * workspace: at least slide_attn_workspace_bytes(..., 1) bytes of device scratch.
+ */
+int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
+                   const float* wk, const float* wv, const float* bias,
+                   void* dq, void* dk, void* dv,
+                   float* dwk, float* dwv, float* dbias,
+                   int B, int H, int W, int C, int heads, int ksize, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* slide_status_string(int status);
+
+/*
+ * Which forward implementation slide_attn_fwd would run for this problem:
+ * 0 = invalid arguments, 1 = general kernel (any supported ksize / head size /
+ * dtype, float32 vector arithmetic), 2 = matrix-core kernel (bf16, d = 32,
+ * ksize 3 or 5).  Host-only; for tests and benchmarks.
+ */
+int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIDE_ATTN_H */

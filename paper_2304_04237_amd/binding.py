@@ -1,0 +1,159 @@
+"""ctypes binding of libslide_attn.so: argument marshalling only.
+
+Function names match the C ABI (include/slide_attn.h).  Tensors must be
+contiguous CUDA(HIP) tensors; activations float32 or bfloat16 [B, C, H, W],
+kernels / bias float32.  Work is enqueued on torch's current stream.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libslide_attn.so")
+_lib = None
+
+SLIDE_F32, SLIDE_BF16 = 0, 1
+_vp = ctypes.c_void_p
+
+
+class SlideAttnError(RuntimeError):
+    pass
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built HIP library; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise SlideAttnError(
+            "libslide_attn.so is not built: run `python -m paper_2304_04237_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i, sz = ctypes.c_int, ctypes.c_size_t
+    lib.slide_status_string.restype = ctypes.c_char_p
+    lib.slide_status_string.argtypes = [i]
+    lib.slide_reparam.restype = i
+    lib.slide_reparam.argtypes = [_vp, _vp, i, i, _vp]
+    lib.slide_attn_workspace_bytes.restype = sz
+    lib.slide_attn_workspace_bytes.argtypes = [i] * 8
+    lib.slide_attn_fwd_path.restype = i
+    lib.slide_attn_fwd_path.argtypes = [i] * 7
+    lib.slide_attn_fwd.restype = i
+    lib.slide_attn_fwd.argtypes = [_vp] * 7 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_bwd.restype = i
+    lib.slide_attn_bwd.argtypes = [_vp] * 13 + [i] * 7 + [_vp, sz, _vp]
+    _lib = lib
+    return lib
+
+
+def slide_status_string(status):
+    return load_library().slide_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise SlideAttnError(slide_status_string(status))
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return SLIDE_F32
+    if t.dtype == torch.bfloat16:
+        return SLIDE_BF16
+    raise SlideAttnError("activations must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _dev(t, name, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise SlideAttnError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise SlideAttnError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise SlideAttnError("%s must be %s" % (name, dtype))
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def slide_attn_workspace_bytes(B, H, W, C, heads, ksize, dtype, backward):
+    code = dtype if isinstance(dtype, int) else (SLIDE_F32 if dtype == torch.float32 else SLIDE_BF16)
+    return int(load_library().slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, int(bool(backward))))
+
+
+def slide_attn_fwd_path(B, H, W, C, heads, ksize, dtype):
+    code = dtype if isinstance(dtype, int) else (SLIDE_F32 if dtype == torch.float32 else SLIDE_BF16)
+    return int(load_library().slide_attn_fwd_path(B, H, W, C, heads, ksize, code))
+
+
+def slide_reparam(w_learned, w_merged=None):
+    """w_merged = one-hot shift kernels + w_learned, float32 [C, k*k, k, k]."""
+    lib = load_library()
+    C, S, kh, kw = w_learned.shape
+    if kh != kw or S != kh * kw:
+        raise SlideAttnError("kernel must be [C, k*k, k, k]")
+    if w_merged is None:
+        w_merged = torch.empty_like(w_learned)
+    _check(lib.slide_reparam(_dev(w_learned, "w_learned", torch.float32),
+                             _dev(w_merged, "w_merged", torch.float32), C, kh, _stream()))
+    return w_merged
+
+
+def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None):
+    """out = slide attention of (q, k, v) with MERGED kernels wk, wv and per-head bias."""
+    lib = load_library()
+    B, C, H, W = q.shape
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if out is None:
+        out = torch.empty_like(q)
+    need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 0)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.slide_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                              _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                              _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
+                              B, H, W, C, heads, ksize, code, ws_ptr, ws_bytes, _stream()))
+    return out
+
+
+def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, outputs=None):
+    """Returns (dq, dk, dv, dwk, dwv, dbias); dbias is None when bias is None."""
+    lib = load_library()
+    B, C, H, W = q.shape
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v"), (dout, "dout")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if outputs is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        dwk, dwv = torch.empty_like(wk), torch.empty_like(wv)
+        dbias = torch.empty_like(bias) if bias is not None else None
+    else:
+        dq, dk, dv, dwk, dwv, dbias = outputs
+    need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    _check(lib.slide_attn_bwd(_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                              _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                              _dev(bias, "bias", torch.float32),
+                              _dev(dq, "dq", q.dtype), _dev(dk, "dk", q.dtype), _dev(dv, "dv", q.dtype),
+                              _dev(dwk, "dwk", torch.float32), _dev(dwv, "dwv", torch.float32),
+                              _dev(dbias, "dbias", torch.float32),
+                              B, H, W, C, heads, ksize, code,
+                              workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                              _stream()))
+    return dq, dk, dv, dwk, dwv, dbias

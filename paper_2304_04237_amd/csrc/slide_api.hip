@@ -1,0 +1,105 @@
+// C ABI of libslide_attn.so: argument validation on the host, then dispatch to
+// the gfx950 kernels.  Declarations and contracts: include/slide_attn.h.
+#include "slide_attn.h"
+#include "slide_internal.h"
+
+using slide::Problem;
+
+static bool ksize_supported(int ksize) { return ksize == 1 || ksize == 3 || ksize == 5 || ksize == 7; }
+
+// Validate the shape arguments common to forward and backward.
+static int check_problem(int B, int H, int W, int C, int heads, int ksize, int dtype)
+{
+    if (dtype != SLIDE_F32 && dtype != SLIDE_BF16) return SLIDE_ERR_DTYPE;
+    if (B < 1 || H < 1 || W < 1 || C < 1 || heads < 1) return SLIDE_ERR_SHAPE;
+    if (C % heads != 0) return SLIDE_ERR_SHAPE;
+    if (!ksize_supported(ksize)) return SLIDE_ERR_SHAPE;
+    if (B > 65535 || heads > 65535) return SLIDE_ERR_SHAPE;          // grid y/z limits
+    if ((long)H * W > 0x7fffffffL / 64) return SLIDE_ERR_SHAPE;       // plane index arithmetic
+    return SLIDE_OK;
+}
+
+static bool aligned_to(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+extern "C" const char* slide_status_string(int status)
+{
+    switch (status) {
+        case SLIDE_OK: return "SLIDE_OK";
+        case SLIDE_ERR_NULL: return "SLIDE_ERR_NULL: a required pointer is NULL";
+        case SLIDE_ERR_SHAPE: return "SLIDE_ERR_SHAPE: bad dimension, C % heads != 0, or unsupported ksize";
+        case SLIDE_ERR_DTYPE: return "SLIDE_ERR_DTYPE: dtype must be SLIDE_F32 or SLIDE_BF16";
+        case SLIDE_ERR_WORKSPACE: return "SLIDE_ERR_WORKSPACE: workspace missing or too small";
+        case SLIDE_ERR_HIP: return "SLIDE_ERR_HIP: kernel launch failed";
+        case SLIDE_ERR_ALIGN: return "SLIDE_ERR_ALIGN: activation pointer not aligned to its element size";
+        default: return "SLIDE_ERR_UNKNOWN";
+    }
+}
+
+extern "C" int slide_reparam(const float* w_learned, float* w_merged, int C, int ksize, void* stream)
+{
+    if (!w_learned || !w_merged) return SLIDE_ERR_NULL;
+    if (C < 1 || !ksize_supported(ksize)) return SLIDE_ERR_SHAPE;
+    hipError_t e = slide::launch_reparam(w_learned, w_merged, C, ksize, (hipStream_t)stream);
+    return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
+extern "C" size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int heads, int ksize,
+                                             int dtype, int backward)
+{
+    if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    return backward ? slide::bwd_generic_workspace_bytes(p) : 0;
+}
+
+extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype)
+{
+    if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    return slide::fwd_mfma_supported(p) ? 2 : 1;
+}
+
+extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias, void* out,
+                              int B, int H, int W, int C, int heads, int ksize, int dtype,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    int st = check_problem(B, H, W, C, heads, ksize, dtype);
+    if (st != SLIDE_OK) return st;
+    if (!q || !k || !v || !wk || !wv || !out) return SLIDE_ERR_NULL;
+    const size_t esz = dtype == SLIDE_F32 ? 4 : 2;
+    if (!aligned_to(q, esz) || !aligned_to(k, esz) || !aligned_to(v, esz) || !aligned_to(out, esz) ||
+        !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4))
+        return SLIDE_ERR_ALIGN;
+    (void)workspace; (void)workspace_bytes;       // the forward needs no scratch
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    hipError_t e;
+    if (slide::fwd_mfma_supported(p))
+        e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
+    else
+        e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
+    return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
+extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias,
+                              void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                              int B, int H, int W, int C, int heads, int ksize, int dtype,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    int st = check_problem(B, H, W, C, heads, ksize, dtype);
+    if (st != SLIDE_OK) return st;
+    if (!dout || !q || !k || !v || !wk || !wv || !dq || !dk || !dv || !dwk || !dwv) return SLIDE_ERR_NULL;
+    if (bias && !dbias) return SLIDE_ERR_NULL;
+    const size_t esz = dtype == SLIDE_F32 ? 4 : 2;
+    const void* acts[] = {dout, q, k, v, dq, dk, dv};
+    for (const void* a : acts)
+        if (!aligned_to(a, esz)) return SLIDE_ERR_ALIGN;
+    if (!aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(dwk, 4) ||
+        !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 4))
+        return SLIDE_ERR_ALIGN;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    if (!workspace || workspace_bytes < slide::bwd_generic_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
+    hipError_t e = slide::launch_bwd_generic(p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv,
+                                             dbias, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}

@@ -1,0 +1,472 @@
+// General Slide Attention kernels for gfx950: every supported window size, head
+// size and element type, float32 vector arithmetic throughout.
+//
+// These kernels state the operator directly (Sec. 4.1-4.3 of the paper): for each
+// pixel the k*k window of every channel is read with zero padding, the merged
+// depthwise kernels are applied on the fly (the k*k-fold shifted tensor is never
+// written to memory), logits get the per-head bias, a softmax runs over the k*k
+// shifts and the shifted values are summed.  They serve float32 problems, head sizes
+// other than 32 and window sizes the matrix-core kernel does not cover, and they
+// are the whole backward pass.
+//
+// Thread mapping: one thread per (pixel, head, batch item); threads of a wavefront
+// walk along W, so every per-channel read of q, k, v is a coalesced row segment and
+// the window re-reads hit the vector L1.  Kernel weights are indexed only by
+// block-uniform values, so the compiler fetches them through the scalar cache.
+#include "slide_internal.h"
+#include "slide_device.h"
+
+namespace slide {
+
+// ------------------------------------------------------------------ re-parameterisation
+__global__ void reparam_kernel(const float* __restrict__ w_learned, float* __restrict__ w_merged,
+                               long n, int S)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    int t = (int)(e % S);
+    int s = (int)((e / S) % S);
+    w_merged[e] = w_learned[e] + (t == s ? 1.0f : 0.0f);
+}
+
+hipError_t launch_reparam(const float* w_learned, float* w_merged, int C, int ksize, hipStream_t st)
+{
+    int S = ksize * ksize;
+    long n = (long)C * S * S;
+    int threads = 256;
+    long blocks = (n + threads - 1) / threads;
+    hipLaunchKernelGGL(reparam_kernel, dim3((unsigned)blocks), dim3(threads), 0, st,
+                       w_learned, w_merged, n, S);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ shared device pieces
+// zero-padded k*k window of one channel plane around pixel (i, j)
+template <typename T, int KS>
+__device__ __forceinline__ void load_window(const T* __restrict__ plane, int i, int j, int H, int W,
+                                            float (&win)[KS * KS])
+{
+    constexpr int R = KS / 2;
+#pragma unroll
+    for (int p = 0; p < KS; ++p) {
+        int y = i + p - R;
+#pragma unroll
+        for (int qq = 0; qq < KS; ++qq) {
+            int x = j + qq - R;
+            bool in = (y >= 0) && (y < H) && (x >= 0) && (x < W);
+            win[p * KS + qq] = in ? Elem<T>::load(plane + (long)y * W + x) : 0.0f;
+        }
+    }
+}
+
+// deformed shift of one channel at one pixel: shifted[s] = sum_t w[s][t] * win[t]
+template <int KS>
+__device__ __forceinline__ void apply_kernels(const float* __restrict__ w_c,
+                                              const float (&win)[KS * KS],
+                                              float (&shifted)[KS * KS])
+{
+    constexpr int S = KS * KS;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        float acc = 0.0f;
+#pragma unroll
+        for (int t = 0; t < S; ++t) acc = fmaf(w_c[s * S + t], win[t], acc);
+        shifted[s] = acc;
+    }
+}
+
+// logits over the S shifts for one pixel of one head, then softmax in place
+template <typename T, int KS>
+__device__ __forceinline__ void attention_weights(const T* __restrict__ q, const T* __restrict__ k,
+                                                  const float* __restrict__ wk,
+                                                  const float* __restrict__ bias,
+                                                  int b, int m, int i, int j, int H, int W, int C,
+                                                  int d, float (&a)[KS * KS])
+{
+    constexpr int S = KS * KS;
+    const long HW = (long)H * W;
+    const long pix = (long)i * W + j;
+    float dot[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) dot[s] = 0.0f;
+    for (int cc = 0; cc < d; ++cc) {
+        int c = m * d + cc;
+        const T* kp = k + ((long)b * C + c) * HW;
+        float win[S], ks[S];
+        load_window<T, KS>(kp, i, j, H, W, win);
+        apply_kernels<KS>(wk + (long)c * S * S, win, ks);
+        float qc = Elem<T>::load(q + ((long)b * C + c) * HW + pix);
+#pragma unroll
+        for (int s = 0; s < S; ++s) dot[s] = fmaf(qc, ks[s], dot[s]);
+    }
+    const float scale = 1.0f / sqrtf((float)d);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        a[s] = fmaf(scale, dot[s], bias ? bias[m * S + s] : 0.0f);
+        mx = fmaxf(mx, a[s]);
+    }
+    float den = 0.0f;
+#pragma unroll
+    for (int s = 0; s < S; ++s) { a[s] = expf(a[s] - mx); den += a[s]; }
+    float inv = 1.0f / den;
+#pragma unroll
+    for (int s = 0; s < S; ++s) a[s] *= inv;
+}
+
+// ------------------------------------------------------------------ forward
+template <typename T, int KS>
+__global__ void __launch_bounds__(256)
+fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
+                   const float* __restrict__ wk, const float* __restrict__ wv,
+                   const float* __restrict__ bias, T* __restrict__ out,
+                   int H, int W, int C, int heads)
+{
+    constexpr int S = KS * KS;
+    const int d = C / heads;
+    const int m = blockIdx.y, b = blockIdx.z;
+    const long HW = (long)H * W;
+    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= HW) return;
+    const int i = (int)(pix / W), j = (int)(pix % W);
+
+    float a[S];
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a);
+
+    for (int cc = 0; cc < d; ++cc) {
+        int c = m * d + cc;
+        const T* vp = v + ((long)b * C + c) * HW;
+        float win[S], vs[S];
+        load_window<T, KS>(vp, i, j, H, W, win);
+        apply_kernels<KS>(wv + (long)c * S * S, win, vs);
+        float acc = 0.0f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) acc = fmaf(a[s], vs[s], acc);
+        Elem<T>::store(out + ((long)b * C + c) * HW + pix, acc);
+    }
+}
+
+template <typename T, int KS>
+static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, const void* v,
+                               const float* wk, const float* wv, const float* bias, void* out,
+                               hipStream_t st)
+{
+    dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+    hipLaunchKernelGGL((fwd_generic_kernel<T, KS>), grid, dim3(256), 0, st,
+                       (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out,
+                       p.H, p.W, p.C, p.heads);
+    return hipGetLastError();
+}
+
+#define SLIDE_DISPATCH(FN, ...)                                                         \
+    do {                                                                                \
+        if (p.dtype == 0) {                                                             \
+            switch (p.ksize) {                                                          \
+                case 1: return FN<float, 1>(__VA_ARGS__);                               \
+                case 3: return FN<float, 3>(__VA_ARGS__);                               \
+                case 5: return FN<float, 5>(__VA_ARGS__);                               \
+                case 7: return FN<float, 7>(__VA_ARGS__);                               \
+            }                                                                           \
+        } else {                                                                        \
+            switch (p.ksize) {                                                          \
+                case 1: return FN<bf16_bits, 1>(__VA_ARGS__);                           \
+                case 3: return FN<bf16_bits, 3>(__VA_ARGS__);                           \
+                case 5: return FN<bf16_bits, 5>(__VA_ARGS__);                           \
+                case 7: return FN<bf16_bits, 7>(__VA_ARGS__);                           \
+            }                                                                           \
+        }                                                                               \
+        return hipErrorInvalidValue;                                                    \
+    } while (0)
+
+hipError_t launch_fwd_generic(const Problem& p, const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias, void* out,
+                              hipStream_t st)
+{
+    SLIDE_DISPATCH(launch_fwd_t, p, q, k, v, wk, wv, bias, out, st);
+}
+
+// ------------------------------------------------------------------ backward
+// Step 1, one thread per (pixel, head, batch item): recompute the attention
+// weights a[s]; da[s] = sum_c dO[c] Vs[c,s]; dl[s] = a[s] (da[s] - sum a da);
+// dq[c] = scale * sum_s dl[s] Ks[c,s].  a and dl go to scratch as
+// [B, heads, S, H, W] float32 for the gather steps below.
+template <typename T, int KS>
+__global__ void __launch_bounds__(256)
+bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* __restrict__ k,
+                 const T* __restrict__ v, const float* __restrict__ wk,
+                 const float* __restrict__ wv, const float* __restrict__ bias,
+                 T* __restrict__ dq, float* __restrict__ attn_ws, float* __restrict__ dl_ws,
+                 int H, int W, int C, int heads)
+{
+    constexpr int S = KS * KS;
+    const int d = C / heads;
+    const int m = blockIdx.y, b = blockIdx.z;
+    const long HW = (long)H * W;
+    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= HW) return;
+    const int i = (int)(pix / W), j = (int)(pix % W);
+
+    float a[S];
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a);
+
+    float da[S];
+#pragma unroll
+    for (int s = 0; s < S; ++s) da[s] = 0.0f;
+    for (int cc = 0; cc < d; ++cc) {
+        int c = m * d + cc;
+        float win[S], vs[S];
+        load_window<T, KS>(v + ((long)b * C + c) * HW, i, j, H, W, win);
+        apply_kernels<KS>(wv + (long)c * S * S, win, vs);
+        float doc = Elem<T>::load(dout + ((long)b * C + c) * HW + pix);
+#pragma unroll
+        for (int s = 0; s < S; ++s) da[s] = fmaf(doc, vs[s], da[s]);
+    }
+    float dsum = 0.0f;
+#pragma unroll
+    for (int s = 0; s < S; ++s) dsum = fmaf(a[s], da[s], dsum);
+    float dl[S];
+    const long ws_base = ((long)b * heads + m) * S * HW + pix;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        dl[s] = a[s] * (da[s] - dsum);
+        attn_ws[ws_base + (long)s * HW] = a[s];
+        dl_ws[ws_base + (long)s * HW] = dl[s];
+    }
+    const float scale = 1.0f / sqrtf((float)d);
+    for (int cc = 0; cc < d; ++cc) {
+        int c = m * d + cc;
+        float win[S], ks[S];
+        load_window<T, KS>(k + ((long)b * C + c) * HW, i, j, H, W, win);
+        apply_kernels<KS>(wk + (long)c * S * S, win, ks);
+        float acc = 0.0f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) acc = fmaf(dl[s], ks[s], acc);
+        Elem<T>::store(dq + ((long)b * C + c) * HW + pix, scale * acc);
+    }
+}
+
+// Step 2, gather form of the transposed depthwise convolutions, one thread per
+// (pixel y, head, batch item):
+//   dk[c,y] = scale * sum_t q[c, y - off(t)] * sum_s wk[c,s,t] dl[s, y - off(t)]
+//   dv[c,y] =         sum_t dO[c, y - off(t)] * sum_s wv[c,s,t] a[s, y - off(t)]
+// over the taps t whose source pixel y - off(t) lies inside the map.
+template <typename T, int KS>
+__global__ void __launch_bounds__(256)
+bwd_dkdv_kernel(const T* __restrict__ dout, const T* __restrict__ q,
+                const float* __restrict__ wk, const float* __restrict__ wv,
+                const float* __restrict__ attn_ws, const float* __restrict__ dl_ws,
+                T* __restrict__ dk, T* __restrict__ dv, int H, int W, int C, int heads)
+{
+    constexpr int S = KS * KS, R = KS / 2, CH = 8;
+    const int d = C / heads;
+    const int m = blockIdx.y, b = blockIdx.z;
+    const long HW = (long)H * W;
+    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (pix >= HW) return;
+    const int i = (int)(pix / W), j = (int)(pix % W);
+    const float scale = 1.0f / sqrtf((float)d);
+    const long ws_head = ((long)b * heads + m) * S * HW;
+
+    for (int c0 = 0; c0 < d; c0 += CH) {
+        float acc_k[CH], acc_v[CH];
+#pragma unroll
+        for (int e = 0; e < CH; ++e) { acc_k[e] = 0.0f; acc_v[e] = 0.0f; }
+#pragma unroll
+        for (int p = 0; p < KS; ++p) {
+#pragma unroll
+            for (int qq = 0; qq < KS; ++qq) {
+                const int t = p * KS + qq;
+                const int y = i - (p - R), x = j - (qq - R);     // source pixel of tap t
+                const bool in = (y >= 0) && (y < H) && (x >= 0) && (x < W);
+                const long src = in ? ((long)y * W + x) : 0;
+                float dl[S], a[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    dl[s] = in ? dl_ws[ws_head + (long)s * HW + src] : 0.0f;
+                    a[s] = in ? attn_ws[ws_head + (long)s * HW + src] : 0.0f;
+                }
+#pragma unroll
+                for (int e = 0; e < CH; ++e) {
+                    if (c0 + e < d) {
+                        const int c = m * d + c0 + e;
+                        const float* wkc = wk + (long)c * S * S + t;
+                        const float* wvc = wv + (long)c * S * S + t;
+                        float ck = 0.0f, cv = 0.0f;
+#pragma unroll
+                        for (int s = 0; s < S; ++s) {
+                            ck = fmaf(wkc[s * S], dl[s], ck);
+                            cv = fmaf(wvc[s * S], a[s], cv);
+                        }
+                        const long off = ((long)b * C + c) * HW + src;
+                        float qs = in ? Elem<T>::load(q + off) : 0.0f;
+                        float ds = in ? Elem<T>::load(dout + off) : 0.0f;
+                        acc_k[e] = fmaf(ck, qs, acc_k[e]);
+                        acc_v[e] = fmaf(cv, ds, acc_v[e]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            if (c0 + e < d) {
+                const long off = ((long)b * C + m * d + c0 + e) * HW + pix;
+                Elem<T>::store(dk + off, scale * acc_k[e]);
+                Elem<T>::store(dv + off, acc_v[e]);
+            }
+        }
+    }
+}
+
+// Step 3, kernel gradients.  Block (c*S + s, chunk) sums over its chunk of
+// (batch, pixel) items
+//   dwk[c,s,t] += scale * dl[s,y] * q[c,y] * k[c, y + off(t)]
+//   dwv[c,s,t] +=          a[s,y] * dO[c,y] * v[c, y + off(t)]
+// per thread in registers, then across the block through LDS in a fixed tree
+// order, and writes one partial per chunk; step 4 adds the chunks in order.
+template <typename T, int KS>
+__global__ void __launch_bounds__(256)
+bwd_dw_partial_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* __restrict__ k,
+                      const T* __restrict__ v, const float* __restrict__ attn_ws,
+                      const float* __restrict__ dl_ws, float* __restrict__ partial,
+                      int B, int H, int W, int C, int heads, long items_per_chunk)
+{
+    constexpr int S = KS * KS;
+    const int d = C / heads;
+    const int c = blockIdx.x / S, s = blockIdx.x % S;
+    const int m = c / d;
+    const long HW = (long)H * W;
+    const long n_items = (long)B * HW;
+    const long begin = (long)blockIdx.y * items_per_chunk;
+    const long end = min(begin + items_per_chunk, n_items);
+    const float scale = 1.0f / sqrtf((float)d);
+
+    float acc_k[S], acc_v[S];
+#pragma unroll
+    for (int t = 0; t < S; ++t) { acc_k[t] = 0.0f; acc_v[t] = 0.0f; }
+    for (long it = begin + threadIdx.x; it < end; it += blockDim.x) {
+        const int b = (int)(it / HW);
+        const long pix = it % HW;
+        const int i = (int)(pix / W), j = (int)(pix % W);
+        const long ws = (((long)b * heads + m) * S + s) * HW + pix;
+        const long act = ((long)b * C + c) * HW;
+        const float gk = scale * dl_ws[ws] * Elem<T>::load(q + act + pix);
+        const float gv = attn_ws[ws] * Elem<T>::load(dout + act + pix);
+        float win[S];
+        load_window<T, KS>(k + act, i, j, H, W, win);
+#pragma unroll
+        for (int t = 0; t < S; ++t) acc_k[t] = fmaf(gk, win[t], acc_k[t]);
+        load_window<T, KS>(v + act, i, j, H, W, win);
+#pragma unroll
+        for (int t = 0; t < S; ++t) acc_v[t] = fmaf(gv, win[t], acc_v[t]);
+    }
+    __shared__ float red[256];
+    float* outp = partial + ((long)blockIdx.y * 2 * C * S + (long)c * S + s) * S;
+    const long side = (long)C * S * S;     // dwv partials follow the dwk partials of a chunk
+#pragma unroll
+    for (int t = 0; t < 2 * S; ++t) {
+        red[threadIdx.x] = (t < S) ? acc_k[t % S] : acc_v[t % S];
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) outp[(t < S ? 0 : side) + (t % S)] = red[0];
+        __syncthreads();
+    }
+}
+
+// Step 4: add the per-chunk partials in chunk order.  n = 2 * C*S*S entries.
+__global__ void bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
+                                     float* __restrict__ dwv, long side, int n_chunks)
+{
+    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= 2 * side) return;
+    float acc = 0.0f;
+    for (int ch = 0; ch < n_chunks; ++ch) acc += partial[(long)ch * 2 * side + e];
+    if (e < side) dwk[e] = acc; else dwv[e - side] = acc;
+}
+
+// Step 5: dbias[m,s] = sum over batch and pixels of dl; one block per (m,s),
+// fixed-order tree reduction.
+__global__ void __launch_bounds__(256)
+bwd_dbias_kernel(const float* __restrict__ dl_ws, float* __restrict__ dbias,
+                 int B, long HW, int heads, int S)
+{
+    const int m = blockIdx.x / S, s = blockIdx.x % S;
+    float acc = 0.0f;
+    for (int b = 0; b < B; ++b) {
+        const float* p = dl_ws + (((long)b * heads + m) * S + s) * HW;
+        for (long x = threadIdx.x; x < HW; x += blockDim.x) acc += p[x];
+    }
+    __shared__ float red[256];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) dbias[blockIdx.x] = red[0];
+}
+
+static int dw_chunks(const Problem& p)
+{
+    long n_items = (long)p.B * p.plane();
+    long want = 4096 / ((long)p.C * p.S()) + 1;
+    long cap = (n_items + 1023) / 1024;          // at least ~1024 items per chunk
+    long n = want < cap ? want : cap;
+    if (n < 1) n = 1;
+    if (n > 64) n = 64;
+    return (int)n;
+}
+
+size_t bwd_generic_workspace_bytes(const Problem& p)
+{
+    size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
+    size_t part = (size_t)dw_chunks(p) * 2 * (size_t)p.C * p.S() * p.S() * sizeof(float);
+    return 2 * per + part;
+}
+
+template <typename T, int KS>
+static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q, const void* k,
+                               const void* v, const float* wk, const float* wv, const float* bias,
+                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                               void* workspace, hipStream_t st)
+{
+    const int S = p.S();
+    const size_t per = (size_t)p.B * p.heads * S * (size_t)p.plane();
+    float* attn_ws = (float*)workspace;
+    float* dl_ws = attn_ws + per;
+    float* partial = dl_ws + per;
+    dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+    hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
+                       (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
+                       (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
+    hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
+                       (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
+                       p.H, p.W, p.C, p.heads);
+    const int n_chunks = dw_chunks(p);
+    const long n_items = (long)p.B * p.plane();
+    const long per_chunk = (n_items + n_chunks - 1) / n_chunks;
+    hipLaunchKernelGGL((bwd_dw_partial_kernel<T, KS>), dim3((unsigned)(p.C * S), (unsigned)n_chunks),
+                       dim3(256), 0, st,
+                       (const T*)dout, (const T*)q, (const T*)k, (const T*)v, attn_ws, dl_ws,
+                       partial, p.B, p.H, p.W, p.C, p.heads, per_chunk);
+    const long side = (long)p.C * S * S;
+    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 255) / 256)), dim3(256),
+                       0, st, partial, dwk, dwv, side, n_chunks);
+    if (dbias)
+        hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
+                           dl_ws, dbias, p.B, p.plane(), p.heads, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,
+                              const void* v, const float* wk, const float* wv, const float* bias,
+                              void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                              void* workspace, hipStream_t st)
+{
+    SLIDE_DISPATCH(launch_bwd_t, p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias,
+                   workspace, st);
+}
+
+}  // namespace slide

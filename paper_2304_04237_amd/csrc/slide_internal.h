@@ -1,0 +1,34 @@
+// Internal declarations shared by the translation units of libslide_attn.so.
+// Not part of the public ABI (see include/slide_attn.h for that).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace slide {
+
+struct Problem {
+    int B, H, W, C, heads, ksize, dtype;
+    int d() const { return C / heads; }
+    int S() const { return ksize * ksize; }
+    long plane() const { return (long)H * W; }
+};
+
+// ---- general kernels (slide_generic.hip): any supported ksize / head size / dtype
+hipError_t launch_reparam(const float* w_learned, float* w_merged, int C, int ksize, hipStream_t st);
+hipError_t launch_fwd_generic(const Problem& p, const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias, void* out,
+                              hipStream_t st);
+size_t bwd_generic_workspace_bytes(const Problem& p);
+hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,
+                              const void* v, const float* wk, const float* wv, const float* bias,
+                              void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                              void* workspace, hipStream_t st);
+
+// ---- matrix-core forward (slide_fwd_mfma.hip): bf16, d == 32, ksize 3 or 5
+bool fwd_mfma_supported(const Problem& p);
+hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
+                           const float* wk, const float* wv, const float* bias, void* out,
+                           hipStream_t st);
+
+}  // namespace slide

@@ -1,0 +1,105 @@
+"""Host-side checks of the C ABI: the library loads without a GPU, exports every
+symbol the public header declares, and rejects bad arguments before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2304_04237_amd as sa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "slide_attn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sa.lib_path()):
+        from paper_2304_04237_amd import build
+        build.build()
+    return sa.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slide_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_calls():
+    names = declared_functions()
+    for required in ("slide_reparam", "slide_attn_fwd", "slide_attn_bwd",
+                     "slide_attn_workspace_bytes", "slide_status_string"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert sa.slide_status_string(0) == "SLIDE_OK"
+    for code in range(1, 7):
+        assert sa.slide_status_string(code).startswith("SLIDE_ERR_")
+    assert "UNKNOWN" in sa.slide_status_string(99)
+
+
+FWD_OK = dict(B=1, H=14, W=14, C=64, heads=2, ksize=3, dtype=0)
+
+
+def call_fwd(lib, ptr=0x1000, **kw):
+    a = dict(FWD_OK); a.update(kw)
+    p = ctypes.c_void_p(ptr)
+    return lib.slide_attn_fwd(p, p, p, p, p, p, p, a["B"], a["H"], a["W"], a["C"], a["heads"],
+                              a["ksize"], a["dtype"], None, 0, None)
+
+
+def test_forward_rejects_bad_arguments_on_the_host(lib):
+    # none of these may reach a kernel launch: the pointers are not real device memory
+    assert call_fwd(lib, heads=3) == 2             # C % heads != 0
+    assert call_fwd(lib, ksize=4) == 2             # even window
+    assert call_fwd(lib, ksize=0) == 2
+    assert call_fwd(lib, ksize=9) == 2             # unsupported instantiation
+    assert call_fwd(lib, B=0) == 2
+    assert call_fwd(lib, H=-1) == 2
+    assert call_fwd(lib, dtype=7) == 3
+    assert call_fwd(lib, ptr=0) == 1               # NULL pointers
+    assert call_fwd(lib, ptr=0x1002) == 6          # misaligned for float32
+    assert call_fwd(lib, ptr=0x1001, dtype=1) == 6 # misaligned for bfloat16
+
+
+def test_backward_rejects_bad_arguments_on_the_host(lib):
+    p = ctypes.c_void_p(0x1000)
+    args13 = [p] * 13
+    shape = [1, 14, 14, 64, 2, 3, 0]
+    need = lib.slide_attn_workspace_bytes(*shape, 1)
+    assert need > 0
+    assert lib.slide_attn_bwd(*args13, *shape, None, 0, None) == 4            # no workspace
+    assert lib.slide_attn_bwd(*args13, *shape, p, need - 1, None) == 4        # too small
+    bad = list(args13); bad[9] = None
+    assert lib.slide_attn_bwd(*bad, *shape, p, need, None) == 1               # dv NULL
+    bad = list(args13); bad[12] = None
+    assert lib.slide_attn_bwd(*bad, *shape, p, need, None) == 1               # bias without dbias
+    shape_bad = [1, 14, 14, 64, 5, 3, 0]
+    assert lib.slide_attn_bwd(*args13, *shape_bad, p, need, None) == 2
+
+
+def test_workspace_query(lib):
+    assert lib.slide_attn_workspace_bytes(1, 14, 14, 64, 2, 3, 0, 0) == 0     # forward needs none
+    assert lib.slide_attn_workspace_bytes(1, 14, 14, 64, 3, 3, 0, 1) == 0     # invalid -> 0
+    small = lib.slide_attn_workspace_bytes(1, 14, 14, 64, 2, 3, 0, 1)
+    big = lib.slide_attn_workspace_bytes(4, 14, 14, 64, 2, 3, 0, 1)
+    assert 0 < small < big
+
+
+def test_reparam_rejects_bad_arguments(lib):
+    p = ctypes.c_void_p(0x1000)
+    assert lib.slide_reparam(None, p, 4, 3, None) == 1
+    assert lib.slide_reparam(p, p, 0, 3, None) == 2
+    assert lib.slide_reparam(p, p, 4, 2, None) == 2
+
+
+def test_forward_path_selection(lib):
+    assert lib.slide_attn_fwd_path(1, 14, 14, 64, 2, 3, 0) == 1     # float32 -> general kernel
+    assert lib.slide_attn_fwd_path(1, 14, 14, 64, 3, 3, 0) == 0
