@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the Slide Attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" = re-parameterise both kernels (slide_reparam x2) + slide_attn_fwd on the
+stage-1 forward workload (B=64, 56x56, C=64, 2 heads, k=3, bf16), inputs already
+resident in HBM.  Inputs rotate through a pool of buffer sets larger than the
+256 MB last-level cache so the figure is HBM bandwidth, not cache bandwidth.
+Prints ONE JSON line: whole-job Gpixel*head/s, the HBM roofline of the forward
+kernel (algorithmic bytes / measured kernel time), the training workload
+(B=128 forward + backward) as extra context, and the CPU oracle timed on this
+machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+POOL_SETS = 4                  # 4 x 103 MB > 256 MB cache
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-train", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the operator needs no second GPU; "
+              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2304_04237_amd as sa
+    from paper_2304_04237_amd import synth
+
+    sa.load_library()                       # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl, data = synth.make_config_inputs(1)
+    B, H, W, C, heads, ksize = wl.B, wl.H, wl.W, wl.C, wl.heads, wl.ksize
+    px_heads = B * H * W * heads
+    esz = 2
+    alg_bytes = 4 * B * C * H * W * esz     # q, k, v read once + out written once
+
+    # pool of input sets (set 0 holds the seeded tensors, the others are seeded copies
+    # of the same distribution so every launch reads memory not touched recently)
+    pool = []
+    for s in range(POOL_SETS):
+        d = data if s == 0 else synth.make_inputs(B, H, W, C, heads, ksize, wl.dtype, seed=5000 + s,
+                                                  with_dout=False)
+        pool.append({n: d[n].to(dev).to(torch.bfloat16) for n in ("q", "k", "v")})
+        pool[-1]["out"] = torch.empty_like(pool[-1]["q"])
+    wk_l = data["wk_learned"].to(dev)
+    wv_l = data["wv_learned"].to(dev)
+    bias = data["bias"].to(dev)
+    wk = torch.empty_like(wk_l)
+    wv = torch.empty_like(wv_l)
+    path = sa.slide_attn_fwd_path(B, H, W, C, heads, ksize, torch.bfloat16)
+
+    def step(i, ev=None):
+        s = pool[i % POOL_SETS]
+        sa.slide_reparam(wk_l, wk)
+        sa.slide_reparam(wv_l, wv)
+        if ev is not None:
+            ev[0].record()
+        sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, heads, ksize, out=s["out"])
+        if ev is not None:
+            ev[1].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(args.steps):
+        step(i, evs[i])
+    end.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    total_ms = start.elapsed_time(end)
+    ms_per_step = total_ms / args.steps
+    fwd_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
+    fwd_med_ms = fwd_ms[len(fwd_ms) // 2]
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+    achieved = alg_bytes / (fwd_avg_ms * 1e-3) / 1e9
+    result = {
+        "metric": "slide-attn fwd Gpixel*head/s at 56x56 stage-1 (reparam + forward per step)",
+        "value": px_heads / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gpixel*head/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "stage1_bf16_fwd: B=64 H=W=56 C=64 heads=2 head_dim=32 ksize=3",
+                   "inputs": "seeded N(0,1) q,k,v; N(0,0.02^2) learned kernels and bias",
+                   "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path,
+                   "host_wall_ms_per_step": wall_ms / args.steps},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "slide_attn_fwd", "algorithmic_bytes": alg_bytes,
+                     "avg_launch_ms": fwd_avg_ms, "median_launch_ms": fwd_med_ms,
+                     "min_launch_ms": fwd_ms[0]},
+    }
+
+    # ---- training workload (B=128 forward + backward), extra context
+    if not args.no_train:
+        del pool
+        torch.cuda.empty_cache()
+        wl5, d5 = synth.make_config_inputs(4)
+        sets = []
+        for s in range(2):
+            d = d5 if s == 0 else synth.make_inputs(wl5.B, wl5.H, wl5.W, wl5.C, wl5.heads, wl5.ksize,
+                                                    wl5.dtype, seed=6000 + s)
+            sets.append({n: d[n].to(dev).to(torch.bfloat16) for n in ("q", "k", "v", "dout")})
+            sets[-1]["out"] = torch.empty_like(sets[-1]["q"])
+        need = sa.slide_attn_workspace_bytes(wl5.B, wl5.H, wl5.W, wl5.C, wl5.heads, wl5.ksize,
+                                             torch.bfloat16, True)
+        ws = torch.empty(max(need, 1), dtype=torch.uint8, device=dev)
+        outs = (torch.empty_like(sets[0]["q"]), torch.empty_like(sets[0]["q"]),
+                torch.empty_like(sets[0]["q"]), torch.empty_like(wk), torch.empty_like(wv),
+                torch.empty_like(bias))
+        n_train = max(3, min(20, args.steps // 10))
+
+        def train_step(i):
+            s = sets[i % 2]
+            sa.slide_reparam(wk_l, wk)
+            sa.slide_reparam(wv_l, wv)
+            sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, wl5.heads, wl5.ksize, out=s["out"])
+            sa.slide_attn_bwd(s["dout"], s["q"], s["k"], s["v"], wk, wv, bias, wl5.heads, wl5.ksize,
+                              workspace=ws, outputs=outs)
+
+        for i in range(2):
+            train_step(i)
+        torch.cuda.synchronize()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n_train):
+            train_step(i)
+        b.record()
+        torch.cuda.synchronize()
+        tms = a.elapsed_time(b) / n_train
+        pxh5 = wl5.B * wl5.H * wl5.W * wl5.heads
+        result["training"] = {"workload": "stage1_bf16_train: B=128 H=W=56 C=64 heads=2 ksize=3, fwd+bwd",
+                              "ms_per_step": tms, "steps": n_train,
+                              "value": pxh5 / (tms * 1e-3) / 1e9, "unit": "Gpixel*head/s",
+                              "workspace_bytes": need}
+        del sets, ws, outs
+        torch.cuda.empty_cache()
+
+    # ---- CPU oracle on this machine's host cores (a reported baseline, not a target)
+    if not args.no_cpu_baseline:
+        from oracle import slide_oracle as oracle
+        nb = 16                                   # bounded sample: 16 of the 64 batch items
+        n = {x: data[x][:nb].double().numpy() for x in ("q", "k", "v")}
+        wkm = oracle.reparam(data["wk_learned"].double().numpy(), ksize)
+        wvm = oracle.reparam(data["wv_learned"].double().numpy(), ksize)
+        bn = data["bias"].double().numpy()
+        oracle.fwd(n["q"][:1], n["k"][:1], n["v"][:1], wkm, wvm, bn, heads, ksize)      # warm up
+        t1 = time.perf_counter()
+        oracle.fwd(n["q"], n["k"], n["v"], wkm, wvm, bn, heads, ksize)
+        dt = time.perf_counter() - t1
+        result["cpu_baseline"] = {"value": nb * H * W * heads / dt / 1e9, "unit": "Gpixel*head/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": "forward of the first %d of 64 batch items of the same "
+                                            "workload, fp64 C loops, OpenMP over (batch, head); "
+                                            "%.2f s wall" % (nb, dt)}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -39,7 +39,7 @@ typedef enum {
     SLIDE_ERR_DTYPE = 3,      /* dtype is not SLIDE_F32 / SLIDE_BF16 */
     SLIDE_ERR_WORKSPACE = 4,  /* workspace NULL or smaller than slide_attn_workspace_bytes() */
     SLIDE_ERR_HIP = 5,        /* a kernel launch failed (hipGetLastError) */
-    SLIDE_ERR_ALIGN = 6       /* an activation pointer is not aligned to its element size */
+    SLIDE_ERR_ALIGN = 6       /* a pointer is not aligned to its element size (workspace: 16 bytes) */
 } slide_status;
 
 typedef enum { SLIDE_F32 = 0, SLIDE_BF16 = 1 } slide_dtype;
@@ -107,7 +107,7 @@ const char* slide_status_string(int status);
  * Which forward implementation slide_attn_fwd would run for this problem:
  * 0 = invalid arguments, 1 = general kernel (any supported ksize / head size /
  * dtype, float32 vector arithmetic), 2 = matrix-core kernel (bf16, d = 32,
- * ksize 3 or 5).  Host-only; for tests and benchmarks.
+ * ksize 3).  Host-only; for tests and benchmarks.
  */
 int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype);
 

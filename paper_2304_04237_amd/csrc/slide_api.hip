@@ -48,7 +48,7 @@ extern "C" size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int hea
 {
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
-    return backward ? slide::bwd_generic_workspace_bytes(p) : 0;
+    return backward ? slide::bwd_generic_workspace_bytes(p) : slide::fwd_mfma_workspace_bytes(p);
 }
 
 extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype)
@@ -70,12 +70,13 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
     if (!aligned_to(q, esz) || !aligned_to(k, esz) || !aligned_to(v, esz) || !aligned_to(out, esz) ||
         !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4))
         return SLIDE_ERR_ALIGN;
-    (void)workspace; (void)workspace_bytes;       // the forward needs no scratch
     Problem p{B, H, W, C, heads, ksize, dtype};
     hipError_t e;
-    if (slide::fwd_mfma_supported(p))
-        e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
-    else
+    if (slide::fwd_mfma_supported(p)) {
+        if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
+        if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
+        e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, workspace, (hipStream_t)stream);
+    } else
         e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }

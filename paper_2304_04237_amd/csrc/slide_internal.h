@@ -25,10 +25,11 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
-// ---- matrix-core forward (slide_fwd_mfma.hip): bf16, d == 32, ksize 3 or 5
+// ---- matrix-core forward (slide_fwd_mfma.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
+size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
-                           hipStream_t st);
+                           void* workspace, hipStream_t st);
 
 }  // namespace slide
