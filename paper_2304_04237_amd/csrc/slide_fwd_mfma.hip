@@ -19,11 +19,13 @@
 // D layout of v_mfma_f32_16x16x16_bf16 with the pixel as column, so no data moves
 // between lanes except two small cross-group reductions (v_permlane{16,32}_swap).
 //
-// K side, per tap t: the products q[c]*k[c,p+t] are formed as a running sum over the
-// lane's 8 channels with v_dot2_f32_bf16 (one operand masked to a single channel), the
-// prefix sums P_0..P_7 are rounded to bf16 and fed to the MFMA against the DIFFERENCED
-// learned weights (w_e - w_{e+1}), which gives sum_e G_e w_e by summation by parts; the
-// last prefix P_7 is the lane's share of the exact shift-path logit for free.
+// K side, per tap t, with G_e = q[e]*k[e,p+t] for the lane's channels e = 0..7: one
+// v_dot2c_f32_bf16 per channel pair y accumulates the running sum R_y = sum_{e <= 2y+1} G_e
+// in place, and one multiply gives the odd product O_y = G_{2y+1}.  (R_y, O_y) are rounded
+// to bf16 and fed to the MFMA against re-combined learned weights
+//     sum_e G_e w_e = sum_y R_y (w_{2y} - w_{2y+2}) + O_y (w_{2y+1} - w_{2y}),   w_8 = 0
+// (summation by parts), and the last running sum R_3 is the lane's share of the exact
+// shift-path logit for free.
 #include "slide_internal.h"
 #include "slide_device.h"
 
@@ -63,37 +65,37 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 }
 
 // ------------------------------------------------------------------ weight preparation
-// grid = heads, block = 256.  Reads the merged float32 kernels [C, 9, 3, 3] and writes
-// the per-head operand image described above.
+// grid = (9 taps, heads), block = 256.  Reads the merged float32 kernels [C, 9, 3, 3] and
+// writes the per-head operand image described above.
 __global__ void __launch_bounds__(256)
 prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
                     const float* __restrict__ bias, uint32_t* __restrict__ image)
 {
-    const int m = blockIdx.x;
+    const int t = blockIdx.x, m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
-    // A1: dword y of lane (i, g) at tap t = learned K weights of channels 8g+2y, 8g+2y+1,
-    // differenced along the lane's channel chain.
-    for (int idx = threadIdx.x; idx < 9 * 64 * 4; idx += blockDim.x) {
-        const int y = idx & 3, lane = (idx >> 2) & 63, t = idx >> 8;
+    const int tid = threadIdx.x;
+    {
+        // A1: dword y of lane (i, g) = weights met by (R_y, O_y) for shift row i, channels
+        // 8g+2y and 8g+2y+1:  (w_{2y} - w_{2y+2},  w_{2y+1} - w_{2y}), learned part only.
+        const int y = tid & 3, lane = tid >> 2;
         const int i = lane & 15, g = lane >> 4;
         const int s = shift_of_row(i);
-        float d[2] = {0.0f, 0.0f};
+        float d0 = 0.0f, d1 = 0.0f;
         if (s >= 0) {
-            for (int h = 0; h < 2; ++h) {
-                const int e = 2 * y + h;
-                const int c = m * D + 8 * g + e;
-                float w0 = wk[((long)c * S + s) * S + t] - (s == t ? 1.0f : 0.0f);
-                float w1 = 0.0f;
-                if (e < 7) w1 = wk[((long)(c + 1) * S + s) * S + t] - (s == t ? 1.0f : 0.0f);
-                d[h] = w0 - w1;
-            }
+            const float id = (s == t) ? 1.0f : 0.0f;
+            const int c = m * D + 8 * g + 2 * y;
+            const float w_even = wk[((long)c * S + s) * S + t] - id;
+            const float w_odd = wk[((long)(c + 1) * S + s) * S + t] - id;
+            const float w_next = (y < 3) ? wk[((long)(c + 2) * S + s) * S + t] - id : 0.0f;
+            d0 = w_even - w_next;
+            d1 = w_odd - w_even;
         }
-        img[IMG_A1 + idx] = pack_bf16(d[0], d[1]);
+        img[IMG_A1 + t * 256 + tid] = pack_bf16(d0, d1);
     }
-    // A2: dword y of lane (i, g) at (tap t, half j) = learned V weights of channel
-    // 8*(i/4) + 4j + (i%4) for the shifts of logit rows 4g+2y, 4g+2y+1.
-    for (int idx = threadIdx.x; idx < 9 * 2 * 64 * 2; idx += blockDim.x) {
-        const int y = idx & 1, lane = (idx >> 1) & 63, j = (idx >> 7) & 1, t = idx >> 8;
+    {
+        // A2: dword y of lane (i, g) at half j = learned V weights of channel
+        // 8*(i/4) + 4j + (i%4) for the shifts of logit rows 4g+2y, 4g+2y+1.
+        const int y = tid & 1, lane = (tid >> 1) & 63, j = tid >> 7;
         const int i = lane & 15, g = lane >> 4;
         const int c = m * D + 8 * (i >> 2) + 4 * j + (i & 3);
         float d[2] = {0.0f, 0.0f};
@@ -101,13 +103,13 @@ prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
             const int s = shift_of_row(4 * g + 2 * y + h);
             if (s >= 0) d[h] = wv[((long)c * S + s) * S + t] - (s == t ? 1.0f : 0.0f);
         }
-        img[IMG_A2 + idx] = pack_bf16(d[0], d[1]);
+        img[IMG_A2 + t * 256 + tid] = pack_bf16(d[0], d[1]);
     }
-    if (threadIdx.x < 16) {
-        const int s = shift_of_row(threadIdx.x);
+    if (t == 0 && tid < 16) {
+        const int s = shift_of_row(tid);
         float b = -INFINITY;
         if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
-        img[IMG_BIAS + threadIdx.x] = __float_as_uint(b);
+        img[IMG_BIAS + tid] = __float_as_uint(b);
     }
 }
 
@@ -214,27 +216,37 @@ fwd_mfma_kernel(const FwdArgs a)
         const int NX = (j0 - 1 + HC - gx0 + 7) >> 3;
         const int n_items = 8 * NX * HR;
         for (int idx = tid; idx < n_items; idx += THREADS) {
+            // item = 8 channels (group o) x 8 columns (chunk x) of one halo row of K or V
             const int o = idx & 3, tsel = (idx >> 2) & 1;
             const int rest = idx >> 3;
             const int hr = rest / NX, x = rest - hr * NX;
             const int gi = i0 - 1 + hr, gx = gx0 + 8 * x;
             const bool row_ok = (gi >= 0) && (gi < a.H);
-            const bf16_bits* src = (tsel ? a.v : a.k) + head_base + ((long)(8 * o) * a.H + gi) * a.W + gx;
+            const bool any_in = row_ok && (gx + 8 > 0) && (gx < a.W);
+            const bf16_bits* plane0 = (tsel ? a.v : a.k) + head_base + (long)(8 * o) * HW;
             uint4_t r[8];
-            if (row_ok && a.vec_ok && gx >= 0 && gx + 8 <= a.W) {
+            if (any_in && a.vec_ok && gx >= 0 && gx + 8 <= a.W) {
+                const bf16_bits* src = plane0 + (long)gi * a.W + gx;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) r[e] = *(const uint4_t*)(src + e * HW);
-            } else {
+            } else if (any_in) {
+                // ragged chunk: element loads from clamped (always valid) columns, then masked
+                const bf16_bits* src = plane0 + (long)gi * a.W;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
 #pragma unroll
                     for (int y = 0; y < 4; ++y) {
                         const int c0 = gx + 2 * y, c1 = c0 + 1;
-                        uint32_t lo = (row_ok && c0 >= 0 && c0 < a.W) ? src[e * HW + 2 * y] : 0;
-                        uint32_t hi = (row_ok && c1 >= 0 && c1 < a.W) ? src[e * HW + 2 * y + 1] : 0;
+                        const int cc0 = min(max(c0, 0), a.W - 1), cc1 = min(max(c1, 0), a.W - 1);
+                        uint32_t lo = src[e * HW + cc0], hi = src[e * HW + cc1];
+                        lo = (c0 == cc0) ? lo : 0u;
+                        hi = (c1 == cc1) ? hi : 0u;
                         r[e][y] = lo | (hi << 16);
                     }
                 }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = uint4_t{0u, 0u, 0u, 0u};
             }
             unsigned char* dst = smem + (tsel ? a.v_base : 0) + hr * HC * 64;
 #pragma unroll
@@ -260,8 +272,13 @@ fwd_mfma_kernel(const FwdArgs a)
     float* ascr = (float*)(smem + a.a_base) + wave * 16 * A_STRIDE + p * A_STRIDE;
     const unsigned char* kl = smem;
     const unsigned char* vl = smem + a.v_base;
+    const bf16_bits* qbase = a.q + head_base;           // block-uniform bases, 32-bit lane offsets
+    bf16_bits* obase = a.out + head_base;
+    const uint32_t hw = (uint32_t)HW;
+    const uint32_t lane_chan = (uint32_t)(8 * g) * hw + (uint32_t)i0 * a.W + j0;
 
-    // q of the first pass
+    // (tile row, tile column) of this lane's pixel in a pass; lanes past the end repeat the
+    // last pixel (they compute but do not store)
     auto pixel_of = [&](int pass, int& ti, int& tj) -> bool {
         int n = pass * 16 + p;
         const bool valid = n < npix;
@@ -270,62 +287,77 @@ fwd_mfma_kernel(const FwdArgs a)
         tj = n - ti * tw_eff;
         return valid;
     };
-    auto load_q = [&](int ti, int tj, uint32_t (&qd)[4]) {
-        const bf16_bits* qp = a.q + head_base + ((long)(8 * g) * a.H + (i0 + ti)) * a.W + (j0 + tj);
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            uint32_t lo = qp[(2 * y) * HW], hi = qp[(2 * y + 1) * HW];
-            qd[y] = lo | (hi << 16);
-        }
-    };
 
-    int ti, tj;
-    uint32_t qd[4];
-    if (wave < npass) {
-        pixel_of(wave, ti, tj);
-        load_q(ti, tj, qd);
+    uint32_t qraw[8];                                   // q of the current pass, one channel per dword
+    {
+        int ti0, tj0;
+        pixel_of(min(wave, npass - 1), ti0, tj0);
+        const uint32_t off = lane_chan + (uint32_t)ti0 * a.W + tj0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qraw[e] = qbase[off + e * hw];
     }
     for (int pass = wave; pass < npass; pass += WAVES) {
+        int ti, tj;
         const bool valid = pixel_of(pass, ti, tj);
-        // prefetch q of this wave's next pass
-        uint32_t qn[4] = {0, 0, 0, 0};
-        if (pass + WAVES < npass) {
+        const uint32_t pix_off = lane_chan + (uint32_t)ti * a.W + tj;
+        // q of this wave's next pass: issued now, consumed at the end of this pass
+        uint32_t qnext[8];
+        {
             int ti2, tj2;
-            pixel_of(pass + WAVES, ti2, tj2);
-            load_q(ti2, tj2, qn);
-        }
-        uint32_t qiso[8];
+            pixel_of(min(pass + WAVES, npass - 1), ti2, tj2);
+            const uint32_t off = lane_chan + (uint32_t)ti2 * a.W + tj2;
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            qiso[2 * y] = qd[y] & 0x0000ffffu;
-            qiso[2 * y + 1] = qd[y] & 0xffff0000u;
+            for (int e = 0; e < 8; ++e) qnext[e] = qbase[off + e * hw];
         }
         int coff[KS];
 #pragma unroll
         for (int tx = 0; tx < KS; ++tx) coff[tx] = col_offset(tj + tx, g);
         const int row0 = ti * HC * 64;
+        uint4_t kd[S];
+#pragma unroll
+        for (int t = 0; t < S; ++t)
+            kd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
 
-        // ---- K side: logits
+        uint32_t qpk[4];        // channel pairs (even low, odd high)
+        float qodd[4];          // the odd channel alone, as float
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            qpk[y] = qraw[2 * y] | (qraw[2 * y + 1] << 16);
+            qodd[y] = __uint_as_float(qraw[2 * y + 1] << 16);
+        }
+
+        // ---- K side: logits.  Three taps (one window row) at a time so that the three
+        // running sums interleave.
         float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
         float idp[S];
 #pragma unroll
-        for (int t = 0; t < S; ++t) {
-            const int ty = t / KS, tx = t % KS;
-            const uint4_t kd = *(const uint4_t*)(kl + row0 + ty * HC * 64 + coff[tx]);
-            float P = 0.0f;
-            float pre[8];
+        for (int ty = 0; ty < KS; ++ty) {
+            float R[KS] = {0.0f, 0.0f, 0.0f};
+            uint4_t bb[KS];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                P = dot2_bf16(qiso[e], kd[e >> 1], P);
-                pre[e] = P;
+            for (int y = 0; y < 4; ++y) {
+#pragma unroll
+                for (int tx = 0; tx < KS; ++tx) {
+                    const uint32_t kw = kd[ty * KS + tx][y];
+                    R[tx] = dot2_bf16(qpk[y], kw, R[tx]);
+                    const float O = qodd[y] * __uint_as_float(kw & 0xffff0000u);
+                    bb[tx][y] = pack_bf16(R[tx], O);
+                }
             }
-            uint4_t bb;
 #pragma unroll
-            for (int y = 0; y < 4; ++y) bb[y] = pack_bf16(pre[2 * y], pre[2 * y + 1]);
-            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1[t], __builtin_bit_cast(bf16x8_t, bb),
-                                                           acc1, 0, 0, 0);
-            idp[t] = P;
+            for (int tx = 0; tx < KS; ++tx) {
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A1[ty * KS + tx],
+                                                               __builtin_bit_cast(bf16x8_t, bb[tx]),
+                                                               acc1, 0, 0, 0);
+                idp[ty * KS + tx] = R[tx];
+            }
         }
+        // V taps: issue the LDS reads now, they land while the softmax runs
+        uint4_t vd[S];
+#pragma unroll
+        for (int t = 0; t < S; ++t)
+            vd[t] = *(const uint4_t*)(vl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+
         // shift-path logits: sum the four channel groups, landing shift 4r+g in group g
         {
             float z1 = fold32(idp[0], idp[2]), z2 = fold32(idp[1], idp[3]);
@@ -351,41 +383,48 @@ fwd_mfma_kernel(const FwdArgs a)
 #pragma unroll
         for (int r = 0; r < 3; ++r) ascr[4 * r + g] = pr[r];
         __builtin_amdgcn_wave_barrier();
+        float at[S];
+#pragma unroll
+        for (int t = 0; t < S; ++t) at[t] = ascr[t];
         uint2_t b2;
         b2[0] = pack_bf16(pr[0], pr[1]);
         b2[1] = pack_bf16(pr[2], 0.0f);
         const short4_t B2 = __builtin_bit_cast(short4_t, b2);
 
-        // ---- V side: out[c] = sum_t v[c, p+t] * (a[t] + learned part)
+        // ---- V side: out[c] = sum_t v[c, p+t] * (a[t] + learned part); a[t] enters as the
+        // MFMA's C operand, so the matrix core adds the two paths
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = 0.0f;
 #pragma unroll
-        for (int t = 0; t < S; ++t) {
-            const int ty = t / KS, tx = t % KS;
-            const uint4_t vd = *(const uint4_t*)(vl + row0 + ty * HC * 64 + coff[tx]);
-            const float at = ascr[t];
-            const float4_t zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int ty = 0; ty < KS; ++ty) {
+            float4_t w[KS][2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const float4_t w = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A2[t][j], B2, zero, 0, 0, 0);
+            for (int tx = 0; tx < KS; ++tx) {
+                const int t = ty * KS + tx;
+                const float4_t c4 = {at[t], at[t], at[t], at[t]};
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = 4 * j + r;
-                    const uint32_t dw = vd[e >> 1];
+                for (int j = 0; j < 2; ++j)
+                    w[tx][j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A2[t][j], B2, c4, 0, 0, 0);
+            }
+#pragma unroll
+            for (int tx = 0; tx < KS; ++tx) {
+                const int t = ty * KS + tx;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t dw = vd[t][e >> 1];
                     const float vf = __uint_as_float((e & 1) ? (dw & 0xffff0000u) : (dw << 16));
-                    o[e] = fmaf(w[r] + at, vf, o[e]);
+                    o[e] = fmaf(w[tx][e >> 2][e & 3], vf, o[e]);
                 }
             }
         }
         // ---- store
         if (valid) {
-            bf16_bits* op = a.out + head_base + ((long)(8 * g) * a.H + (i0 + ti)) * a.W + (j0 + tj);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) op[e * HW] = f32_to_bf16(o[e]);
+            for (int e = 0; e < 8; ++e) obase[pix_off + e * hw] = f32_to_bf16(o[e]);
         }
 #pragma unroll
-        for (int y = 0; y < 4; ++y) qd[y] = qn[y];
+        for (int e = 0; e < 8; ++e) qraw[e] = qnext[e];
     }
 }
 
@@ -431,7 +470,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
 {
     const TilePlan t = plan_tiles(p);
     uint32_t* image = (uint32_t*)workspace;
-    hipLaunchKernelGGL(prep_weights_kernel, dim3((unsigned)p.heads), dim3(256), 0, st,
+    hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
                        wk, wv, bias, image);
     FwdArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
