@@ -1,0 +1,308 @@
+// Kernel and bias gradients of Slide Attention on the matrix cores (gfx950): bf16
+// activations, head size 32, 3x3 window, W a multiple of 8.
+//
+// What is computed (chain rule through Sec. 4.1-4.3; the paper gives no backward):
+//     dwk[c,s,t] = scale * sum_{b,p} dl[b,m,s,p] * q[b,c,p] * k[b,c,p + off(t)]
+//     dwv[c,s,t] =         sum_{b,p}  a[b,m,s,p] * dO[b,c,p] * v[b,c,p + off(t)]
+//     dbias[m,s] =         sum_{b,p} dl[b,m,s,p]
+// with a the attention weights, dl the logit gradients (both produced by the per-pixel
+// backward kernel as float32 [B, heads, 9, H, W]) and zero padding outside the map.
+//
+// Per channel this is a (9 taps) x (9 shifts) matrix whose contraction index is the pixel,
+// so it runs as v_mfma_f32_16x16x32_f16 with K = 32 consecutive pixels of a row:
+//     A[t, p] = q[c,p] * k[c, p + off(t)]      (two packed multiplies per dword, from LDS)
+//     B[p, s] = dl[s, p]                        (shared by all channels of the head)
+// Activations keep their natural layout (pixels contiguous), converted to half precision
+// once while they are staged in LDS; q and dO are divided by 16 there so that products up
+// to 2^20 stay finite, and the factor is restored with the final scale.  The tap windows
+// of k and v start at odd pixel offsets, which the LDS serves as unaligned 16-byte reads.
+// Accumulation is fp32 in the MFMA accumulators across all pixels a block visits; blocks
+// write partial sums that a second kernel adds in a fixed order (reproducible results).
+#include "slide_internal.h"
+#include "slide_device.h"
+
+namespace slide {
+namespace dwpath {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((ext_vector_type(4))) float float4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t uint4_t;
+
+constexpr int S = 9, D = 32;
+constexpr int WAVES = 8, THREADS = WAVES * 64;
+constexpr int CPW = D / WAVES;        // channels per wave (4)
+constexpr int R = 3;                  // rows of one work unit
+constexpr int TW = 56;                // columns of one work unit (a multiple of 8)
+constexpr int QP = 64;                // halves per staged row of q, dO, dl, a
+constexpr int KP = 72;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin
+constexpr float IN_SCALE = 0.0625f;   // q and dO are staged divided by 16
+
+// LDS map (bytes)
+constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 23040
+constexpr int QH_BYTES = D * R * QP * 2;                  // 12288
+constexpr int DL_BYTES = S * R * QP * 2;                  // 3456
+constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
+              OFF_DO = OFF_Q + QH_BYTES, OFF_DL = OFF_DO + QH_BYTES, OFF_A = OFF_DL + DL_BYTES,
+              OFF_ZERO = OFF_A + DL_BYTES, LDS_BYTES = OFF_ZERO + 256;
+
+struct Args {
+    const bf16_bits* dout; const bf16_bits* q; const bf16_bits* k; const bf16_bits* v;
+    const float* attn; const float* dl;       // [B, heads, 9, H, W]
+    float* partial;                           // [NB][2][C][9][9]
+    float* dbias_partial;                     // [NB][heads][9]
+    int B, H, W, C, heads;
+    int n_strips, n_ct, NB;
+    float scale;
+};
+
+__device__ __forceinline__ half2_t as_half2(uint32_t x) { return __builtin_bit_cast(half2_t, x); }
+__device__ __forceinline__ uint32_t as_dword(half2_t x) { return __builtin_bit_cast(uint32_t, x); }
+
+// 8 consecutive bf16 (one 16-byte load) -> 8 halves, same order, times `mul`
+__device__ __forceinline__ uint4_t bf16x8_to_half(uint4_t r, half2_t mul)
+{
+    uint4_t o;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // low half: shift up; high half: the dword itself, its 16 junk bits are truncated by
+        // the round-toward-zero conversion except 3 that the mask clears
+        const uint32_t d = r[j];
+        const uint32_t pk = __builtin_bit_cast(uint32_t,
+            __builtin_amdgcn_cvt_pkrtz(__uint_as_float(d << 16), __uint_as_float(d))) & 0xfff8ffffu;
+        o[j] = as_dword(as_half2(pk) * mul);
+    }
+    return o;
+}
+
+__global__ void __launch_bounds__(THREADS, 4)
+bwd_dw_kernel(const Args a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int m = blockIdx.x / a.NB, j = blockIdx.x - m * a.NB;
+    const long HW = (long)a.H * a.W;
+    const int c0 = m * D + wave * CPW;            // first channel of this wave
+
+    // zero all of LDS once: margins and the zero block stay zero for the whole kernel
+    for (int o = tid * 16; o < LDS_BYTES; o += THREADS * 16) *(uint4_t*)(smem + o) = uint4_t{0u, 0u, 0u, 0u};
+
+    // per-lane read offsets that do not depend on the unit
+    const int ty = (i < S) ? i / 3 : 0, tx = (i < S) ? i - 3 * (i / 3) : 0;
+    const int kwin_off = (ty * KP + 8 + 8 * g + tx - 1) * 2;      // + (cc*(R+2) + r)*KP*2 + 64*h
+    const int q_off = (i < S) ? (8 * g) * 2 : -1;                 // -1: masked row, read zeros
+    const int b_off = (i < S) ? ((i * R) * QP + 8 * g) * 2 : -1;  // + r*QP*2 + 64*h
+
+    float4_t acc_k[CPW], acc_v[CPW];
+#pragma unroll
+    for (int cc = 0; cc < CPW; ++cc) { acc_k[cc] = float4_t{0, 0, 0, 0}; acc_v[cc] = float4_t{0, 0, 0, 0}; }
+    const half2_t one2 = {(_Float16)1.0f, (_Float16)1.0f};
+    const half2_t in2 = {(_Float16)IN_SCALE, (_Float16)IN_SCALE};
+    const bool bias_lane = (wave == 0) && (i == S);               // row 9 of channel 0 sums dl
+
+    const int n_units = a.B * a.n_strips * a.n_ct;
+    __syncthreads();
+    for (int u = j; u < n_units; u += a.NB) {
+        const int ct = u % a.n_ct, us = u / a.n_ct;
+        const int strip = us % a.n_strips, b = us / a.n_strips;
+        const int i0 = strip * R, j0 = ct * TW;
+        const int rows_eff = min(R, a.H - i0), cols_eff = min(TW, a.W - j0);
+        const int nxc = cols_eff >> 3;                            // 16-byte chunks per row
+
+        // ---- stage k, v (with halo), q, dO of this wave's channels: wave-private regions
+        {
+            // k, v: CPW channels x (R+2) rows x 8 chunk slots
+            const int n_kv = CPW * (R + 2) * 8;
+            for (int idx = lane; idx < 2 * n_kv; idx += 64) {
+                const int tsel = idx >= n_kv, id = idx - tsel * n_kv;
+                const int x = id & 7, rj = id >> 3;
+                const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+                const int gi = i0 - 1 + hr;
+                if (x >= nxc) continue;                           // stale data there is finite: fine
+                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
+                if (gi >= 0 && gi < a.H) {
+                    const bf16_bits* src = (tsel ? a.v : a.k) + ((long)b * a.C + c0 + cc) * HW + (long)gi * a.W + j0 + 8 * x;
+                    val = bf16x8_to_half(*(const uint4_t*)src, one2);
+                }
+                *(uint4_t*)(smem + (tsel ? OFF_V : OFF_K) + (((wave * CPW + cc) * (R + 2) + hr) * KP + 8 + 8 * x) * 2) = val;
+            }
+            // halo columns of k, v: one element left and right of the tile
+            const int n_hc = CPW * (R + 2) * 2;
+            for (int idx = lane; idx < 2 * n_hc; idx += 64) {
+                const int tsel = idx >= n_hc, id = idx - tsel * n_hc;
+                const int side = id & 1, rj = id >> 1;
+                const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+                const int gi = i0 - 1 + hr, gj = side ? j0 + cols_eff : j0 - 1;
+                _Float16 hv = (_Float16)0.0f;
+                if (gi >= 0 && gi < a.H && gj >= 0 && gj < a.W) {
+                    const bf16_bits raw = ((tsel ? a.v : a.k) + ((long)b * a.C + c0 + cc) * HW)[(long)gi * a.W + gj];
+                    hv = (_Float16)bf16_to_f32(raw);
+                }
+                *(_Float16*)(smem + (tsel ? OFF_V : OFF_K) +
+                             (((wave * CPW + cc) * (R + 2) + hr) * KP + (side ? 8 + cols_eff : 7)) * 2) = hv;
+            }
+            // q, dO: CPW channels x R rows x 8 chunk slots (zeros past the tile)
+            const int n_q = CPW * R * 8;
+            for (int idx = lane; idx < 2 * n_q; idx += 64) {
+                const int tsel = idx >= n_q, id = idx - tsel * n_q;
+                const int x = id & 7, rj = id >> 3;
+                const int cc = rj / R, r = rj - cc * R;
+                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
+                if (x < nxc && r < rows_eff) {
+                    const bf16_bits* src = (tsel ? a.dout : a.q) + ((long)b * a.C + c0 + cc) * HW + (long)(i0 + r) * a.W + j0 + 8 * x;
+                    val = bf16x8_to_half(*(const uint4_t*)src, in2);
+                }
+                *(uint4_t*)(smem + (tsel ? OFF_DO : OFF_Q) + (((wave * CPW + cc) * R + r) * QP + 8 * x) * 2) = val;
+            }
+        }
+        // ---- stage dl and a of the head (shared by the block): 9 shifts x R rows x 8 chunks
+        {
+            const int n_d = S * R * 8;
+            for (int idx = tid; idx < 2 * n_d; idx += THREADS) {
+                const int tsel = idx >= n_d, id = idx - tsel * n_d;
+                const int x = id & 7, rj = id >> 3;
+                const int s = rj / R, r = rj - s * R;
+                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
+                if (x < nxc && r < rows_eff) {
+                    const float* src = (tsel ? a.attn : a.dl) + (((long)b * a.heads + m) * S + s) * HW + (long)(i0 + r) * a.W + j0 + 8 * x;
+                    const float4_t f0 = *(const float4_t*)src, f1 = *(const float4_t*)(src + 4);
+                    half2_t h;
+                    h = half2_t{(_Float16)f0[0], (_Float16)f0[1]}; val[0] = as_dword(h);
+                    h = half2_t{(_Float16)f0[2], (_Float16)f0[3]}; val[1] = as_dword(h);
+                    h = half2_t{(_Float16)f1[0], (_Float16)f1[1]}; val[2] = as_dword(h);
+                    h = half2_t{(_Float16)f1[2], (_Float16)f1[3]}; val[3] = as_dword(h);
+                }
+                *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * QP + 8 * x) * 2) = val;
+            }
+        }
+        __syncthreads();
+
+        // ---- accumulate: for every 32-pixel chunk, one MFMA per channel and side
+        for (int r = 0; r < rows_eff; ++r) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (32 * h >= cols_eff) continue;
+                const int dl_addr = (b_off >= 0) ? OFF_DL + b_off + r * QP * 2 + 64 * h : OFF_ZERO;
+                const int a_addr = (b_off >= 0) ? OFF_A + b_off + r * QP * 2 + 64 * h : OFF_ZERO;
+                const half8_t Bdl = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + dl_addr));
+                const half8_t Ba = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + a_addr));
+#pragma unroll
+                for (int cc = 0; cc < CPW; ++cc) {
+                    const int ch = wave * CPW + cc;
+                    const int qo = (q_off >= 0) ? ((ch * R + r) * QP) * 2 + q_off + 64 * h : -1;
+                    const int ko = ((ch * (R + 2) + r) * KP) * 2 + kwin_off + 64 * h;
+                    const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
+                    const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
+                    uint4_t kw, vw;
+                    __builtin_memcpy(&kw, smem + OFF_K + ko, 16);      // unaligned 16-byte LDS reads
+                    __builtin_memcpy(&vw, smem + OFF_V + ko, 16);
+                    uint4_t ak, av;
+#pragma unroll
+                    for (int y = 0; y < 4; ++y) {
+                        ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[y]));
+                        av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[y]));
+                    }
+                    if (cc == 0 && wave == 0) {
+#pragma unroll
+                        for (int y = 0; y < 4; ++y) ak[y] = bias_lane ? as_dword(one2) : ak[y];
+                    }
+                    acc_k[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[cc], 0, 0, 0);
+                    acc_v[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[cc], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- partial sums of this block.  Result register r of lane (n, g) is row t = 4g + r,
+    // column s = n of the 16x16 product.
+    const int n = i;
+    const float out_scale = 1.0f / IN_SCALE;
+    if (n < S) {
+        const long side = (long)a.C * S * S;
+        float* base = a.partial + (long)j * 2 * side;
+#pragma unroll
+        for (int cc = 0; cc < CPW; ++cc) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = 4 * g + r;
+                if (t < S) {
+                    base[((long)(c0 + cc) * S + n) * S + t] = acc_k[cc][r] * (a.scale * out_scale);
+                    base[side + ((long)(c0 + cc) * S + n) * S + t] = acc_v[cc][r] * out_scale;
+                }
+            }
+        }
+        if (wave == 0 && g == 2)                                   // row 9 = 4*2 + 1
+            a.dbias_partial[((long)j * a.heads + m) * S + n] = acc_k[0][1];
+    }
+}
+
+// adds the per-block bias partials in block order: dbias[m,s] = sum_j partial[j][m][s]
+__global__ void bwd_dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias,
+                                        int n, int NB)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n) return;
+    float acc = 0.0f;
+    for (int jj = 0; jj < NB; ++jj) acc += partial[(long)jj * n + e];
+    dbias[e] = acc;
+}
+
+static int blocks_per_head(const Problem& p)
+{
+    const long units = (long)p.B * ((p.H + R - 1) / R) * ((p.W + TW - 1) / TW);
+    long nb = 512 / p.heads;                 // two blocks per compute unit
+    if (nb < 1) nb = 1;
+    if (nb > units) nb = units;
+    return (int)nb;
+}
+
+}  // namespace dwpath
+
+bool bwd_dw_mfma_supported(const Problem& p)
+{
+    return p.dtype == 1 && p.ksize == 3 && p.C == p.heads * dwpath::D && (p.W % 8) == 0;
+}
+
+// floats: per-block kernel-gradient partials, then per-block bias partials
+size_t bwd_dw_mfma_partial_floats(const Problem& p)
+{
+    const size_t nb = (size_t)dwpath::blocks_per_head(p);
+    return nb * 2 * (size_t)p.C * 81 + nb * (size_t)p.heads * 9;
+}
+
+hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q, const void* k,
+                              const void* v, const float* attn_ws, const float* dl_ws,
+                              float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st)
+{
+    using namespace dwpath;
+    Args a;
+    a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.attn = attn_ws; a.dl = dl_ws;
+    a.NB = blocks_per_head(p);
+    a.partial = partial;
+    a.dbias_partial = partial + (size_t)a.NB * 2 * p.C * 81;
+    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
+    a.n_strips = (p.H + R - 1) / R; a.n_ct = (p.W + TW - 1) / TW;
+    a.scale = 1.0f / sqrtf((float)D);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)bwd_dw_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
+    const long side = (long)p.C * 81;
+    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, st);
+    if (dbias) {
+        const int nbias = p.heads * 9;
+        hipLaunchKernelGGL(bwd_dbias_reduce_kernel, dim3((unsigned)((nbias + 63) / 64)), dim3(64), 0, st,
+                           a.dbias_partial, dbias, nbias, a.NB);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace slide

@@ -15,6 +15,7 @@
 // block-uniform values, so the compiler fetches them through the scalar cache.
 #include "slide_internal.h"
 #include "slide_device.h"
+#include <initializer_list>
 
 namespace slide {
 
@@ -419,11 +420,31 @@ static int dw_chunks(const Problem& p)
     return (int)n;
 }
 
+hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
+                                hipStream_t st)
+{
+    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 255) / 256)), dim3(256),
+                       0, st, partial, dwk, dwv, side, n_chunks);
+    return hipGetLastError();
+}
+
 size_t bwd_generic_workspace_bytes(const Problem& p)
 {
     size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
     size_t part = (size_t)dw_chunks(p) * 2 * (size_t)p.C * p.S() * p.S() * sizeof(float);
+    if (bwd_dw_mfma_supported(p)) {
+        const size_t part2 = bwd_dw_mfma_partial_floats(p) * sizeof(float);
+        if (part2 > part) part = part2;
+    }
     return 2 * per + part;
+}
+
+// every activation pointer and the workspace are 16-byte aligned (vector loads)
+static bool aligned16(std::initializer_list<const void*> ptrs)
+{
+    for (const void* x : ptrs)
+        if ((uintptr_t)x % 16 != 0) return false;
+    return true;
 }
 
 template <typename T, int KS>
@@ -444,6 +465,10 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
                        (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
                        p.H, p.W, p.C, p.heads);
+    if (bwd_dw_mfma_supported(p) && aligned16({dout, q, k, v, workspace})) {
+        // kernel and bias gradients on the matrix cores
+        return launch_bwd_dw_mfma(p, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias, st);
+    }
     const int n_chunks = dw_chunks(p);
     const long n_items = (long)p.B * p.plane();
     const long per_chunk = (n_items + n_chunks - 1) / n_chunks;

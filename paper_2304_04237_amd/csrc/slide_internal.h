@@ -25,7 +25,17 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
-// ---- matrix-core forward (slide_fwd_mfma.hip): bf16, d == 32, ksize 3
+hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
+                                hipStream_t st);
+
+// ---- matrix-core kernel/bias gradients (slide_bwd_dw.hip): bf16, d == 32, ksize 3, W % 8 == 0
+bool bwd_dw_mfma_supported(const Problem& p);
+size_t bwd_dw_mfma_partial_floats(const Problem& p);
+hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q, const void* k,
+                              const void* v, const float* attn_ws, const float* dl_ws,
+                              float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st);
+
+// ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
