@@ -103,81 +103,137 @@ bwd_dw_kernel(const Args a)
     const bool bias_lane = (wave == 0) && (i == S);               // row 9 of channel 0 sums dl
 
     const int n_units = a.B * a.n_strips * a.n_ct;
-    __syncthreads();
-    for (int u = j; u < n_units; u += a.NB) {
-        const int ct = u % a.n_ct, us = u / a.n_ct;
-        const int strip = us % a.n_strips, b = us / a.n_strips;
-        const int i0 = strip * R, j0 = ct * TW;
-        const int rows_eff = min(R, a.H - i0), cols_eff = min(TW, a.W - j0);
-        const int nxc = cols_eff >> 3;                            // 16-byte chunks per row
 
-        // ---- stage k, v (with halo), q, dO of this wave's channels: wave-private regions
-        {
-            // k, v: CPW channels x (R+2) rows x 8 chunk slots
-            const int n_kv = CPW * (R + 2) * 8;
-            for (int idx = lane; idx < 2 * n_kv; idx += 64) {
-                const int tsel = idx >= n_kv, id = idx - tsel * n_kv;
-                const int x = id & 7, rj = id >> 3;
-                const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
-                const int gi = i0 - 1 + hr;
-                if (x >= nxc) continue;                           // stale data there is finite: fine
-                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
-                if (gi >= 0 && gi < a.H) {
-                    const bf16_bits* src = (tsel ? a.v : a.k) + ((long)b * a.C + c0 + cc) * HW + (long)gi * a.W + j0 + 8 * x;
-                    val = bf16x8_to_half(*(const uint4_t*)src, one2);
-                }
-                *(uint4_t*)(smem + (tsel ? OFF_V : OFF_K) + (((wave * CPW + cc) * (R + 2) + hr) * KP + 8 + 8 * x) * 2) = val;
+    // Geometry of a work unit (uniform): one strip of R rows x TW columns of one batch item.
+    struct Unit { int b, i0, j0, rows_eff, cols_eff, nxc; };
+    auto unit_of = [&](int u) {
+        Unit t;
+        const int ct = u % a.n_ct, us = u / a.n_ct;
+        const int strip = us % a.n_strips;
+        t.b = us / a.n_strips;
+        t.i0 = strip * R; t.j0 = ct * TW;
+        t.rows_eff = min(R, a.H - t.i0); t.cols_eff = min(TW, a.W - t.j0);
+        t.nxc = t.cols_eff >> 3;                                  // 16-byte chunks per row
+        return t;
+    };
+
+    // Staging registers of one unit.  The loads of the next unit are issued before the
+    // current unit is accumulated and are converted into LDS afterwards, so global latency
+    // hides behind the matrix work.  Slots: k/v chunks, k/v halo columns, q/dO chunks of this
+    // wave's channels (wave-private LDS regions), and this thread's share of dl / a.
+    constexpr int N_KV = CPW * (R + 2) * 8, KV_SLOTS = (2 * N_KV + 63) / 64;        // 5
+    constexpr int N_HC = CPW * (R + 2) * 2, HC_SLOTS = (2 * N_HC + 63) / 64;        // 2
+    constexpr int N_Q = CPW * R * 8, Q_SLOTS = (2 * N_Q + 63) / 64;                 // 3
+    constexpr int N_D = S * R * 8;                                                  // 216 per tensor
+    static_assert(2 * N_D <= THREADS, "one dl/a item per thread");
+    uint4_t pre_kv[KV_SLOTS], pre_q[Q_SLOTS];
+    uint32_t pre_hc[HC_SLOTS];
+    float4_t pre_d[2];
+
+    auto issue_loads = [&](const Unit& t) {
+#pragma unroll
+        for (int sl = 0; sl < KV_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_KV, id = idx - tsel * N_KV;
+            const int x = id & 7, rj = id >> 3;
+            const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+            const int gi = t.i0 - 1 + hr;
+            pre_kv[sl] = uint4_t{0u, 0u, 0u, 0u};
+            if (idx < 2 * N_KV && x < t.nxc && gi >= 0 && gi < a.H) {
+                const bf16_bits* src = (tsel ? a.v : a.k) + ((long)t.b * a.C + c0 + cc) * HW + (long)gi * a.W + t.j0 + 8 * x;
+                pre_kv[sl] = *(const uint4_t*)src;
             }
-            // halo columns of k, v: one element left and right of the tile
-            const int n_hc = CPW * (R + 2) * 2;
-            for (int idx = lane; idx < 2 * n_hc; idx += 64) {
-                const int tsel = idx >= n_hc, id = idx - tsel * n_hc;
-                const int side = id & 1, rj = id >> 1;
-                const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
-                const int gi = i0 - 1 + hr, gj = side ? j0 + cols_eff : j0 - 1;
-                _Float16 hv = (_Float16)0.0f;
-                if (gi >= 0 && gi < a.H && gj >= 0 && gj < a.W) {
-                    const bf16_bits raw = ((tsel ? a.v : a.k) + ((long)b * a.C + c0 + cc) * HW)[(long)gi * a.W + gj];
-                    hv = (_Float16)bf16_to_f32(raw);
-                }
+        }
+#pragma unroll
+        for (int sl = 0; sl < HC_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_HC, id = idx - tsel * N_HC;
+            const int side = id & 1, rj = id >> 1;
+            const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+            const int gi = t.i0 - 1 + hr, gj = side ? t.j0 + t.cols_eff : t.j0 - 1;
+            pre_hc[sl] = 0u;
+            if (idx < 2 * N_HC && gi >= 0 && gi < a.H && gj >= 0 && gj < a.W)
+                pre_hc[sl] = ((tsel ? a.v : a.k) + ((long)t.b * a.C + c0 + cc) * HW)[(long)gi * a.W + gj];
+        }
+#pragma unroll
+        for (int sl = 0; sl < Q_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_Q, id = idx - tsel * N_Q;
+            const int x = id & 7, rj = id >> 3;
+            const int cc = rj / R, r = rj - cc * R;
+            pre_q[sl] = uint4_t{0u, 0u, 0u, 0u};
+            if (idx < 2 * N_Q && x < t.nxc && r < t.rows_eff) {
+                const bf16_bits* src = (tsel ? a.dout : a.q) + ((long)t.b * a.C + c0 + cc) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
+                pre_q[sl] = *(const uint4_t*)src;
+            }
+        }
+        {
+            const int tsel = tid >= N_D, id = tid - tsel * N_D;
+            const int x = id & 7, rj = id >> 3;
+            const int s = rj / R, r = rj - s * R;
+            pre_d[0] = float4_t{0, 0, 0, 0}; pre_d[1] = float4_t{0, 0, 0, 0};
+            if (tid < 2 * N_D && x < t.nxc && r < t.rows_eff) {
+                const float* src = (tsel ? a.attn : a.dl) + (((long)t.b * a.heads + m) * S + s) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
+                pre_d[0] = *(const float4_t*)src; pre_d[1] = *(const float4_t*)(src + 4);
+            }
+        }
+    };
+
+    auto commit_to_lds = [&](const Unit& t) {
+#pragma unroll
+        for (int sl = 0; sl < KV_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_KV, id = idx - tsel * N_KV;
+            const int x = id & 7, rj = id >> 3;
+            const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+            // slots past the tile keep stale (finite) data: they only ever meet a zero q
+            if (idx < 2 * N_KV && x < t.nxc)
+                *(uint4_t*)(smem + (tsel ? OFF_V : OFF_K) + (((wave * CPW + cc) * (R + 2) + hr) * KP + 8 + 8 * x) * 2) =
+                    bf16x8_to_half(pre_kv[sl], one2);
+        }
+#pragma unroll
+        for (int sl = 0; sl < HC_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_HC, id = idx - tsel * N_HC;
+            const int side = id & 1, rj = id >> 1;
+            const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
+            if (idx < 2 * N_HC)
                 *(_Float16*)(smem + (tsel ? OFF_V : OFF_K) +
-                             (((wave * CPW + cc) * (R + 2) + hr) * KP + (side ? 8 + cols_eff : 7)) * 2) = hv;
-            }
-            // q, dO: CPW channels x R rows x 8 chunk slots (zeros past the tile)
-            const int n_q = CPW * R * 8;
-            for (int idx = lane; idx < 2 * n_q; idx += 64) {
-                const int tsel = idx >= n_q, id = idx - tsel * n_q;
-                const int x = id & 7, rj = id >> 3;
-                const int cc = rj / R, r = rj - cc * R;
-                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
-                if (x < nxc && r < rows_eff) {
-                    const bf16_bits* src = (tsel ? a.dout : a.q) + ((long)b * a.C + c0 + cc) * HW + (long)(i0 + r) * a.W + j0 + 8 * x;
-                    val = bf16x8_to_half(*(const uint4_t*)src, in2);
-                }
-                *(uint4_t*)(smem + (tsel ? OFF_DO : OFF_Q) + (((wave * CPW + cc) * R + r) * QP + 8 * x) * 2) = val;
-            }
+                             (((wave * CPW + cc) * (R + 2) + hr) * KP + (side ? 8 + t.cols_eff : 7)) * 2) =
+                    (_Float16)bf16_to_f32((bf16_bits)pre_hc[sl]);
         }
-        // ---- stage dl and a of the head (shared by the block): 9 shifts x R rows x 8 chunks
-        {
-            const int n_d = S * R * 8;
-            for (int idx = tid; idx < 2 * n_d; idx += THREADS) {
-                const int tsel = idx >= n_d, id = idx - tsel * n_d;
-                const int x = id & 7, rj = id >> 3;
-                const int s = rj / R, r = rj - s * R;
-                uint4_t val = uint4_t{0u, 0u, 0u, 0u};
-                if (x < nxc && r < rows_eff) {
-                    const float* src = (tsel ? a.attn : a.dl) + (((long)b * a.heads + m) * S + s) * HW + (long)(i0 + r) * a.W + j0 + 8 * x;
-                    const float4_t f0 = *(const float4_t*)src, f1 = *(const float4_t*)(src + 4);
-                    half2_t h;
-                    h = half2_t{(_Float16)f0[0], (_Float16)f0[1]}; val[0] = as_dword(h);
-                    h = half2_t{(_Float16)f0[2], (_Float16)f0[3]}; val[1] = as_dword(h);
-                    h = half2_t{(_Float16)f1[0], (_Float16)f1[1]}; val[2] = as_dword(h);
-                    h = half2_t{(_Float16)f1[2], (_Float16)f1[3]}; val[3] = as_dword(h);
-                }
-                *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * QP + 8 * x) * 2) = val;
-            }
+#pragma unroll
+        for (int sl = 0; sl < Q_SLOTS; ++sl) {
+            const int idx = sl * 64 + lane;
+            const int tsel = idx >= N_Q, id = idx - tsel * N_Q;
+            const int x = id & 7, rj = id >> 3;
+            const int cc = rj / R, r = rj - cc * R;
+            if (idx < 2 * N_Q)
+                *(uint4_t*)(smem + (tsel ? OFF_DO : OFF_Q) + (((wave * CPW + cc) * R + r) * QP + 8 * x) * 2) =
+                    bf16x8_to_half(pre_q[sl], in2);
         }
+        if (tid < 2 * N_D) {
+            const int tsel = tid >= N_D, id = tid - tsel * N_D;
+            const int x = id & 7, rj = id >> 3;
+            const int s = rj / R, r = rj - s * R;
+            uint4_t val;
+            half2_t h;
+            h = half2_t{(_Float16)pre_d[0][0], (_Float16)pre_d[0][1]}; val[0] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[0][2], (_Float16)pre_d[0][3]}; val[1] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[1][0], (_Float16)pre_d[1][1]}; val[2] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[1][2], (_Float16)pre_d[1][3]}; val[3] = as_dword(h);
+            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * QP + 8 * x) * 2) = val;
+        }
+    };
+
+    if (j < n_units) issue_loads(unit_of(j));
+    for (int u = j; u < n_units; u += a.NB) {
+        const Unit t = unit_of(u);
+        __syncthreads();                       // the previous unit's reads of LDS are done
+        commit_to_lds(t);
         __syncthreads();
+        if (u + a.NB < n_units) issue_loads(unit_of(u + a.NB));
+        const int rows_eff = t.rows_eff, cols_eff = t.cols_eff;
 
         // ---- accumulate: for every 32-pixel chunk, one MFMA per channel and side
         for (int r = 0; r < rows_eff; ++r) {
@@ -210,10 +266,10 @@ bwd_dw_kernel(const Args a)
                     }
                     acc_k[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[cc], 0, 0, 0);
                     acc_v[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[cc], 0, 0, 0);
+                    if (cc & 1) __builtin_amdgcn_sched_barrier(0);   // keep two channels in flight, not four
                 }
             }
         }
-        __syncthreads();
     }
 
     // ---- partial sums of this block.  Result register r of lane (n, g) is row t = 4g + r,
@@ -239,15 +295,17 @@ bwd_dw_kernel(const Args a)
     }
 }
 
-// adds the per-block bias partials in block order: dbias[m,s] = sum_j partial[j][m][s]
-__global__ void bwd_dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias,
-                                        int n, int NB)
+// dbias[m,s] = sum_j partial[j][m][s]: one wavefront per entry, lane l adds blocks l, l+64, ...
+// in order, then a fixed butterfly over the lanes
+__global__ void __launch_bounds__(64)
+bwd_dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int n, int NB)
 {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n) return;
+    const int e = blockIdx.x, lane = threadIdx.x;
     float acc = 0.0f;
-    for (int jj = 0; jj < NB; ++jj) acc += partial[(long)jj * n + e];
-    dbias[e] = acc;
+    for (int jj = lane; jj < NB; jj += 64) acc += partial[(long)jj * n + e];
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) acc += __shfl_xor(acc, w, 64);
+    if (lane == 0) dbias[e] = acc;
 }
 
 static int blocks_per_head(const Problem& p)
@@ -299,7 +357,7 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, st);
     if (dbias) {
         const int nbias = p.heads * 9;
-        hipLaunchKernelGGL(bwd_dbias_reduce_kernel, dim3((unsigned)((nbias + 63) / 64)), dim3(64), 0, st,
+        hipLaunchKernelGGL(bwd_dbias_reduce_kernel, dim3((unsigned)nbias), dim3(64), 0, st,
                            a.dbias_partial, dbias, nbias, a.NB);
     }
     return hipGetLastError();

@@ -376,15 +376,21 @@ bwd_dw_partial_kernel(const T* __restrict__ dout, const T* __restrict__ q, const
     }
 }
 
-// Step 4: add the per-chunk partials in chunk order.  n = 2 * C*S*S entries.
-__global__ void bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
-                                     float* __restrict__ dwv, long side, int n_chunks)
+// Step 4: add the per-chunk partials.  One wavefront per output entry: lane l adds chunks
+// l, l+64, ... in order, then the 64 lane sums are combined by a fixed butterfly, so the
+// result does not depend on timing.  n = 2 * C*S*S entries.
+__global__ void __launch_bounds__(256)
+bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
+                     float* __restrict__ dwv, long side, int n_chunks)
 {
-    long e = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long e = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (e >= 2 * side) return;
     float acc = 0.0f;
-    for (int ch = 0; ch < n_chunks; ++ch) acc += partial[(long)ch * 2 * side + e];
-    if (e < side) dwk[e] = acc; else dwv[e - side] = acc;
+    for (int ch = lane; ch < n_chunks; ch += 64) acc += partial[(long)ch * 2 * side + e];
+#pragma unroll
+    for (int w = 32; w > 0; w >>= 1) acc += __shfl_xor(acc, w, 64);
+    if (lane == 0) { if (e < side) dwk[e] = acc; else dwv[e - side] = acc; }
 }
 
 // Step 5: dbias[m,s] = sum over batch and pixels of dl; one block per (m,s),
@@ -423,7 +429,7 @@ static int dw_chunks(const Problem& p)
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
                                 hipStream_t st)
 {
-    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 255) / 256)), dim3(256),
+    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 3) / 4)), dim3(256),
                        0, st, partial, dwk, dwv, side, n_chunks);
     return hipGetLastError();
 }
@@ -477,8 +483,7 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
                        (const T*)dout, (const T*)q, (const T*)k, (const T*)v, attn_ws, dl_ws,
                        partial, p.B, p.H, p.W, p.C, p.heads, per_chunk);
     const long side = (long)p.C * S * S;
-    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 255) / 256)), dim3(256),
-                       0, st, partial, dwk, dwv, side, n_chunks);
+    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, st);
     if (dbias)
         hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
                            dl_ws, dbias, p.B, p.plane(), p.heads, S);
