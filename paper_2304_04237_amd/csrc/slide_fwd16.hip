@@ -28,20 +28,12 @@
 // the B-operand layout of v_mfma_f32_16x16x32_f16 with the channel as K index, and the
 // D layout of v_mfma_f32_16x16x16_f16 with the pixel as column, so no data moves
 // between lanes except two small cross-group reductions (v_permlane{16,32}_swap).
-#include "slide_internal.h"
-#include "slide_device.h"
+#include "slide_tile16.h"
 
 namespace slide {
 namespace f16path {
+using namespace t16;
 
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef __attribute__((ext_vector_type(4))) float float4_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t uint4_t;
-typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
-
-constexpr int KS = 3, S = 9, D = 32;
 constexpr int A_STRIDE = 12;                       // floats per pixel in the attention scratch
 constexpr float G_SCALE = 0.0625f;                 // q is divided by 16 for the MFMA products ...
 constexpr float WK_SCALE = 16.0f;                  // ... and the learned K kernel multiplied by 16
@@ -51,30 +43,6 @@ constexpr float WK_SCALE = 16.0f;                  // ... and the learned K kern
 //   [2304, 4608)   A2: product u (18) x lane (64) x 2 dwords  -- learned V kernel
 //   [4608, 4624)   bias row r (16) as float, times log2(e); -inf on unused rows
 constexpr int IMG_A1 = 0, IMG_A2 = 2304, IMG_BIAS = 4608, IMG_DWORDS = 4624;
-
-// MFMA row 4g+r of the logit tile <-> shift index.  Rows are spread so that each lane
-// group holds at most three live shifts: rows r=0,1 of every group and row 2 of group 0.
-__host__ __device__ constexpr int shift_of_row(int row)
-{
-    const int g = row >> 2, r = row & 3;
-    const int s = 4 * r + g;
-    return (r < 2 || (r == 2 && g == 0)) ? s : -1;
-}
-
-__device__ __forceinline__ uint32_t pack_half(float lo, float hi)
-{
-    half2_t v = {(_Float16)lo, (_Float16)hi};
-    return __builtin_bit_cast(uint32_t, v);
-}
-// Reinterpret a dword as two halves.  Taking the dword by value matters: a bit cast applied
-// directly to an element of a vector variable picks element 0 with this compiler.
-__device__ __forceinline__ half2_t as_half2(uint32_t x) { return __builtin_bit_cast(half2_t, x); }
-__device__ __forceinline__ uint32_t as_dword(half2_t x) { return __builtin_bit_cast(uint32_t, x); }
-// round toward zero: saturates instead of overflowing to infinity
-__device__ __forceinline__ uint32_t pack_half_rtz(float lo, float hi)
-{
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
-}
 
 // ------------------------------------------------------------------ weight preparation
 // grid = (9, heads), block = 256.  Reads the merged float32 kernels [C, 9, 3, 3] and
@@ -128,176 +96,14 @@ prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
     }
 }
 
-// ------------------------------------------------------------------ cross-group reductions
-// lanes l and l+32:  returns a[l] + a[l+32] in lanes 0..31 and b[l-32] + b[l] in lanes 32..63
-__device__ __forceinline__ float fold32(float a, float b)
-{
-    uint2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// rows of 16 lanes: returns (a.r0+a.r1, b.r0+b.r1, a.r2+a.r3, b.r2+b.r3)
-__device__ __forceinline__ float fold16(float a, float b)
-{
-    uint2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ float allmax_groups(float x)
-{
-    uint2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float allsum_groups(float x)
-{
-    uint2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-// byte offset of (halo column hc, channel group g) inside a halo row: 64 B per pixel,
-// the four 16-byte channel-group slots XOR-swizzled by the column so that 8 consecutive
-// pixels of one group fall on 8 different bank quads.
-__device__ __forceinline__ int col_offset(int hc, int g)
-{
-    return hc * 64 + ((g ^ ((hc >> 1) & 3)) << 4);
-}
-
 struct FwdArgs {
     const bf16_bits* q; const bf16_bits* k; const bf16_bits* v; bf16_bits* out;
     const uint32_t* image;   // per-head MFMA operand images
-    int B, H, W, C, heads;
-    int th, tw, n_tc;        // full tile height, tile width, column tiles per plane
-    int nA;                  // full-height row tiles per plane column (class A)
-    int nB, hb;              // remainder rows: nB tiles of height hb (class B)
-    int TA, TB;              // tiles in each class; the queue serves class A first
-    int v_off;               // byte offset of the V halo inside a tile buffer
+    TileGrid g;
     int buf_stride;          // bytes between the two tile buffers
     int a_base;              // byte offset of the attention scratch
-    int vec_ok;              // rows are 16-byte aligned: W % 8 == 0 and 16-byte aligned bases
     float scale_log2e;
 };
-
-// One tile of one (batch, head) plane; every field is wavefront-uniform.
-struct Tile {
-    int i0, j0, rows, cols, m;
-    int gxa, NX, n_items;    // first chunk column, chunks per halo row, staging items
-    long head_base;          // element offset of channel 0 of the head
-};
-
-// List index -> tile.  Class A (full-height tiles) comes first so that dealing the list
-// round-robin to the blocks balances them; inside a class tiles are ordered head, batch, column tile, row tile,
-// and consecutive queue indices are dealt to the 8 XCDs (blocks are dealt round-robin over
-// XCDs too), so vertically adjacent tiles are staged through the same L2 at about the same
-// time and a block rarely changes head.
-__device__ __forceinline__ Tile decode_tile(const FwdArgs& a, int i)
-{
-    int k, n_r, hgt, row_base, cnt;
-    if (i < a.TA) { k = i; n_r = a.nA; hgt = a.th; row_base = 0; cnt = a.TA; }
-    else          { k = i - a.TA; n_r = a.nB; hgt = a.hb; row_base = a.nA * a.th; cnt = a.TB; }
-    if ((cnt & 7) == 0) k = (k & 7) * (cnt >> 3) + (k >> 3);
-    const int per_plane = a.n_tc * n_r;
-    const int plane = k / per_plane;
-    const int rem = k - plane * per_plane;
-    const int tcx = rem / n_r, tr = rem - tcx * n_r;
-    Tile t;
-    t.m = plane / a.B;
-    const int b = plane - t.m * a.B;
-    t.i0 = row_base + tr * hgt;
-    t.rows = min(hgt, a.H - t.i0);
-    t.j0 = tcx * a.tw;
-    t.cols = min(a.tw, a.W - t.j0);
-    t.head_base = ((long)b * a.C + (long)t.m * D) * ((long)a.H * a.W);
-    t.gxa = max(t.j0 - 1, 0) & ~7;
-    const int gxb = min((t.j0 + t.cols + 1 + 7) & ~7, (a.W + 7) & ~7);
-    t.NX = (gxb - t.gxa) >> 3;
-    t.n_items = 8 * t.NX * (t.rows + 2);
-    return t;
-}
-
-// Staging item idx of a tile = 8 channels (group o) x 8 columns (chunk x) of one halo row of
-// K or V.  item_load fetches it from global memory (zeros outside the map); item_store
-// transposes it to 8 pixels x 8 channels, converts to half and writes it to the tile buffer.
-__device__ __forceinline__ void item_load(const FwdArgs& a, const Tile& t, int idx, uint4_t (&r)[8])
-{
-    const int o = idx & 3, tsel = (idx >> 2) & 1;
-    const int rest = idx >> 3;
-    const int hr = rest / t.NX, x = rest - hr * t.NX;
-    const int gi = t.i0 - 1 + hr, gx = t.gxa + 8 * x;
-    const long HW = (long)a.H * a.W;
-    if (gi < 0 || gi >= a.H) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = uint4_t{0u, 0u, 0u, 0u};
-        return;
-    }
-    const bf16_bits* plane0 = (tsel ? a.v : a.k) + t.head_base + (long)(8 * o) * HW;
-    if (a.vec_ok && gx + 8 <= a.W) {
-        const bf16_bits* src = plane0 + (long)gi * a.W + gx;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = *(const uint4_t*)(src + e * HW);
-    } else {
-        // ragged chunk: element loads from clamped (always valid) columns, then masked
-        const bf16_bits* src = plane0 + (long)gi * a.W;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-#pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                const int c0 = gx + 2 * y, c1 = c0 + 1;
-                const int cc0 = min(c0, a.W - 1), cc1 = min(c1, a.W - 1);
-                uint32_t lo = src[e * HW + cc0], hi = src[e * HW + cc1];
-                lo = (c0 == cc0) ? lo : 0u;
-                hi = (c1 == cc1) ? hi : 0u;
-                r[e][y] = lo | (hi << 16);
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ void item_store(const FwdArgs& a, const Tile& t, int idx,
-                                           const uint4_t (&r)[8], unsigned char* buf)
-{
-    const int o = idx & 3, tsel = (idx >> 2) & 1;
-    const int rest = idx >> 3;
-    const int hr = rest / t.NX, x = rest - hr * t.NX;
-    const int gx = t.gxa + 8 * x;
-    const int HC = a.tw + 2;
-    unsigned char* dst = buf + (tsel ? a.v_off : 0) + hr * HC * 64;
-    // Even columns sit in the low half of a dword (shift up to get the float); odd columns
-    // sit in the high half: the float is the dword itself with 16 junk bits below the bf16
-    // mantissa, which a round-toward-zero conversion truncates away except for 3 bits that
-    // the mask clears.
-#pragma unroll
-    for (int px = 0; px < 8; ++px) {
-        uint4_t t4;
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const uint32_t lo = r[2 * y][px >> 1], hi = r[2 * y + 1][px >> 1];
-            if (px & 1)
-                t4[y] = pack_half_rtz(__uint_as_float(lo), __uint_as_float(hi)) & 0xfff8fff8u;
-            else
-                t4[y] = pack_half_rtz(__uint_as_float(lo << 16), __uint_as_float(hi << 16));
-        }
-        const int hc = gx + px - (t.j0 - 1);
-        if (hc >= 0 && hc < t.cols + 2) *(uint4_t*)(dst + col_offset(hc, o)) = t4;
-    }
-}
-
-// halo columns that lie outside the map (left of column 0, right of column W-1) are zero
-__device__ __forceinline__ void zero_pad_columns(const FwdArgs& a, const Tile& t, unsigned char* buf,
-                                                 int tid, int threads)
-{
-    const bool left = (t.j0 == 0), right = (t.j0 + t.cols == a.W);
-    if (!left && !right) return;
-    const int HC = a.tw + 2;
-    const int n = (t.rows + 2) * 16;                    // row x side x tensor x channel group
-    for (int idx = tid; idx < n; idx += threads) {
-        const int o = idx & 3, tsel = (idx >> 2) & 1, side = (idx >> 3) & 1, hr = idx >> 4;
-        if (side ? !right : !left) continue;
-        const int hc = side ? t.cols + 1 : 0;
-        *(uint4_t*)(buf + (tsel ? a.v_off : 0) + hr * HC * 64 + col_offset(hc, o)) = uint4_t{0u, 0u, 0u, 0u};
-    }
-}
 
 // ------------------------------------------------------------------ the fused forward
 // Persistent blocks, one per compute unit.  Block b works through tiles b, b + grid, ... of
@@ -314,12 +120,12 @@ fwd16_kernel(const FwdArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int p = lane & 15, g = lane >> 4;
-    const int n_tiles = a.TA + a.TB;
-    const int HC = a.tw + 2;
-    const uint32_t hw2 = (uint32_t)a.H * (uint32_t)a.W * 2u;
+    const int n_tiles = a.g.TA + a.g.TB;
+    const int HC = a.g.tw + 2;
+    const uint32_t hw2 = (uint32_t)a.g.H * (uint32_t)a.g.W * 2u;
 
     int cur = blockIdx.x;                               // gridDim.x <= n_tiles
-    Tile tcur = decode_tile(a, cur);
+    Tile tcur = decode_tile(a.g, cur);
     // first tile: issue the loads of up to three items per thread before converting any,
     // so that many requests are in flight
     for (int base = 0; base < tcur.n_items; base += 3 * THREADS) {
@@ -327,15 +133,15 @@ fwd16_kernel(const FwdArgs a)
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
             const int idx = base + u * THREADS + tid;
-            if (idx < tcur.n_items) item_load(a, tcur, idx, r[u]);
+            if (idx < tcur.n_items) item_load(a.g, tcur, a.k, a.v, idx, r[u]);
         }
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
             const int idx = base + u * THREADS + tid;
-            if (idx < tcur.n_items) item_store(a, tcur, idx, r[u], smem);
+            if (idx < tcur.n_items) item_store(a.g, tcur, idx, r[u], smem);
         }
     }
-    zero_pad_columns(a, tcur, smem, tid, THREADS);
+    zero_pad_columns(a.g, tcur, smem, tid, THREADS);
 
     half8_t A1[S];
     half4_t A2[2 * S];
@@ -352,8 +158,8 @@ fwd16_kernel(const FwdArgs a)
         Tile tnext = tcur;
         uint4_t pre[8];
         if (has_next) {
-            tnext = decode_tile(a, nxt);
-            if (tid < tnext.n_items) item_load(a, tnext, tid, pre);
+            tnext = decode_tile(a.g, nxt);
+            if (tid < tnext.n_items) item_load(a.g, tnext, a.k, a.v, tid, pre);
         }
         // ---- MFMA weight operands of this head (coalesced reads of the prepared image)
         if (tcur.m != m_loaded) {
@@ -374,14 +180,14 @@ fwd16_kernel(const FwdArgs a)
         }
         bool staged = !has_next;
         auto stage_next = [&]() {
-            if (tid < tnext.n_items) item_store(a, tnext, tid, pre, buf_next);
+            if (tid < tnext.n_items) item_store(a.g, tnext, tid, pre, buf_next);
             uint4_t r[8];
             // items beyond one per thread go to the last waves first: they have the fewest passes
             for (int idx = THREADS + ((tid + 64) & (THREADS - 1)); idx < tnext.n_items; idx += THREADS) {
-                item_load(a, tnext, idx, r);
-                item_store(a, tnext, idx, r, buf_next);
+                item_load(a.g, tnext, a.k, a.v, idx, r);
+                item_store(a.g, tnext, idx, r, buf_next);
             }
-            zero_pad_columns(a, tnext, buf_next, tid, THREADS);
+            zero_pad_columns(a.g, tnext, buf_next, tid, THREADS);
         };
 
         // ---- passes of 16 pixels over the current tile
@@ -389,12 +195,12 @@ fwd16_kernel(const FwdArgs a)
         const int npass = (npix + 15) >> 4;
         const float inv_tw = 1.0f / (float)tcur.cols;
         const unsigned char* kl = buf;
-        const unsigned char* vl = buf + a.v_off;
+        const unsigned char* vl = buf + a.g.v_off;
         // q and out addressing: one block-uniform base (scalar registers) plus a 32-bit byte
         // offset per lane; a head spans 32 * H * W * 2 bytes, far below 4 GB
         const char* qb = (const char*)(a.q + tcur.head_base);
         char* ob = (char*)(a.out + tcur.head_base);
-        const uint32_t lane_chan = (uint32_t)(8 * g) * hw2 + ((uint32_t)tcur.i0 * a.W + tcur.j0) * 2u;
+        const uint32_t lane_chan = (uint32_t)(8 * g) * hw2 + ((uint32_t)tcur.i0 * a.g.W + tcur.j0) * 2u;
 
         // (tile row, tile column) of this lane's pixel in a pass; lanes past the end repeat
         // the last pixel (they compute but do not store)
@@ -411,14 +217,14 @@ fwd16_kernel(const FwdArgs a)
         {
             int ti0, tj0;
             pixel_of(min(wave, npass - 1), ti0, tj0);
-            const uint32_t off = lane_chan + ((uint32_t)ti0 * a.W + tj0) * 2u;
+            const uint32_t off = lane_chan + ((uint32_t)ti0 * a.g.W + tj0) * 2u;
 #pragma unroll
             for (int e = 0; e < 8; ++e) qraw[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
         }
         for (int pass = wave; pass < npass; pass += WAVES) {
             int ti, tj;
             const bool valid = pixel_of(pass, ti, tj);
-            const uint32_t pix_off = lane_chan + ((uint32_t)ti * a.W + tj) * 2u;
+            const uint32_t pix_off = lane_chan + ((uint32_t)ti * a.g.W + tj) * 2u;
             int coff[KS];
 #pragma unroll
             for (int tx = 0; tx < KS; ++tx) coff[tx] = col_offset(tj + tx, g);
@@ -459,7 +265,7 @@ fwd16_kernel(const FwdArgs a)
             {
                 int ti2, tj2;
                 pixel_of(min(pass + WAVES, npass - 1), ti2, tj2);
-                const uint32_t off = lane_chan + ((uint32_t)ti2 * a.W + tj2) * 2u;
+                const uint32_t off = lane_chan + ((uint32_t)ti2 * a.g.W + tj2) * 2u;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qnext[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
             }
@@ -559,72 +365,12 @@ fwd16_kernel(const FwdArgs a)
 // ------------------------------------------------------------------ host side
 constexpr int FWD_WAVES = 4;
 constexpr bool PERSISTENT = false;   // false: one tile per block, two blocks per compute unit
-constexpr int NUM_CU = 256;
-constexpr int LDS_LIMIT = 160 * 1024;
+constexpr int SCRATCH_BYTES = FWD_WAVES * 16 * A_STRIDE * 4;
 
-struct TilePlan {
-    int th, tw, n_tc, nA, nB, hb, TA, TB;
-    int v_off, buf_stride, a_base, lds_bytes, grid;
-};
-
-// makespan of dealing big-first: TA tiles of cost cA first, then TB tiles of cost cB, G blocks
-static double queue_makespan(long TA, double cA, long TB, double cB, int G)
+static TilePlan plan_fwd(const Problem& p)
 {
-    const long qa = TA / G, ra = TA % G;
-    const double lo = qa * cA, hi = (ra ? qa + 1 : qa) * cA;
-    if (TB == 0) return hi;
-    // smallest M with sum_b floor((M - L_b) / cB) >= TB, tried on the grid lo + j*cB, hi + j*cB
-    double best = 1e300;
-    for (long j = 0; j <= TB / G + 2; ++j) {
-        for (int w = 0; w < 2; ++w) {
-            const double M = (w ? hi : lo) + j * cB;
-            if (M < hi) continue;
-            const long cap = (G - ra) * (long)((M - lo) / cB + 1e-9) + ra * (long)((M - hi) / cB + 1e-9);
-            if (cap >= TB && M < best) best = M;
-        }
-    }
-    return best;
-}
-
-static TilePlan plan_tiles(const Problem& p)
-{
-    TilePlan t;
-    t.tw = p.W <= 64 ? p.W : 64;
-    t.n_tc = (p.W + t.tw - 1) / t.tw;
-    const int scratch = FWD_WAVES * 16 * A_STRIDE * 4 + 64;
-    const int per_buf = (PERSISTENT ? (LDS_LIMIT - scratch) / 2 : LDS_LIMIT / 2 - scratch) - 256;
-    int th_max = per_buf / (128 * (t.tw + 2)) - 2;
-    if (th_max < 1) th_max = 1;
-    if (th_max > p.H) th_max = p.H;
-    const long planes = (long)p.B * p.heads * t.n_tc;
-    // choose the tile heights that minimise the greedy queue's makespan (cost of a tile:
-    // its rows plus a fixed share for the halo rows and the per-tile overhead)
-    double best = 1e300;
-    t.th = th_max; t.nA = p.H / th_max; t.nB = (p.H % th_max) ? 1 : 0; t.hb = p.H % th_max;
-    for (int th = th_max; th >= 1 && th >= th_max / 2; --th) {
-        for (int drop = 0; drop < 2; ++drop) {
-            const int nA = p.H / th - drop;
-            if (nA < 0) continue;
-            const int rem = p.H - nA * th;
-            for (int nB = (rem + th - 1) / th; nB <= (rem + th - 1) / th + 2; ++nB) {
-                if ((rem == 0) != (nB == 0)) continue;
-                const int hb = nB ? (rem + nB - 1) / nB : 0;
-                if (nB && (hb < 1 || (long)hb * (nB - 1) >= rem)) continue;
-                const double ms = queue_makespan(planes * nA, th + 1.5, planes * nB, hb + 1.5, NUM_CU);
-                if (ms < best - 1e-9) { best = ms; t.th = th; t.nA = nA; t.nB = nB; t.hb = hb; }
-            }
-        }
-    }
-    t.TA = (int)(planes * t.nA);
-    t.TB = (int)(planes * t.nB);
-    const int halo = (t.th + 2) * (t.tw + 2) * 64;
-    t.v_off = halo + ((halo & 127) ? 0 : 64);             // K and V halos start 64 B apart mod 128
-    t.buf_stride = (t.v_off + halo + 127) & ~127;
-    t.a_base = (PERSISTENT ? 2 : 1) * t.buf_stride;
-    t.lds_bytes = t.a_base + FWD_WAVES * 16 * A_STRIDE * 4;
-    const long n_tiles = (long)t.TA + t.TB;
-    t.grid = (int)((PERSISTENT && n_tiles > NUM_CU) ? NUM_CU : n_tiles);
-    return t;
+    const int budget = PERSISTENT ? (LDS_LIMIT - SCRATCH_BYTES) / 2 : LDS_LIMIT / 2 - SCRATCH_BYTES;
+    return plan_tiles(p, budget, 64, 64);
 }
 
 }  // namespace f16path
@@ -647,19 +393,18 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
                            void* workspace, hipStream_t st)
 {
     using namespace f16path;
-    const TilePlan t = plan_tiles(p);
+    const TilePlan t = plan_fwd(p);
     uint32_t* image = (uint32_t*)workspace;
     hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
                        wk, wv, bias, image);
     FwdArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.image = image;
-    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
-    a.th = t.th; a.tw = t.tw; a.n_tc = t.n_tc; a.nA = t.nA; a.nB = t.nB; a.hb = t.hb;
-    a.TA = t.TA; a.TB = t.TB;
-    a.v_off = t.v_off; a.buf_stride = t.buf_stride; a.a_base = t.a_base;
-    a.vec_ok = (p.W % 8 == 0) && (((uintptr_t)k | (uintptr_t)v) % 16 == 0);
+    fill_grid(a.g, p, t, k, v);
+    a.buf_stride = t.buf_bytes;
+    a.a_base = (PERSISTENT ? 2 : 1) * t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    const int lds_bytes = a.a_base + SCRATCH_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)fwd16_kernel<FWD_WAVES, PERSISTENT>,
@@ -667,8 +412,10 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((fwd16_kernel<FWD_WAVES, PERSISTENT>), dim3((unsigned)t.grid), dim3(FWD_WAVES * 64),
-                       (size_t)t.lds_bytes, st, a);
+    const long n_tiles = (long)t.TA + t.TB;
+    const unsigned grid = (unsigned)((PERSISTENT && n_tiles > NUM_CU) ? NUM_CU : n_tiles);
+    hipLaunchKernelGGL((fwd16_kernel<FWD_WAVES, PERSISTENT>), dim3(grid), dim3(FWD_WAVES * 64),
+                       (size_t)lds_bytes, st, a);
     return hipGetLastError();
 }
 
