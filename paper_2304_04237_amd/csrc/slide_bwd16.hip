@@ -1,0 +1,264 @@
+// Matrix-core backward of Slide Attention for gfx950 (bf16 activations, head size 32, 3x3
+// window): the gradients of the keys and values.
+//
+// The paper gives no backward; this is the chain rule through the operator of Sec. 4.1-4.3.
+// With a the attention weights and dl the logit gradients of a pixel (both produced by the
+// per-pixel backward kernel, float32 [B, heads, 9, H, W]) the deformed shift is a depthwise
+// cross-correlation, so its transpose gathers, for a target pixel y, from the 9 source
+// pixels p' = y - off(t) that see y through tap t:
+//     dk[c,y] = scale * sum_t q[c,p']  * ( dl[p',t] + sum_s wl_k[c,s,t] dl[p',s] )
+//     dv[c,y] =         sum_t dO[c,p'] * (  a[p',t] + sum_s wl_v[c,s,t]  a[p',s] )
+// (source pixels outside the map contribute nothing; wl = merged kernel minus one-hot).
+// The inner sums over s are the dense part: per source pixel a [32 channels x 9] x [9]
+// product, run as v_mfma_f32_16x16x16_f16 with the 16 target pixels of a pass as columns.
+// Walking the 3x3 window position u around y, the source pixel is y + off(u) and its tap is
+// t = 8 - u.
+//
+// Tiles of q and dO are staged like the forward's k and v tiles; a and dl of the halo pixels
+// are staged as 16-half records in the MFMA operand order (slot 4g+r holds shift 4r+g).
+#include "slide_tile16.h"
+
+namespace slide {
+namespace b16path {
+using namespace t16;
+
+constexpr int WAVES = 4, THREADS = WAVES * 64;
+constexpr int REC_BYTES = 32;                       // 16 halves per halo pixel and tensor
+
+// Per-head image of the MFMA weight operands (dwords), written by prep_dkdv_weights_kernel:
+//   side (K: 0, V: 1) x tap t (9) x channel half j (2) x lane (64) x 2 dwords.
+// Row i of product (t, j) is channel 8*(i/4) + 4j + (i%4); dword y of lane (i, g) holds the
+// learned weights for the shifts of operand slots 4g+2y and 4g+2y+1.
+constexpr int IMG_DWORDS = 2 * S * 2 * 64 * 2;      // 4608
+
+__global__ void __launch_bounds__(256)
+prep_dkdv_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
+                         uint32_t* __restrict__ image)
+{
+    const int t = blockIdx.x, m = blockIdx.y;
+    uint32_t* img = image + (long)m * IMG_DWORDS;
+    for (int idx = threadIdx.x; idx < 2 * 2 * 128; idx += 256) {
+        const int y = idx & 1, lane = (idx >> 1) & 63, j = (idx >> 7) & 1, side = idx >> 8;
+        const int i = lane & 15, g = lane >> 4;
+        const int c = m * D + 8 * (i >> 2) + 4 * j + (i & 3);
+        const float* w = side ? wv : wk;
+        float d[2] = {0.0f, 0.0f};
+        for (int h = 0; h < 2; ++h) {
+            const int s = shift_of_row(4 * g + 2 * y + h);
+            if (s >= 0) d[h] = w[((long)c * S + s) * S + t] - (s == t ? 1.0f : 0.0f);
+        }
+        img[((side * S + t) * 2 + j) * 128 + lane * 2 + y] = pack_half(d[0], d[1]);
+    }
+}
+
+struct DkdvArgs {
+    const bf16_bits* q; const bf16_bits* dout;
+    const float* attn; const float* dl;       // [B, heads, 9, H, W]
+    bf16_bits* dk; bf16_bits* dv;
+    const uint32_t* image;
+    TileGrid g;                               // first staged tensor q, second dO
+    int rec_dl, rec_a;                        // byte offsets of the dl / a records in LDS
+    float scale;
+};
+
+// halo pixel record of one tensor (a or dl): 16 halves, slot kk holds shift shift_of_row(kk)
+__device__ __forceinline__ void make_record(const float (&x)[S], uint4_t& lo, uint4_t& hi)
+{
+    lo[0] = pack_half(x[0], x[4]);  lo[1] = pack_half(x[8], 0.0f);   // slots 0..3
+    lo[2] = pack_half(x[1], x[5]);  lo[3] = 0u;                      // slots 4..7
+    hi[0] = pack_half(x[2], x[6]);  hi[1] = 0u;                      // slots 8..11
+    hi[2] = pack_half(x[3], x[7]);  hi[3] = 0u;                      // slots 12..15
+}
+// byte offset inside a record of the half that holds shift s
+__host__ __device__ constexpr int rec_slot_bytes(int s) { return 2 * (4 * (s & 3) + (s >> 2)); }
+
+__global__ void __launch_bounds__(THREADS, 2)
+bwd_dkdv_kernel16(const DkdvArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int p = lane & 15, g = lane >> 4;
+    const int HC = a.g.tw + 2;
+    const long HW = (long)a.g.H * a.g.W;
+    const uint32_t hw2 = (uint32_t)HW * 2u;
+
+    const Tile tcur = decode_tile(a.g, blockIdx.x);
+
+    // ---- stage q and dO halo tiles (loads of up to three items per thread in flight)
+    for (int base = 0; base < tcur.n_items; base += 3 * THREADS) {
+        uint4_t r[3][8];
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int idx = base + u * THREADS + tid;
+            if (idx < tcur.n_items) item_load(a.g, tcur, a.q, a.dout, idx, r[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int idx = base + u * THREADS + tid;
+            if (idx < tcur.n_items) item_store(a.g, tcur, idx, r[u], smem);
+        }
+    }
+    zero_pad_columns(a.g, tcur, smem, tid, THREADS);
+
+    // ---- stage the dl and a records of every halo pixel (zero outside the map)
+    {
+        const int hrows = tcur.rows + 2, hcols = tcur.cols + 2;
+        const int n_px = hrows * hcols;
+        const float inv_hc = 1.0f / (float)hcols;
+        const long plane_ws = ((long)(tcur.head_base / (HW * D))) * S * HW;   // (b*heads + m) * 9 * HW
+        for (int idx = tid; idx < 2 * n_px; idx += THREADS) {
+            const int tsel = idx >= n_px, id = idx - tsel * n_px;
+            const int hr = (int)(((float)id + 0.5f) * inv_hc), hc = id - hr * hcols;
+            const int gi = tcur.i0 - 1 + hr, gj = tcur.j0 - 1 + hc;
+            float x[S];
+#pragma unroll
+            for (int s = 0; s < S; ++s) x[s] = 0.0f;
+            if (gi >= 0 && gi < a.g.H && gj >= 0 && gj < a.g.W) {
+                const float* src = (tsel ? a.attn : a.dl) + plane_ws + (long)gi * a.g.W + gj;
+#pragma unroll
+                for (int s = 0; s < S; ++s) x[s] = src[(long)s * HW];
+            }
+            uint4_t lo, hi;
+            make_record(x, lo, hi);
+            unsigned char* dst = smem + (tsel ? a.rec_a : a.rec_dl) + (hr * HC + hc) * REC_BYTES;
+            *(uint4_t*)dst = lo;
+            *(uint4_t*)(dst + 16) = hi;
+        }
+    }
+
+    __syncthreads();
+
+    // ---- MFMA weight operands of this head (loaded after the barrier: the staging registers
+    // are free by now)
+    const uint32_t* img = a.image + (long)tcur.m * IMG_DWORDS;
+    half4_t Ak[S][2], Av[S][2];
+#pragma unroll
+    for (int t = 0; t < S; ++t) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint2_t wk2 = *(const uint2_t*)(img + ((0 * S + t) * 2 + j) * 128 + lane * 2);
+            const uint2_t wv2 = *(const uint2_t*)(img + ((1 * S + t) * 2 + j) * 128 + lane * 2);
+            Ak[t][j] = __builtin_bit_cast(half4_t, wk2);
+            Av[t][j] = __builtin_bit_cast(half4_t, wv2);
+        }
+    }
+
+    // ---- passes of 16 target pixels
+    const int npix = tcur.rows * tcur.cols;
+    const int npass = (npix + 15) >> 4;
+    const float inv_tw = 1.0f / (float)tcur.cols;
+    const unsigned char* ql = smem;
+    const unsigned char* dol = smem + a.g.v_off;
+    char* dkb = (char*)(a.dk + tcur.head_base);
+    char* dvb = (char*)(a.dv + tcur.head_base);
+    const uint32_t lane_chan = (uint32_t)(8 * g) * hw2 + ((uint32_t)tcur.i0 * a.g.W + tcur.j0) * 2u;
+    const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    for (int pass = wave; pass < npass; pass += WAVES) {
+        int n = pass * 16 + p;
+        const bool valid = n < npix;
+        n = valid ? n : npix - 1;
+        const int ti = (int)(((float)n + 0.5f) * inv_tw);
+        const int tj = n - ti * tcur.cols;
+        const uint32_t pix_off = lane_chan + ((uint32_t)ti * a.g.W + tj) * 2u;
+
+        float dk[8], dv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { dk[e] = 0.0f; dv[e] = 0.0f; }
+#pragma unroll
+        for (int u = 0; u < S; ++u) {
+            const int uy = u / KS, ux = u % KS;
+            const int t = S - 1 - u;                               // tap through which y + off(u) sees y
+            const int hpix = (ti + uy) * HC + tj + ux;             // halo pixel index of the source
+            const unsigned char* rdl = smem + a.rec_dl + hpix * REC_BYTES;
+            const unsigned char* ra = smem + a.rec_a + hpix * REC_BYTES;
+            const half4_t Bdl = __builtin_bit_cast(half4_t, *(const uint2_t*)(rdl + 8 * g));
+            const half4_t Ba = __builtin_bit_cast(half4_t, *(const uint2_t*)(ra + 8 * g));
+            const float dl_t = (float)*(const _Float16*)(rdl + rec_slot_bytes(t));
+            const float a_t = (float)*(const _Float16*)(ra + rec_slot_bytes(t));
+            const int toff = (ti + uy) * HC * 64 + col_offset(tj + ux, g);
+            const uint4_t qd = *(const uint4_t*)(ql + toff);
+            const uint4_t dod = *(const uint4_t*)(dol + toff);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float4_t Lk = __builtin_amdgcn_mfma_f32_16x16x16f16(Ak[t][j], Bdl, zero4, 0, 0, 0);
+                const float4_t Lv = __builtin_amdgcn_mfma_f32_16x16x16f16(Av[t][j], Ba, zero4, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = 4 * j + r;
+                    const half2_t qh = as_half2(qd[e >> 1]), dh = as_half2(dod[e >> 1]);
+                    dk[e] = fmaf(Lk[r] + dl_t, (float)qh[e & 1], dk[e]);
+                    dv[e] = fmaf(Lv[r] + a_t, (float)dh[e & 1], dv[e]);
+                }
+            }
+            if (ux == KS - 1) {
+                // one window row at a time: pin the partial sums here so that the multiply-adds
+                // of this row are not all deferred to the end of the pass (which would keep
+                // every MFMA result live at once)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(dk[e]), "+v"(dv[e]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (valid) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                *(bf16_bits*)(dkb + (pix_off + (uint32_t)e * hw2)) = f32_to_bf16(dk[e] * a.scale);
+                *(bf16_bits*)(dvb + (pix_off + (uint32_t)e * hw2)) = f32_to_bf16(dv[e]);
+            }
+        }
+    }
+}
+
+static TilePlan plan_dkdv(const Problem& p)
+{
+    return plan_tiles(p, LDS_LIMIT / 2, 64, 64, 2 * REC_BYTES);
+}
+
+}  // namespace b16path
+
+bool bwd_dkdv_mfma_supported(const Problem& p)
+{
+    if (p.dtype != 1 || p.ksize != 3 || p.C != p.heads * t16::D) return false;
+    const long planes = (long)p.B * p.heads * ((p.W + 63) / 64);
+    return planes * p.H < (1L << 30);
+}
+
+size_t bwd_dkdv_mfma_image_bytes(const Problem& p)
+{
+    return (size_t)p.heads * b16path::IMG_DWORDS * sizeof(uint32_t);
+}
+
+hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
+                                const float* wk, const float* wv,
+                                const float* attn_ws, const float* dl_ws,
+                                void* dk, void* dv, void* image_ws, hipStream_t st)
+{
+    using namespace b16path;
+    const TilePlan t = plan_dkdv(p);
+    uint32_t* image = (uint32_t*)image_ws;
+    hipLaunchKernelGGL(prep_dkdv_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st, wk, wv, image);
+    DkdvArgs a;
+    a.q = (const bf16_bits*)q; a.dout = (const bf16_bits*)dout;
+    a.attn = attn_ws; a.dl = dl_ws;
+    a.dk = (bf16_bits*)dk; a.dv = (bf16_bits*)dv;
+    a.image = image;
+    fill_grid(a.g, p, t, q, dout);
+    a.rec_dl = t.buf_bytes;
+    a.rec_a = t.buf_bytes + t.halo_px * REC_BYTES;
+    a.scale = 1.0f / sqrtf((float)D);
+    const int lds_bytes = t.buf_bytes + 2 * t.halo_px * REC_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const unsigned grid = (unsigned)((long)t.TA + t.TB);
+    hipLaunchKernelGGL(bwd_dkdv_kernel16, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace slide

@@ -434,15 +434,21 @@ hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, lo
     return hipGetLastError();
 }
 
-size_t bwd_generic_workspace_bytes(const Problem& p)
+// bytes of the partial kernel-gradient region (whichever kernel runs), a multiple of 16
+static size_t bwd_partial_bytes(const Problem& p)
 {
-    size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
     size_t part = (size_t)dw_chunks(p) * 2 * (size_t)p.C * p.S() * p.S() * sizeof(float);
     if (bwd_dw_mfma_supported(p)) {
         const size_t part2 = bwd_dw_mfma_partial_floats(p) * sizeof(float);
         if (part2 > part) part = part2;
     }
-    return 2 * per + part;
+    return (part + 15) & ~(size_t)15;
+}
+
+size_t bwd_generic_workspace_bytes(const Problem& p)
+{
+    size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
+    return 2 * per + bwd_partial_bytes(p) + (bwd_dkdv_mfma_supported(p) ? bwd_dkdv_mfma_image_bytes(p) : 0);
 }
 
 // every activation pointer and the workspace are 16-byte aligned (vector loads)
@@ -468,9 +474,14 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
                        (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
                        (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
-    hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
-                       (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
-                       p.H, p.W, p.C, p.heads);
+    if (bwd_dkdv_mfma_supported(p) && aligned16({dout, q, workspace})) {
+        void* image_ws = (char*)partial + bwd_partial_bytes(p);
+        hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, dk, dv, image_ws, st);
+        if (e != hipSuccess) return e;
+    } else
+        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
+                           (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
+                           p.H, p.W, p.C, p.heads);
     if (bwd_dw_mfma_supported(p) && aligned16({dout, q, k, v, workspace})) {
         // kernel and bias gradients on the matrix cores
         return launch_bwd_dw_mfma(p, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias, st);

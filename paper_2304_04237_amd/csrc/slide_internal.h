@@ -35,6 +35,14 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
                               const void* v, const float* attn_ws, const float* dl_ws,
                               float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st);
 
+// ---- matrix-core key/value gradients (slide_bwd16.hip): bf16, d == 32, ksize 3
+bool bwd_dkdv_mfma_supported(const Problem& p);
+size_t bwd_dkdv_mfma_image_bytes(const Problem& p);
+hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
+                                const float* wk, const float* wv,
+                                const float* attn_ws, const float* dl_ws,
+                                void* dk, void* dv, void* image_ws, hipStream_t st);
+
 // ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head

@@ -224,6 +224,7 @@ constexpr int LDS_LIMIT = 160 * 1024;
 struct TilePlan {
     int th, tw, n_tc, nA, nB, hb, TA, TB;
     int v_off, buf_bytes;    // the two halo tensors of a tile occupy buf_bytes of LDS
+    int halo_px;             // halo pixels of a full tile: (th + 2) * (tw + 2)
 };
 
 // makespan of dealing big-first: TA tiles of cost cA first, then TB tiles of cost cB, G blocks
@@ -247,12 +248,14 @@ inline double queue_makespan(long TA, double cA, long TB, double cB, int G)
 
 // Tile heights for a kernel that may spend lds_budget bytes on one tile buffer holding two
 // halo tensors of px_bytes per halo pixel each (64 for a staged activation tensor).
-inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int px_bytes_b)
+// px_bytes_extra: further LDS bytes per halo pixel that the kernel places after the buffer.
+inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int px_bytes_b,
+                           int px_bytes_extra = 0)
 {
     TilePlan t;
     t.tw = p.W <= 64 ? p.W : 64;
     t.n_tc = (p.W + t.tw - 1) / t.tw;
-    const int px_bytes = px_bytes_a + px_bytes_b;
+    const int px_bytes = px_bytes_a + px_bytes_b + px_bytes_extra;
     int th_max = (lds_budget - 256) / (px_bytes * (t.tw + 2)) - 2;
     if (th_max < 1) th_max = 1;
     if (th_max > p.H) th_max = p.H;
@@ -279,6 +282,7 @@ inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int
     t.TA = (int)(planes * t.nA);
     t.TB = (int)(planes * t.nB);
     const int halo_px = (t.th + 2) * (t.tw + 2);
+    t.halo_px = halo_px;
     t.v_off = halo_px * px_bytes_a;
     if ((t.v_off & 127) == 0) t.v_off += 64;             // the two tensors start 64 B apart mod 128
     t.buf_bytes = (t.v_off + halo_px * px_bytes_b + 127) & ~127;
