@@ -211,12 +211,351 @@ bwd_dkdv_kernel16(const DkdvArgs a)
     }
 }
 
+// ------------------------------------------------------------------ per-pixel backward
+// For every pixel of a tile: recompute the attention weights a (as the forward does), then
+//     da[s] = sum_c dO[c] Vs[c,s]        (same shape as the logits, with dO, v, wv)
+//     dl[s] = a[s] (da[s] - sum_s' a[s'] da[s'])
+//     dq[c] = scale * sum_t k[c,p+t] (dl[t] + sum_s dl[s] wl_k[c,s,t])   (same shape as out)
+// a and dl go to the workspace as float32 [B, heads, 9, H, W] for the other two kernels.
+//
+// Per-head operand image (dwords): A1k [0,2304): learned K kernel (times 16), tap t x lane x 4;
+// A1v [2304,4608): learned V kernel (times 16), same arrangement; A2k [4608,6912): learned K
+// kernel, product u (18) x lane x 2, arranged like the forward's V-side operand; bias rows.
+constexpr int PX_A1K = 0, PX_A1V = 2304, PX_A2K = 4608, PX_BIAS = 6912, PX_IMG_DWORDS = 6928;
+constexpr int A_STRIDE = 12;
+constexpr float G_SCALE = 0.0625f, W_SCALE = 16.0f;
+
+__global__ void __launch_bounds__(256)
+prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
+                          const float* __restrict__ bias, uint32_t* __restrict__ image)
+{
+    const int t = blockIdx.x, m = blockIdx.y;
+    uint32_t* img = image + (long)m * PX_IMG_DWORDS;
+    const int tid = threadIdx.x;
+    {
+        // A1 arrangement, tap t: dword y of lane (i, g) = learned weights of channels 8g+2y,
+        // 8g+2y+1 for the shift of logit row i
+        const int y = tid & 3, lane = tid >> 2;
+        const int i = lane & 15, g = lane >> 4;
+        const int s = shift_of_row(i);
+        float k0 = 0.0f, k1 = 0.0f, v0 = 0.0f, v1 = 0.0f;
+        if (s >= 0) {
+            const float id = (s == t) ? 1.0f : 0.0f;
+            const int c = m * D + 8 * g + 2 * y;
+            k0 = (wk[((long)c * S + s) * S + t] - id) * W_SCALE;
+            k1 = (wk[((long)(c + 1) * S + s) * S + t] - id) * W_SCALE;
+            v0 = (wv[((long)c * S + s) * S + t] - id) * W_SCALE;
+            v1 = (wv[((long)(c + 1) * S + s) * S + t] - id) * W_SCALE;
+        }
+        img[PX_A1K + t * 256 + tid] = pack_half(k0, k1);
+        img[PX_A1V + t * 256 + tid] = pack_half(v0, v1);
+    }
+    {
+        // A2 arrangement of the K kernel, products u = 2t and 2t+1 (see the forward kernel)
+        const int y = tid & 1, lane = (tid >> 1) & 63, u = 2 * t + (tid >> 7);
+        const int i = lane & 15, g = lane >> 4;
+        int c, tap;
+        if (u < 16) { c = 8 * (i >> 2) + (u & 7); tap = 4 * (u >> 3) + (i & 3); }
+        else        { c = 8 * (i >> 2) + 4 * (u - 16) + (i & 3); tap = 8; }
+        c += m * D;
+        float d[2] = {0.0f, 0.0f};
+        for (int h = 0; h < 2; ++h) {
+            const int s = shift_of_row(4 * g + 2 * y + h);
+            if (s >= 0) d[h] = wk[((long)c * S + s) * S + tap] - (s == tap ? 1.0f : 0.0f);
+        }
+        img[PX_A2K + u * 128 + (tid & 127)] = pack_half(d[0], d[1]);
+    }
+    if (t == 0 && tid < 16) {
+        const int s = shift_of_row(tid);
+        float b = -INFINITY;
+        if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
+        img[PX_BIAS + tid] = __float_as_uint(b);
+    }
+}
+
+struct PixelArgs {
+    const bf16_bits* dout; const bf16_bits* q; const bf16_bits* k; const bf16_bits* v;
+    bf16_bits* dq;
+    float* attn; float* dl;                   // [B, heads, 9, H, W]
+    const uint32_t* image;
+    TileGrid g;                               // first staged tensor k, second v
+    int a_base;                               // byte offset of the per-wave scratch
+    float scale, scale_log2e;
+};
+
+// x . (deformed shift of y) for the 9 shifts: the learned part through the matrix core
+// (accumulated into acc, rows 4g+r of the 16x16 tile), the shift part exactly into idp
+__device__ __forceinline__ void window_dots(const uint4_t (&yd)[S], const half2_t (&xpk)[4],
+                                            const half2_t (&xs)[4], const half8_t (&A)[S],
+                                            float4_t& acc, float (&idp)[S])
+{
+#pragma unroll
+    for (int t = 0; t < S; ++t) {
+        float R = 0.0f;
+        uint4_t bb;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const half2_t w = as_half2(yd[t][y]);
+            R = __builtin_amdgcn_fdot2(xpk[y], w, R, false);
+            bb[y] = as_dword(xs[y] * w);
+        }
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
+        idp[t] = R;
+    }
+}
+// sums the four channel groups of the exact dot products, landing shift 4r+g in group g
+__device__ __forceinline__ void fold_groups(const float (&idp)[S], float4_t& acc)
+{
+    float z1 = fold32(idp[0], idp[2]), z2 = fold32(idp[1], idp[3]);
+    acc[0] += fold16(z1, z2);
+    z1 = fold32(idp[4], idp[6]); z2 = fold32(idp[5], idp[7]);
+    acc[1] += fold16(z1, z2);
+    z1 = fold32(idp[8], 0.0f);
+    acc[2] += fold16(z1, 0.0f);
+}
+__device__ __forceinline__ void raw_to_halves(const uint32_t (&raw)[8], half2_t (&pk)[4], half2_t (&sc)[4])
+{
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+        pk[y] = as_half2(pack_half_rtz(__uint_as_float(raw[2 * y] << 16), __uint_as_float(raw[2 * y + 1] << 16)));
+        sc[y] = pk[y] * half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
+    }
+}
+
+__global__ void __launch_bounds__(THREADS, 2)
+bwd_pixel_kernel16(const PixelArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int p = lane & 15, g = lane >> 4;
+    const int HC = a.g.tw + 2;
+    const long HW = (long)a.g.H * a.g.W;
+    const uint32_t hw2 = (uint32_t)HW * 2u;
+
+    const Tile tcur = decode_tile(a.g, blockIdx.x);
+    for (int base = 0; base < tcur.n_items; base += 3 * THREADS) {
+        uint4_t r[3][8];
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int idx = base + u * THREADS + tid;
+            if (idx < tcur.n_items) item_load(a.g, tcur, a.k, a.v, idx, r[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 3; ++u) {
+            const int idx = base + u * THREADS + tid;
+            if (idx < tcur.n_items) item_store(a.g, tcur, idx, r[u], smem);
+        }
+    }
+    zero_pad_columns(a.g, tcur, smem, tid, THREADS);
+    __syncthreads();
+
+    const uint32_t* img = a.image + (long)tcur.m * PX_IMG_DWORDS;
+    half8_t A1k[S], A1v[S];
+    half4_t A2k[2 * S];
+#pragma unroll
+    for (int t = 0; t < S; ++t) {
+        A1k[t] = __builtin_bit_cast(half8_t, *(const uint4_t*)(img + PX_A1K + (t * 64 + lane) * 4));
+        A1v[t] = __builtin_bit_cast(half8_t, *(const uint4_t*)(img + PX_A1V + (t * 64 + lane) * 4));
+    }
+#pragma unroll
+    for (int u = 0; u < 2 * S; ++u)
+        A2k[u] = __builtin_bit_cast(half4_t, *(const uint2_t*)(img + PX_A2K + (u * 64 + lane) * 2));
+    float bias2[3];
+#pragma unroll
+    for (int r = 0; r < 3; ++r) bias2[r] = __uint_as_float(img[PX_BIAS + 4 * g + r]);
+
+    const int npix = tcur.rows * tcur.cols;
+    const int npass = (npix + 15) >> 4;
+    const float inv_tw = 1.0f / (float)tcur.cols;
+    float* ascr = (float*)(smem + a.a_base) + wave * 16 * A_STRIDE + p * A_STRIDE;
+    const unsigned char* kl = smem;
+    const unsigned char* vl = smem + a.g.v_off;
+    const char* qb = (const char*)(a.q + tcur.head_base);
+    const char* dob = (const char*)(a.dout + tcur.head_base);
+    char* dqb = (char*)(a.dq + tcur.head_base);
+    const uint32_t lane_chan = (uint32_t)(8 * g) * hw2 + ((uint32_t)tcur.i0 * a.g.W + tcur.j0) * 2u;
+    const long ws_plane = ((long)(tcur.head_base / (HW * D))) * S * HW + (long)tcur.i0 * a.g.W + tcur.j0;
+
+    auto pixel_of = [&](int pass, int& ti, int& tj) -> bool {
+        int n = pass * 16 + p;
+        const bool valid = n < npix;
+        n = valid ? n : npix - 1;
+        ti = (int)(((float)n + 0.5f) * inv_tw);
+        tj = n - ti * tcur.cols;
+        return valid;
+    };
+
+    uint32_t qraw[8], draw[8];
+    {
+        int ti0, tj0;
+        pixel_of(min(wave, npass - 1), ti0, tj0);
+        const uint32_t off = lane_chan + ((uint32_t)ti0 * a.g.W + tj0) * 2u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            qraw[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
+            draw[e] = *(const bf16_bits*)(dob + (off + (uint32_t)e * hw2));
+        }
+    }
+    for (int pass = wave; pass < npass; pass += WAVES) {
+        int ti, tj;
+        const bool valid = pixel_of(pass, ti, tj);
+        const uint32_t pix_off = lane_chan + ((uint32_t)ti * a.g.W + tj) * 2u;
+        int coff[KS];
+#pragma unroll
+        for (int tx = 0; tx < KS; ++tx) coff[tx] = col_offset(tj + tx, g);
+        const int row0 = ti * HC * 64;
+
+        // ---- attention weights (as in the forward)
+        uint4_t xd[S];
+#pragma unroll
+        for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+        half2_t xpk[4], xs[4];
+        raw_to_halves(qraw, xpk, xs);
+        float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        float idp[S];
+        window_dots(xd, xpk, xs, A1k, acc, idp);
+        // next pass's q and dO: issued now, used at the end of this pass
+        uint32_t qnext[8], dnext[8];
+        {
+            int ti2, tj2;
+            pixel_of(min(pass + WAVES, npass - 1), ti2, tj2);
+            const uint32_t off = lane_chan + ((uint32_t)ti2 * a.g.W + tj2) * 2u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                qnext[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
+                dnext[e] = *(const bf16_bits*)(dob + (off + (uint32_t)e * hw2));
+            }
+        }
+        // v taps for the da step
+#pragma unroll
+        for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(vl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+        fold_groups(idp, acc);
+        float l[3], pr[3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) l[r] = fmaf(acc[r], a.scale_log2e, bias2[r]);
+        const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
+#pragma unroll
+        for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
+        const float inv = __builtin_amdgcn_rcpf(allsum_groups(pr[0] + pr[1] + pr[2]));
+#pragma unroll
+        for (int r = 0; r < 3; ++r) pr[r] *= inv;
+
+        // ---- da[s] = dO . Vs[s], then dl
+        raw_to_halves(draw, xpk, xs);
+        acc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        window_dots(xd, xpk, xs, A1v, acc, idp);
+        // k taps again for the dq step
+#pragma unroll
+        for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+        fold_groups(idp, acc);
+        const float dsum = allsum_groups(pr[0] * acc[0] + pr[1] * acc[1] + pr[2] * acc[2]);
+        float dl[3];
+#pragma unroll
+        for (int r = 0; r < 3; ++r) dl[r] = pr[r] * (acc[r] - dsum);
+        if (valid) {
+            const long wo = ws_plane + (long)ti * a.g.W + tj;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                if (r < 2 || g == 0) {
+                    a.attn[wo + (long)(4 * r + g) * HW] = pr[r];
+                    a.dl[wo + (long)(4 * r + g) * HW] = dl[r];
+                }
+            }
+        }
+
+        // ---- dq[c] = scale * sum_t k[c,p+t] (dl[t] + learned part); dl[t] enters as the MFMA's
+        // C operand
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < 3; ++r) ascr[4 * r + g] = dl[r];          // slots 9..11 are never read
+        __builtin_amdgcn_wave_barrier();
+        const float4_t c0 = *(const float4_t*)(ascr), c1 = *(const float4_t*)(ascr + 4);
+        const float c8s = ascr[8];
+        uint2_t b2;
+        b2[0] = pack_half(dl[0], dl[1]);
+        b2[1] = pack_half(dl[2], 0.0f);
+        const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float4_t w0 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[e], B2, c0, 0, 0, 0);
+            const float4_t w1 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[8 + e], B2, c1, 0, 0, 0);
+            float s0 = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s0 = fmaf(w0[r], (float)as_half2(xd[r][e >> 1])[e & 1], s0);
+                s0 = fmaf(w1[r], (float)as_half2(xd[4 + r][e >> 1])[e & 1], s0);
+            }
+            o[e] = s0;
+            if ((e & 1) == 1) {
+                asm volatile("" : "+v"(o[e - 1]), "+v"(o[e]));         // bound the live MFMA results
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        {
+            const float4_t c8 = {c8s, c8s, c8s, c8s};
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float4_t w8 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[16 + j], B2, c8, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = 4 * j + r;
+                    o[e] = fmaf(w8[r], (float)as_half2(xd[8][e >> 1])[e & 1], o[e]);
+                }
+            }
+        }
+        if (valid) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *(bf16_bits*)(dqb + (pix_off + (uint32_t)e * hw2)) = f32_to_bf16(o[e] * a.scale);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { qraw[e] = qnext[e]; draw[e] = dnext[e]; }
+    }
+}
+
 static TilePlan plan_dkdv(const Problem& p)
 {
     return plan_tiles(p, LDS_LIMIT / 2, 64, 64, 2 * REC_BYTES);
 }
 
 }  // namespace b16path
+
+size_t bwd_pixel_mfma_image_bytes(const Problem& p)
+{
+    return (size_t)p.heads * b16path::PX_IMG_DWORDS * sizeof(uint32_t);
+}
+
+hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
+                                 const void* v, const float* wk, const float* wv, const float* bias,
+                                 void* dq, float* attn_ws, float* dl_ws, void* image_ws, hipStream_t st)
+{
+    using namespace b16path;
+    constexpr int SCRATCH = WAVES * 16 * A_STRIDE * 4;
+    const TilePlan t = plan_tiles(p, LDS_LIMIT / 2 - SCRATCH, 64, 64);
+    uint32_t* image = (uint32_t*)image_ws;
+    hipLaunchKernelGGL(prep_pixel_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
+                       wk, wv, bias, image);
+    PixelArgs a;
+    a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q;
+    a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.dq = (bf16_bits*)dq; a.attn = attn_ws; a.dl = dl_ws; a.image = image;
+    fill_grid(a.g, p, t, k, v);
+    a.a_base = t.buf_bytes;
+    a.scale = 1.0f / sqrtf((float)D);
+    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const unsigned grid = (unsigned)((long)t.TA + t.TB);
+    hipLaunchKernelGGL(bwd_pixel_kernel16, dim3(grid), dim3(THREADS), (size_t)(t.buf_bytes + SCRATCH), st, a);
+    return hipGetLastError();
+}
 
 bool bwd_dkdv_mfma_supported(const Problem& p)
 {

@@ -448,7 +448,7 @@ static size_t bwd_partial_bytes(const Problem& p)
 size_t bwd_generic_workspace_bytes(const Problem& p)
 {
     size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
-    return 2 * per + bwd_partial_bytes(p) + (bwd_dkdv_mfma_supported(p) ? bwd_dkdv_mfma_image_bytes(p) : 0);
+    return 2 * per + bwd_partial_bytes(p) + (bwd_dkdv_mfma_supported(p) ? bwd_dkdv_mfma_image_bytes(p) + bwd_pixel_mfma_image_bytes(p) : 0);
 }
 
 // every activation pointer and the workspace are 16-byte aligned (vector loads)
@@ -471,10 +471,16 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     float* dl_ws = attn_ws + per;
     float* partial = dl_ws + per;
     dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
-    hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
-                       (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
-                       (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
-    if (bwd_dkdv_mfma_supported(p) && aligned16({dout, q, workspace})) {
+    const bool fast = bwd_dkdv_mfma_supported(p) && aligned16({dout, q, k, v, workspace});
+    if (fast) {
+        void* image_ws = (char*)partial + bwd_partial_bytes(p) + bwd_dkdv_mfma_image_bytes(p);
+        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, image_ws, st);
+        if (e != hipSuccess) return e;
+    } else
+        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
+                           (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
+                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
+    if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
         hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, dk, dv, image_ws, st);
         if (e != hipSuccess) return e;

@@ -38,6 +38,10 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
 // ---- matrix-core key/value gradients (slide_bwd16.hip): bf16, d == 32, ksize 3
 bool bwd_dkdv_mfma_supported(const Problem& p);
 size_t bwd_dkdv_mfma_image_bytes(const Problem& p);
+size_t bwd_pixel_mfma_image_bytes(const Problem& p);
+hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
+                                 const void* v, const float* wk, const float* wv, const float* bias,
+                                 void* dq, float* attn_ws, float* dl_ws, void* image_ws, hipStream_t st);
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
                                 const float* attn_ws, const float* dl_ws,
