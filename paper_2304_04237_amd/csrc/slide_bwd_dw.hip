@@ -15,7 +15,7 @@
 // Activations keep their natural layout (pixels contiguous), converted to half precision
 // once while they are staged in LDS; q and dO are divided by 16 there so that products up
 // to 2^20 stay finite, and the factor is restored with the final scale.  The tap windows
-// of k and v start at odd pixel offsets, which the LDS serves as unaligned 16-byte reads.
+// of k and v start at odd pixel offsets; they are read as aligned dwords and funnel-shifted.
 // Accumulation is fp32 in the MFMA accumulators across all pixels a block visits; blocks
 // write partial sums that a second kernel adds in a fixed order (reproducible results).
 #include "slide_internal.h"
@@ -75,6 +75,29 @@ __device__ __forceinline__ uint4_t bf16x8_to_half(uint4_t r, half2_t mul)
     return o;
 }
 
+// Five consecutive dwords from each of two 4-byte aligned LDS addresses, as dword-granular
+// reads.  Written in assembly because the compiler fuses such reads into 16-byte reads, and
+// a 16-byte LDS read at an address that is not 16-byte aligned stalls the LDS pipe.
+__device__ __forceinline__ void lds_read_2x5_dwords(uint32_t addr_a, uint32_t addr_b,
+                                                    uint32_t (&a)[5], uint32_t (&b)[5])
+{
+    typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
+    uint2_t a01, a23, b01, b23;
+    uint32_t a4, b4;
+    asm volatile("ds_read2_b32 %0, %6 offset1:1\n\t"
+                 "ds_read2_b32 %1, %6 offset0:2 offset1:3\n\t"
+                 "ds_read_b32 %2, %6 offset:16\n\t"
+                 "ds_read2_b32 %3, %7 offset1:1\n\t"
+                 "ds_read2_b32 %4, %7 offset0:2 offset1:3\n\t"
+                 "ds_read_b32 %5, %7 offset:16\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(a01), "=&v"(a23), "=&v"(a4), "=&v"(b01), "=&v"(b23), "=&v"(b4)
+                 : "v"(addr_a), "v"(addr_b)
+                 : "memory");
+    a[0] = a01[0]; a[1] = a01[1]; a[2] = a23[0]; a[3] = a23[1]; a[4] = a4;
+    b[0] = b01[0]; b[1] = b01[1]; b[2] = b23[0]; b[3] = b23[1]; b[4] = b4;
+}
+
 __global__ void __launch_bounds__(THREADS, 4)
 bwd_dw_kernel(const Args a)
 {
@@ -91,7 +114,11 @@ bwd_dw_kernel(const Args a)
 
     // per-lane read offsets that do not depend on the unit
     const int ty = (i < S) ? i / 3 : 0, tx = (i < S) ? i - 3 * (i / 3) : 0;
-    const int kwin_off = (ty * KP + 8 + 8 * g + tx - 1) * 2;      // + (cc*(R+2) + r)*KP*2 + 64*h
+    // The tap window of k (v) is the aligned 8-pixel run moved by tx-1 pixels.  It is read as
+    // five aligned dwords starting one dword early (tx = 0) or at the run (tx = 1, 2) and funnel-
+    // shifted by 16 bits for the odd offsets: misaligned 16-byte LDS reads stall the LDS pipe.
+    const int kwin_off = (ty * KP + 8 + 8 * g) * 2 - 4 + (tx >= 1 ? 4 : 0);   // + (cc*(R+2) + r)*KP*2 + 64*h
+    const uint32_t win_shift = (tx == 1) ? 0u : 16u;
     const int q_off = (i < S) ? (8 * g) * 2 : -1;                 // -1: masked row, read zeros
     const int b_off = (i < S) ? ((i * R) * QP + 8 * g) * 2 : -1;  // + r*QP*2 + 64*h
 
@@ -251,9 +278,15 @@ bwd_dw_kernel(const Args a)
                     const int ko = ((ch * (R + 2) + r) * KP) * 2 + kwin_off + 64 * h;
                     const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
                     const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
+                    uint32_t km[5], vm[5];
+                    lds_read_2x5_dwords((uint32_t)(uintptr_t)(smem + OFF_K + ko),
+                                        (uint32_t)(uintptr_t)(smem + OFF_V + ko), km, vm);
                     uint4_t kw, vw;
-                    __builtin_memcpy(&kw, smem + OFF_K + ko, 16);      // unaligned 16-byte LDS reads
-                    __builtin_memcpy(&vw, smem + OFF_V + ko, 16);
+#pragma unroll
+                    for (int y = 0; y < 4; ++y) {
+                        kw[y] = __builtin_amdgcn_alignbit(km[y + 1], km[y], win_shift);
+                        vw[y] = __builtin_amdgcn_alignbit(vm[y + 1], vm[y], win_shift);
+                    }
                     uint4_t ak, av;
 #pragma unroll
                     for (int y = 0; y < 4; ++y) {
