@@ -65,11 +65,9 @@ __device__ __forceinline__ uint4_t bf16x8_to_half(uint4_t r, half2_t mul)
     uint4_t o;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        // low half: shift up; high half: the dword itself, its 16 junk bits are truncated by
-        // the round-toward-zero conversion except 3 that the mask clears
         const uint32_t d = r[j];
         const uint32_t pk = __builtin_bit_cast(uint32_t,
-            __builtin_amdgcn_cvt_pkrtz(__uint_as_float(d << 16), __uint_as_float(d))) & 0xfff8ffffu;
+            __builtin_amdgcn_cvt_pkrtz(__uint_as_float(d << 16), __uint_as_float(d & 0xffff0000u)));
         o[j] = as_dword(as_half2(pk) * mul);
     }
     return o;

@@ -15,8 +15,8 @@
 //
 // Number format inside the kernel: the bf16 inputs are converted to IEEE half precision
 // while they are staged (k, v) or loaded (q).  A bf16 value has 8 significant bits, a half
-// has 11, so the conversion is exact for 2^-14 <= |x| <= 65504; smaller values lose at
-// most 2^-25 absolutely, larger ones saturate at +-65280.  Half precision is what lets the
+// has 11, so the conversion is exact for 2^-17 <= |x| <= 65504; smaller values are
+// truncated to a multiple of 2^-24, larger ones saturate at +-65504.  Half precision is what lets the
 // vector ALU form two q*k products per instruction (v_pk_mul_f16), accumulate the exact
 // dot product with v_dot2c_f32_f16, and feed v halves straight into fp32 FMAs
 // (v_fma_mix_f32) with no unpacking.  The q*k products that enter the matrix core are
@@ -322,7 +322,12 @@ fwd16_kernel(const FwdArgs a)
                 for (int r = 0; r < 4; ++r)
                     acc = fmaf(w0[r], (float)as_half2(vd[r][e >> 1])[e & 1], acc);
                 o[e] = acc;
-                if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // bound the live MFMA results
+                if ((e & 3) == 3) {
+                    // pin the sums so the multiply-adds are not deferred past later MFMAs
+                    // (that would keep every MFMA result live at once)
+                    asm volatile("" : "+v"(o[e - 3]), "+v"(o[e - 2]), "+v"(o[e - 1]), "+v"(o[e]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -330,7 +335,10 @@ fwd16_kernel(const FwdArgs a)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     o[e] = fmaf(w1[r], (float)as_half2(vd[4 + r][e >> 1])[e & 1], o[e]);
-                if ((e & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+                if ((e & 3) == 3) {
+                    asm volatile("" : "+v"(o[e - 3]), "+v"(o[e - 2]), "+v"(o[e - 1]), "+v"(o[e]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             {
                 const float4_t c8 = {at8, at8, at8, at8};

@@ -181,10 +181,9 @@ __device__ __forceinline__ void item_store(const TileGrid& a, const Tile& t, int
     const int gx = t.gxa + 8 * x;
     const int HC = a.tw + 2;
     unsigned char* dst = buf + (tsel ? a.v_off : 0) + hr * HC * 64;
-    // Even columns sit in the low half of a dword (shift up to get the float); odd columns
-    // sit in the high half: the float is the dword itself with 16 junk bits below the bf16
-    // mantissa, which a round-toward-zero conversion truncates away except for 3 bits that
-    // the mask clears.
+    // Even columns sit in the low half of a dword, odd columns in the high half; either way the
+    // float is the bf16 pattern in the upper 16 bits.  The conversion to half is exact for
+    // every bf16 value whose last bit weighs at least 2^-24 (round toward zero below that).
 #pragma unroll
     for (int px = 0; px < 8; ++px) {
         uint4_t t4;
@@ -192,7 +191,7 @@ __device__ __forceinline__ void item_store(const TileGrid& a, const Tile& t, int
         for (int y = 0; y < 4; ++y) {
             const uint32_t lo = r[2 * y][px >> 1], hi = r[2 * y + 1][px >> 1];
             if (px & 1)
-                t4[y] = pack_half_rtz(__uint_as_float(lo), __uint_as_float(hi)) & 0xfff8fff8u;
+                t4[y] = pack_half_rtz(__uint_as_float(lo & 0xffff0000u), __uint_as_float(hi & 0xffff0000u));
             else
                 t4[y] = pack_half_rtz(__uint_as_float(lo << 16), __uint_as_float(hi << 16));
         }

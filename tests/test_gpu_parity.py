@@ -137,7 +137,12 @@ def test_forward_special_cases_on_gpu():
         out = sa.slide_attn_fwd(torch.randn_like(v), k, v, w, w, bias, heads, ksize)
         expect = torch.zeros_like(v)
         expect[:, :, 1:, 1:] = v[:, :, :-1, :-1]
-        assert torch.equal(out, expect)
+        if dtype == torch.float32:
+            assert torch.equal(out, expect)
+        else:
+            # the bf16 path holds v in half precision inside the kernel: exact down to 2^-17,
+            # multiples of 2^-24 below that
+            assert (out.float() - expect.float()).abs().max().item() <= 2.0 ** -24
 
 
 BWD_SHAPES = [
