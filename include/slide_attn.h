@@ -107,7 +107,8 @@ const char* slide_status_string(int status);
  * Which forward implementation slide_attn_fwd would run for this problem:
  * 0 = invalid arguments, 1 = general kernel (any supported ksize / head size /
  * dtype, float32 vector arithmetic), 2 = matrix-core kernel (bf16, d = 32,
- * ksize 3).  Host-only; for tests and benchmarks.
+ * ksize 3), 3 = matrix-core kernel for ksize 5 (bf16, d = 32).  Host-only; for
+ * tests and benchmarks.
  */
 int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype);
 

@@ -48,14 +48,15 @@ extern "C" size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int hea
 {
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
-    return backward ? slide::bwd_generic_workspace_bytes(p) : slide::fwd_mfma_workspace_bytes(p);
+    if (backward) return slide::bwd_generic_workspace_bytes(p);
+    return slide::fwd_mfma_supported(p) ? slide::fwd_mfma_workspace_bytes(p) : slide::fwd_mfma5_workspace_bytes(p);
 }
 
 extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype)
 {
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
-    return slide::fwd_mfma_supported(p) ? 2 : 1;
+    return slide::fwd_mfma_supported(p) ? 2 : (slide::fwd_mfma5_supported(p) ? 3 : 1);
 }
 
 extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
@@ -76,6 +77,10 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
         if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
         e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, workspace, (hipStream_t)stream);
+    } else if (slide::fwd_mfma5_supported(p)) {
+        if (!workspace || workspace_bytes < slide::fwd_mfma5_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
+        if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
+        e = slide::launch_fwd_mfma5(p, q, k, v, wk, wv, bias, out, workspace, (hipStream_t)stream);
     } else
         e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;

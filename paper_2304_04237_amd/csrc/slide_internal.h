@@ -54,4 +54,11 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
                            const float* wk, const float* wv, const float* bias, void* out,
                            void* workspace, hipStream_t st);
 
+// ---- matrix-core forward, 5x5 window (slide_fwd16_k5.hip): bf16, d == 32, ksize 5
+bool fwd_mfma5_supported(const Problem& p);
+size_t fwd_mfma5_workspace_bytes(const Problem& p);
+hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, const void* v,
+                            const float* wk, const float* wv, const float* bias, void* out,
+                            void* workspace, hipStream_t st);
+
 }  // namespace slide

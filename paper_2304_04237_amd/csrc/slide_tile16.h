@@ -94,6 +94,7 @@ struct TileGrid {
     int TA, TB;              // tiles in each class; the list holds class A first
     int v_off;               // byte offset of the second halo tensor inside a tile buffer
     int vec_ok;              // rows are 16-byte aligned: W % 8 == 0 and 16-byte aligned bases
+    int r;                   // halo radius (ksize / 2)
 };
 
 // One tile of one (batch, head) plane; every field is wavefront-uniform.
@@ -126,10 +127,10 @@ __device__ __forceinline__ Tile decode_tile(const TileGrid& a, int i)
     t.j0 = tcx * a.tw;
     t.cols = min(a.tw, a.W - t.j0);
     t.head_base = ((long)b * a.C + (long)t.m * D) * ((long)a.H * a.W);
-    t.gxa = max(t.j0 - 1, 0) & ~7;
-    const int gxb = min((t.j0 + t.cols + 1 + 7) & ~7, (a.W + 7) & ~7);
+    t.gxa = max(t.j0 - a.r, 0) & ~7;
+    const int gxb = min((t.j0 + t.cols + a.r + 7) & ~7, (a.W + 7) & ~7);
     t.NX = (gxb - t.gxa) >> 3;
-    t.n_items = 8 * t.NX * (t.rows + 2);
+    t.n_items = 8 * t.NX * (t.rows + 2 * a.r);
     return t;
 }
 
@@ -142,7 +143,7 @@ __device__ __forceinline__ void item_load(const TileGrid& a, const Tile& t, cons
     const int o = idx & 3, tsel = (idx >> 2) & 1;
     const int rest = idx >> 3;
     const int hr = rest / t.NX, x = rest - hr * t.NX;
-    const int gi = t.i0 - 1 + hr, gx = t.gxa + 8 * x;
+    const int gi = t.i0 - a.r + hr, gx = t.gxa + 8 * x;
     const long HW = (long)a.H * a.W;
     if (gi < 0 || gi >= a.H) {
 #pragma unroll
@@ -179,7 +180,7 @@ __device__ __forceinline__ void item_store(const TileGrid& a, const Tile& t, int
     const int rest = idx >> 3;
     const int hr = rest / t.NX, x = rest - hr * t.NX;
     const int gx = t.gxa + 8 * x;
-    const int HC = a.tw + 2;
+    const int HC = a.tw + 2 * a.r;
     unsigned char* dst = buf + (tsel ? a.v_off : 0) + hr * HC * 64;
     // Even columns sit in the low half of a dword, odd columns in the high half; either way the
     // float is the bf16 pattern in the upper 16 bits.  The conversion to half is exact for
@@ -195,8 +196,8 @@ __device__ __forceinline__ void item_store(const TileGrid& a, const Tile& t, int
             else
                 t4[y] = pack_half_rtz(__uint_as_float(lo << 16), __uint_as_float(hi << 16));
         }
-        const int hc = gx + px - (t.j0 - 1);
-        if (hc >= 0 && hc < t.cols + 2) *(uint4_t*)(dst + col_offset(hc, o)) = t4;
+        const int hc = gx + px - (t.j0 - a.r);
+        if (hc >= 0 && hc < t.cols + 2 * a.r) *(uint4_t*)(dst + col_offset(hc, o)) = t4;
     }
 }
 
@@ -206,12 +207,14 @@ __device__ __forceinline__ void zero_pad_columns(const TileGrid& a, const Tile& 
 {
     const bool left = (t.j0 == 0), right = (t.j0 + t.cols == a.W);
     if (!left && !right) return;
-    const int HC = a.tw + 2;
-    const int n = (t.rows + 2) * 16;                    // row x side x tensor x channel group
+    const int HC = a.tw + 2 * a.r;
+    const int n = (t.rows + 2 * a.r) * a.r * 16;        // row x radius x side x tensor x channel group
     for (int idx = tid; idx < n; idx += threads) {
-        const int o = idx & 3, tsel = (idx >> 2) & 1, side = (idx >> 3) & 1, hr = idx >> 4;
+        const int o = idx & 3, tsel = (idx >> 2) & 1, side = (idx >> 3) & 1;
+        const int rest = idx >> 4;
+        const int k = rest % a.r, hr = rest / a.r;
         if (side ? !right : !left) continue;
-        const int hc = side ? t.cols + 1 : 0;
+        const int hc = side ? t.cols + a.r + k : k;
         *(uint4_t*)(buf + (tsel ? a.v_off : 0) + hr * HC * 64 + col_offset(hc, o)) = uint4_t{0u, 0u, 0u, 0u};
     }
 }
@@ -223,7 +226,7 @@ constexpr int LDS_LIMIT = 160 * 1024;
 struct TilePlan {
     int th, tw, n_tc, nA, nB, hb, TA, TB;
     int v_off, buf_bytes;    // the two halo tensors of a tile occupy buf_bytes of LDS
-    int halo_px;             // halo pixels of a full tile: (th + 2) * (tw + 2)
+    int halo_px;             // halo pixels of a full tile: (th + 2r) * (tw + 2r)
 };
 
 // makespan of dealing big-first: TA tiles of cost cA first, then TB tiles of cost cB, G blocks
@@ -251,11 +254,12 @@ inline double queue_makespan(long TA, double cA, long TB, double cB, int G)
 inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int px_bytes_b,
                            int px_bytes_extra = 0)
 {
+    const int r2 = 2 * (p.ksize / 2);
     TilePlan t;
     t.tw = p.W <= 64 ? p.W : 64;
     t.n_tc = (p.W + t.tw - 1) / t.tw;
     const int px_bytes = px_bytes_a + px_bytes_b + px_bytes_extra;
-    int th_max = (lds_budget - 256) / (px_bytes * (t.tw + 2)) - 2;
+    int th_max = (lds_budget - 256) / (px_bytes * (t.tw + r2)) - r2;
     if (th_max < 1) th_max = 1;
     if (th_max > p.H) th_max = p.H;
     const long planes = (long)p.B * p.heads * t.n_tc;
@@ -280,7 +284,7 @@ inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int
     }
     t.TA = (int)(planes * t.nA);
     t.TB = (int)(planes * t.nB);
-    const int halo_px = (t.th + 2) * (t.tw + 2);
+    const int halo_px = (t.th + r2) * (t.tw + r2);
     t.halo_px = halo_px;
     t.v_off = halo_px * px_bytes_a;
     if ((t.v_off & 127) == 0) t.v_off += 64;             // the two tensors start 64 B apart mod 128
@@ -292,7 +296,7 @@ inline void fill_grid(TileGrid& g, const Problem& p, const TilePlan& t, const vo
 {
     g.B = p.B; g.H = p.H; g.W = p.W; g.C = p.C; g.heads = p.heads;
     g.th = t.th; g.tw = t.tw; g.n_tc = t.n_tc; g.nA = t.nA; g.nB = t.nB; g.hb = t.hb;
-    g.TA = t.TA; g.TB = t.TB; g.v_off = t.v_off;
+    g.TA = t.TA; g.TB = t.TB; g.v_off = t.v_off; g.r = p.ksize / 2;
     g.vec_ok = (p.W % 8 == 0) && (((uintptr_t)src_a | (uintptr_t)src_b) % 16 == 0);
 }
 
