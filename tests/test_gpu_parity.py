@@ -85,6 +85,10 @@ FWD_SHAPES = [
     (1, 1, 1, 32, 1, 3, "bf16"),         # single pixel
     (1, 20, 40, 96, 3, 3, "bf16"),       # three heads
     (3, 8, 56, 64, 2, 3, "bf16"),        # stage-1 width
+    (1, 9, 70, 32, 1, 5, "bf16"),        # 5x5, wider than one tile
+    (1, 3, 4, 32, 1, 5, "bf16"),         # 5x5, map smaller than the window
+    (2, 30, 28, 64, 2, 5, "bf16"),       # 5x5, several tiles per plane, two heads
+    (1, 5, 130, 64, 2, 3, "bf16"),       # three column tiles, ragged last one
 ]
 
 
@@ -153,6 +157,11 @@ BWD_SHAPES = [
     (2, 5, 9, 16, 2, 1, "f32"),
     (1, 3, 2, 8, 2, 7, "f32"),
     (3, 8, 56, 64, 2, 3, "bf16"),
+    (1, 20, 40, 96, 3, 3, "bf16"),       # three heads
+    (2, 13, 72, 32, 1, 3, "bf16"),       # two column tiles
+    (1, 5, 8, 32, 1, 3, "bf16"),         # tiny
+    (1, 1, 16, 32, 1, 3, "bf16"),        # single row
+    (2, 31, 24, 64, 2, 3, "bf16"),       # rows not a multiple of the strip height
 ]
 
 
@@ -170,6 +179,14 @@ def test_backward_matches_oracle(shape):
     again = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize)
     for a, b in zip(grads, again):
         assert torch.equal(a, b)
+
+
+def test_kernel_selection():
+    """Which forward kernel serves which problem (host-side query of the C ABI)."""
+    assert sa.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, torch.bfloat16) == 2
+    assert sa.slide_attn_fwd_path(64, 28, 28, 128, 4, 5, torch.bfloat16) == 3
+    assert sa.slide_attn_fwd_path(1, 14, 14, 64, 2, 3, torch.float32) == 1
+    assert sa.slide_attn_fwd_path(1, 14, 14, 48, 2, 3, torch.bfloat16) == 1
 
 
 def sample_positions(B, heads, H, W, n, seed):
