@@ -104,7 +104,7 @@ def test_forward_path_selection(lib):
     assert lib.slide_attn_fwd_path(1, 14, 14, 64, 2, 3, 0) == 1     # float32 -> general kernel
     assert lib.slide_attn_fwd_path(1, 14, 14, 64, 3, 3, 0) == 0
     assert lib.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, 1) == 2    # bf16, head size 32, 3x3 -> matrix cores
-    assert lib.slide_attn_fwd_path(64, 28, 28, 128, 4, 5, 1) == 1   # 5x5 -> general kernel
+    assert lib.slide_attn_fwd_path(64, 28, 28, 128, 4, 5, 1) == 3   # 5x5 -> matrix cores, 5x5 kernel
     assert lib.slide_attn_workspace_bytes(64, 56, 56, 64, 2, 3, 1, 0) > 0
     p = ctypes.c_void_p(0x1000)
     # the matrix-core forward needs its workspace
