@@ -48,60 +48,86 @@ constexpr float WK_SCALE = 16.0f;                  // ... and the learned K kern
 constexpr int IMG_A1 = 0, IMG_A2 = 2304, IMG_BIAS = 4608, IMG_DWORDS = 4624;
 
 // ------------------------------------------------------------------ weight preparation
-// grid = (9, heads), block = 256.  Reads the merged float32 kernels [C, 9, 3, 3] and
-// writes the per-head operand image described above (learned part = merged - one-hot).
+// Dword idx < IMG_BIAS of a head's operand image is pack_half(f(w[off0]), f(w[off1])) with
+// f(x) = ok ? (x - sub) * scale : 0 and w the merged K (A1 part) or V (A2 part) kernel
+// [C, 9, 3, 3] of float32: the learned part is the merged kernel minus the one-hot.  The
+// loads are unconditional so that a caller can issue many of them before using any.
+struct ImageSource {
+    int off0, off1;          // element offsets into the kernel tensor
+    float sub0, sub1, scale;
+    bool ok0, ok1, from_v;
+};
+__device__ __forceinline__ ImageSource image_source(int m, int idx)
+{
+    ImageSource r;
+    if (idx < IMG_A2) {
+        // A1, tap t: dword y of lane (i, g) = learned K weights of channels 8g+2y, 8g+2y+1
+        // for the shift of logit row i.
+        const int t = idx >> 8, y = idx & 3, lane = (idx >> 2) & 63;
+        const int i = lane & 15, g = lane >> 4;
+        const int s = shift_of_row(i);
+        const int c = m * D + 8 * g + 2 * y;
+        r.off0 = (c * S + max(s, 0)) * S + t;
+        r.off1 = r.off0 + S * S;
+        r.sub0 = r.sub1 = (s == t) ? 1.0f : 0.0f;
+        r.ok0 = r.ok1 = s >= 0;
+        r.scale = WK_SCALE;
+        r.from_v = false;
+    } else {
+        // A2, product u.  u < 16: channel slot e = u & 7, tap quad tq = u >> 3; row i of the
+        // product is channel 8*(i/4) + e at tap 4*tq + (i%4).  Products 16, 17 (j = u - 16):
+        // row i is channel 8*(i/4) + 4j + (i%4) at tap 8.  Dword y of lane (i, g) holds the
+        // learned V weights for the shifts of logit rows 4g+2y and 4g+2y+1.
+        const int q = idx - IMG_A2;
+        const int u = q >> 7, y = q & 1, lane = (q >> 1) & 63;
+        const int i = lane & 15, g = lane >> 4;
+        const int c = m * D + 8 * (i >> 2) + (u < 16 ? (u & 7) : 4 * (u - 16) + (i & 3));
+        const int tap = u < 16 ? 4 * (u >> 3) + (i & 3) : 8;
+        const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
+        r.off0 = (c * S + max(s0, 0)) * S + tap;
+        r.off1 = (c * S + max(s1, 0)) * S + tap;
+        r.sub0 = (s0 == tap) ? 1.0f : 0.0f;
+        r.sub1 = (s1 == tap) ? 1.0f : 0.0f;
+        r.ok0 = s0 >= 0;
+        r.ok1 = s1 >= 0;
+        r.scale = 1.0f;
+        r.from_v = true;
+    }
+    return r;
+}
+__device__ __forceinline__ uint32_t image_value(const ImageSource& r, float w0, float w1)
+{
+    return pack_half(r.ok0 ? (w0 - r.sub0) * r.scale : 0.0f, r.ok1 ? (w1 - r.sub1) * r.scale : 0.0f);
+}
+// dwords IMG_BIAS .. IMG_DWORDS-1: bias of logit row r times log2(e); -inf on unused rows
+__device__ __forceinline__ uint32_t image_bias(const float* __restrict__ bias, int m, int row)
+{
+    const int s = shift_of_row(row);
+    float b = -INFINITY;
+    if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
+    return __float_as_uint(b);
+}
+
+// grid = (9, heads), block = 256: the images in global memory, for the one-tile-per-block kernel
 __global__ void __launch_bounds__(256)
 prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
                     const float* __restrict__ bias, uint32_t* __restrict__ image)
 {
-    const int t = blockIdx.x, m = blockIdx.y;
+    const int m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
-    const int tid = threadIdx.x;
-    {
-        // A1, tap t: dword y of lane (i, g) = learned K weights of channels 8g+2y, 8g+2y+1
-        // for the shift of logit row i.
-        const int y = tid & 3, lane = tid >> 2;
-        const int i = lane & 15, g = lane >> 4;
-        const int s = shift_of_row(i);
-        float d0 = 0.0f, d1 = 0.0f;
-        if (s >= 0) {
-            const float id = (s == t) ? 1.0f : 0.0f;
-            const int c = m * D + 8 * g + 2 * y;
-            d0 = (wk[((long)c * S + s) * S + t] - id) * WK_SCALE;
-            d1 = (wk[((long)(c + 1) * S + s) * S + t] - id) * WK_SCALE;
-        }
-        img[IMG_A1 + t * 256 + tid] = pack_half(d0, d1);
+    for (int idx = blockIdx.x * 256 + threadIdx.x; idx < IMG_BIAS; idx += gridDim.x * 256) {
+        const ImageSource r = image_source(m, idx);
+        const float* w = r.from_v ? wv : wk;
+        img[idx] = image_value(r, w[r.off0], w[r.off1]);
     }
-    {
-        // A2, products u = 2t and 2t+1.  Product u < 16: channel slot e = u & 7, tap quad
-        // tq = u >> 3; row i of the product is channel 8*(i/4) + e at tap 4*tq + (i%4).
-        // Products 16, 17 (j = u - 16): row i is channel 8*(i/4) + 4j + (i%4) at tap 8.
-        // Dword y of lane (i, g) holds the learned V weights for the shifts of logit rows
-        // 4g+2y and 4g+2y+1.
-        const int y = tid & 1, lane = (tid >> 1) & 63, u = 2 * t + (tid >> 7);
-        const int i = lane & 15, g = lane >> 4;
-        int c, tap;
-        if (u < 16) { c = 8 * (i >> 2) + (u & 7); tap = 4 * (u >> 3) + (i & 3); }
-        else        { c = 8 * (i >> 2) + 4 * (u - 16) + (i & 3); tap = 8; }
-        c += m * D;
-        float d[2] = {0.0f, 0.0f};
-        for (int h = 0; h < 2; ++h) {
-            const int s = shift_of_row(4 * g + 2 * y + h);
-            if (s >= 0) d[h] = wv[((long)c * S + s) * S + tap] - (s == tap ? 1.0f : 0.0f);
-        }
-        img[IMG_A2 + u * 128 + (tid & 127)] = pack_half(d[0], d[1]);
-    }
-    if (t == 0 && tid < 16) {
-        const int s = shift_of_row(tid);
-        float b = -INFINITY;
-        if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
-        img[IMG_BIAS + tid] = __float_as_uint(b);
-    }
+    if (blockIdx.x == 0 && threadIdx.x < IMG_DWORDS - IMG_BIAS)
+        img[IMG_BIAS + threadIdx.x] = image_bias(bias, m, threadIdx.x);
 }
 
 struct FwdArgs {
     const bf16_bits* q; const bf16_bits* k; const bf16_bits* v; bf16_bits* out;
-    const uint32_t* image;   // per-head MFMA operand images
+    const uint32_t* image;   // per-head MFMA operand images (one-tile-per-block kernel)
+    const float* wk; const float* wv; const float* bias;   // merged kernels (pipelined kernel)
     TileGrid g;
     int buf_stride;          // bytes between the two tile buffers (pipelined kernel)
     int a_base;              // byte offset of the per-wave scratch (1 KB per wave)
@@ -111,20 +137,20 @@ struct FwdArgs {
 // The arithmetic of one pass: 16 pixels, lane = (pixel p, channel group g); (ti, tj) is the
 // lane's pixel inside the tile, qraw its 8 q channels (bf16 patterns, one per dword).
 // Returns the 8 output channels in o.  `ascr` is the lane's row of the wave's scratch.
-__device__ __forceinline__ void slide_pass(const unsigned char* kl, const unsigned char* vl, int HC,
+__device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int VD,
                                            int ti, int tj, int g, const uint32_t (&qraw)[8],
                                            const half8_t (&A1)[S], const half4_t (&A2)[2 * S],
                                            const float (&bias2)[3], float scale_log2e, float* ascr,
                                            float (&o)[8])
 {
-    int coff[KS];
+    // halo row stride RS bytes; the V pixel sits VD bytes after the K pixel.  With both known
+    // at compile time every tap address is one of three registers plus an immediate.
+    const unsigned char* cb[KS];
 #pragma unroll
-    for (int tx = 0; tx < KS; ++tx) coff[tx] = col_offset(tj + tx, g);
-    const int row0 = ti * HC * 64;
+    for (int tx = 0; tx < KS; ++tx) cb[tx] = kl + ti * RS + col_offset(tj + tx, g);
     uint4_t kd[S];
 #pragma unroll
-    for (int t = 0; t < S; ++t)
-        kd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+    for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS);
 
     half2_t qpk[4], qs[4];  // channel pairs as halves; qs = q / 16
 #pragma unroll
@@ -155,7 +181,7 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, const unsign
     uint4_t vd[S];
 #pragma unroll
     for (int t = 0; t < 4; ++t)
-        vd[t] = *(const uint4_t*)(vl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+        vd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS + VD);
 
     // shift-path logits: sum the four channel groups, landing shift 4r+g in group g
     {
@@ -194,7 +220,7 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, const unsign
     // in its four result registers, the weights of channel e for taps 4tq..4tq+3.
 #pragma unroll
     for (int t = 4; t < S; ++t)
-        vd[t] = *(const uint4_t*)(vl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
+        vd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS + VD);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const float4_t w0 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[e], B2, at0, 0, 0, 0);
@@ -328,7 +354,7 @@ fwd16_kernel(const FwdArgs a)
             for (int e = 0; e < 8; ++e) qnext[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
         }
         float o[8];
-        slide_pass(smem, smem + a.g.v_off, HC, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
+        slide_pass(smem, HC * 64, a.g.v_off, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
         if (valid) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -343,39 +369,71 @@ fwd16_kernel(const FwdArgs a)
 // Persistent blocks of 8 waves, one per compute unit, for problems whose rows are 16-byte
 // aligned (W % 8 == 0).  Block b works through tiles b, b + grid, ... of the tile list.  Two
 // LDS tile buffers: while the passes of one tile run, each pass also fetches a share of the
-// next tile (half an item per lane: 4 channels x 8 columns, four 16-byte loads issued at the
-// start of the pass, converted into the other buffer at its end), so global loads and
-// arithmetic overlap inside the block instead of alternating across the whole chip.
+// next tile (four 16-byte loads per lane at the start of the pass, converted into the other
+// buffer one pass later), so global loads and arithmetic overlap inside the block instead of
+// alternating across the whole chip.  The block also builds its head's operand image itself.
 // q comes in and results go out as 16-byte row segments: lane (c = lane/2, h = lane%2) moves
 // pixels 16*pass + 8h .. +7 of channel c, and the wave's scratch transposes between that and
 // the per-lane (pixel, 8 channels) view.  Vector memory operations retire in order, so the q
 // segment is fetched two passes ahead.
+//
+// Tile buffer of this kernel: halo row hr = [K pixels HC x 64 B][V pixels HC x 64 B], pixel
+// = 32 channels as halves with the 16-byte channel octets swizzled as in col_offset().
+// TW is the tile width when known at compile time (then tap addresses need no arithmetic),
+// 0 = read it from the arguments.
 constexpr int PIPE_WAVES = 8;
 
-// half item h of a tile: tensor (h & 1), channel quad (h >> 1) & 7, then (halo row, chunk)
-__device__ __forceinline__ void half_item_load(const FwdArgs& a, const Tile& t, int h, uint4_t (&r)[4])
+// Staging unit ("share") n of a tile: wave-sized group hb = n / 64 handles tensor hb & 1;
+// inside the tensor, unit u = (hb / 2) * 64 + n % 64 is channel quad u & 7 of 16-byte chunk
+// u / 8 = (halo row, chunk in row): 4 channels x 8 columns.
+struct ShareGeom {
+    int n_units;             // units per tensor: 8 * NX * (rows + 2)
+    int n_groups;            // wave-sized groups over both tensors
+    uint32_t recip_nx;       // ceil(65536 / NX): (x * recip_nx) >> 16 == x / NX for x < 4096
+};
+__device__ __forceinline__ ShareGeom share_geom(const Tile& t)
 {
-    const int tsel = h & 1, cq = (h >> 1) & 7, rest = h >> 4;
-    const int hr = rest / t.NX, x = rest - hr * t.NX;
-    const int gi = t.i0 - 1 + hr, gx = t.gxa + 8 * x;
-    const long HW = (long)a.g.H * a.g.W;
-    if (gi < 0 || gi >= a.g.H || gx + 8 > a.g.W) {
+    ShareGeom s;
+    s.n_units = t.n_items;                              // 8 * NX * (rows + 2)
+    s.n_groups = 2 * ((s.n_units + 63) >> 6);
+    s.recip_nx = (65536u + (uint32_t)t.NX - 1u) / (uint32_t)t.NX;
+    return s;
+}
+
+__device__ __forceinline__ void share_load(const FwdArgs& a, const Tile& t, const ShareGeom& sg, int hb,
+                                           int lane, uint32_t hw2, uint4_t (&r)[4])
+{
+    const int u = (hb >> 1) * 64 + lane;
+    const int cq = u & 7, rest = u >> 3;
+    const int hr = (int)(((uint32_t)rest * sg.recip_nx) >> 16), x = rest - hr * t.NX;
+    const int gi = t.i0 - 1 + hr;
+    if (u >= sg.n_units || gi < 0 || gi >= a.g.H) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) r[e] = uint4_t{0u, 0u, 0u, 0u};
         return;
     }
-    const bf16_bits* src = (tsel ? a.v : a.k) + t.head_base + (long)(4 * cq) * HW + (long)gi * a.g.W + gx;
+    const char* base = (const char*)(((hb & 1) ? a.v : a.k) + t.head_base);   // wave-uniform
+    const uint32_t off = (uint32_t)(4 * cq) * hw2 + (uint32_t)(gi * a.g.W + t.gxa + 8 * x) * 2u;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = *(const uint4_t*)(src + e * HW);
+    for (int e = 0; e < 4; ++e) r[e] = *(const uint4_t*)(base + (off + (uint32_t)e * hw2));
 }
-__device__ __forceinline__ void half_item_store(const FwdArgs& a, const Tile& t, int h,
-                                                const uint4_t (&r)[4], unsigned char* buf)
+
+template <bool EDGE_CHECK>
+__device__ __forceinline__ void share_store(const Tile& t, const ShareGeom& sg, int hb, int lane, int HC,
+                                            const uint4_t (&r)[4], unsigned char* buf)
 {
-    const int tsel = h & 1, cq = (h >> 1) & 7, rest = h >> 4;
-    const int hr = rest / t.NX, x = rest - hr * t.NX;
-    const int gx = t.gxa + 8 * x;
-    const int HC = a.g.tw + 2;
-    unsigned char* dst = buf + (tsel ? a.g.v_off : 0) + hr * HC * 64;
+    const int u = (hb >> 1) * 64 + lane;
+    if (u >= sg.n_units) return;
+    const int cq = u & 7, rest = u >> 3;
+    const int hr = (int)(((uint32_t)rest * sg.recip_nx) >> 16), x = rest - hr * t.NX;
+    // first halo column of the chunk: a multiple of 8 plus 1 (the chunk grid is 8-aligned and
+    // a tile starts at a multiple of 64), so the swizzle term of column hc0 + px depends on px only
+    const int hc0 = t.gxa + 8 * x - (t.j0 - 1);
+    unsigned char* dst = buf + (2 * hr + (hb & 1)) * (HC * 64) + hc0 * 64 + (cq & 1) * 8;
+    const int o4 = (cq >> 1) << 4;
+    unsigned char* dsw[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) dsw[c] = dst + (o4 ^ (c << 4));
 #pragma unroll
     for (int px = 0; px < 8; ++px) {
         uint2_t t2;
@@ -387,11 +445,50 @@ __device__ __forceinline__ void half_item_store(const FwdArgs& a, const Tile& t,
             else
                 t2[y] = pack_half_rtz(__uint_as_float(lo << 16), __uint_as_float(hi << 16));
         }
-        const int hc = gx + px - (t.j0 - 1);
-        if (hc >= 0 && hc < t.cols + 2) *(uint2_t*)(dst + col_offset(hc, cq >> 1) + (cq & 1) * 8) = t2;
+        const int hc = hc0 + px;
+        if (!EDGE_CHECK || (hc >= 0 && hc < t.cols + 2))
+            *(uint2_t*)(dsw[((1 + px) >> 1) & 3] + px * 64) = t2;
     }
 }
 
+// halo columns outside the map are zero (both tensors, all rows of the tile)
+__device__ __forceinline__ void pipe_zero_pad(const TileGrid& a, const Tile& t, int HC, unsigned char* buf,
+                                              int tid, int threads)
+{
+    const bool left = (t.j0 == 0), right = (t.j0 + t.cols == a.W);
+    if (!left && !right) return;
+    const int n = (t.rows + 2) * 16;                    // row x side x tensor x channel octet
+    for (int idx = tid; idx < n; idx += threads) {
+        const int o = idx & 3, tsel = (idx >> 2) & 1, side = (idx >> 3) & 1, hr = idx >> 4;
+        if (side ? !right : !left) continue;
+        const int hc = side ? t.cols + 1 : 0;
+        *(uint4_t*)(buf + (2 * hr + tsel) * (HC * 64) + col_offset(hc, o)) = uint4_t{0u, 0u, 0u, 0u};
+    }
+}
+
+// One block builds a head's operand image in LDS (THREADS threads, every weight load issued
+// before the first use).
+template <int THREADS>
+__device__ __forceinline__ void build_image(const float* __restrict__ wk, const float* __restrict__ wv,
+                                            const float* __restrict__ bias, int m, uint32_t* dst, int tid)
+{
+    constexpr int N = IMG_BIAS / THREADS;
+    static_assert(N * THREADS == IMG_BIAS, "whole rounds");
+    float w0[N], w1[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const ImageSource src = image_source(m, tid + i * THREADS);
+        const float* w = src.from_v ? wv : wk;
+        w0[i] = w[src.off0];
+        w1[i] = w[src.off1];
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+        dst[tid + i * THREADS] = image_value(image_source(m, tid + i * THREADS), w0[i], w1[i]);
+    if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
+}
+
+template <int TW>
 __global__ void __launch_bounds__(PIPE_WAVES * 64, 2)
 fwd16_pipe_kernel(const FwdArgs a)
 {
@@ -400,7 +497,8 @@ fwd16_pipe_kernel(const FwdArgs a)
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int p = lane & 15, g = lane >> 4;
-    const int HC = a.g.tw + 2;
+    const int HC = (TW ? TW : a.g.tw) + 2;
+    const bool single_col = a.g.n_tc == 1;              // then no staged column falls outside a tile
     const uint32_t hw2 = (uint32_t)a.g.H * (uint32_t)a.g.W * 2u;
     const int n_tiles = a.g.TA + a.g.TB;
     unsigned char* wbuf = smem + a.a_base + wave * WAVE_SCRATCH;
@@ -409,21 +507,21 @@ fwd16_pipe_kernel(const FwdArgs a)
 
     int cur = blockIdx.x;                               // gridDim.x <= n_tiles
     Tile tcur = decode_tile(a.g, cur);
-    // the first tile is staged without overlap
-    for (int base = 0; base < tcur.n_items; base += 3 * THREADS) {
-        uint4_t r[3][8];
-#pragma unroll
-        for (int u = 0; u < 3; ++u) {
-            const int idx = base + u * THREADS + tid;
-            if (idx < tcur.n_items) item_load(a.g, tcur, a.k, a.v, idx, r[u]);
+    // The block builds the operand image of its head in the second tile buffer, which is
+    // free until the first pass (no separate preparation kernel on this path).
+    build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)(smem + a.buf_stride), tid);
+    // the first tile is staged without overlap, two shares per lane in flight
+    {
+        const ShareGeom sg = share_geom(tcur);
+        for (int hb = wave; hb < sg.n_groups; hb += 2 * WAVES) {
+            uint4_t r0[4], r1[4];
+            share_load(a, tcur, sg, hb, lane, hw2, r0);
+            if (hb + WAVES < sg.n_groups) share_load(a, tcur, sg, hb + WAVES, lane, hw2, r1);
+            share_store<true>(tcur, sg, hb, lane, HC, r0, smem);
+            if (hb + WAVES < sg.n_groups) share_store<true>(tcur, sg, hb + WAVES, lane, HC, r1, smem);
         }
-#pragma unroll
-        for (int u = 0; u < 3; ++u) {
-            const int idx = base + u * THREADS + tid;
-            if (idx < tcur.n_items) item_store(a.g, tcur, idx, r[u], smem);
-        }
+        pipe_zero_pad(a.g, tcur, HC, smem, tid, THREADS);
     }
-    zero_pad_columns(a.g, tcur, smem, tid, THREADS);
 
     half8_t A1[S];
     half4_t A2[2 * S];
@@ -436,11 +534,8 @@ fwd16_pipe_kernel(const FwdArgs a)
         const int nxt = cur + (int)gridDim.x;
         const bool has_next = nxt < n_tiles;
         const Tile tnext = decode_tile(a.g, has_next ? nxt : cur);
-        const int n_half = has_next ? 2 * tnext.n_items : 0;
-        if (tcur.m != m_loaded) {
-            load_operands(a.image + (long)tcur.m * IMG_DWORDS, lane, g, A1, A2, bias2);
-            m_loaded = tcur.m;
-        }
+        ShareGeom sg = share_geom(tnext);
+        if (!has_next) sg.n_groups = 0;
         const int npix = tcur.rows * tcur.cols;
         const int npass = (npix + 15) >> 4;
         const float inv_tw = 1.0f / (float)tcur.cols;
@@ -464,7 +559,24 @@ fwd16_pipe_kernel(const FwdArgs a)
             if (ok) qseg1 = *(const uint4_t*)(qb + off);
         }
         __syncthreads();                                // buf is complete, buf_next is free
+        if (tcur.m != m_loaded) {
+            if (it > 0) {                               // the block moves on to another head
+                build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)buf_next, tid);
+                __syncthreads();
+            }
+            load_operands((const uint32_t*)buf_next, lane, g, A1, A2, bias2);
+            m_loaded = tcur.m;
+            __syncthreads();                            // everyone holds the operands: buf_next is free again
+        }
 
+        // K and V of the next tile: the loads of a pass's share are issued at its start and
+        // converted into buf_next at the end of the wave's following pass
+        uint4_t pre_old[4];
+        int hb_old = sg.n_groups;
+        auto store_share = [&](int hb, const uint4_t (&r)[4]) {
+            if (single_col) share_store<false>(tnext, sg, hb, lane, HC, r, buf_next);
+            else            share_store<true>(tnext, sg, hb, lane, HC, r, buf_next);
+        };
         for (int pass = wave; pass < npass; pass += WAVES) {
             int n = pass * 16 + p;
             n = n < npix ? n : npix - 1;
@@ -477,9 +589,8 @@ fwd16_pipe_kernel(const FwdArgs a)
                 const uint32_t off = seg_offset(min(pass + 2 * WAVES, npass - 1), ok);
                 if (ok) qseg2 = *(const uint4_t*)(qb + off);
             }
-            const int h = pass * 64 + lane;
             uint4_t pre[4];
-            if (h < n_half) half_item_load(a, tnext, h, pre);
+            if (pass < sg.n_groups) share_load(a, tnext, sg, pass, lane, hw2, pre);
 
             // q segment -> per-lane channels through the wave's scratch
             uint32_t qraw[8];
@@ -491,7 +602,7 @@ fwd16_pipe_kernel(const FwdArgs a)
             __builtin_amdgcn_wave_barrier();
 
             float o[8];
-            slide_pass(buf, buf + a.g.v_off, HC, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
+            slide_pass(buf, 2 * HC * 64, HC * 64, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
 
             // results -> 16-byte segments through the scratch
             __builtin_amdgcn_wave_barrier();
@@ -505,18 +616,22 @@ fwd16_pipe_kernel(const FwdArgs a)
                 if (ok) *(uint4_t*)(ob + off) = ov;
             }
             __builtin_amdgcn_wave_barrier();
-            if (h < n_half) half_item_store(a, tnext, h, pre, buf_next);
+            if (hb_old < sg.n_groups) store_share(hb_old, pre_old);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) pre_old[e] = pre[e];
+            hb_old = pass;
             qseg = qseg1;
             qseg1 = qseg2;
         }
+        if (hb_old < sg.n_groups) store_share(hb_old, pre_old);
         // what the passes did not cover of the next tile (short tiles before tall ones)
-        for (int h = npass * 64 + tid; h < n_half; h += THREADS) {
+        for (int hb = wave + ((npass - wave + WAVES - 1) / WAVES) * WAVES; hb < sg.n_groups; hb += WAVES) {
             uint4_t pre[4];
-            half_item_load(a, tnext, h, pre);
-            half_item_store(a, tnext, h, pre, buf_next);
+            share_load(a, tnext, sg, hb, lane, hw2, pre);
+            store_share(hb, pre);
         }
         if (!has_next) break;
-        zero_pad_columns(a.g, tnext, buf_next, tid, THREADS);
+        pipe_zero_pad(a.g, tnext, HC, buf_next, tid, THREADS);
         cur = nxt;
         tcur = tnext;
     }
@@ -537,6 +652,7 @@ static TilePlan plan_fwd(const Problem& p, bool pipelined)
 bool fwd_mfma_supported(const Problem& p)
 {
     if (p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16path::D) return false;
+    if ((long)p.H * p.W * 2 * f16path::D >= (1L << 31)) return false;   // 32-bit byte offsets inside a head
     const long planes = (long)p.B * p.heads * ((p.W + 63) / 64);
     return planes * p.H < (1L << 30);                    // tile count fits an int
 }
@@ -559,11 +675,13 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     const bool pipelined = aligned && ((long)t.TA + t.TB >= 2L * NUM_CU);
     if (!pipelined) t = plan_fwd(p, false);
     uint32_t* image = (uint32_t*)workspace;
-    hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
-                       wk, wv, bias, image);
+    if (!pipelined)
+        hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
+                           wk, wv, bias, image);
     FwdArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.image = image;
+    a.wk = wk; a.wv = wv; a.bias = bias;
     fill_grid(a.g, p, t, k, v);
     a.buf_stride = t.buf_bytes;
     a.a_base = (pipelined ? 2 : 1) * t.buf_bytes;
@@ -573,15 +691,21 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
         hipError_t e = hipFuncSetAttribute((const void*)fwd16_kernel<FWD_WAVES>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)fwd16_pipe_kernel,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
+        const void* pipes[3] = {(const void*)fwd16_pipe_kernel<0>, (const void*)fwd16_pipe_kernel<56>,
+                                (const void*)fwd16_pipe_kernel<64>};
+        for (const void* f : pipes) {
+            e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
     const long n_tiles = (long)t.TA + t.TB;
     if (pipelined) {
         const int lds_bytes = a.a_base + PIPE_WAVES * WAVE_SCRATCH;
-        hipLaunchKernelGGL(fwd16_pipe_kernel, dim3(NUM_CU), dim3(PIPE_WAVES * 64), (size_t)lds_bytes, st, a);
+        const dim3 grid(NUM_CU), block(PIPE_WAVES * 64);
+        if (t.tw == 56)      hipLaunchKernelGGL((fwd16_pipe_kernel<56>), grid, block, (size_t)lds_bytes, st, a);
+        else if (t.tw == 64) hipLaunchKernelGGL((fwd16_pipe_kernel<64>), grid, block, (size_t)lds_bytes, st, a);
+        else                 hipLaunchKernelGGL((fwd16_pipe_kernel<0>), grid, block, (size_t)lds_bytes, st, a);
     } else {
         const int lds_bytes = a.a_base + FWD_WAVES * WAVE_SCRATCH;
         hipLaunchKernelGGL(fwd16_kernel<FWD_WAVES>, dim3((unsigned)n_tiles), dim3(FWD_WAVES * 64),
