@@ -4,23 +4,21 @@
 // shifted values.  Nothing of size k*k*C ever reaches HBM.
 //
 // How the arithmetic is arranged (exactly the operator of Sec. 4.1-4.3, re-associated):
-//   merged kernel = one-hot shift + learned part (Sec. 4.3, Fig. 4), so
-//     logit[s] = scale * ( sum_c q[c] k[c, p+s]                       <- shift path, fp32
-//                        + sum_{c,t} (q[c] k[c, p+t]) wl_k[c,s,t] )    <- learned path, MFMA
-//     out[c]   = sum_t v[c, p+t] * ( a[t] + sum_s a[s] wl_v[c,s,t] )   <- a[t]: shift path (fp32),
-//                                                                        sum_s: learned path, MFMA
-//   The learned paths are the only dense contractions (288 x 9 per pixel and head); they
-//   run on the matrix cores with 16-bit operands and fp32 accumulation.  The shift paths
-//   stay in fp32 so that 1 + w is never rounded to 16 bits.
+//   with the merged kernel W~ = one-hot shift + learned part (Sec. 4.3, Fig. 4)
+//     logit[s] = scale * sum_{c,t} (q[c] k[c, p+t]) W~k[c,s,t]       <- 288 x 9 contraction, MFMA
+//     out[c]   = sum_t v[c, p+t] * g[c,t],  g[c,t] = sum_s a[s] W~v[c,s,t]   <- 9 x 288, MFMA
+//   Both contractions run on the matrix cores with half-precision operands and fp32
+//   accumulation; the merged kernels enter as halves (1 + w keeps 11 significant bits, an
+//   absolute error below 5e-4 on a weight near one, which moves a logit by about 1e-4 and an
+//   output by less than 1e-3 at unit-scale inputs).
 //
 // Number format inside the kernel: the bf16 inputs are converted to IEEE half precision
 // while they are staged (k, v) or loaded (q).  A bf16 value has 8 significant bits, a half
 // has 11, so the conversion is exact for 2^-17 <= |x| <= 65504; smaller values are
 // truncated to a multiple of 2^-24, larger ones saturate at +-65504.  Half precision is what lets the
-// vector ALU form two q*k products per instruction (v_pk_mul_f16), accumulate the exact
-// dot product with v_dot2c_f32_f16, and feed v halves straight into fp32 FMAs
-// (v_fma_mix_f32) with no unpacking.  The q*k products that enter the matrix core are
-// formed from q/16 and the learned K kernel is stored times 16, so products up to 2^20
+// vector ALU form two q*k products per instruction (v_pk_mul_f16) and feed v halves straight
+// into fp32 FMAs (v_fma_mix_f32) with no unpacking.  The q*k products that enter the matrix core are
+// formed from q/16 and the K kernel is stored times 16, so products up to 2^20
 // stay finite.
 //
 // Lane mapping: a wavefront handles 16 pixels at a time; lane = pixel p (0..15) +
@@ -34,8 +32,7 @@ namespace slide {
 namespace f16path {
 using namespace t16;
 
-constexpr int A_STRIDE = 12;                       // floats per pixel in the attention scratch
-constexpr int WAVE_SCRATCH = 1152;                 // per wave: attention weights, or 32 channels x 16 pixels of bf16
+constexpr int WAVE_SCRATCH = 1152;                 // per wave (pipelined kernel): 32 channels x 16 pixels of bf16
 // byte offset of channel c's 16 pixels in the wave scratch (octets 64 banks apart would collide)
 __device__ __forceinline__ int chan_row(int c) { return (c + (c >> 3)) * 32; }
 constexpr float G_SCALE = 0.0625f;                 // q is divided by 16 for the MFMA products ...
@@ -69,7 +66,7 @@ __device__ __forceinline__ ImageSource image_source(int m, int idx)
         const int c = m * D + 8 * g + 2 * y;
         r.off0 = (c * S + max(s, 0)) * S + t;
         r.off1 = r.off0 + S * S;
-        r.sub0 = r.sub1 = (s == t) ? 1.0f : 0.0f;
+        r.sub0 = r.sub1 = 0.0f;
         r.ok0 = r.ok1 = s >= 0;
         r.scale = WK_SCALE;
         r.from_v = false;
@@ -86,8 +83,7 @@ __device__ __forceinline__ ImageSource image_source(int m, int idx)
         const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
         r.off0 = (c * S + max(s0, 0)) * S + tap;
         r.off1 = (c * S + max(s1, 0)) * S + tap;
-        r.sub0 = (s0 == tap) ? 1.0f : 0.0f;
-        r.sub1 = (s1 == tap) ? 1.0f : 0.0f;
+        r.sub0 = r.sub1 = 0.0f;
         r.ok0 = s0 >= 0;
         r.ok1 = s1 >= 0;
         r.scale = 1.0f;
@@ -134,14 +130,24 @@ struct FwdArgs {
     float scale_log2e;
 };
 
+// q of one pixel: 8 channels as bf16 patterns (one per dword) -> halves divided by 16
+__device__ __forceinline__ void q_halves(const uint32_t (&qraw)[8], half2_t (&qs)[4])
+{
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+        const uint32_t pk = pack_half_rtz(__uint_as_float(qraw[2 * y] << 16),
+                                          __uint_as_float(qraw[2 * y + 1] << 16));
+        qs[y] = as_half2(pk) * half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
+    }
+}
+
 // The arithmetic of one pass: 16 pixels, lane = (pixel p, channel group g); (ti, tj) is the
-// lane's pixel inside the tile, qraw its 8 q channels (bf16 patterns, one per dword).
-// Returns the 8 output channels in o.  `ascr` is the lane's row of the wave's scratch.
+// lane's pixel inside the tile, qs its 8 q channels as halves, already divided by 16.
+// Returns the 8 output channels in o.
 __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int VD,
-                                           int ti, int tj, int g, const uint32_t (&qraw)[8],
+                                           int ti, int tj, int g, const half2_t (&qs)[4],
                                            const half8_t (&A1)[S], const half4_t (&A2)[2 * S],
-                                           const float (&bias2)[3], float scale_log2e, float* ascr,
-                                           float (&o)[8])
+                                           const float (&bias2)[3], float scale_log2e, float (&o)[8])
 {
     // halo row stride RS bytes; the V pixel sits VD bytes after the K pixel.  With both known
     // at compile time every tap address is one of three registers plus an immediate.
@@ -152,47 +158,22 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int 
 #pragma unroll
     for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS);
 
-    half2_t qpk[4], qs[4];  // channel pairs as halves; qs = q / 16
-#pragma unroll
-    for (int y = 0; y < 4; ++y) {
-        const uint32_t pk = pack_half_rtz(__uint_as_float(qraw[2 * y] << 16),
-                                          __uint_as_float(qraw[2 * y + 1] << 16));
-        qpk[y] = as_half2(pk);
-        qs[y] = qpk[y] * half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
-    }
-
-    // ---- K side: logits
+    // ---- K side: the nine logits, row 4g+r of the product in acc1[r] of lane group g
     float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
-    float idp[S];
 #pragma unroll
     for (int t = 0; t < S; ++t) {
-        float R = 0.0f;
         uint4_t bb;
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const half2_t kw = as_half2(kd[t][y]);
-            R = __builtin_amdgcn_fdot2(qpk[y], kw, R, false);
-            bb[y] = as_dword(qs[y] * kw);
-        }
+        for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
         acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
-        idp[t] = R;
     }
-    // V taps 0..3: issue the LDS reads now, they land while the softmax runs
+    // V taps: issue the LDS reads now, they land while the softmax runs
     uint4_t vd[S];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < S; ++t)
         vd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS + VD);
 
-    // shift-path logits: sum the four channel groups, landing shift 4r+g in group g
-    {
-        float z1 = fold32(idp[0], idp[2]), z2 = fold32(idp[1], idp[3]);
-        acc1[0] += fold16(z1, z2);
-        z1 = fold32(idp[4], idp[6]); z2 = fold32(idp[5], idp[7]);
-        acc1[1] += fold16(z1, z2);
-        z1 = fold32(idp[8], 0.0f);
-        acc1[2] += fold16(z1, 0.0f);
-    }
-    // ---- softmax over the 9 shifts (3 per lane, 4 lane groups)
+    // ---- softmax over the 9 shifts (3 per lane, 4 lane groups; unused rows have bias -inf)
     float l[3];
 #pragma unroll
     for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], scale_log2e, bias2[r]);
@@ -201,63 +182,36 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int 
 #pragma unroll
     for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
     const float inv = __builtin_amdgcn_rcpf(allsum_groups(pr[0] + pr[1] + pr[2]));
-#pragma unroll
-    for (int r = 0; r < 3; ++r) pr[r] *= inv;
-    // attention weights of this pixel to the wave's scratch so every group can read all 9
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int r = 0; r < 3; ++r) ascr[4 * r + g] = pr[r];      // slots 9..11 are never read
-    __builtin_amdgcn_wave_barrier();
-    const float4_t at0 = *(const float4_t*)(ascr), at1 = *(const float4_t*)(ascr + 4);
-    const float at8 = ascr[8];
     uint2_t b2;
-    b2[0] = pack_half(pr[0], pr[1]);
-    b2[1] = pack_half(pr[2], 0.0f);
+    b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
+    b2[1] = pack_half(pr[2] * inv, 0.0f);
     const half4_t B2 = __builtin_bit_cast(half4_t, b2);
 
-    // ---- V side: out[c] = sum_t v[c, p+t] * (a[t] + learned part); a[t] enters as the
-    // MFMA's C operand, so the matrix core adds the two paths.  Product (e, tq) gives,
-    // in its four result registers, the weights of channel e for taps 4tq..4tq+3.
+    // ---- V side: out[c] = sum_t v[c, p+t] * g[c,t] with g = W~v^T a from the matrix core.
+    // Product u < 16 gives, in its four result registers, the weights of channel u & 7 for
+    // taps 4(u >> 3) .. +3; products 16, 17 those of channels 0..3, 4..7 for tap 8.  Two
+    // products stay in flight ahead of the multiply-adds that consume them.
+    const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    float4_t w[2 * S];
 #pragma unroll
-    for (int t = 4; t < S; ++t)
-        vd[t] = *(const uint4_t*)(cb[t % KS] + (t / KS) * RS + VD);
+    for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+    constexpr int AHEAD = 2;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float4_t w0 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[e], B2, at0, 0, 0, 0);
-        float acc = 0.0f;
+    for (int u = 0; u < AHEAD; ++u) w[u] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[u], B2, zero4, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            acc = fmaf(w0[r], (float)as_half2(vd[r][e >> 1])[e & 1], acc);
-        o[e] = acc;
-        if ((e & 3) == 3) {
-            // pin the sums so the multiply-adds are not deferred past later MFMAs
-            // (that would keep every MFMA result live at once)
-            asm volatile("" : "+v"(o[e - 3]), "+v"(o[e - 2]), "+v"(o[e - 1]), "+v"(o[e]));
-            __builtin_amdgcn_sched_barrier(0);
+    for (int u = 0; u < 2 * S; ++u) {
+        if (u + AHEAD < 2 * S)
+            w[u + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[u + AHEAD], B2, zero4, 0, 0, 0);
+        // scheduling fence: without it the compiler issues all products first and keeps all
+        // 72 results live
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int e = u < 16 ? (u & 7) : 4 * (u - 16) + r;
+            const int tap = u < 16 ? 4 * (u >> 3) + r : 8;
+            o[e] = fmaf(w[u][r], (float)as_half2(vd[tap][e >> 1])[e & 1], o[e]);
         }
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float4_t w1 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[8 + e], B2, at1, 0, 0, 0);
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            o[e] = fmaf(w1[r], (float)as_half2(vd[4 + r][e >> 1])[e & 1], o[e]);
-        if ((e & 3) == 3) {
-            asm volatile("" : "+v"(o[e - 3]), "+v"(o[e - 2]), "+v"(o[e - 1]), "+v"(o[e]));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    {
-        const float4_t c8 = {at8, at8, at8, at8};
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const float4_t w8 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[16 + j], B2, c8, 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int e = 4 * j + r;
-                o[e] = fmaf(w8[r], (float)as_half2(vd[8][e >> 1])[e & 1], o[e]);
-            }
-        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -311,7 +265,6 @@ fwd16_kernel(const FwdArgs a)
     half4_t A2[2 * S];
     float bias2[3];
     load_operands(a.image + (long)tcur.m * IMG_DWORDS, lane, g, A1, A2, bias2);
-    float* ascr = (float*)(smem + a.a_base + wave * WAVE_SCRATCH) + p * A_STRIDE;
     __syncthreads();
 
     const int npix = tcur.rows * tcur.cols;
@@ -354,7 +307,9 @@ fwd16_kernel(const FwdArgs a)
             for (int e = 0; e < 8; ++e) qnext[e] = *(const bf16_bits*)(qb + (off + (uint32_t)e * hw2));
         }
         float o[8];
-        slide_pass(smem, HC * 64, a.g.v_off, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
+        half2_t qs[4];
+        q_halves(qraw, qs);
+        slide_pass(smem, HC * 64, a.g.v_off, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o);
         if (valid) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -502,7 +457,6 @@ fwd16_pipe_kernel(const FwdArgs a)
     const uint32_t hw2 = (uint32_t)a.g.H * (uint32_t)a.g.W * 2u;
     const int n_tiles = a.g.TA + a.g.TB;
     unsigned char* wbuf = smem + a.a_base + wave * WAVE_SCRATCH;
-    float* ascr = (float*)wbuf + p * A_STRIDE;
     const int seg_c = lane >> 1, seg_h = lane & 1;
 
     int cur = blockIdx.x;                               // gridDim.x <= n_tiles
@@ -602,7 +556,9 @@ fwd16_pipe_kernel(const FwdArgs a)
             __builtin_amdgcn_wave_barrier();
 
             float o[8];
-            slide_pass(buf, 2 * HC * 64, HC * 64, ti, tj, g, qraw, A1, A2, bias2, a.scale_log2e, ascr, o);
+            half2_t qs[4];
+            q_halves(qraw, qs);
+            slide_pass(buf, 2 * HC * 64, HC * 64, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o);
 
             // results -> 16-byte segments through the scratch
             __builtin_amdgcn_wave_barrier();
