@@ -28,7 +28,7 @@ constexpr int REC_BYTES = 32;                       // 16 halves per halo pixel 
 // Per-head image of the MFMA weight operands (dwords), written by prep_dkdv_weights_kernel:
 //   side (K: 0, V: 1) x tap t (9) x channel half j (2) x lane (64) x 2 dwords.
 // Row i of product (t, j) is channel 8*(i/4) + 4j + (i%4); dword y of lane (i, g) holds the
-// learned weights for the shifts of operand slots 4g+2y and 4g+2y+1.
+// merged weights (one-hot shift included) for the shifts of operand slots 4g+2y and 4g+2y+1.
 constexpr int IMG_DWORDS = 2 * S * 2 * 64 * 2;      // 4608
 
 __global__ void __launch_bounds__(256)
@@ -45,7 +45,7 @@ prep_dkdv_weights_kernel(const float* __restrict__ wk, const float* __restrict__
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_row(4 * g + 2 * y + h);
-            if (s >= 0) d[h] = w[((long)c * S + s) * S + t] - (s == t ? 1.0f : 0.0f);
+            if (s >= 0) d[h] = w[((long)c * S + s) * S + t];
         }
         img[((side * S + t) * 2 + j) * 128 + lane * 2 + y] = pack_half(d[0], d[1]);
     }
@@ -69,8 +69,6 @@ __device__ __forceinline__ void make_record(const float (&x)[S], uint4_t& lo, ui
     hi[0] = pack_half(x[2], x[6]);  hi[1] = 0u;                      // slots 8..11
     hi[2] = pack_half(x[3], x[7]);  hi[3] = 0u;                      // slots 12..15
 }
-// byte offset inside a record of the half that holds shift s
-__host__ __device__ constexpr int rec_slot_bytes(int s) { return 2 * (4 * (s & 3) + (s >> 2)); }
 
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_dkdv_kernel16(const DkdvArgs a)
@@ -175,8 +173,6 @@ bwd_dkdv_kernel16(const DkdvArgs a)
             const unsigned char* ra = smem + a.rec_a + hpix * REC_BYTES;
             const half4_t Bdl = __builtin_bit_cast(half4_t, *(const uint2_t*)(rdl + 8 * g));
             const half4_t Ba = __builtin_bit_cast(half4_t, *(const uint2_t*)(ra + 8 * g));
-            const float dl_t = (float)*(const _Float16*)(rdl + rec_slot_bytes(t));
-            const float a_t = (float)*(const _Float16*)(ra + rec_slot_bytes(t));
             const int toff = (ti + uy) * HC * 64 + col_offset(tj + ux, g);
             const uint4_t qd = *(const uint4_t*)(ql + toff);
             const uint4_t dod = *(const uint4_t*)(dol + toff);
@@ -188,8 +184,8 @@ bwd_dkdv_kernel16(const DkdvArgs a)
                 for (int r = 0; r < 4; ++r) {
                     const int e = 4 * j + r;
                     const half2_t qh = as_half2(qd[e >> 1]), dh = as_half2(dod[e >> 1]);
-                    dk[e] = fmaf(Lk[r] + dl_t, (float)qh[e & 1], dk[e]);
-                    dv[e] = fmaf(Lv[r] + a_t, (float)dh[e & 1], dv[e]);
+                    dk[e] = fmaf(Lk[r], (float)qh[e & 1], dk[e]);
+                    dv[e] = fmaf(Lv[r], (float)dh[e & 1], dv[e]);
                 }
             }
             if (ux == KS - 1) {
@@ -215,14 +211,14 @@ bwd_dkdv_kernel16(const DkdvArgs a)
 // For every pixel of a tile: recompute the attention weights a (as the forward does), then
 //     da[s] = sum_c dO[c] Vs[c,s]        (same shape as the logits, with dO, v, wv)
 //     dl[s] = a[s] (da[s] - sum_s' a[s'] da[s'])
-//     dq[c] = scale * sum_t k[c,p+t] (dl[t] + sum_s dl[s] wl_k[c,s,t])   (same shape as out)
+//     dq[c] = scale * sum_t k[c,p+t] * sum_s dl[s] W~k[c,s,t]            (same shape as out)
 // a and dl go to the workspace as float32 [B, heads, 9, H, W] for the other two kernels.
 //
-// Per-head operand image (dwords): A1k [0,2304): learned K kernel (times 16), tap t x lane x 4;
-// A1v [2304,4608): learned V kernel (times 16), same arrangement; A2k [4608,6912): learned K
+// Per-head operand image (dwords): A1k [0,2304): merged K kernel (times 16), tap t x lane x 4;
+// A1v [2304,4608): merged V kernel (times 16), same arrangement; A2k [4608,6912): merged K
 // kernel, product u (18) x lane x 2, arranged like the forward's V-side operand; bias rows.
+// The kernels enter as halves, one-hot shift included (as in the forward).
 constexpr int PX_A1K = 0, PX_A1V = 2304, PX_A2K = 4608, PX_BIAS = 6912, PX_IMG_DWORDS = 6928;
-constexpr int A_STRIDE = 12;
 constexpr float G_SCALE = 0.0625f, W_SCALE = 16.0f;
 
 __global__ void __launch_bounds__(256)
@@ -233,19 +229,18 @@ prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict_
     uint32_t* img = image + (long)m * PX_IMG_DWORDS;
     const int tid = threadIdx.x;
     {
-        // A1 arrangement, tap t: dword y of lane (i, g) = learned weights of channels 8g+2y,
+        // A1 arrangement, tap t: dword y of lane (i, g) = merged weights of channels 8g+2y,
         // 8g+2y+1 for the shift of logit row i
         const int y = tid & 3, lane = tid >> 2;
         const int i = lane & 15, g = lane >> 4;
         const int s = shift_of_row(i);
         float k0 = 0.0f, k1 = 0.0f, v0 = 0.0f, v1 = 0.0f;
         if (s >= 0) {
-            const float id = (s == t) ? 1.0f : 0.0f;
             const int c = m * D + 8 * g + 2 * y;
-            k0 = (wk[((long)c * S + s) * S + t] - id) * W_SCALE;
-            k1 = (wk[((long)(c + 1) * S + s) * S + t] - id) * W_SCALE;
-            v0 = (wv[((long)c * S + s) * S + t] - id) * W_SCALE;
-            v1 = (wv[((long)(c + 1) * S + s) * S + t] - id) * W_SCALE;
+            k0 = wk[((long)c * S + s) * S + t] * W_SCALE;
+            k1 = wk[((long)(c + 1) * S + s) * S + t] * W_SCALE;
+            v0 = wv[((long)c * S + s) * S + t] * W_SCALE;
+            v1 = wv[((long)(c + 1) * S + s) * S + t] * W_SCALE;
         }
         img[PX_A1K + t * 256 + tid] = pack_half(k0, k1);
         img[PX_A1V + t * 256 + tid] = pack_half(v0, v1);
@@ -261,7 +256,7 @@ prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict_
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_row(4 * g + 2 * y + h);
-            if (s >= 0) d[h] = wk[((long)c * S + s) * S + tap] - (s == tap ? 1.0f : 0.0f);
+            if (s >= 0) d[h] = wk[((long)c * S + s) * S + tap];
         }
         img[PX_A2K + u * 128 + (tid & 127)] = pack_half(d[0], d[1]);
     }
@@ -279,47 +274,29 @@ struct PixelArgs {
     float* attn; float* dl;                   // [B, heads, 9, H, W]
     const uint32_t* image;
     TileGrid g;                               // first staged tensor k, second v
-    int a_base;                               // byte offset of the per-wave scratch
     float scale, scale_log2e;
 };
 
-// x . (deformed shift of y) for the 9 shifts: the learned part through the matrix core
-// (accumulated into acc, rows 4g+r of the 16x16 tile), the shift part exactly into idp
-__device__ __forceinline__ void window_dots(const uint4_t (&yd)[S], const half2_t (&xpk)[4],
-                                            const half2_t (&xs)[4], const half8_t (&A)[S],
-                                            float4_t& acc, float (&idp)[S])
+// x . (deformed shift of y) for the 9 shifts, through the matrix core with the merged kernel
+// as half-precision operand (accumulated into acc, rows 4g+r of the 16x16 tile)
+__device__ __forceinline__ void window_dots(const uint4_t (&yd)[S], const half2_t (&xs)[4],
+                                            const half8_t (&A)[S], float4_t& acc)
 {
 #pragma unroll
     for (int t = 0; t < S; ++t) {
-        float R = 0.0f;
         uint4_t bb;
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const half2_t w = as_half2(yd[t][y]);
-            R = __builtin_amdgcn_fdot2(xpk[y], w, R, false);
-            bb[y] = as_dword(xs[y] * w);
-        }
+        for (int y = 0; y < 4; ++y) bb[y] = as_dword(xs[y] * as_half2(yd[t][y]));
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
-        idp[t] = R;
     }
 }
-// sums the four channel groups of the exact dot products, landing shift 4r+g in group g
-__device__ __forceinline__ void fold_groups(const float (&idp)[S], float4_t& acc)
-{
-    float z1 = fold32(idp[0], idp[2]), z2 = fold32(idp[1], idp[3]);
-    acc[0] += fold16(z1, z2);
-    z1 = fold32(idp[4], idp[6]); z2 = fold32(idp[5], idp[7]);
-    acc[1] += fold16(z1, z2);
-    z1 = fold32(idp[8], 0.0f);
-    acc[2] += fold16(z1, 0.0f);
-}
-__device__ __forceinline__ void raw_to_halves(const uint32_t (&raw)[8], half2_t (&pk)[4], half2_t (&sc)[4])
+// 8 channels as bf16 patterns (one per dword) -> halves divided by 16
+__device__ __forceinline__ void raw_to_halves(const uint32_t (&raw)[8], half2_t (&sc)[4])
 {
 #pragma unroll
-    for (int y = 0; y < 4; ++y) {
-        pk[y] = as_half2(pack_half_rtz(__uint_as_float(raw[2 * y] << 16), __uint_as_float(raw[2 * y + 1] << 16)));
-        sc[y] = pk[y] * half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
-    }
+    for (int y = 0; y < 4; ++y)
+        sc[y] = as_half2(pack_half_rtz(__uint_as_float(raw[2 * y] << 16), __uint_as_float(raw[2 * y + 1] << 16))) *
+                half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
 }
 
 __global__ void __launch_bounds__(THREADS, 2)
@@ -368,7 +345,6 @@ bwd_pixel_kernel16(const PixelArgs a)
     const int npix = tcur.rows * tcur.cols;
     const int npass = (npix + 15) >> 4;
     const float inv_tw = 1.0f / (float)tcur.cols;
-    float* ascr = (float*)(smem + a.a_base) + wave * 16 * A_STRIDE + p * A_STRIDE;
     const unsigned char* kl = smem;
     const unsigned char* vl = smem + a.g.v_off;
     const char* qb = (const char*)(a.q + tcur.head_base);
@@ -410,11 +386,10 @@ bwd_pixel_kernel16(const PixelArgs a)
         uint4_t xd[S];
 #pragma unroll
         for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
-        half2_t xpk[4], xs[4];
-        raw_to_halves(qraw, xpk, xs);
+        half2_t xs[4];
+        raw_to_halves(qraw, xs);
         float4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-        float idp[S];
-        window_dots(xd, xpk, xs, A1k, acc, idp);
+        window_dots(xd, xs, A1k, acc);
         // next pass's q and dO: issued now, used at the end of this pass
         uint32_t qnext[8], dnext[8];
         {
@@ -430,7 +405,6 @@ bwd_pixel_kernel16(const PixelArgs a)
         // v taps for the da step
 #pragma unroll
         for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(vl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
-        fold_groups(idp, acc);
         float l[3], pr[3];
 #pragma unroll
         for (int r = 0; r < 3; ++r) l[r] = fmaf(acc[r], a.scale_log2e, bias2[r]);
@@ -442,13 +416,12 @@ bwd_pixel_kernel16(const PixelArgs a)
         for (int r = 0; r < 3; ++r) pr[r] *= inv;
 
         // ---- da[s] = dO . Vs[s], then dl
-        raw_to_halves(draw, xpk, xs);
+        raw_to_halves(draw, xs);
         acc = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-        window_dots(xd, xpk, xs, A1v, acc, idp);
+        window_dots(xd, xs, A1v, acc);
         // k taps again for the dq step
 #pragma unroll
         for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kl + row0 + (t / KS) * HC * 64 + coff[t % KS]);
-        fold_groups(idp, acc);
         const float dsum = allsum_groups(pr[0] * acc[0] + pr[1] * acc[1] + pr[2] * acc[2]);
         float dl[3];
 #pragma unroll
@@ -464,14 +437,9 @@ bwd_pixel_kernel16(const PixelArgs a)
             }
         }
 
-        // ---- dq[c] = scale * sum_t k[c,p+t] (dl[t] + learned part); dl[t] enters as the MFMA's
-        // C operand
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int r = 0; r < 3; ++r) ascr[4 * r + g] = dl[r];          // slots 9..11 are never read
-        __builtin_amdgcn_wave_barrier();
-        const float4_t c0 = *(const float4_t*)(ascr), c1 = *(const float4_t*)(ascr + 4);
-        const float c8s = ascr[8];
+        // ---- dq[c] = scale * sum_t k[c,p+t] * (sum_s dl[s] W~k[c,s,t]): the inner sum on the
+        // matrix core, as the forward's V side
+        const float4_t c0 = {0.0f, 0.0f, 0.0f, 0.0f}, c1 = c0;
         uint2_t b2;
         b2[0] = pack_half(dl[0], dl[1]);
         b2[1] = pack_half(dl[2], 0.0f);
@@ -494,7 +462,7 @@ bwd_pixel_kernel16(const PixelArgs a)
             }
         }
         {
-            const float4_t c8 = {c8s, c8s, c8s, c8s};
+            const float4_t c8 = c0;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const float4_t w8 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[16 + j], B2, c8, 0, 0, 0);
@@ -532,8 +500,7 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
                                  void* dq, float* attn_ws, float* dl_ws, void* image_ws, hipStream_t st)
 {
     using namespace b16path;
-    constexpr int SCRATCH = WAVES * 16 * A_STRIDE * 4;
-    const TilePlan t = plan_tiles(p, LDS_LIMIT / 2 - SCRATCH, 64, 64);
+    const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
     uint32_t* image = (uint32_t*)image_ws;
     hipLaunchKernelGGL(prep_pixel_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
                        wk, wv, bias, image);
@@ -542,7 +509,6 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
     a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.dq = (bf16_bits*)dq; a.attn = attn_ws; a.dl = dl_ws; a.image = image;
     fill_grid(a.g, p, t, k, v);
-    a.a_base = t.buf_bytes;
     a.scale = 1.0f / sqrtf((float)D);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     static bool attr_set = false;
@@ -553,7 +519,7 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
         attr_set = true;
     }
     const unsigned grid = (unsigned)((long)t.TA + t.TB);
-    hipLaunchKernelGGL(bwd_pixel_kernel16, dim3(grid), dim3(THREADS), (size_t)(t.buf_bytes + SCRATCH), st, a);
+    hipLaunchKernelGGL(bwd_pixel_kernel16, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
     return hipGetLastError();
 }
 

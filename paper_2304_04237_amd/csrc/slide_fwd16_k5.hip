@@ -1,11 +1,12 @@
 // Matrix-core forward of Slide Attention for gfx950, 5x5 window: bf16 activations, head
 // size 32, 25 shifts and 25 taps.
 //
-// Same arithmetic arrangement as the 3x3 kernel (Sec. 4.1-4.3 re-associated):
-//     logit[s] = scale * ( sum_c q[c] k[c, p+s]  +  sum_{c,t} (q[c] k[c, p+t]) wl_k[c,s,t] )
-//     out[c]   = sum_t v[c, p+t] * ( a[t] + sum_s a[s] wl_v[c,s,t] )
-// with the shift path in fp32 and the learned path (800 x 25 per pixel and head, each side)
-// on v_mfma_f32_16x16x32_f16.  What differs from 3x3: the learned kernels of one head are
+// Same arithmetic arrangement as the 3x3 kernel (Sec. 4.1-4.3 re-associated), with the
+// merged kernels W~ = one-hot shift + learned part as half-precision matrix operands:
+//     logit[s] = scale * sum_{c,t} (q[c] k[c, p+t]) W~k[c,s,t]
+//     out[c]   = sum_t v[c, p+t] * g[c,t],   g[c,t] = sum_s a[s] W~v[c,s,t]
+// both contractions (800 x 25 per pixel and head, each side) on v_mfma_f32_16x16x32_f16.
+// What differs from 3x3: the kernels of one head are
 // 2 x 50 KB of MFMA operands, far too many for registers, so a block keeps them in LDS next
 // to the K/V halo tile and reads them as it goes; blocks are persistent and walk the tile
 // list, reloading the operands only when the head changes.  The 25 logits of a pixel live
@@ -18,7 +19,6 @@ using namespace t16;
 
 constexpr int K5 = 5, S5 = 25;
 constexpr int WAVES = 8, THREADS = WAVES * 64;
-constexpr int A_STRIDE = 28;                        // floats per pixel in the attention scratch
 constexpr float G_SCALE = 0.0625f, WK_SCALE = 16.0f;
 
 // Per-head operand image (dwords): A1: (tap t (25) x tile (2)) x lane (64) x 4; A2: product u
@@ -51,7 +51,7 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
     const int t = blockIdx.x, m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
     const int tid = threadIdx.x;
-    // A1, tap t, both tiles: dword y of lane (i, g) = learned K weights (times 16) of channels
+    // A1, tap t, both tiles: dword y of lane (i, g) = merged K weights (times 16) of channels
     // 8g+2y, 8g+2y+1 for the shift of row i of the tile
     for (int tile = 0; tile < 2; ++tile) {
         const int y = tid & 3, lane = tid >> 2;
@@ -59,16 +59,15 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
         const int s = shift_of_row5(16 * tile + i);
         float d0 = 0.0f, d1 = 0.0f;
         if (s >= 0) {
-            const float id = (s == t) ? 1.0f : 0.0f;
             const int c = m * D + 8 * g + 2 * y;
-            d0 = (wk[((long)c * S5 + s) * S5 + t] - id) * WK_SCALE;
-            d1 = (wk[((long)(c + 1) * S5 + s) * S5 + t] - id) * WK_SCALE;
+            d0 = wk[((long)c * S5 + s) * S5 + t] * WK_SCALE;
+            d1 = wk[((long)(c + 1) * S5 + s) * S5 + t] * WK_SCALE;
         }
         img[IMG_A1 + (t * 2 + tile) * 256 + tid] = pack_half(d0, d1);
     }
     // A2, products u = 2t and 2t+1.  u < 48: channel slot e = u % 8, tap quad tq = u / 8; row i
     // is channel 8*(i/4) + e at tap 4*tq + (i%4).  u = 48 + j: row i is channel
-    // 8*(i/4) + 4j + (i%4) at tap 24.  Dword y of lane (i, g) holds the learned V weights for
+    // 8*(i/4) + 4j + (i%4) at tap 24.  Dword y of lane (i, g) holds the merged V weights for
     // the shifts of slots 8g+2y, 8g+2y+1.
     for (int uu = 0; uu < 2; ++uu) {
         const int u = 2 * t + uu;
@@ -81,7 +80,7 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_slot5(8 * g + 2 * y + h);
-            if (s >= 0) d[h] = wv[((long)c * S5 + s) * S5 + tap] - (s == tap ? 1.0f : 0.0f);
+            if (s >= 0) d[h] = wv[((long)c * S5 + s) * S5 + tap];
         }
         img[IMG_A2 + u * 256 + tid] = pack_half(d[0], d[1]);
     }
@@ -98,7 +97,6 @@ struct Fwd5Args {
     const uint32_t* image;
     TileGrid g;
     int w_base;              // byte offset of the operand image in LDS
-    int a_base;              // byte offset of the attention scratch
     float scale_log2e;
 };
 
@@ -113,7 +111,6 @@ fwd16_k5_kernel(const Fwd5Args a)
     const uint32_t hw2 = (uint32_t)a.g.H * (uint32_t)a.g.W * 2u;
     const int n_tiles = a.g.TA + a.g.TB;
     const unsigned char* wl = smem + a.w_base;
-    float* ascr = (float*)(smem + a.a_base) + wave * 16 * A_STRIDE + p * A_STRIDE;
     int m_loaded = -1;
 
     for (int cur = blockIdx.x; cur < n_tiles; cur += gridDim.x) {
@@ -182,13 +179,12 @@ fwd16_k5_kernel(const Fwd5Args a)
             for (int tx = 0; tx < K5; ++tx) coff[tx] = col_offset(tj + tx, g);
             const int row0 = ti * HC * 64;
 
-            half2_t qpk[4], qs[4];
+            half2_t qs[4];
 #pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                qpk[y] = as_half2(pack_half_rtz(__uint_as_float(qraw[2 * y] << 16),
-                                                __uint_as_float(qraw[2 * y + 1] << 16)));
-                qs[y] = qpk[y] * half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
-            }
+            for (int y = 0; y < 4; ++y)
+                qs[y] = as_half2(pack_half_rtz(__uint_as_float(qraw[2 * y] << 16),
+                                               __uint_as_float(qraw[2 * y + 1] << 16))) *
+                        half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
             // q of this wave's next pass in this tile
             if (pass + WAVES < npass) {
                 int ti2, tj2;
@@ -200,35 +196,19 @@ fwd16_k5_kernel(const Fwd5Args a)
 
             // ---- K side: 25 logits in two MFMA tiles
             float4_t accA = {0.0f, 0.0f, 0.0f, 0.0f}, accB = {0.0f, 0.0f, 0.0f, 0.0f};
-            float idp[S5];
 #pragma unroll
             for (int t = 0; t < S5; ++t) {
                 const uint4_t kd = *(const uint4_t*)(kl + row0 + (t / K5) * HC * 64 + coff[t % K5]);
                 const half8_t A1a = __builtin_bit_cast(half8_t, *(const uint4_t*)(wl + ((IMG_A1 + (t * 2) * 256) + lane * 4) * 4));
                 const half8_t A1b = __builtin_bit_cast(half8_t, *(const uint4_t*)(wl + ((IMG_A1 + (t * 2 + 1) * 256) + lane * 4) * 4));
-                float R = 0.0f;
                 uint4_t bb;
 #pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                    const half2_t kw = as_half2(kd[y]);
-                    R = __builtin_amdgcn_fdot2(qpk[y], kw, R, false);
-                    bb[y] = as_dword(qs[y] * kw);
-                }
+                for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[y]));
                 const half8_t G = __builtin_bit_cast(half8_t, bb);
                 accA = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1a, G, accA, 0, 0, 0);
                 accB = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1b, G, accB, 0, 0, 0);
-                idp[t] = R;
                 if (t % K5 == K5 - 1) __builtin_amdgcn_sched_barrier(0);     // one window row at a time
             }
-            // shift-path logits: sum the four channel groups, landing shift 4r+g (16+4r+g) in group g
-#pragma unroll
-            for (int r = 0; r < 6; ++r) {
-                const float z1 = fold32(idp[4 * r], idp[4 * r + 2]), z2 = fold32(idp[4 * r + 1], idp[4 * r + 3]);
-                const float sum = fold16(z1, z2);
-                if (r < 4) accA[r] += sum; else accB[r - 4] += sum;
-            }
-            accB[2] += fold16(fold32(idp[24], 0.0f), 0.0f);
-
             // ---- softmax over the 25 shifts (7 per lane, 4 lane groups)
             float l[7], pr[7];
 #pragma unroll
@@ -245,27 +225,18 @@ fwd16_k5_kernel(const Fwd5Args a)
             const float inv = __builtin_amdgcn_rcpf(allsum_groups(sum));
 #pragma unroll
             for (int r = 0; r < 7; ++r) pr[r] *= inv;
-            // all 25 attention weights of the pixel for every lane group, through the scratch
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int r = 0; r < 4; ++r) ascr[4 * r + g] = pr[r];
-            ascr[16 + g] = pr[4];
-            ascr[20 + g] = pr[5];
-            ascr[24 + g] = pr[6];                                  // slots 25..27 are never read
-            __builtin_amdgcn_wave_barrier();
             uint4_t b2;
             b2[0] = pack_half(pr[0], pr[1]); b2[1] = pack_half(pr[2], pr[3]);
             b2[2] = pack_half(pr[4], pr[5]); b2[3] = pack_half(pr[6], 0.0f);
             const half8_t B2 = __builtin_bit_cast(half8_t, b2);
 
-            // ---- V side: product (e, tq) gives the weights of channel e for taps 4tq..4tq+3;
-            // a[t] enters as the C operand
+            // ---- V side: product (e, tq) gives the weights g[c,t] of channel e for taps 4tq..4tq+3
             float o[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = 0.0f;
 #pragma unroll
             for (int tq = 0; tq < 6; ++tq) {
-                const float4_t c4 = *(const float4_t*)(ascr + 4 * tq);
+                const float4_t c4 = {0.0f, 0.0f, 0.0f, 0.0f};
                 uint4_t vd[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -285,8 +256,7 @@ fwd16_k5_kernel(const Fwd5Args a)
                 __builtin_amdgcn_sched_barrier(0);
             }
             {
-                const float a24 = ascr[24];
-                const float4_t c24 = {a24, a24, a24, a24};
+                const float4_t c24 = {0.0f, 0.0f, 0.0f, 0.0f};
                 const uint4_t vd24 = *(const uint4_t*)(vl + row0 + 4 * HC * 64 + coff[4]);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
@@ -308,8 +278,7 @@ fwd16_k5_kernel(const Fwd5Args a)
     }
 }
 
-constexpr int SCRATCH_BYTES = WAVES * 16 * A_STRIDE * 4;
-constexpr int TILE_BUDGET = LDS_LIMIT - IMG_BYTES - SCRATCH_BYTES - 256;
+constexpr int TILE_BUDGET = LDS_LIMIT - IMG_BYTES - 256;
 
 }  // namespace f16k5
 
@@ -339,9 +308,8 @@ hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, cons
     a.out = (bf16_bits*)out; a.image = image;
     fill_grid(a.g, p, t, k, v);
     a.w_base = t.buf_bytes;
-    a.a_base = t.buf_bytes + IMG_BYTES;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
-    const int lds_bytes = a.a_base + SCRATCH_BYTES;
+    const int lds_bytes = t.buf_bytes + IMG_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)fwd16_k5_kernel,
