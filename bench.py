@@ -7,6 +7,10 @@ One "step" = re-parameterise both kernels (slide_reparam x2) + slide_attn_fwd on
 stage-1 forward workload (B=64, 56x56, C=64, 2 heads, k=3, bf16), inputs already
 resident in HBM.  Inputs rotate through a pool of buffer sets larger than the
 256 MB last-level cache so the figure is HBM bandwidth, not cache bandwidth.
+The timed steps are replayed from a HIP graph that holds one step per buffer set
+(the three launches of a step take about as long to submit from Python as to run);
+the per-launch time of the forward kernel for the roofline comes from HIP events
+around eager calls on the same stream.
 Prints ONE JSON line: whole-job Gpixel*head/s, the HBM roofline of the forward
 kernel (algorithmic bytes / measured kernel time), the training workload
 (B=128 forward + backward) as extra context, and the CPU oracle timed on this
@@ -69,35 +73,78 @@ def main():
     wv = torch.empty_like(wv_l)
     path = sa.slide_attn_fwd_path(B, H, W, C, heads, ksize, torch.bfloat16)
 
+    ws_need = sa.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, torch.bfloat16, False)
+    ws = torch.empty(max(ws_need, 1), dtype=torch.uint8, device=dev)
+
     def step(i, ev=None):
         s = pool[i % POOL_SETS]
         sa.slide_reparam(wk_l, wk)
         sa.slide_reparam(wv_l, wv)
         if ev is not None:
             ev[0].record()
-        sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, heads, ksize, out=s["out"])
+        sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, heads, ksize, out=s["out"], workspace=ws)
         if ev is not None:
             ev[1].record()
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+
+    # forward kernel alone: HIP events around eager launches (on the launch stream)
+    n_ev = max(20, min(args.steps, 200))
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(args.steps)]
+           for _ in range(n_ev)]
+    for i in range(n_ev):
+        step(i, evs[i])
+    torch.cuda.synchronize()
+    fwd_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
+    fwd_med_ms = fwd_ms[len(fwd_ms) // 2]
+
+    # the timed region: exactly args.steps steps, replayed from a graph of POOL_SETS steps
+    launch = "hip graph of %d steps, replayed" % POOL_SETS
+    graph = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(POOL_SETS):
+                step(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(POOL_SETS):
+                step(i)
+        # a replay must reproduce the eager results bit for bit, on every buffer set, twice
+        eager = [pool[i]["out"].clone() for i in range(POOL_SETS)]
+        for _ in range(2):
+            for i in range(POOL_SETS):
+                pool[i]["out"].zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            if not all(torch.equal(pool[i]["out"], eager[i]) for i in range(POOL_SETS)):
+                raise RuntimeError("graph replay differs from eager launches")
+        del eager
+    except Exception as exc:                      # no graph support: plain launches
+        graph = None
+        launch = "eager (graph capture failed: %s)" % type(exc).__name__
+        torch.cuda.synchronize()
+    n_replay, n_tail = (args.steps // POOL_SETS, args.steps % POOL_SETS) if graph is not None else (0, args.steps)
     t0 = time.perf_counter()
     start = torch.cuda.Event(enable_timing=True)
     end = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
     start.record()
-    for i in range(args.steps):
-        step(i, evs[i])
+    for _ in range(n_replay):
+        graph.replay()
+    for i in range(n_tail):
+        step(i)
     end.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     total_ms = start.elapsed_time(end)
     ms_per_step = total_ms / args.steps
-    fwd_ms = sorted(a.elapsed_time(b) for a, b in evs)
-    fwd_avg_ms = sum(fwd_ms) / len(fwd_ms)
-    fwd_med_ms = fwd_ms[len(fwd_ms) // 2]
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json")
@@ -117,7 +164,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "stage1_bf16_fwd: B=64 H=W=56 C=64 heads=2 head_dim=32 ksize=3",
                    "inputs": "seeded N(0,1) q,k,v; N(0,0.02^2) learned kernels and bias",
-                   "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path,
+                   "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path, "launch": launch,
                    "host_wall_ms_per_step": wall_ms / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
