@@ -96,7 +96,7 @@ __device__ __forceinline__ void lds_read_2x5_dwords(uint32_t addr_a, uint32_t ad
     b[0] = b01[0]; b[1] = b01[1]; b[2] = b23[0]; b[3] = b23[1]; b[4] = b4;
 }
 
-__global__ void __launch_bounds__(THREADS, 4)
+__global__ void __launch_bounds__(THREADS, 2)
 bwd_dw_kernel(const Args a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -149,11 +149,10 @@ bwd_dw_kernel(const Args a)
     constexpr int N_KV = CPW * (R + 2) * 8, KV_SLOTS = (2 * N_KV + 63) / 64;        // 5
     constexpr int N_HC = CPW * (R + 2) * 2, HC_SLOTS = (2 * N_HC + 63) / 64;        // 2
     constexpr int N_Q = CPW * R * 8, Q_SLOTS = (2 * N_Q + 63) / 64;                 // 3
-    constexpr int N_D = S * R * 8;                                                  // 216 per tensor
-    static_assert(2 * N_D <= THREADS, "one dl/a item per thread");
+    constexpr int N_D = S * R * 8, D_SLOTS = (2 * N_D + THREADS - 1) / THREADS;     // dl / a items: 8 floats each
     uint4_t pre_kv[KV_SLOTS], pre_q[Q_SLOTS];
     uint32_t pre_hc[HC_SLOTS];
-    float4_t pre_d[2];
+    float4_t pre_d[D_SLOTS][2];
 
     auto issue_loads = [&](const Unit& t) {
 #pragma unroll
@@ -192,14 +191,16 @@ bwd_dw_kernel(const Args a)
                 pre_q[sl] = *(const uint4_t*)src;
             }
         }
-        {
-            const int tsel = tid >= N_D, id = tid - tsel * N_D;
+#pragma unroll
+        for (int sl = 0; sl < D_SLOTS; ++sl) {
+            const int idx = sl * THREADS + tid;
+            const int tsel = idx >= N_D, id = idx - tsel * N_D;
             const int x = id & 7, rj = id >> 3;
             const int s = rj / R, r = rj - s * R;
-            pre_d[0] = float4_t{0, 0, 0, 0}; pre_d[1] = float4_t{0, 0, 0, 0};
-            if (tid < 2 * N_D && x < t.nxc && r < t.rows_eff) {
+            pre_d[sl][0] = float4_t{0, 0, 0, 0}; pre_d[sl][1] = float4_t{0, 0, 0, 0};
+            if (idx < 2 * N_D && x < t.nxc && r < t.rows_eff) {
                 const float* src = (tsel ? a.attn : a.dl) + (((long)t.b * a.heads + m) * S + s) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
-                pre_d[0] = *(const float4_t*)src; pre_d[1] = *(const float4_t*)(src + 4);
+                pre_d[sl][0] = *(const float4_t*)src; pre_d[sl][1] = *(const float4_t*)(src + 4);
             }
         }
     };
@@ -237,16 +238,19 @@ bwd_dw_kernel(const Args a)
                 *(uint4_t*)(smem + (tsel ? OFF_DO : OFF_Q) + (((wave * CPW + cc) * R + r) * QP + 8 * x) * 2) =
                     bf16x8_to_half(pre_q[sl], in2);
         }
-        if (tid < 2 * N_D) {
-            const int tsel = tid >= N_D, id = tid - tsel * N_D;
+#pragma unroll
+        for (int sl = 0; sl < D_SLOTS; ++sl) {
+            const int idx = sl * THREADS + tid;
+            if (idx >= 2 * N_D) continue;
+            const int tsel = idx >= N_D, id = idx - tsel * N_D;
             const int x = id & 7, rj = id >> 3;
             const int s = rj / R, r = rj - s * R;
             uint4_t val;
             half2_t h;
-            h = half2_t{(_Float16)pre_d[0][0], (_Float16)pre_d[0][1]}; val[0] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[0][2], (_Float16)pre_d[0][3]}; val[1] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[1][0], (_Float16)pre_d[1][1]}; val[2] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[1][2], (_Float16)pre_d[1][3]}; val[3] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[sl][0][0], (_Float16)pre_d[sl][0][1]}; val[0] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[sl][0][2], (_Float16)pre_d[sl][0][3]}; val[1] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[sl][1][0], (_Float16)pre_d[sl][1][1]}; val[2] = as_dword(h);
+            h = half2_t{(_Float16)pre_d[sl][1][2], (_Float16)pre_d[sl][1][3]}; val[3] = as_dword(h);
             *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * QP + 8 * x) * 2) = val;
         }
     };
@@ -342,7 +346,7 @@ bwd_dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ d
 static int blocks_per_head(const Problem& p)
 {
     const long units = (long)p.B * ((p.H + R - 1) / R) * ((p.W + TW - 1) / TW);
-    long nb = 512 / p.heads;                 // two blocks per compute unit
+    long nb = 256 / p.heads;                 // one block per compute unit
     if (nb < 1) nb = 1;
     if (nb > units) nb = units;
     return (int)nb;
