@@ -34,14 +34,16 @@ constexpr int WAVES = 8, THREADS = WAVES * 64;
 constexpr int CPW = D / WAVES;        // channels per wave (4)
 constexpr int R = 3;                  // rows of one work unit
 constexpr int TW = 56;                // columns of one work unit (a multiple of 8)
-constexpr int QP = 64;                // halves per staged row of q, dO, dl, a
-constexpr int KP = 72;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin
+constexpr int QP = 64;                // halves per staged row of q, dO
+constexpr int DP = 64;                // halves per staged row of dl, a
+constexpr int KP = 88;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin, 16 padding (the three
+                                      // window rows of a tap read then fall on different LDS banks)
 constexpr float IN_SCALE = 0.0625f;   // q and dO are staged divided by 16
 
 // LDS map (bytes)
-constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 23040
+constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 28160
 constexpr int QH_BYTES = D * R * QP * 2;                  // 12288
-constexpr int DL_BYTES = S * R * QP * 2;                  // 3456
+constexpr int DL_BYTES = S * R * DP * 2;                  // 3456
 constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
               OFF_DO = OFF_Q + QH_BYTES, OFF_DL = OFF_DO + QH_BYTES, OFF_A = OFF_DL + DL_BYTES,
               OFF_ZERO = OFF_A + DL_BYTES, LDS_BYTES = OFF_ZERO + 256;
@@ -118,7 +120,7 @@ bwd_dw_kernel(const Args a)
     const int kwin_off = (ty * KP + 8 + 8 * g) * 2 - 4 + (tx >= 1 ? 4 : 0);   // + (cc*(R+2) + r)*KP*2 + 64*h
     const uint32_t win_shift = (tx == 1) ? 0u : 16u;
     const int q_off = (i < S) ? (8 * g) * 2 : -1;                 // -1: masked row, read zeros
-    const int b_off = (i < S) ? ((i * R) * QP + 8 * g) * 2 : -1;  // + r*QP*2 + 64*h
+    const int b_off = (i < S) ? ((i * R) * DP + 8 * g) * 2 : -1;  // + r*DP*2 + 64*h
 
     float4_t acc_k[CPW], acc_v[CPW];
 #pragma unroll
@@ -251,7 +253,7 @@ bwd_dw_kernel(const Args a)
             h = half2_t{(_Float16)pre_d[sl][0][2], (_Float16)pre_d[sl][0][3]}; val[1] = as_dword(h);
             h = half2_t{(_Float16)pre_d[sl][1][0], (_Float16)pre_d[sl][1][1]}; val[2] = as_dword(h);
             h = half2_t{(_Float16)pre_d[sl][1][2], (_Float16)pre_d[sl][1][3]}; val[3] = as_dword(h);
-            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * QP + 8 * x) * 2) = val;
+            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * DP + 8 * x) * 2) = val;
         }
     };
 
@@ -269,8 +271,8 @@ bwd_dw_kernel(const Args a)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if (32 * h >= cols_eff) continue;
-                const int dl_addr = (b_off >= 0) ? OFF_DL + b_off + r * QP * 2 + 64 * h : OFF_ZERO;
-                const int a_addr = (b_off >= 0) ? OFF_A + b_off + r * QP * 2 + 64 * h : OFF_ZERO;
+                const int dl_addr = (b_off >= 0) ? OFF_DL + b_off + r * DP * 2 + 64 * h : OFF_ZERO;
+                const int a_addr = (b_off >= 0) ? OFF_A + b_off + r * DP * 2 + 64 * h : OFF_ZERO;
                 const half8_t Bdl = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + dl_addr));
                 const half8_t Ba = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + a_addr));
 #pragma unroll
