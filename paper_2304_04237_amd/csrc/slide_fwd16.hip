@@ -503,14 +503,11 @@ fwd16_pipe_kernel(const FwdArgs a)
             const int stj = nn - sti * tcur.cols;
             return (uint32_t)seg_c * hw2 + ((uint32_t)(tcur.i0 + sti) * a.g.W + tcur.j0 + stj) * 2u;
         };
-        // q segments of this wave's first two passes
-        uint4_t qseg = {0u, 0u, 0u, 0u}, qseg1 = {0u, 0u, 0u, 0u};
+        // q segment of this wave's first pass
+        uint4_t qseg;
         {
             bool ok;
-            uint32_t off = seg_offset(min(wave, npass - 1), ok);
-            if (ok) qseg = *(const uint4_t*)(qb + off);
-            off = seg_offset(min(wave + WAVES, npass - 1), ok);
-            if (ok) qseg1 = *(const uint4_t*)(qb + off);
+            qseg = *(const uint4_t*)(qb + seg_offset(min(wave, npass - 1), ok));
         }
         __syncthreads();                                // buf is complete, buf_next is free
         if (tcur.m != m_loaded) {
@@ -524,28 +521,21 @@ fwd16_pipe_kernel(const FwdArgs a)
         }
 
         // K and V of the next tile: the loads of a pass's share are issued at its start and
-        // converted into buf_next at the end of the wave's following pass
-        uint4_t pre_old[4];
-        int hb_old = sg.n_groups;
+        // converted into buf_next at its end, before the pass's results are stored.  Nothing
+        // that a load fills is copied or carried into another iteration: the only wait for
+        // vector memory sits before the conversion, where everything it waits for was issued a
+        // pass ago or longer (the store of the previous pass included).  A wait placed after a
+        // store would expose the store's completion time in every pass.
         auto store_share = [&](int hb, const uint4_t (&r)[4]) {
             if (single_col) share_store<false>(tnext, sg, hb, lane, HC, r, buf_next);
             else            share_store<true>(tnext, sg, hb, lane, HC, r, buf_next);
         };
+        asm volatile("" :: "v"(qseg));                  // the first q has arrived before the loop starts
         for (int pass = wave; pass < npass; pass += WAVES) {
             int n = pass * 16 + p;
             n = n < npix ? n : npix - 1;
             const int ti = (int)(((float)n + 0.5f) * inv_tw);
             const int tj = n - ti * tcur.cols;
-            // q two passes ahead, then this pass's share of the next tile
-            uint4_t qseg2 = {0u, 0u, 0u, 0u};
-            {
-                bool ok;
-                const uint32_t off = seg_offset(min(pass + 2 * WAVES, npass - 1), ok);
-                if (ok) qseg2 = *(const uint4_t*)(qb + off);
-            }
-            uint4_t pre[4];
-            if (pass < sg.n_groups) share_load(a, tnext, sg, pass, lane, hw2, pre);
-
             // q segment -> per-lane channels through the wave's scratch
             uint32_t qraw[8];
             __builtin_amdgcn_wave_barrier();
@@ -554,6 +544,14 @@ fwd16_pipe_kernel(const FwdArgs a)
 #pragma unroll
             for (int e = 0; e < 8; ++e) qraw[e] = *(const bf16_bits*)(wbuf + chan_row(8 * g + e) + p * 2);
             __builtin_amdgcn_wave_barrier();
+            // q of the wave's next pass, then this pass's share of the next tile
+            {
+                bool ok;
+                const uint32_t off = seg_offset(min(pass + WAVES, npass - 1), ok);
+                qseg = *(const uint4_t*)(qb + off);     // (the offset is valid even when the segment is not)
+            }
+            uint4_t pre[4];
+            if (pass < sg.n_groups) share_load(a, tnext, sg, pass, lane, hw2, pre);
 
             float o[8];
             half2_t qs[4];
@@ -565,26 +563,24 @@ fwd16_pipe_kernel(const FwdArgs a)
 #pragma unroll
             for (int e = 0; e < 8; ++e) *(bf16_bits*)(wbuf + chan_row(8 * g + e) + p * 2) = f32_to_bf16(o[e]);
             __builtin_amdgcn_wave_barrier();
+            const uint4_t ov = *(const uint4_t*)(wbuf + chan_row(seg_c) + seg_h * 16);
+            __builtin_amdgcn_wave_barrier();
+            if (pass < sg.n_groups) store_share(pass, pre);
+            // every load of this pass counts as used here, on every path: the waits sit here,
+            // before the store, and nothing is left pending that a later wait would have to cover
+            asm volatile("" :: "v"(qseg), "v"(pre[0]), "v"(pre[1]), "v"(pre[2]), "v"(pre[3]));
             {
                 bool ok;
                 const uint32_t off = seg_offset(pass, ok);
-                const uint4_t ov = *(const uint4_t*)(wbuf + chan_row(seg_c) + seg_h * 16);
                 if (ok) *(uint4_t*)(ob + off) = ov;
             }
-            __builtin_amdgcn_wave_barrier();
-            if (hb_old < sg.n_groups) store_share(hb_old, pre_old);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pre_old[e] = pre[e];
-            hb_old = pass;
-            qseg = qseg1;
-            qseg1 = qseg2;
         }
-        if (hb_old < sg.n_groups) store_share(hb_old, pre_old);
         // what the passes did not cover of the next tile (short tiles before tall ones)
         for (int hb = wave + ((npass - wave + WAVES - 1) / WAVES) * WAVES; hb < sg.n_groups; hb += WAVES) {
             uint4_t pre[4];
             share_load(a, tnext, sg, hb, lane, hw2, pre);
             store_share(hb, pre);
+            asm volatile("" :: "v"(pre[0]), "v"(pre[1]), "v"(pre[2]), "v"(pre[3]));
         }
         if (!has_next) break;
         pipe_zero_pad(a.g, tnext, HC, buf_next, tid, THREADS);
