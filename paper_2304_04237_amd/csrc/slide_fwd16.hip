@@ -423,23 +423,32 @@ __device__ __forceinline__ void pipe_zero_pad(const TileGrid& a, const Tile& t, 
 
 // One block builds a head's operand image in LDS (THREADS threads, every weight load issued
 // before the first use).
+// The head's kernels (2 x 32 x 81 floats, contiguous) come in as coalesced 16-byte loads and
+// are gathered from LDS: `raw` is IMG_RAW_BYTES of LDS that does not overlap dst.  Contains a
+// block barrier; every thread of the block must call it.
+constexpr int IMG_RAW_AT = 20480;                         // byte offset of `raw` behind an image (IMG_DWORDS * 4 = 18496)
+constexpr int HEAD_W = D * S * S;                         // floats of one head in a kernel tensor
+constexpr int IMG_RAW_BYTES = 2 * HEAD_W * 4;             // 20736
 template <int THREADS>
 __device__ __forceinline__ void build_image(const float* __restrict__ wk, const float* __restrict__ wv,
-                                            const float* __restrict__ bias, int m, uint32_t* dst, int tid)
+                                            const float* __restrict__ bias, int m, uint32_t* dst,
+                                            float* raw, int tid)
 {
-    constexpr int N = IMG_BIAS / THREADS;
+    constexpr int N = IMG_BIAS / THREADS, CHUNKS = HEAD_W / 4;
     static_assert(N * THREADS == IMG_BIAS, "whole rounds");
-    float w0[N], w1[N];
+    static_assert(CHUNKS * 4 == HEAD_W, "16-byte chunks");
+    for (int i = tid; i < 2 * CHUNKS; i += THREADS) {
+        const bool is_v = i >= CHUNKS;
+        const float* src = (is_v ? wv : wk) + (long)m * HEAD_W;               // 16-byte aligned: HEAD_W % 4 == 0
+        *(float4_t*)(raw + 4 * i) = *(const float4_t*)(src + 4 * (i - (is_v ? CHUNKS : 0)));
+    }
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < N; ++i) {
         const ImageSource src = image_source(m, tid + i * THREADS);
-        const float* w = src.from_v ? wv : wk;
-        w0[i] = w[src.off0];
-        w1[i] = w[src.off1];
+        const float* w = raw + (src.from_v ? HEAD_W : 0) - m * HEAD_W;
+        dst[tid + i * THREADS] = image_value(src, w[src.off0], w[src.off1]);
     }
-#pragma unroll
-    for (int i = 0; i < N; ++i)
-        dst[tid + i * THREADS] = image_value(image_source(m, tid + i * THREADS), w0[i], w1[i]);
     if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
 }
 
@@ -463,7 +472,8 @@ fwd16_pipe_kernel(const FwdArgs a)
     Tile tcur = decode_tile(a.g, cur);
     // The block builds the operand image of its head in the second tile buffer, which is
     // free until the first pass (no separate preparation kernel on this path).
-    build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)(smem + a.buf_stride), tid);
+    build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)(smem + a.buf_stride),
+                         (float*)(smem + a.buf_stride + IMG_RAW_AT), tid);
     // the first tile is staged without overlap, two shares per lane in flight
     {
         const ShareGeom sg = share_geom(tcur);
@@ -512,7 +522,8 @@ fwd16_pipe_kernel(const FwdArgs a)
         __syncthreads();                                // buf is complete, buf_next is free
         if (tcur.m != m_loaded) {
             if (it > 0) {                               // the block moves on to another head
-                build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)buf_next, tid);
+                build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)buf_next,
+                                     (float*)(buf_next + IMG_RAW_AT), tid);
                 __syncthreads();
             }
             load_operands((const uint32_t*)buf_next, lane, g, A1, A2, bias2);
@@ -622,7 +633,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     using namespace f16path;
     // the pipelined kernel needs 16-byte aligned rows everywhere and enough tiles per block
     const bool aligned = (p.W % 8 == 0) &&
-                         (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) % 16 == 0);
+                         (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out |
+                           (uintptr_t)wk | (uintptr_t)wv) % 16 == 0);
     TilePlan t = plan_fwd(p, true);
     const bool pipelined = aligned && ((long)t.TA + t.TB >= 2L * NUM_CU);
     if (!pipelined) t = plan_fwd(p, false);
@@ -635,6 +647,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     a.out = (bf16_bits*)out; a.image = image;
     a.wk = wk; a.wv = wv; a.bias = bias;
     fill_grid(a.g, p, t, k, v);
+    a.g.small_first = pipelined;
     a.buf_stride = t.buf_bytes;
     a.a_base = (pipelined ? 2 : 1) * t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);

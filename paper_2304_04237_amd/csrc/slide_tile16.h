@@ -95,6 +95,7 @@ struct TileGrid {
     int v_off;               // byte offset of the second halo tensor inside a tile buffer
     int vec_ok;              // rows are 16-byte aligned: W % 8 == 0 and 16-byte aligned bases
     int r;                   // halo radius (ksize / 2)
+    int small_first;         // the tile list starts with the remainder tiles (class B)
 };
 
 // One tile of one (batch, head) plane; every field is wavefront-uniform.
@@ -105,15 +106,18 @@ struct Tile {
 };
 
 // List index -> tile.  Class A (full-height tiles) comes first so that dealing the list
-// round-robin to the blocks balances them; inside a class tiles are ordered head, batch, column tile, row tile,
+// round-robin to the blocks balances them (a persistent kernel may ask for class B first: its
+// blocks then start on a small tile, which shortens the part of the run where nothing
+// overlaps the first staging); inside a class tiles are ordered head, batch, column tile, row tile,
 // and consecutive queue indices are dealt to the 8 XCDs (blocks are dealt round-robin over
 // XCDs too), so vertically adjacent tiles are staged through the same L2 at about the same
 // time and a block rarely changes head.
 __device__ __forceinline__ Tile decode_tile(const TileGrid& a, int i)
 {
     int k, n_r, hgt, row_base, cnt;
-    if (i < a.TA) { k = i; n_r = a.nA; hgt = a.th; row_base = 0; cnt = a.TA; }
-    else          { k = i - a.TA; n_r = a.nB; hgt = a.hb; row_base = a.nA * a.th; cnt = a.TB; }
+    const bool cls_a = a.small_first ? i >= a.TB : i < a.TA;
+    if (cls_a) { k = a.small_first ? i - a.TB : i; n_r = a.nA; hgt = a.th; row_base = 0; cnt = a.TA; }
+    else       { k = a.small_first ? i : i - a.TA; n_r = a.nB; hgt = a.hb; row_base = a.nA * a.th; cnt = a.TB; }
     if ((cnt & 7) == 0) k = (k & 7) * (cnt >> 3) + (k >> 3);
     const int per_plane = a.n_tc * n_r;
     const int plane = k / per_plane;
@@ -297,6 +301,7 @@ inline void fill_grid(TileGrid& g, const Problem& p, const TilePlan& t, const vo
     g.B = p.B; g.H = p.H; g.W = p.W; g.C = p.C; g.heads = p.heads;
     g.th = t.th; g.tw = t.tw; g.n_tc = t.n_tc; g.nA = t.nA; g.nB = t.nB; g.hb = t.hb;
     g.TA = t.TA; g.TB = t.TB; g.v_off = t.v_off; g.r = p.ksize / 2;
+    g.small_first = 0;
     g.vec_ok = (p.W % 8 == 0) && (((uintptr_t)src_a | (uintptr_t)src_b) % 16 == 0);
 }
 
