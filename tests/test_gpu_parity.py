@@ -181,6 +181,28 @@ def test_backward_matches_oracle(shape):
         assert torch.equal(a, b)
 
 
+def test_forward_unaligned_parameters_and_activations():
+    """Pointers that are aligned to their element size only (4 bytes for the kernels, 2 for
+    the activations): the forward must not take the paths that need 16-byte alignment."""
+    B, H, W, C, heads, ksize = 32, 56, 56, 64, 2, 3                  # enough tiles for the pipelined kernel
+    d, g, n = gpu_problem(B, H, W, C, heads, ksize, "bf16", seed=321)
+    ref = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, ksize)
+
+    def shifted(t, elems):
+        buf = torch.empty(t.numel() + elems, dtype=t.dtype, device=t.device)
+        view = buf[elems:].view(t.shape)
+        view.copy_(t)
+        return view
+
+    wk1, wv1 = shifted(g["wk"], 1), shifted(g["wv"], 1)              # 4 bytes past a 16-byte boundary
+    assert wk1.data_ptr() % 16 == 4
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], wk1, wv1, g["bias"], heads, ksize)
+    check("out (kernels at 4-byte alignment)", "bf16", out, ref)
+    q1, k1, v1 = shifted(g["q"], 1), shifted(g["k"], 1), shifted(g["v"], 1)   # 2 bytes past
+    out = sa.slide_attn_fwd(q1, k1, v1, g["wk"], g["wv"], g["bias"], heads, ksize)
+    check("out (activations at 2-byte alignment)", "bf16", out, ref)
+
+
 def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
     assert sa.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, torch.bfloat16) == 2
