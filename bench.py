@@ -39,8 +39,9 @@ def main():
     ap.add_argument("--no-train", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the operator needs no second GPU; "
-              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (batch items, heads and tiles are "
+              "independent, so the operator would shard without exchange; nothing here uses a "
+              "second GPU); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
