@@ -130,12 +130,14 @@ void oracle_deformed_shift(const double *x, const double *w, double *out,
 
 /* Forward for ONE pixel of ONE head: fills out_px[d] (and attn_px[S], Ks/Vs
  * scratch [d*S]) -- Eq. 2 restricted to the k*k neighbourhood, keys and
- * values taken from the deformed shift. */
+ * values taken from the deformed shift.  If lse_px is not NULL it receives the
+ * logarithm of the softmax denominator of Eq. 2, log sum_s exp(logit[s]). */
 static void forward_pixel(const double *q, const double *k, const double *v,
                           const double *wk, const double *wv, const double *bias,
                           int two_branch, int b, int m, int i, int j,
                           int H, int W, int C, int heads, int ksize,
-                          double *Ks, double *Vs, double *attn_px, double *out_px)
+                          double *Ks, double *Vs, double *attn_px, double *out_px,
+                          double *lse_px)
 {
     int S = ksize * ksize, d = C / heads;
     double scale = 1.0 / sqrt((double)d);
@@ -164,6 +166,7 @@ static void forward_pixel(const double *q, const double *k, const double *v,
     double den = 0.0;
     for (int s = 0; s < S; ++s) { attn_px[s] = exp(attn_px[s] - mx); den += attn_px[s]; }
     for (int s = 0; s < S; ++s) attn_px[s] /= den;
+    if (lse_px) *lse_px = mx + log(den);
     for (int cc = 0; cc < d; ++cc) {
         double acc = 0.0;
         for (int s = 0; s < S; ++s) acc += attn_px[s] * Vs[cc * S + s];
@@ -171,11 +174,12 @@ static void forward_pixel(const double *q, const double *k, const double *v,
     }
 }
 
-/* Whole-tensor forward.  out [B,C,H,W]; attn [B,heads,S,H,W] or NULL.
+/* Whole-tensor forward.  out [B,C,H,W]; attn [B,heads,S,H,W] or NULL; lse
+ * [B,heads,H,W] or NULL (log of the softmax denominator per pixel and head).
  * two_branch selects the training form (wk/wv learned) or the merged form. */
 void oracle_fwd(const double *q, const double *k, const double *v,
                 const double *wk, const double *wv, const double *bias,
-                double *out, double *attn,
+                double *out, double *attn, double *lse,
                 int B, int H, int W, int C, int heads, int ksize, int two_branch)
 {
     int S = ksize * ksize, d = C / heads;
@@ -189,7 +193,8 @@ void oracle_fwd(const double *q, const double *k, const double *v,
             for (int i = 0; i < H; ++i)
                 for (int j = 0; j < W; ++j) {
                     forward_pixel(q, k, v, wk, wv, bias, two_branch, b, m, i, j,
-                                  H, W, C, heads, ksize, Ks, Vs, a, o);
+                                  H, W, C, heads, ksize, Ks, Vs, a, o,
+                                  lse ? lse + (((long)b * heads + m) * H + i) * W + j : NULL);
                     for (int cc = 0; cc < d; ++cc)
                         out[IDX4(b, m * d + cc, i, j, C, H, W)] = o[cc];
                     if (attn)
@@ -216,7 +221,7 @@ void oracle_fwd_samples(const double *q, const double *k, const double *v,
     for (int n = 0; n < n_pos; ++n)
         forward_pixel(q, k, v, wk, wv, bias, two_branch,
                       pos[4 * n], pos[4 * n + 1], pos[4 * n + 2], pos[4 * n + 3],
-                      H, W, C, heads, ksize, Ks, Vs, a, out_samples + (long)n * d);
+                      H, W, C, heads, ksize, Ks, Vs, a, out_samples + (long)n * d, NULL);
     free(Ks); free(Vs); free(a);
 }
 
@@ -263,7 +268,7 @@ void oracle_bwd(const double *dout, const double *q, const double *k, const doub
             for (int i = 0; i < H; ++i)
                 for (int j = 0; j < W; ++j) {
                     forward_pixel(q, k, v, wk, wv, bias, 0, b, m, i, j,
-                                  H, W, C, heads, ksize, Ks, Vs, a, o);
+                                  H, W, C, heads, ksize, Ks, Vs, a, o, NULL);
                     double dsum = 0.0;
                     for (int s = 0; s < S; ++s) {
                         double acc = 0.0;

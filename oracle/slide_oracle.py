@@ -72,8 +72,11 @@ def deformed_shift(x, w, ksize, two_branch):
     return out
 
 
-def fwd(q, k, v, wk, wv, bias, heads, ksize, two_branch=False, return_attn=False):
-    """Forward.  wk/wv are merged kernels, or learned ones when two_branch."""
+def fwd(q, k, v, wk, wv, bias, heads, ksize, two_branch=False, return_attn=False, return_lse=False):
+    """Forward.  wk/wv are merged kernels, or learned ones when two_branch.
+
+    Returns out, then attn [B, heads, S, H, W] if return_attn, then lse [B, heads, H, W]
+    (log of the softmax denominator of Eq. 2) if return_lse."""
     q, qp = _d(q); k, kp = _d(k); v, vp = _d(v)
     wk, wkp = _d(wk); wv, wvp = _d(wv)
     B, C, H, W = q.shape
@@ -83,10 +86,13 @@ def fwd(q, k, v, wk, wv, bias, heads, ksize, two_branch=False, return_attn=False
         bias, bp = _d(bias)
     out = np.empty_like(q)
     attn = np.empty((B, heads, S, H, W), dtype=np.float64) if return_attn else None
+    lse = np.empty((B, heads, H, W), dtype=np.float64) if return_lse else None
     _load().oracle_fwd(qp, kp, vp, wkp, wvp, bp, out.ctypes.data_as(_dp),
                        attn.ctypes.data_as(_dp) if return_attn else None,
+                       lse.ctypes.data_as(_dp) if return_lse else None,
                        B, H, W, C, int(heads), int(ksize), int(bool(two_branch)))
-    return (out, attn) if return_attn else out
+    res = (out,) + ((attn,) if return_attn else ()) + ((lse,) if return_lse else ())
+    return res if len(res) > 1 else out
 
 
 def fwd_samples(q, k, v, wk, wv, bias, heads, ksize, positions, two_branch=False):

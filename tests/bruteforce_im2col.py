@@ -23,13 +23,15 @@ def window(x_c, i, j, ksize):
     return col
 
 
-def local_attention(q, k, v, wk_learned, wv_learned, bias, heads, ksize):
+def local_attention(q, k, v, wk_learned, wv_learned, bias, heads, ksize, return_logits=False):
+    """out, attn (and the raw logits [B, heads, S, H, W] when asked for)."""
     B, C, H, W = q.shape
     S = ksize * ksize
     d = C // heads
     eye = np.eye(S)
     out = np.zeros_like(q, dtype=np.float64)
     attn = np.zeros((B, heads, S, H, W))
+    all_logits = np.zeros((B, heads, S, H, W))
     for b in range(B):
         for m in range(heads):
             for i in range(H):
@@ -43,8 +45,9 @@ def local_attention(q, k, v, wk_learned, wv_learned, bias, heads, ksize):
                     logits = q[b, m * d:(m + 1) * d, i, j] @ keys / np.sqrt(d)
                     if bias is not None:
                         logits = logits + bias[m]
+                    all_logits[b, m, :, i, j] = logits
                     e = np.exp(logits - logits.max())
                     a = e / e.sum()
                     attn[b, m, :, i, j] = a
                     out[b, m * d:(m + 1) * d, i, j] = vals @ a
-    return out, attn
+    return (out, attn, all_logits) if return_logits else (out, attn)

@@ -252,6 +252,59 @@ def test_softmax_and_structural_invariants():
     np.testing.assert_allclose(dbias.sum(1), 0.0, rtol=0, atol=1e-12)
 
 
+# ---------------------------------------------------------------- log of the softmax denominator
+@pytest.mark.parametrize("shape", SHAPES)
+def test_lse_matches_bruteforce_logits_and_library_logsumexp(shape):
+    """lse = log sum_s exp(logit[s]) (denominator of Eq. 2): against the column-view brute
+    force's raw logits (summed naively here: they are O(1)) and torch.logsumexp of the
+    grouped-conv statement."""
+    B, H, W, C, heads, ksize = shape
+    q, k, v, _, wk, wv, bias = rand_problem(*shape, seed=21)
+    _, _, logits = brute_local_attention(q, k, v, wk, wv, bias, heads, ksize, return_logits=True)
+    wkm, wvm = oracle.reparam(wk, ksize), oracle.reparam(wv, ksize)
+    out, attn, lse = oracle.fwd(q, k, v, wkm, wvm, bias, heads, ksize, return_attn=True, return_lse=True)
+    assert lse.shape == (B, heads, H, W)
+    np.testing.assert_allclose(lse, np.log(np.exp(logits).sum(2)), rtol=0, atol=1e-12)
+    # attention weights, logits and lse belong together: a[s] = exp(l[s] - lse)
+    np.testing.assert_allclose(attn, np.exp(logits - lse[:, :, None]), rtol=0, atol=1e-12)
+    t = [torch.from_numpy(x) for x in (q, k, v, wkm, wvm, bias)]
+    d, S = C // heads, ksize * ksize
+    Ks = F.conv2d(t[1], t[3].reshape(C * S, 1, ksize, ksize), padding=ksize // 2, groups=C)
+    tl = (t[0].reshape(B, heads, d, 1, H, W) * Ks.reshape(B, heads, d, S, H, W)).sum(2) / math.sqrt(d)
+    tl = tl + t[5][None, :, :, None, None]
+    np.testing.assert_allclose(lse, torch.logsumexp(tl, dim=2).numpy(), rtol=0, atol=1e-12)
+    # the two-branch form gives the same lse, and asking for lse does not change out
+    out2, lse2 = oracle.fwd(q, k, v, wk, wv, bias, heads, ksize, two_branch=True, return_lse=True)
+    np.testing.assert_allclose(lse2, lse, rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(out, oracle.fwd(q, k, v, wkm, wvm, bias, heads, ksize))
+
+
+def test_lse_closed_forms():
+    B, H, W, C, heads, ksize = 1, 4, 3, 4, 2, 3
+    q, k, v, _, wk, wv, bias = rand_problem(B, H, W, C, heads, ksize, seed=22)
+    wkm, wvm = oracle.reparam(wk, ksize), oracle.reparam(wv, ksize)
+    # q = 0, no bias: nine equal logits of zero -> lse = log 9 everywhere, borders included
+    # (padded neighbours stay in the softmax)
+    _, lse = oracle.fwd(np.zeros_like(q), k, v, wkm, wvm, None, heads, ksize, return_lse=True)
+    np.testing.assert_allclose(lse, math.log(9.0), rtol=0, atol=1e-14)
+    # q = 0 with bias: lse depends on the head's bias row only
+    _, lse = oracle.fwd(np.zeros_like(q), k, v, wkm, wvm, bias, heads, ksize, return_lse=True)
+    for m in range(heads):
+        np.testing.assert_allclose(lse[:, m], math.log(sum(math.exp(x) for x in bias[m])), rtol=0, atol=1e-13)
+    # a constant added to a head's bias row moves that head's lse by the constant
+    _, lse_a = oracle.fwd(q, k, v, wkm, wvm, bias, heads, ksize, return_lse=True)
+    b2 = bias.copy(); b2[1] += 3.7
+    _, lse_b = oracle.fwd(q, k, v, wkm, wvm, b2, heads, ksize, return_lse=True)
+    np.testing.assert_allclose(lse_b[:, 0], lse_a[:, 0], rtol=0, atol=1e-13)
+    np.testing.assert_allclose(lse_b[:, 1], lse_a[:, 1] + 3.7, rtol=0, atol=1e-12)
+    # ksize 1: a single logit, lse is that logit: scale * sum_c q[c] (1 + wk[c]) k[c] + bias
+    q1, k1, v1, _, wk1, wv1, bias1 = rand_problem(2, 3, 4, 4, 2, 1, seed=23)
+    _, lse1 = oracle.fwd(q1, k1, v1, oracle.reparam(wk1, 1), oracle.reparam(wv1, 1), bias1, 2, 1, return_lse=True)
+    prod = q1 * k1 * (1.0 + wk1[:, 0, 0, 0])[None, :, None, None]
+    expect = prod.reshape(2, 2, 2, 3, 4).sum(2) / math.sqrt(2.0) + bias1[:, 0][None, :, None, None]
+    np.testing.assert_allclose(lse1, expect, rtol=0, atol=1e-13)
+
+
 def test_sampled_forward_equals_full_forward():
     B, H, W, C, heads, ksize = 2, 4, 5, 4, 2, 3
     q, k, v, _, wk, wv, bias = rand_problem(B, H, W, C, heads, ksize, seed=10)
