@@ -71,30 +71,39 @@ size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int heads, int ksi
  * slide_reparam), float32 [C,S,ksize,ksize].  bias: float32 [heads,S] or NULL
  * (= zero).  out is overwritten and must not alias an input.  The k*k-fold
  * shifted tensors are never written to memory.
+ * lse: float32 [B,heads,H,W] or NULL.  When given it receives, per pixel and head,
+ * the natural logarithm of the softmax denominator of Eq. 2, log sum_s exp(l[m,s]),
+ * so that a[s] = exp(l[m,s] - lse); NULL skips it at no cost.
  * workspace: device scratch of at least slide_attn_workspace_bytes(..., 0) bytes
  * (may be NULL when that is 0); contents are undefined afterwards.
  */
 int slide_attn_fwd(const void* q, const void* k, const void* v,
                    const float* wk, const float* wv, const float* bias,
-                   void* out,
+                   void* out, float* lse,
                    int B, int H, int W, int C, int heads, int ksize, int dtype,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Backward of slide_attn_fwd (chain rule through the definition above; the
- * attention weights are recomputed, nothing is saved by the forward):
+ * attention weights are recomputed from q and k):
  *     dq, dk, dv : [B,C,H,W] of `dtype`   (overwritten)
  *     dwk, dwv   : float32 [C,S,ksize,ksize] (overwritten; gradient with respect
  *                  to the merged kernel, which equals the gradient with respect
  *                  to the learned kernel)
  *     dbias      : float32 [heads,S] (overwritten; may be NULL if bias is NULL)
  * dout is the gradient of the loss with respect to `out`, same layout and dtype.
+ * out, lse: the forward's results for the same inputs, or NULL.  They are optional
+ * so that a caller that kept them can hand them over; this library recomputes the
+ * attention weights from q and k in either case (the recomputation costs less than
+ * reading them back), checks the two pointers for alignment only and never reads
+ * through them.
  * Parameter gradients are accumulated in float32 in a fixed order (results are
  * reproducible run to run).
  * workspace: at least slide_attn_workspace_bytes(..., 1) bytes of device scratch.
  */
 int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
                    const float* wk, const float* wv, const float* bias,
+                   const void* out, const float* lse,
                    void* dq, void* dk, void* dv,
                    float* dwk, float* dwv, float* dbias,
                    int B, int H, int W, int C, int heads, int ksize, int dtype,

@@ -45,9 +45,9 @@ def load_library():
     lib.slide_attn_fwd_path.restype = i
     lib.slide_attn_fwd_path.argtypes = [i] * 7
     lib.slide_attn_fwd.restype = i
-    lib.slide_attn_fwd.argtypes = [_vp] * 7 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_bwd.restype = i
-    lib.slide_attn_bwd.argtypes = [_vp] * 13 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_bwd.argtypes = [_vp] * 15 + [i] * 7 + [_vp, sz, _vp]
     _lib = lib
     return lib
 
@@ -108,8 +108,11 @@ def slide_reparam(w_learned, w_merged=None):
     return w_merged
 
 
-def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None):
-    """out = slide attention of (q, k, v) with MERGED kernels wk, wv and per-head bias."""
+def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None, lse=None):
+    """out = slide attention of (q, k, v) with MERGED kernels wk, wv and per-head bias.
+
+    lse: optional float32 [B, heads, H, W] tensor that receives the log of the softmax
+    denominator per pixel and head."""
     lib = load_library()
     B, C, H, W = q.shape
     code = _dtype_code(q)
@@ -118,6 +121,8 @@ def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None
             raise SlideAttnError("%s must match q in shape and dtype" % n)
     if out is None:
         out = torch.empty_like(q)
+    if lse is not None and tuple(lse.shape) != (B, heads, H, W):
+        raise SlideAttnError("lse must be [B, heads, H, W]")
     need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 0)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -126,12 +131,16 @@ def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None
     _check(lib.slide_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
                               _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
                               _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
+                              _dev(lse, "lse", torch.float32),
                               B, H, W, C, heads, ksize, code, ws_ptr, ws_bytes, _stream()))
     return out
 
 
-def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, outputs=None):
-    """Returns (dq, dk, dv, dwk, dwv, dbias); dbias is None when bias is None."""
+def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, outputs=None,
+                   out=None, lse=None):
+    """Returns (dq, dk, dv, dwk, dwv, dbias); dbias is None when bias is None.
+
+    out, lse: the forward's results, if the caller kept them (optional; passed through)."""
     lib = load_library()
     B, C, H, W = q.shape
     code = _dtype_code(q)
@@ -150,6 +159,7 @@ def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, ou
     _check(lib.slide_attn_bwd(_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
                               _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
                               _dev(bias, "bias", torch.float32),
+                              _dev(out, "out", q.dtype), _dev(lse, "lse", torch.float32),
                               _dev(dq, "dq", q.dtype), _dev(dk, "dk", q.dtype), _dev(dv, "dv", q.dtype),
                               _dev(dwk, "dwk", torch.float32), _dev(dwv, "dwv", torch.float32),
                               _dev(dbias, "dbias", torch.float32),

@@ -61,6 +61,7 @@ extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ks
 
 extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
                               const float* wk, const float* wv, const float* bias, void* out,
+                              float* lse,
                               int B, int H, int W, int C, int heads, int ksize, int dtype,
                               void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -69,25 +70,26 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
     if (!q || !k || !v || !wk || !wv || !out) return SLIDE_ERR_NULL;
     const size_t esz = dtype == SLIDE_F32 ? 4 : 2;
     if (!aligned_to(q, esz) || !aligned_to(k, esz) || !aligned_to(v, esz) || !aligned_to(out, esz) ||
-        !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4))
+        !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(lse, 4))
         return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, ksize, dtype};
     hipError_t e;
     if (slide::fwd_mfma_supported(p)) {
         if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
-        e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, workspace, (hipStream_t)stream);
+        e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
     } else if (slide::fwd_mfma5_supported(p)) {
         if (!workspace || workspace_bytes < slide::fwd_mfma5_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
-        e = slide::launch_fwd_mfma5(p, q, k, v, wk, wv, bias, out, workspace, (hipStream_t)stream);
+        e = slide::launch_fwd_mfma5(p, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
     } else
-        e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, (hipStream_t)stream);
+        e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, lse, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }
 
 extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
                               const float* wk, const float* wv, const float* bias,
+                              const void* out, const float* lse,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               int B, int H, int W, int C, int heads, int ksize, int dtype,
                               void* workspace, size_t workspace_bytes, void* stream)
@@ -97,11 +99,12 @@ extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, co
     if (!dout || !q || !k || !v || !wk || !wv || !dq || !dk || !dv || !dwk || !dwv) return SLIDE_ERR_NULL;
     if (bias && !dbias) return SLIDE_ERR_NULL;
     const size_t esz = dtype == SLIDE_F32 ? 4 : 2;
-    const void* acts[] = {dout, q, k, v, dq, dk, dv};
+    // out and lse are optional and not read: the attention weights are recomputed from q and k
+    const void* acts[] = {dout, q, k, v, dq, dk, dv, out};
     for (const void* a : acts)
         if (!aligned_to(a, esz)) return SLIDE_ERR_ALIGN;
     if (!aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(dwk, 4) ||
-        !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 4))
+        !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 4) || !aligned_to(lse, 4))
         return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, ksize, dtype};
     if (!workspace || workspace_bytes < slide::bwd_generic_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;

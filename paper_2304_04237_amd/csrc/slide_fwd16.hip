@@ -122,6 +122,7 @@ prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
 
 struct FwdArgs {
     const bf16_bits* q; const bf16_bits* k; const bf16_bits* v; bf16_bits* out;
+    float* lse;              // [B, heads, H, W] log of the softmax denominator, or null
     const uint32_t* image;   // per-head MFMA operand images (one-tile-per-block kernel)
     const float* wk; const float* wv; const float* bias;   // merged kernels (pipelined kernel)
     TileGrid g;
@@ -143,11 +144,15 @@ __device__ __forceinline__ void q_halves(const uint32_t (&qraw)[8], half2_t (&qs
 
 // The arithmetic of one pass: 16 pixels, lane = (pixel p, channel group g); (ti, tj) is the
 // lane's pixel inside the tile, qs its 8 q channels as halves, already divided by 16.
-// Returns the 8 output channels in o.
+// Returns the 8 output channels in o.  With LSE, lanes whose lse_dst is not null also store
+// the natural logarithm of their pixel's softmax denominator there (as soon as it is known,
+// so that nothing of it stays live through the V side).
+template <bool LSE>
 __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int VD,
                                            int ti, int tj, int g, const half2_t (&qs)[4],
                                            const half8_t (&A1)[S], const half4_t (&A2)[2 * S],
-                                           const float (&bias2)[3], float scale_log2e, float (&o)[8])
+                                           const float (&bias2)[3], float scale_log2e, float (&o)[8],
+                                           float* lse_dst)
 {
     // halo row stride RS bytes; the V pixel sits VD bytes after the K pixel.  With both known
     // at compile time every tap address is one of three registers plus an immediate.
@@ -181,7 +186,9 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int 
     float pr[3];
 #pragma unroll
     for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
-    const float inv = __builtin_amdgcn_rcpf(allsum_groups(pr[0] + pr[1] + pr[2]));
+    const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
+    const float inv = __builtin_amdgcn_rcpf(den);
+    if (LSE && lse_dst) *lse_dst = LN2 * (mx + __builtin_amdgcn_logf(den));
     uint2_t b2;
     b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
     b2[1] = pack_half(pr[2] * inv, 0.0f);
@@ -309,7 +316,9 @@ fwd16_kernel(const FwdArgs a)
         float o[8];
         half2_t qs[4];
         q_halves(qraw, qs);
-        slide_pass(smem, HC * 64, a.g.v_off, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o);
+        float* lse_dst = (a.lse && valid && g == 0)
+            ? a.lse + tcur.head_base / D + (long)(tcur.i0 + ti) * a.g.W + tcur.j0 + tj : nullptr;
+        slide_pass<true>(smem, HC * 64, a.g.v_off, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o, lse_dst);
         if (valid) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -335,7 +344,7 @@ fwd16_kernel(const FwdArgs a)
 // Tile buffer of this kernel: halo row hr = [K pixels HC x 64 B][V pixels HC x 64 B], pixel
 // = 32 channels as halves with the 16-byte channel octets swizzled as in col_offset().
 // TW is the tile width when known at compile time (then tap addresses need no arithmetic),
-// 0 = read it from the arguments.
+// 0 = read it from the arguments.  LSE: also write the log of the softmax denominator.
 constexpr int PIPE_WAVES = 8;
 
 // Staging unit ("share") n of a tile: wave-sized group hb = n / 64 handles tensor hb & 1;
@@ -452,7 +461,7 @@ __device__ __forceinline__ void build_image(const float* __restrict__ wk, const 
     if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
 }
 
-template <int TW>
+template <int TW, bool LSE>
 __global__ void __launch_bounds__(PIPE_WAVES * 64, 2)
 fwd16_pipe_kernel(const FwdArgs a)
 {
@@ -567,7 +576,10 @@ fwd16_pipe_kernel(const FwdArgs a)
             float o[8];
             half2_t qs[4];
             q_halves(qraw, qs);
-            slide_pass(buf, 2 * HC * 64, HC * 64, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o);
+            float* lse_dst = nullptr;
+            if (LSE && g == 0 && pass * 16 + p < npix)
+                lse_dst = a.lse + tcur.head_base / D + (long)(tcur.i0 + ti) * a.g.W + tcur.j0 + tj;
+            slide_pass<LSE>(buf, 2 * HC * 64, HC * 64, ti, tj, g, qs, A1, A2, bias2, a.scale_log2e, o, lse_dst);
 
             // results -> 16-byte segments through the scratch
             __builtin_amdgcn_wave_barrier();
@@ -628,7 +640,7 @@ size_t fwd_mfma_workspace_bytes(const Problem& p)
 
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
-                           void* workspace, hipStream_t st)
+                           float* lse, void* workspace, hipStream_t st)
 {
     using namespace f16path;
     // the pipelined kernel needs 16-byte aligned rows everywhere and enough tiles per block
@@ -644,7 +656,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
                            wk, wv, bias, image);
     FwdArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
-    a.out = (bf16_bits*)out; a.image = image;
+    a.out = (bf16_bits*)out; a.lse = lse; a.image = image;
     a.wk = wk; a.wv = wv; a.bias = bias;
     fill_grid(a.g, p, t, k, v);
     a.g.small_first = pipelined;
@@ -656,8 +668,9 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
         hipError_t e = hipFuncSetAttribute((const void*)fwd16_kernel<FWD_WAVES>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
         if (e != hipSuccess) return e;
-        const void* pipes[3] = {(const void*)fwd16_pipe_kernel<0>, (const void*)fwd16_pipe_kernel<56>,
-                                (const void*)fwd16_pipe_kernel<64>};
+        const void* pipes[6] = {(const void*)fwd16_pipe_kernel<0, false>, (const void*)fwd16_pipe_kernel<56, false>,
+                                (const void*)fwd16_pipe_kernel<64, false>, (const void*)fwd16_pipe_kernel<0, true>,
+                                (const void*)fwd16_pipe_kernel<56, true>, (const void*)fwd16_pipe_kernel<64, true>};
         for (const void* f : pipes) {
             e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
             if (e != hipSuccess) return e;
@@ -668,9 +681,15 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     if (pipelined) {
         const int lds_bytes = a.a_base + PIPE_WAVES * WAVE_SCRATCH;
         const dim3 grid(NUM_CU), block(PIPE_WAVES * 64);
-        if (t.tw == 56)      hipLaunchKernelGGL((fwd16_pipe_kernel<56>), grid, block, (size_t)lds_bytes, st, a);
-        else if (t.tw == 64) hipLaunchKernelGGL((fwd16_pipe_kernel<64>), grid, block, (size_t)lds_bytes, st, a);
-        else                 hipLaunchKernelGGL((fwd16_pipe_kernel<0>), grid, block, (size_t)lds_bytes, st, a);
+#define SLIDE_PIPE(TWV)                                                                                      \
+        do {                                                                                                 \
+            if (lse) hipLaunchKernelGGL((fwd16_pipe_kernel<TWV, true>), grid, block, (size_t)lds_bytes, st, a);  \
+            else     hipLaunchKernelGGL((fwd16_pipe_kernel<TWV, false>), grid, block, (size_t)lds_bytes, st, a); \
+        } while (0)
+        if (t.tw == 56)      SLIDE_PIPE(56);
+        else if (t.tw == 64) SLIDE_PIPE(64);
+        else                 SLIDE_PIPE(0);
+#undef SLIDE_PIPE
     } else {
         const int lds_bytes = a.a_base + FWD_WAVES * WAVE_SCRATCH;
         hipLaunchKernelGGL(fwd16_kernel<FWD_WAVES>, dim3((unsigned)n_tiles), dim3(FWD_WAVES * 64),

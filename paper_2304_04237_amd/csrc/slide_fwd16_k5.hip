@@ -94,6 +94,7 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
 
 struct Fwd5Args {
     const bf16_bits* q; const bf16_bits* k; const bf16_bits* v; bf16_bits* out;
+    float* lse;              // [B, heads, H, W] log of the softmax denominator, or null
     const uint32_t* image;
     TileGrid g;
     int w_base;              // byte offset of the operand image in LDS
@@ -222,7 +223,11 @@ fwd16_k5_kernel(const Fwd5Args a)
             float sum = 0.0f;
 #pragma unroll
             for (int r = 0; r < 7; ++r) { pr[r] = __builtin_amdgcn_exp2f(l[r] - mx); sum += pr[r]; }
-            const float inv = __builtin_amdgcn_rcpf(allsum_groups(sum));
+            const float den = allsum_groups(sum);
+            const float inv = __builtin_amdgcn_rcpf(den);
+            if (a.lse && valid && g == 0)
+                a.lse[tcur.head_base / D + (long)(tcur.i0 + ti) * a.g.W + tcur.j0 + tj] =
+                    LN2 * (mx + __builtin_amdgcn_logf(den));
 #pragma unroll
             for (int r = 0; r < 7; ++r) pr[r] *= inv;
             uint4_t b2;
@@ -296,7 +301,7 @@ size_t fwd_mfma5_workspace_bytes(const Problem& p)
 
 hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, const void* v,
                             const float* wk, const float* wv, const float* bias, void* out,
-                            void* workspace, hipStream_t st)
+                            float* lse, void* workspace, hipStream_t st)
 {
     using namespace f16k5;
     const TilePlan t = plan_tiles(p, TILE_BUDGET, 64, 64);
@@ -305,7 +310,7 @@ hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, cons
                        wk, wv, bias, image);
     Fwd5Args a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
-    a.out = (bf16_bits*)out; a.image = image;
+    a.out = (bf16_bits*)out; a.lse = lse; a.image = image;
     fill_grid(a.g, p, t, k, v);
     a.w_base = t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);

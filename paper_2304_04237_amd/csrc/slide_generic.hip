@@ -76,13 +76,14 @@ __device__ __forceinline__ void apply_kernels(const float* __restrict__ w_c,
     }
 }
 
-// logits over the S shifts for one pixel of one head, then softmax in place
+// logits over the S shifts for one pixel of one head, then softmax in place; lse receives
+// the log of the softmax denominator, log sum_s exp(logit[s])
 template <typename T, int KS>
 __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const T* __restrict__ k,
                                                   const float* __restrict__ wk,
                                                   const float* __restrict__ bias,
                                                   int b, int m, int i, int j, int H, int W, int C,
-                                                  int d, float (&a)[KS * KS])
+                                                  int d, float (&a)[KS * KS], float& lse)
 {
     constexpr int S = KS * KS;
     const long HW = (long)H * W;
@@ -111,6 +112,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
 #pragma unroll
     for (int s = 0; s < S; ++s) { a[s] = expf(a[s] - mx); den += a[s]; }
     float inv = 1.0f / den;
+    lse = mx + logf(den);
 #pragma unroll
     for (int s = 0; s < S; ++s) a[s] *= inv;
 }
@@ -120,7 +122,7 @@ template <typename T, int KS>
 __global__ void __launch_bounds__(256)
 fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                    const float* __restrict__ wk, const float* __restrict__ wv,
-                   const float* __restrict__ bias, T* __restrict__ out,
+                   const float* __restrict__ bias, T* __restrict__ out, float* __restrict__ lse,
                    int H, int W, int C, int heads)
 {
     constexpr int S = KS * KS;
@@ -131,8 +133,9 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
     if (pix >= HW) return;
     const int i = (int)(pix / W), j = (int)(pix % W);
 
-    float a[S];
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a);
+    float a[S], lse_px;
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a, lse_px);
+    if (lse) lse[((long)b * heads + m) * HW + pix] = lse_px;
 
     for (int cc = 0; cc < d; ++cc) {
         int c = m * d + cc;
@@ -150,11 +153,11 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
 template <typename T, int KS>
 static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, const void* v,
                                const float* wk, const float* wv, const float* bias, void* out,
-                               hipStream_t st)
+                               float* lse, hipStream_t st)
 {
     dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
     hipLaunchKernelGGL((fwd_generic_kernel<T, KS>), grid, dim3(256), 0, st,
-                       (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out,
+                       (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
                        p.H, p.W, p.C, p.heads);
     return hipGetLastError();
 }
@@ -181,9 +184,9 @@ static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, c
 
 hipError_t launch_fwd_generic(const Problem& p, const void* q, const void* k, const void* v,
                               const float* wk, const float* wv, const float* bias, void* out,
-                              hipStream_t st)
+                              float* lse, hipStream_t st)
 {
-    SLIDE_DISPATCH(launch_fwd_t, p, q, k, v, wk, wv, bias, out, st);
+    SLIDE_DISPATCH(launch_fwd_t, p, q, k, v, wk, wv, bias, out, lse, st);
 }
 
 // ------------------------------------------------------------------ backward
@@ -207,8 +210,8 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
     if (pix >= HW) return;
     const int i = (int)(pix / W), j = (int)(pix % W);
 
-    float a[S];
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a);
+    float a[S], lse_px;
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a, lse_px);
 
     float da[S];
 #pragma unroll

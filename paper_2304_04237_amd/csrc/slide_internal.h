@@ -18,7 +18,7 @@ struct Problem {
 hipError_t launch_reparam(const float* w_learned, float* w_merged, int C, int ksize, hipStream_t st);
 hipError_t launch_fwd_generic(const Problem& p, const void* q, const void* k, const void* v,
                               const float* wk, const float* wv, const float* bias, void* out,
-                              hipStream_t st);
+                              float* lse, hipStream_t st);
 size_t bwd_generic_workspace_bytes(const Problem& p);
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,
                               const void* v, const float* wk, const float* wv, const float* bias,
@@ -52,13 +52,13 @@ bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
-                           void* workspace, hipStream_t st);
+                           float* lse, void* workspace, hipStream_t st);
 
 // ---- matrix-core forward, 5x5 window (slide_fwd16_k5.hip): bf16, d == 32, ksize 5
 bool fwd_mfma5_supported(const Problem& p);
 size_t fwd_mfma5_workspace_bytes(const Problem& p);
 hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, const void* v,
                             const float* wk, const float* wv, const float* bias, void* out,
-                            void* workspace, hipStream_t st);
+                            float* lse, void* workspace, hipStream_t st);
 
 }  // namespace slide

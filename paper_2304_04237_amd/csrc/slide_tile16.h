@@ -23,6 +23,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t uint4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
 
 constexpr int KS = 3, S = 9, D = 32;
+constexpr float LN2 = 0.693147180559945309f;
 
 
 // MFMA row 4g+r of the logit tile <-> shift index.  Rows are spread so that each lane

@@ -48,10 +48,10 @@ def test_status_strings(lib):
 FWD_OK = dict(B=1, H=14, W=14, C=64, heads=2, ksize=3, dtype=0)
 
 
-def call_fwd(lib, ptr=0x1000, **kw):
+def call_fwd(lib, ptr=0x1000, lse=None, **kw):
     a = dict(FWD_OK); a.update(kw)
     p = ctypes.c_void_p(ptr)
-    return lib.slide_attn_fwd(p, p, p, p, p, p, p, a["B"], a["H"], a["W"], a["C"], a["heads"],
+    return lib.slide_attn_fwd(p, p, p, p, p, p, p, lse, a["B"], a["H"], a["W"], a["C"], a["heads"],
                               a["ksize"], a["dtype"], None, 0, None)
 
 
@@ -67,20 +67,27 @@ def test_forward_rejects_bad_arguments_on_the_host(lib):
     assert call_fwd(lib, ptr=0) == 1               # NULL pointers
     assert call_fwd(lib, ptr=0x1002) == 6          # misaligned for float32
     assert call_fwd(lib, ptr=0x1001, dtype=1) == 6 # misaligned for bfloat16
+    assert call_fwd(lib, heads=3, lse=ctypes.c_void_p(0x1000)) == 2   # lse given: same checks
+    assert call_fwd(lib, lse=ctypes.c_void_p(0x1002)) == 6            # lse not 4-byte aligned
 
 
 def test_backward_rejects_bad_arguments_on_the_host(lib):
     p = ctypes.c_void_p(0x1000)
-    args13 = [p] * 13
+    # dout q k v wk wv bias | out lse (optional) | dq dk dv dwk dwv dbias
+    args13 = [p] * 7 + [None, None] + [p] * 6
     shape = [1, 14, 14, 64, 2, 3, 0]
     need = lib.slide_attn_workspace_bytes(*shape, 1)
     assert need > 0
     assert lib.slide_attn_bwd(*args13, *shape, None, 0, None) == 4            # no workspace
     assert lib.slide_attn_bwd(*args13, *shape, p, need - 1, None) == 4        # too small
-    bad = list(args13); bad[9] = None
+    bad = list(args13); bad[11] = None
     assert lib.slide_attn_bwd(*bad, *shape, p, need, None) == 1               # dv NULL
-    bad = list(args13); bad[12] = None
+    bad = list(args13); bad[14] = None
     assert lib.slide_attn_bwd(*bad, *shape, p, need, None) == 1               # bias without dbias
+    given = list(args13); given[7] = p; given[8] = ctypes.c_void_p(0x1002)
+    assert lib.slide_attn_bwd(*given, *shape, p, need, None) == 6             # lse given but misaligned
+    given[7] = ctypes.c_void_p(0x1002); given[8] = p
+    assert lib.slide_attn_bwd(*given, *shape, p, need, None) == 6             # out given but misaligned
     shape_bad = [1, 14, 14, 64, 5, 3, 0]
     assert lib.slide_attn_bwd(*args13, *shape_bad, p, need, None) == 2
 
@@ -108,4 +115,4 @@ def test_forward_path_selection(lib):
     assert lib.slide_attn_workspace_bytes(64, 56, 56, 64, 2, 3, 1, 0) > 0
     p = ctypes.c_void_p(0x1000)
     # the matrix-core forward needs its workspace
-    assert lib.slide_attn_fwd(p, p, p, p, p, p, p, 64, 56, 56, 64, 2, 3, 1, None, 0, None) == 4
+    assert lib.slide_attn_fwd(p, p, p, p, p, p, p, None, 64, 56, 56, 64, 2, 3, 1, None, 0, None) == 4

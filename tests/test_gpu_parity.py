@@ -3,7 +3,7 @@ element by element on the same seeded inputs.
 
 Tolerances (written here, from the problem statement):
   float32 : max|x - o| <= 1e-5 * max|o|                       per tensor
-  bfloat16: max|x - o| <= 2e-2                                out, dq, dk, dv
+  bfloat16: max|x - o| <= 2e-2                                out, lse, dq, dk, dv
             max|x - o| <= 2e-2 * max(1, max|o|)               dwk, dwv, dbias
 The oracle receives the inputs already rounded to the storage dtype, so both
 sides see identical values.
@@ -105,6 +105,12 @@ def test_forward_matches_oracle(shape):
     out0 = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], None, heads, ksize)
     ref0 = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], None, heads, ksize)
     check("out(no bias)", dtype, out0, ref0)
+    # with the log of the softmax denominator as a second result: out is unchanged
+    lse = torch.full((B, heads, H, W), float("nan"), dtype=torch.float32, device=out.device)
+    out1 = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize, lse=lse)
+    assert torch.equal(out1, out)
+    _, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, ksize, return_lse=True)
+    check("lse", dtype, lse, ref_lse)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -179,6 +185,13 @@ def test_backward_matches_oracle(shape):
     again = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize)
     for a, b in zip(grads, again):
         assert torch.equal(a, b)
+    # a caller that kept the forward's results may pass them: same gradients
+    lse = torch.empty((B, heads, H, W), dtype=torch.float32, device=g["q"].device)
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize, lse=lse)
+    kept = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize,
+                             out=out, lse=lse)
+    for a, b in zip(grads, kept):
+        assert torch.equal(a, b)
 
 
 def test_forward_unaligned_parameters_and_activations():
@@ -247,13 +260,21 @@ def test_forward_full_size_configs_sampled(index):
     got = np.stack([out[b, m * dd:(m + 1) * dd, i, j] for b, m, i, j in pos])
     err = np.abs(got - ref).max()
     assert err <= 2e-2, err
+    # the same launch with the log of the softmax denominator as a second result
+    lse = torch.full((wl.B, wl.heads, wl.H, wl.W), float("nan"), dtype=torch.float32, device=dev)
+    out_l = sa.slide_attn_fwd(q, k, v, wk, wv, bias, wl.heads, wl.ksize, lse=lse)
+    torch.cuda.synchronize()
+    assert np.array_equal(out_l.float().cpu().numpy(), out)
+    lse = lse.cpu().numpy()
+    assert np.isfinite(lse).all()
     # whole planes of the first and last batch item, element by element
     for b in (0, wl.B - 1):
         sl = slice(b, b + 1)
-        refp = oracle.fwd(d["q"][sl].numpy(), d["k"][sl].numpy(), d["v"][sl].numpy(),
-                          wk.double().cpu().numpy(), wv.double().cpu().numpy(),
-                          d["bias"].double().numpy(), wl.heads, wl.ksize)
+        refp, ref_lse = oracle.fwd(d["q"][sl].numpy(), d["k"][sl].numpy(), d["v"][sl].numpy(),
+                                   wk.double().cpu().numpy(), wv.double().cpu().numpy(),
+                                   d["bias"].double().numpy(), wl.heads, wl.ksize, return_lse=True)
         assert np.abs(out[sl] - refp).max() <= 2e-2
+        assert np.abs(lse[sl] - ref_lse).max() <= 2e-2
 
 
 def test_training_config_full_size():
