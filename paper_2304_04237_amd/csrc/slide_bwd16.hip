@@ -3,7 +3,7 @@
 //
 // The paper gives no backward; this is the chain rule through the operator of Sec. 4.1-4.3.
 // With a the attention weights and dl the logit gradients of a pixel (both produced by the
-// per-pixel backward kernel, float32 [B, heads, 9, H, W]) the deformed shift is a depthwise
+// per-pixel backward kernel, [B, heads, 9, H, W] as halves or float32) the deformed shift is a depthwise
 // cross-correlation, so its transpose gathers, for a target pixel y, from the 9 source
 // pixels p' = y - off(t) that see y through tap t:
 //     dk[c,y] = scale * sum_t q[c,p']  * ( dl[p',t] + sum_s wl_k[c,s,t] dl[p',s] )
@@ -53,7 +53,7 @@ prep_dkdv_weights_kernel(const float* __restrict__ wk, const float* __restrict__
 
 struct DkdvArgs {
     const bf16_bits* q; const bf16_bits* dout;
-    const float* attn; const float* dl;       // [B, heads, 9, H, W]
+    const void* attn; const void* dl;         // [B, heads, 9, H, W], float32 or half (HALF_WS)
     bf16_bits* dk; bf16_bits* dv;
     const uint32_t* image;
     TileGrid g;                               // first staged tensor q, second dO
@@ -70,6 +70,19 @@ __device__ __forceinline__ void make_record(const float (&x)[S], uint4_t& lo, ui
     hi[2] = pack_half(x[3], x[7]);  hi[3] = 0u;                      // slots 12..15
 }
 
+// the same record from values that are halves already
+__device__ __forceinline__ void make_record(const _Float16 (&x)[S], uint4_t& lo, uint4_t& hi)
+{
+    const _Float16 z = (_Float16)0.0f;
+    lo[0] = as_dword(half2_t{x[0], x[4]});  lo[1] = as_dword(half2_t{x[8], z});
+    lo[2] = as_dword(half2_t{x[1], x[5]});  lo[3] = 0u;
+    hi[0] = as_dword(half2_t{x[2], x[6]});  hi[1] = 0u;
+    hi[2] = as_dword(half2_t{x[3], x[7]});  hi[3] = 0u;
+}
+
+// HALF_WS: a and dl come as halves (written so by the per-pixel kernel when every kernel of
+// the backward is a matrix-core one), else as float32.
+template <bool HALF_WS>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_dkdv_kernel16(const DkdvArgs a)
 {
@@ -109,16 +122,30 @@ bwd_dkdv_kernel16(const DkdvArgs a)
             const int tsel = idx >= n_px, id = idx - tsel * n_px;
             const int hr = (int)(((float)id + 0.5f) * inv_hc), hc = id - hr * hcols;
             const int gi = tcur.i0 - 1 + hr, gj = tcur.j0 - 1 + hc;
-            float x[S];
-#pragma unroll
-            for (int s = 0; s < S; ++s) x[s] = 0.0f;
-            if (gi >= 0 && gi < a.g.H && gj >= 0 && gj < a.g.W) {
-                const float* src = (tsel ? a.attn : a.dl) + plane_ws + (long)gi * a.g.W + gj;
-#pragma unroll
-                for (int s = 0; s < S; ++s) x[s] = src[(long)s * HW];
-            }
+            const bool inside = gi >= 0 && gi < a.g.H && gj >= 0 && gj < a.g.W;
+            const long at = plane_ws + (long)gi * a.g.W + gj;
             uint4_t lo, hi;
-            make_record(x, lo, hi);
+            if (HALF_WS) {
+                _Float16 x[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) x[s] = (_Float16)0.0f;
+                if (inside) {
+                    const _Float16* src = (const _Float16*)(tsel ? a.attn : a.dl) + at;
+#pragma unroll
+                    for (int s = 0; s < S; ++s) x[s] = src[(long)s * HW];
+                }
+                make_record(x, lo, hi);
+            } else {
+                float x[S];
+#pragma unroll
+                for (int s = 0; s < S; ++s) x[s] = 0.0f;
+                if (inside) {
+                    const float* src = (const float*)(tsel ? a.attn : a.dl) + at;
+#pragma unroll
+                    for (int s = 0; s < S; ++s) x[s] = src[(long)s * HW];
+                }
+                make_record(x, lo, hi);
+            }
             unsigned char* dst = smem + (tsel ? a.rec_a : a.rec_dl) + (hr * HC + hc) * REC_BYTES;
             *(uint4_t*)dst = lo;
             *(uint4_t*)(dst + 16) = hi;
@@ -212,7 +239,9 @@ bwd_dkdv_kernel16(const DkdvArgs a)
 //     da[s] = sum_c dO[c] Vs[c,s]        (same shape as the logits, with dO, v, wv)
 //     dl[s] = a[s] (da[s] - sum_s' a[s'] da[s'])
 //     dq[c] = scale * sum_t k[c,p+t] * sum_s dl[s] W~k[c,s,t]            (same shape as out)
-// a and dl go to the workspace as float32 [B, heads, 9, H, W] for the other two kernels.
+// a and dl go to the workspace as [B, heads, 9, H, W] for the other two kernels: as halves
+// when both of them are matrix-core kernels (which feed them to the matrix cores as halves
+// anyway), as float32 when a general kernel reads them.
 //
 // Per-head operand image (dwords): A1k [0,2304): merged K kernel (times 16), tap t x lane x 4;
 // A1v [2304,4608): merged V kernel (times 16), same arrangement; A2k [4608,6912): merged K
@@ -271,7 +300,7 @@ prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict_
 struct PixelArgs {
     const bf16_bits* dout; const bf16_bits* q; const bf16_bits* k; const bf16_bits* v;
     bf16_bits* dq;
-    float* attn; float* dl;                   // [B, heads, 9, H, W]
+    void* attn; void* dl;                     // [B, heads, 9, H, W], float32 or half (HALF_WS)
     const uint32_t* image;
     TileGrid g;                               // first staged tensor k, second v
     float scale, scale_log2e;
@@ -299,6 +328,7 @@ __device__ __forceinline__ void raw_to_halves(const uint32_t (&raw)[8], half2_t 
                 half2_t{(_Float16)G_SCALE, (_Float16)G_SCALE};
 }
 
+template <bool HALF_WS>
 __global__ void __launch_bounds__(THREADS, 2)
 bwd_pixel_kernel16(const PixelArgs a)
 {
@@ -431,8 +461,14 @@ bwd_pixel_kernel16(const PixelArgs a)
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
                 if (r < 2 || g == 0) {
-                    a.attn[wo + (long)(4 * r + g) * HW] = pr[r];
-                    a.dl[wo + (long)(4 * r + g) * HW] = dl[r];
+                    const long at = wo + (long)(4 * r + g) * HW;
+                    if (HALF_WS) {
+                        ((_Float16*)a.attn)[at] = (_Float16)pr[r];
+                        ((_Float16*)a.dl)[at] = (_Float16)dl[r];
+                    } else {
+                        ((float*)a.attn)[at] = pr[r];
+                        ((float*)a.dl)[at] = dl[r];
+                    }
                 }
             }
         }
@@ -497,7 +533,8 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p)
 
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
-                                 void* dq, float* attn_ws, float* dl_ws, void* image_ws, hipStream_t st)
+                                 void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
+                                 hipStream_t st)
 {
     using namespace b16path;
     const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
@@ -513,13 +550,17 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16,
+        hipError_t e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16<true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const unsigned grid = (unsigned)((long)t.TA + t.TB);
-    hipLaunchKernelGGL(bwd_pixel_kernel16, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
+    if (half_ws) hipLaunchKernelGGL(bwd_pixel_kernel16<true>, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
+    else         hipLaunchKernelGGL(bwd_pixel_kernel16<false>, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
     return hipGetLastError();
 }
 
@@ -537,7 +578,7 @@ size_t bwd_dkdv_mfma_image_bytes(const Problem& p)
 
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
-                                const float* attn_ws, const float* dl_ws,
+                                const void* attn_ws, const void* dl_ws, bool half_ws,
                                 void* dk, void* dv, void* image_ws, hipStream_t st)
 {
     using namespace b16path;
@@ -556,13 +597,17 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
     const int lds_bytes = t.buf_bytes + 2 * t.halo_px * REC_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16,
+        hipError_t e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16<false>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16<true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const unsigned grid = (unsigned)((long)t.TA + t.TB);
-    hipLaunchKernelGGL(bwd_dkdv_kernel16, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
+    if (half_ws) hipLaunchKernelGGL(bwd_dkdv_kernel16<true>, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
+    else         hipLaunchKernelGGL(bwd_dkdv_kernel16<false>, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
     return hipGetLastError();
 }
 

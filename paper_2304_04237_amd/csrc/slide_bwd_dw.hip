@@ -6,7 +6,7 @@
 //     dwv[c,s,t] =         sum_{b,p}  a[b,m,s,p] * dO[b,c,p] * v[b,c,p + off(t)]
 //     dbias[m,s] =         sum_{b,p} dl[b,m,s,p]
 // with a the attention weights, dl the logit gradients (both produced by the per-pixel
-// backward kernel as float32 [B, heads, 9, H, W]) and zero padding outside the map.
+// backward kernel as halves [B, heads, 9, H, W]) and zero padding outside the map.
 //
 // Per channel this is a (9 taps) x (9 shifts) matrix whose contraction index is the pixel,
 // so it runs as v_mfma_f32_16x16x32_f16 with K = 32 consecutive pixels of a row:
@@ -50,7 +50,7 @@ constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
 
 struct Args {
     const bf16_bits* dout; const bf16_bits* q; const bf16_bits* k; const bf16_bits* v;
-    const float* attn; const float* dl;       // [B, heads, 9, H, W]
+    const _Float16* attn; const _Float16* dl; // [B, heads, 9, H, W] as halves
     float* partial;                           // [NB][2][C][9][9]
     float* dbias_partial;                     // [NB][heads][9]
     int B, H, W, C, heads;
@@ -151,10 +151,10 @@ bwd_dw_kernel(const Args a)
     constexpr int N_KV = CPW * (R + 2) * 8, KV_SLOTS = (2 * N_KV + 63) / 64;        // 5
     constexpr int N_HC = CPW * (R + 2) * 2, HC_SLOTS = (2 * N_HC + 63) / 64;        // 2
     constexpr int N_Q = CPW * R * 8, Q_SLOTS = (2 * N_Q + 63) / 64;                 // 3
-    constexpr int N_D = S * R * 8, D_SLOTS = (2 * N_D + THREADS - 1) / THREADS;     // dl / a items: 8 floats each
+    constexpr int N_D = S * R * 8, D_SLOTS = (2 * N_D + THREADS - 1) / THREADS;     // dl / a items: 8 halves each
     uint4_t pre_kv[KV_SLOTS], pre_q[Q_SLOTS];
     uint32_t pre_hc[HC_SLOTS];
-    float4_t pre_d[D_SLOTS][2];
+    uint4_t pre_d[D_SLOTS];
 
     auto issue_loads = [&](const Unit& t) {
 #pragma unroll
@@ -199,10 +199,10 @@ bwd_dw_kernel(const Args a)
             const int tsel = idx >= N_D, id = idx - tsel * N_D;
             const int x = id & 7, rj = id >> 3;
             const int s = rj / R, r = rj - s * R;
-            pre_d[sl][0] = float4_t{0, 0, 0, 0}; pre_d[sl][1] = float4_t{0, 0, 0, 0};
+            pre_d[sl] = uint4_t{0u, 0u, 0u, 0u};
             if (idx < 2 * N_D && x < t.nxc && r < t.rows_eff) {
-                const float* src = (tsel ? a.attn : a.dl) + (((long)t.b * a.heads + m) * S + s) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
-                pre_d[sl][0] = *(const float4_t*)src; pre_d[sl][1] = *(const float4_t*)(src + 4);
+                const _Float16* src = (tsel ? a.attn : a.dl) + (((long)t.b * a.heads + m) * S + s) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
+                pre_d[sl] = *(const uint4_t*)src;
             }
         }
     };
@@ -247,13 +247,7 @@ bwd_dw_kernel(const Args a)
             const int tsel = idx >= N_D, id = idx - tsel * N_D;
             const int x = id & 7, rj = id >> 3;
             const int s = rj / R, r = rj - s * R;
-            uint4_t val;
-            half2_t h;
-            h = half2_t{(_Float16)pre_d[sl][0][0], (_Float16)pre_d[sl][0][1]}; val[0] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[sl][0][2], (_Float16)pre_d[sl][0][3]}; val[1] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[sl][1][0], (_Float16)pre_d[sl][1][1]}; val[2] = as_dword(h);
-            h = half2_t{(_Float16)pre_d[sl][1][2], (_Float16)pre_d[sl][1][3]}; val[3] = as_dword(h);
-            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * DP + 8 * x) * 2) = val;
+            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * DP + 8 * x) * 2) = pre_d[sl];
         }
     };
 
@@ -369,13 +363,13 @@ size_t bwd_dw_mfma_partial_floats(const Problem& p)
 }
 
 hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q, const void* k,
-                              const void* v, const float* attn_ws, const float* dl_ws,
+                              const void* v, const void* attn_ws, const void* dl_ws,
                               float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st)
 {
     using namespace dwpath;
     Args a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
-    a.attn = attn_ws; a.dl = dl_ws;
+    a.attn = (const _Float16*)attn_ws; a.dl = (const _Float16*)dl_ws;
     a.NB = blocks_per_head(p);
     a.partial = partial;
     a.dbias_partial = partial + (size_t)a.NB * 2 * p.C * 81;

@@ -475,9 +475,12 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     float* partial = dl_ws + per;
     dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
     const bool fast = bwd_dkdv_mfma_supported(p) && aligned16({dout, q, k, v, workspace});
+    // when all three kernels are matrix-core kernels a and dl cross the workspace as halves
+    // (in the first half of the same two regions)
+    const bool half_ws = fast && bwd_dw_mfma_supported(p);
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p) + bwd_dkdv_mfma_image_bytes(p);
-        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, image_ws, st);
+        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws, st);
         if (e != hipSuccess) return e;
     } else
         hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
@@ -485,13 +488,13 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
                            (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
-        hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, dk, dv, image_ws, st);
+        hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
         if (e != hipSuccess) return e;
     } else
         hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
                            (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
                            p.H, p.W, p.C, p.heads);
-    if (bwd_dw_mfma_supported(p) && aligned16({dout, q, k, v, workspace})) {
+    if (half_ws) {
         // kernel and bias gradients on the matrix cores
         return launch_bwd_dw_mfma(p, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias, st);
     }

@@ -32,7 +32,7 @@ hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, lo
 bool bwd_dw_mfma_supported(const Problem& p);
 size_t bwd_dw_mfma_partial_floats(const Problem& p);
 hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q, const void* k,
-                              const void* v, const float* attn_ws, const float* dl_ws,
+                              const void* v, const void* attn_ws, const void* dl_ws,   // halves
                               float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st);
 
 // ---- matrix-core key/value gradients (slide_bwd16.hip): bf16, d == 32, ksize 3
@@ -41,10 +41,11 @@ size_t bwd_dkdv_mfma_image_bytes(const Problem& p);
 size_t bwd_pixel_mfma_image_bytes(const Problem& p);
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
-                                 void* dq, float* attn_ws, float* dl_ws, void* image_ws, hipStream_t st);
+                                 void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
+                                 hipStream_t st);
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
-                                const float* attn_ws, const float* dl_ws,
+                                const void* attn_ws, const void* dl_ws, bool half_ws,
                                 void* dk, void* dv, void* image_ws, hipStream_t st);
 
 // ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
