@@ -12,6 +12,9 @@
 // so it runs as v_mfma_f32_16x16x32_f16 with K = 32 consecutive pixels of a row:
 //     A[t, p] = q[c,p] * k[c, p + off(t)]      (two packed multiplies per dword, from LDS)
 //     B[p, s] = dl[s, p]                        (shared by all channels of the head)
+// The 16 rows of one product hold the three taps of one window row for four channels (12
+// rows in use), so a wave's four channels take three products per 32 pixels and side, and
+// q (dO) of a row is read once for the three window rows.
 // Activations keep their natural layout (pixels contiguous), converted to half precision
 // once while they are staged in LDS; q and dO are divided by 16 there so that products up
 // to 2^20 stay finite, and the factor is restored with the final scale.  The tap windows
@@ -112,22 +115,25 @@ bwd_dw_kernel(const Args a)
     // zero all of LDS once: margins and the zero block stay zero for the whole kernel
     for (int o = tid * 16; o < LDS_BYTES; o += THREADS * 16) *(uint4_t*)(smem + o) = uint4_t{0u, 0u, 0u, 0u};
 
-    // per-lane read offsets that do not depend on the unit
-    const int ty = (i < S) ? i / 3 : 0, tx = (i < S) ? i - 3 * (i / 3) : 0;
+    // Rows of the products: one product covers one window row ty of this wave's four channels,
+    // row i < 12 = (channel cc = i / 3, window column tx = i % 3), i.e. tap t = 3 ty + tx; rows
+    // 12..15 are masked (zero q), except that row 12 of wave 0's first product sums dl.
+    constexpr int ROWS = 3 * CPW;
+    const int lcc = (i < ROWS) ? i / 3 : 0, tx = (i < ROWS) ? i - 3 * (i / 3) : 0;
     // The tap window of k (v) is the aligned 8-pixel run moved by tx-1 pixels.  It is read as
     // five aligned dwords starting one dword early (tx = 0) or at the run (tx = 1, 2) and funnel-
     // shifted by 16 bits for the odd offsets: misaligned 16-byte LDS reads stall the LDS pipe.
-    const int kwin_off = (ty * KP + 8 + 8 * g) * 2 - 4 + (tx >= 1 ? 4 : 0);   // + (cc*(R+2) + r)*KP*2 + 64*h
+    const int kwin_off = (((wave * CPW + lcc) * (R + 2)) * KP + 8 + 8 * g) * 2 - 4 + (tx >= 1 ? 4 : 0);   // + (ty + r)*KP*2 + 64*h
     const uint32_t win_shift = (tx == 1) ? 0u : 16u;
-    const int q_off = (i < S) ? (8 * g) * 2 : -1;                 // -1: masked row, read zeros
+    const int q_off = (i < ROWS) ? (((wave * CPW + lcc) * R) * QP + 8 * g) * 2 : -1;   // + r*QP*2 + 64*h; -1: masked row, read zeros
     const int b_off = (i < S) ? ((i * R) * DP + 8 * g) * 2 : -1;  // + r*DP*2 + 64*h
 
-    float4_t acc_k[CPW], acc_v[CPW];
+    float4_t acc_k[3], acc_v[3];                  // one accumulator per window row
 #pragma unroll
-    for (int cc = 0; cc < CPW; ++cc) { acc_k[cc] = float4_t{0, 0, 0, 0}; acc_v[cc] = float4_t{0, 0, 0, 0}; }
+    for (int ty = 0; ty < 3; ++ty) { acc_k[ty] = float4_t{0, 0, 0, 0}; acc_v[ty] = float4_t{0, 0, 0, 0}; }
     const half2_t one2 = {(_Float16)1.0f, (_Float16)1.0f};
     const half2_t in2 = {(_Float16)IN_SCALE, (_Float16)IN_SCALE};
-    const bool bias_lane = (wave == 0) && (i == S);               // row 9 of channel 0 sums dl
+    const bool bias_lane = (wave == 0) && (i == ROWS);            // row 12 of the first product sums dl
 
     const int n_units = a.B * a.n_strips * a.n_ct;
 
@@ -269,13 +275,13 @@ bwd_dw_kernel(const Args a)
                 const int a_addr = (b_off >= 0) ? OFF_A + b_off + r * DP * 2 + 64 * h : OFF_ZERO;
                 const half8_t Bdl = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + dl_addr));
                 const half8_t Ba = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + a_addr));
+                // q and dO of the row's channel: the same for the three window rows
+                const int qo = (q_off >= 0) ? q_off + r * QP * 2 + 64 * h : -1;
+                const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
+                const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
 #pragma unroll
-                for (int cc = 0; cc < CPW; ++cc) {
-                    const int ch = wave * CPW + cc;
-                    const int qo = (q_off >= 0) ? ((ch * R + r) * QP) * 2 + q_off + 64 * h : -1;
-                    const int ko = ((ch * (R + 2) + r) * KP) * 2 + kwin_off + 64 * h;
-                    const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
-                    const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
+                for (int ty = 0; ty < 3; ++ty) {
+                    const int ko = kwin_off + (ty + r) * KP * 2 + 64 * h;
                     uint32_t km[5], vm[5];
                     lds_read_2x5_dwords((uint32_t)(uintptr_t)(smem + OFF_K + ko),
                                         (uint32_t)(uintptr_t)(smem + OFF_V + ko), km, vm);
@@ -291,38 +297,39 @@ bwd_dw_kernel(const Args a)
                         ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[y]));
                         av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[y]));
                     }
-                    if (cc == 0 && wave == 0) {
+                    if (ty == 0 && wave == 0) {
 #pragma unroll
                         for (int y = 0; y < 4; ++y) ak[y] = bias_lane ? as_dword(one2) : ak[y];
                     }
-                    acc_k[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[cc], 0, 0, 0);
-                    acc_v[cc] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[cc], 0, 0, 0);
-                    if (cc & 1) __builtin_amdgcn_sched_barrier(0);   // keep two channels in flight, not four
+                    acc_k[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[ty], 0, 0, 0);
+                    acc_v[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[ty], 0, 0, 0);
+                    if (ty == 1) __builtin_amdgcn_sched_barrier(0);   // keep two products in flight, not three
                 }
             }
         }
     }
 
-    // ---- partial sums of this block.  Result register r of lane (n, g) is row t = 4g + r,
-    // column s = n of the 16x16 product.
+    // ---- partial sums of this block.  Result register r of lane (n, g) is row 4g + r =
+    // (channel, window column), column s = n of the 16x16 product of window row ty.
     const int n = i;
     const float out_scale = 1.0f / IN_SCALE;
     if (n < S) {
         const long side = (long)a.C * S * S;
         float* base = a.partial + (long)j * 2 * side;
 #pragma unroll
-        for (int cc = 0; cc < CPW; ++cc) {
+        for (int ty = 0; ty < 3; ++ty) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int t = 4 * g + r;
-                if (t < S) {
-                    base[((long)(c0 + cc) * S + n) * S + t] = acc_k[cc][r] * (a.scale * out_scale);
-                    base[side + ((long)(c0 + cc) * S + n) * S + t] = acc_v[cc][r] * out_scale;
+                const int row = 4 * g + r;
+                if (row < ROWS) {
+                    const int cc = row / 3, t = 3 * ty + row - 3 * cc;
+                    base[((long)(c0 + cc) * S + n) * S + t] = acc_k[ty][r] * (a.scale * out_scale);
+                    base[side + ((long)(c0 + cc) * S + n) * S + t] = acc_v[ty][r] * out_scale;
                 }
             }
         }
-        if (wave == 0 && g == 2)                                   // row 9 = 4*2 + 1
-            a.dbias_partial[((long)j * a.heads + m) * S + n] = acc_k[0][1];
+        if (wave == 0 && g == 3)                                   // row 12 = 4*3 + 0
+            a.dbias_partial[((long)j * a.heads + m) * S + n] = acc_k[0][0];
     }
 }
 
