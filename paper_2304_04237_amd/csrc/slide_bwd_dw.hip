@@ -18,7 +18,10 @@
 // Activations keep their natural layout (pixels contiguous), converted to half precision
 // once while they are staged in LDS; q and dO are divided by 16 there so that products up
 // to 2^20 stay finite, and the factor is restored with the final scale.  The tap windows
-// of k and v start at odd pixel offsets; they are read as aligned dwords and funnel-shifted.
+// of k and v start one pixel left or right of an aligned 8-pixel run; k and v are therefore
+// staged twice, the second copy moved right by one pixel, so that every window is four
+// dwords at a dword-aligned address (left: the moved copy at the run, middle: the plain copy
+// at the run, right: the moved copy one dword on) and needs no shifting in registers.
 // Accumulation is fp32 in the MFMA accumulators across all pixels a block visits; blocks
 // write partial sums that a second kernel adds in a fixed order (reproducible results).
 #include "slide_internal.h"
@@ -39,8 +42,9 @@ constexpr int R = 3;                  // rows of one work unit
 constexpr int TW = 56;                // columns of one work unit (a multiple of 8)
 constexpr int QP = 64;                // halves per staged row of q, dO
 constexpr int DP = 64;                // halves per staged row of dl, a
-constexpr int KP = 88;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin, 16 padding (the three
-                                      // window rows of a tap read then fall on different LDS banks)
+constexpr int KP = 96;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin, 24 padding: the
+                                      // (R + 2) rows of a channel then take 240 dwords, so the four channels of a
+                                      // wave read their windows from four different quarters of the 64 LDS banks
 constexpr float IN_SCALE = 0.0625f;   // q and dO are staged divided by 16
 
 // LDS map (bytes)
@@ -49,7 +53,11 @@ constexpr int QH_BYTES = D * R * QP * 2;                  // 12288
 constexpr int DL_BYTES = S * R * DP * 2;                  // 3456
 constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
               OFF_DO = OFF_Q + QH_BYTES, OFF_DL = OFF_DO + QH_BYTES, OFF_A = OFF_DL + DL_BYTES,
-              OFF_ZERO = OFF_A + DL_BYTES, LDS_BYTES = OFF_ZERO + 256;
+              OFF_ZERO = OFF_A + DL_BYTES,
+              // K1, V1: k and v moved right by one pixel; they start 8 bytes off a 16-byte boundary
+              // so that a window in them and the window at the same place in K, V use different banks
+              OFF_K1 = OFF_ZERO + 256 + 8, OFF_V1 = OFF_K1 + KH_BYTES, LDS_BYTES = OFF_V1 + KH_BYTES + 8;
+static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 
 struct Args {
     const bf16_bits* dout; const bf16_bits* q; const bf16_bits* k; const bf16_bits* v;
@@ -78,27 +86,46 @@ __device__ __forceinline__ uint4_t bf16x8_to_half(uint4_t r, half2_t mul)
     return o;
 }
 
-// Five consecutive dwords from each of two 4-byte aligned LDS addresses, as dword-granular
-// reads.  Written in assembly because the compiler fuses such reads into 16-byte reads, and
-// a 16-byte LDS read at an address that is not 16-byte aligned stalls the LDS pipe.
-__device__ __forceinline__ void lds_read_2x5_dwords(uint32_t addr_a, uint32_t addr_b,
-                                                    uint32_t (&a)[5], uint32_t (&b)[5])
+// one bf16 pattern -> half pattern, converted like bf16x8_to_half does (round toward zero)
+__device__ __forceinline__ uint32_t bf16_to_half_bits(uint32_t b)
 {
-    typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
-    uint2_t a01, a23, b01, b23;
-    uint32_t a4, b4;
-    asm volatile("ds_read2_b32 %0, %6 offset1:1\n\t"
-                 "ds_read2_b32 %1, %6 offset0:2 offset1:3\n\t"
-                 "ds_read_b32 %2, %6 offset:16\n\t"
-                 "ds_read2_b32 %3, %7 offset1:1\n\t"
-                 "ds_read2_b32 %4, %7 offset0:2 offset1:3\n\t"
-                 "ds_read_b32 %5, %7 offset:16\n\t"
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(__uint_as_float(b << 16), 0.0f)) & 0xffffu;
+}
+
+// The tap windows of the three window rows for one 32-pixel step: four consecutive dwords at
+// rows 0, 1, 2 (KP halves apart) from each of two dword-aligned LDS addresses, as 8-byte
+// two-dword reads.  Written in assembly because the compiler fuses such reads into 16-byte
+// reads, and a 16-byte LDS read at an address that is not 16-byte aligned stalls the LDS pipe.
+typedef __attribute__((ext_vector_type(2))) uint32_t uint2_t;
+static_assert(KP * 2 / 4 == 48, "row stride of the k/v tiles in dwords, as spelled in the assembly below");
+static_assert(OFF_K % 16 == 0 && OFF_V % 16 == 0 && OFF_K1 % 16 == 8 && OFF_V1 % 16 == 8, "bank phase of the copies");
+__device__ __forceinline__ void lds_read_windows(uint32_t addr_k, uint32_t addr_v,
+                                                 uint32_t (&k)[3][4], uint32_t (&v)[3][4])
+{
+    uint2_t k0a, k0b, k1a, k1b, k2a, k2b, v0a, v0b, v1a, v1b, v2a, v2b;
+    asm volatile("ds_read2_b32 %0, %12 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %1, %12 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %6, %13 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %7, %13 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %2, %12 offset0:48 offset1:49\n\t"
+                 "ds_read2_b32 %3, %12 offset0:50 offset1:51\n\t"
+                 "ds_read2_b32 %8, %13 offset0:48 offset1:49\n\t"
+                 "ds_read2_b32 %9, %13 offset0:50 offset1:51\n\t"
+                 "ds_read2_b32 %4, %12 offset0:96 offset1:97\n\t"
+                 "ds_read2_b32 %5, %12 offset0:98 offset1:99\n\t"
+                 "ds_read2_b32 %10, %13 offset0:96 offset1:97\n\t"
+                 "ds_read2_b32 %11, %13 offset0:98 offset1:99\n\t"
                  "s_waitcnt lgkmcnt(0)"
-                 : "=&v"(a01), "=&v"(a23), "=&v"(a4), "=&v"(b01), "=&v"(b23), "=&v"(b4)
-                 : "v"(addr_a), "v"(addr_b)
+                 : "=&v"(k0a), "=&v"(k0b), "=&v"(k1a), "=&v"(k1b), "=&v"(k2a), "=&v"(k2b),
+                   "=&v"(v0a), "=&v"(v0b), "=&v"(v1a), "=&v"(v1b), "=&v"(v2a), "=&v"(v2b)
+                 : "v"(addr_k), "v"(addr_v)
                  : "memory");
-    a[0] = a01[0]; a[1] = a01[1]; a[2] = a23[0]; a[3] = a23[1]; a[4] = a4;
-    b[0] = b01[0]; b[1] = b01[1]; b[2] = b23[0]; b[3] = b23[1]; b[4] = b4;
+    k[0][0] = k0a[0]; k[0][1] = k0a[1]; k[0][2] = k0b[0]; k[0][3] = k0b[1];
+    k[1][0] = k1a[0]; k[1][1] = k1a[1]; k[1][2] = k1b[0]; k[1][3] = k1b[1];
+    k[2][0] = k2a[0]; k[2][1] = k2a[1]; k[2][2] = k2b[0]; k[2][3] = k2b[1];
+    v[0][0] = v0a[0]; v[0][1] = v0a[1]; v[0][2] = v0b[0]; v[0][3] = v0b[1];
+    v[1][0] = v1a[0]; v[1][1] = v1a[1]; v[1][2] = v1b[0]; v[1][3] = v1b[1];
+    v[2][0] = v2a[0]; v[2][1] = v2a[1]; v[2][2] = v2b[0]; v[2][3] = v2b[1];
 }
 
 __global__ void __launch_bounds__(THREADS, 2)
@@ -120,11 +147,11 @@ bwd_dw_kernel(const Args a)
     // 12..15 are masked (zero q), except that row 12 of wave 0's first product sums dl.
     constexpr int ROWS = 3 * CPW;
     const int lcc = (i < ROWS) ? i / 3 : 0, tx = (i < ROWS) ? i - 3 * (i / 3) : 0;
-    // The tap window of k (v) is the aligned 8-pixel run moved by tx-1 pixels.  It is read as
-    // five aligned dwords starting one dword early (tx = 0) or at the run (tx = 1, 2) and funnel-
-    // shifted by 16 bits for the odd offsets: misaligned 16-byte LDS reads stall the LDS pipe.
-    const int kwin_off = (((wave * CPW + lcc) * (R + 2)) * KP + 8 + 8 * g) * 2 - 4 + (tx >= 1 ? 4 : 0);   // + (ty + r)*KP*2 + 64*h
-    const uint32_t win_shift = (tx == 1) ? 0u : 16u;
+    // The tap window of k (v) is the aligned 8-pixel run moved by tx-1 pixels: four dwords of
+    // the moved copy at the run (tx = 0), of the plain copy at the run (tx = 1), or of the moved
+    // copy one dword past the run (tx = 2).
+    const int kwin_off = (((wave * CPW + lcc) * (R + 2)) * KP + 8 + 8 * g) * 2 + (tx == 2 ? 4 : 0) +
+                         (tx == 1 ? 0 : OFF_K1 - OFF_K);          // + (ty + r)*KP*2 + 64*h; the same offset from OFF_V for v
     const int q_off = (i < ROWS) ? (((wave * CPW + lcc) * R) * QP + 8 * g) * 2 : -1;   // + r*QP*2 + 64*h; -1: masked row, read zeros
     const int b_off = (i < S) ? ((i * R) * DP + 8 * g) * 2 : -1;  // + r*DP*2 + 64*h
 
@@ -159,6 +186,7 @@ bwd_dw_kernel(const Args a)
     constexpr int N_Q = CPW * R * 8, Q_SLOTS = (2 * N_Q + 63) / 64;                 // 3
     constexpr int N_D = S * R * 8, D_SLOTS = (2 * N_D + THREADS - 1) / THREADS;     // dl / a items: 8 halves each
     uint4_t pre_kv[KV_SLOTS], pre_q[Q_SLOTS];
+    uint32_t pre_kp[KV_SLOTS];                  // the pixel left of each k/v chunk (for the moved copy)
     uint32_t pre_hc[HC_SLOTS];
     uint4_t pre_d[D_SLOTS];
 
@@ -171,9 +199,11 @@ bwd_dw_kernel(const Args a)
             const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
             const int gi = t.i0 - 1 + hr;
             pre_kv[sl] = uint4_t{0u, 0u, 0u, 0u};
+            pre_kp[sl] = 0u;
             if (idx < 2 * N_KV && x < t.nxc && gi >= 0 && gi < a.H) {
                 const bf16_bits* src = (tsel ? a.v : a.k) + ((long)t.b * a.C + c0 + cc) * HW + (long)gi * a.W + t.j0 + 8 * x;
                 pre_kv[sl] = *(const uint4_t*)src;
+                if (t.j0 + 8 * x > 0) pre_kp[sl] = src[-1];
             }
         }
 #pragma unroll
@@ -221,9 +251,22 @@ bwd_dw_kernel(const Args a)
             const int x = id & 7, rj = id >> 3;
             const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
             // slots past the tile keep stale (finite) data: they only ever meet a zero q
-            if (idx < 2 * N_KV && x < t.nxc)
-                *(uint4_t*)(smem + (tsel ? OFF_V : OFF_K) + (((wave * CPW + cc) * (R + 2) + hr) * KP + 8 + 8 * x) * 2) =
-                    bf16x8_to_half(pre_kv[sl], one2);
+            if (idx < 2 * N_KV && x < t.nxc) {
+                const uint4_t val = bf16x8_to_half(pre_kv[sl], one2);
+                const int at = (((wave * CPW + cc) * (R + 2) + hr) * KP + 8 + 8 * x) * 2;
+                *(uint4_t*)(smem + (tsel ? OFF_V : OFF_K) + at) = val;
+                // the copy moved right by one pixel: (left neighbour, pixels 0..6) here, pixel 7
+                // opens the next chunk (written there by that chunk's lane, or below at the end)
+                const uint32_t left = bf16_to_half_bits(pre_kp[sl]);
+                uint4_t mv;
+                mv[0] = (val[0] << 16) | left;
+#pragma unroll
+                for (int y = 1; y < 4; ++y) mv[y] = __builtin_amdgcn_alignbit(val[y], val[y - 1], 16);
+                *(uint2_t*)(smem + (tsel ? OFF_V1 : OFF_K1) + at) = uint2_t{mv[0], mv[1]};
+                *(uint2_t*)(smem + (tsel ? OFF_V1 : OFF_K1) + at + 8) = uint2_t{mv[2], mv[3]};
+                if (x == t.nxc - 1)
+                    *(uint16_t*)(smem + (tsel ? OFF_V1 : OFF_K1) + at + 16) = (uint16_t)(val[3] >> 16);
+            }
         }
 #pragma unroll
         for (int sl = 0; sl < HC_SLOTS; ++sl) {
@@ -231,10 +274,14 @@ bwd_dw_kernel(const Args a)
             const int tsel = idx >= N_HC, id = idx - tsel * N_HC;
             const int side = id & 1, rj = id >> 1;
             const int cc = rj / (R + 2), hr = rj - cc * (R + 2);
-            if (idx < 2 * N_HC)
-                *(_Float16*)(smem + (tsel ? OFF_V : OFF_K) +
-                             (((wave * CPW + cc) * (R + 2) + hr) * KP + (side ? 8 + t.cols_eff : 7)) * 2) =
-                    (_Float16)bf16_to_f32((bf16_bits)pre_hc[sl]);
+            if (idx < 2 * N_HC) {
+                const uint16_t hv = (uint16_t)bf16_to_half_bits(pre_hc[sl]);
+                const int at = (((wave * CPW + cc) * (R + 2) + hr) * KP + (side ? 8 + t.cols_eff : 7)) * 2;
+                *(uint16_t*)(smem + (tsel ? OFF_V : OFF_K) + at) = hv;
+                // moved copy: the right halo column sits one further right; the left one is the
+                // "left neighbour" of chunk 0
+                if (side) *(uint16_t*)(smem + (tsel ? OFF_V1 : OFF_K1) + at + 2) = hv;
+            }
         }
 #pragma unroll
         for (int sl = 0; sl < Q_SLOTS; ++sl) {
@@ -279,23 +326,19 @@ bwd_dw_kernel(const Args a)
                 const int qo = (q_off >= 0) ? q_off + r * QP * 2 + 64 * h : -1;
                 const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
                 const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
+                uint32_t kw[3][4], vw[3][4];
+                {
+                    const int ko = kwin_off + r * KP * 2 + 64 * h;
+                    lds_read_windows((uint32_t)(uintptr_t)(smem + OFF_K + ko),
+                                     (uint32_t)(uintptr_t)(smem + OFF_V + ko), kw, vw);
+                }
 #pragma unroll
                 for (int ty = 0; ty < 3; ++ty) {
-                    const int ko = kwin_off + (ty + r) * KP * 2 + 64 * h;
-                    uint32_t km[5], vm[5];
-                    lds_read_2x5_dwords((uint32_t)(uintptr_t)(smem + OFF_K + ko),
-                                        (uint32_t)(uintptr_t)(smem + OFF_V + ko), km, vm);
-                    uint4_t kw, vw;
-#pragma unroll
-                    for (int y = 0; y < 4; ++y) {
-                        kw[y] = __builtin_amdgcn_alignbit(km[y + 1], km[y], win_shift);
-                        vw[y] = __builtin_amdgcn_alignbit(vm[y + 1], vm[y], win_shift);
-                    }
                     uint4_t ak, av;
 #pragma unroll
                     for (int y = 0; y < 4; ++y) {
-                        ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[y]));
-                        av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[y]));
+                        ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[ty][y]));
+                        av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[ty][y]));
                     }
                     if (ty == 0 && wave == 0) {
 #pragma unroll
