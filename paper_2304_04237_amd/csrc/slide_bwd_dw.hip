@@ -11,7 +11,9 @@
 // Per channel this is a (9 taps) x (9 shifts) matrix whose contraction index is the pixel,
 // so it runs as v_mfma_f32_16x16x32_f16 with K = 32 consecutive pixels of a row:
 //     A[t, p] = q[c,p] * k[c, p + off(t)]      (two packed multiplies per dword, from LDS)
-//     B[p, s] = dl[s, p]                        (shared by all channels of the head)
+//     B[p, s] = dl[s, p]                        (shared by all channels of the head; 16 contiguous
+//                                                bytes of the workspace per lane, read from
+//                                                global memory one work unit ahead)
 // The 16 rows of one product hold the three taps of one window row for four channels (12
 // rows in use), so a wave's four channels take three products per 32 pixels and side, and
 // q (dO) of a row is read once for the three window rows.
@@ -22,6 +24,9 @@
 // staged twice, the second copy moved right by one pixel, so that every window is four
 // dwords at a dword-aligned address (left: the moved copy at the run, middle: the plain copy
 // at the run, right: the moved copy one dword on) and needs no shifting in registers.
+// Each wave stages k, v, q, dO of its own four channels in its own part of LDS and shares
+// nothing with the other waves of the block, so the loop over work units has no block
+// barrier: the waves drift apart and one wave's staging overlaps another's matrix work.
 // Accumulation is fp32 in the MFMA accumulators across all pixels a block visits; blocks
 // write partial sums that a second kernel adds in a fixed order (reproducible results).
 #include "slide_internal.h"
@@ -41,7 +46,6 @@ constexpr int CPW = D / WAVES;        // channels per wave (4)
 constexpr int R = 3;                  // rows of one work unit
 constexpr int TW = 56;                // columns of one work unit (a multiple of 8)
 constexpr int QP = 64;                // halves per staged row of q, dO
-constexpr int DP = 64;                // halves per staged row of dl, a
 constexpr int KP = 96;                // halves per staged row of k, v: 8 margin, 56 data, 8 margin, 24 padding: the
                                       // (R + 2) rows of a channel then take 240 dwords, so the four channels of a
                                       // wave read their windows from four different quarters of the 64 LDS banks
@@ -50,10 +54,8 @@ constexpr float IN_SCALE = 0.0625f;   // q and dO are staged divided by 16
 // LDS map (bytes)
 constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 28160
 constexpr int QH_BYTES = D * R * QP * 2;                  // 12288
-constexpr int DL_BYTES = S * R * DP * 2;                  // 3456
 constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
-              OFF_DO = OFF_Q + QH_BYTES, OFF_DL = OFF_DO + QH_BYTES, OFF_A = OFF_DL + DL_BYTES,
-              OFF_ZERO = OFF_A + DL_BYTES,
+              OFF_DO = OFF_Q + QH_BYTES, OFF_ZERO = OFF_DO + QH_BYTES,
               // K1, V1: k and v moved right by one pixel; they start 8 bytes off a 16-byte boundary
               // so that a window in them and the window at the same place in K, V use different banks
               OFF_K1 = OFF_ZERO + 256 + 8, OFF_V1 = OFF_K1 + KH_BYTES, LDS_BYTES = OFF_V1 + KH_BYTES + 8;
@@ -153,7 +155,6 @@ bwd_dw_kernel(const Args a)
     const int kwin_off = (((wave * CPW + lcc) * (R + 2)) * KP + 8 + 8 * g) * 2 + (tx == 2 ? 4 : 0) +
                          (tx == 1 ? 0 : OFF_K1 - OFF_K);          // + (ty + r)*KP*2 + 64*h; the same offset from OFF_V for v
     const int q_off = (i < ROWS) ? (((wave * CPW + lcc) * R) * QP + 8 * g) * 2 : -1;   // + r*QP*2 + 64*h; -1: masked row, read zeros
-    const int b_off = (i < S) ? ((i * R) * DP + 8 * g) * 2 : -1;  // + r*DP*2 + 64*h
 
     float4_t acc_k[3], acc_v[3];                  // one accumulator per window row
 #pragma unroll
@@ -180,15 +181,13 @@ bwd_dw_kernel(const Args a)
     // Staging registers of one unit.  The loads of the next unit are issued before the
     // current unit is accumulated and are converted into LDS afterwards, so global latency
     // hides behind the matrix work.  Slots: k/v chunks, k/v halo columns, q/dO chunks of this
-    // wave's channels (wave-private LDS regions), and this thread's share of dl / a.
+    // wave's channels (wave-private LDS regions).
     constexpr int N_KV = CPW * (R + 2) * 8, KV_SLOTS = (2 * N_KV + 63) / 64;        // 5
     constexpr int N_HC = CPW * (R + 2) * 2, HC_SLOTS = (2 * N_HC + 63) / 64;        // 2
     constexpr int N_Q = CPW * R * 8, Q_SLOTS = (2 * N_Q + 63) / 64;                 // 3
-    constexpr int N_D = S * R * 8, D_SLOTS = (2 * N_D + THREADS - 1) / THREADS;     // dl / a items: 8 halves each
     uint4_t pre_kv[KV_SLOTS], pre_q[Q_SLOTS];
     uint32_t pre_kp[KV_SLOTS];                  // the pixel left of each k/v chunk (for the moved copy)
     uint32_t pre_hc[HC_SLOTS];
-    uint4_t pre_d[D_SLOTS];
 
     auto issue_loads = [&](const Unit& t) {
 #pragma unroll
@@ -227,18 +226,6 @@ bwd_dw_kernel(const Args a)
             if (idx < 2 * N_Q && x < t.nxc && r < t.rows_eff) {
                 const bf16_bits* src = (tsel ? a.dout : a.q) + ((long)t.b * a.C + c0 + cc) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
                 pre_q[sl] = *(const uint4_t*)src;
-            }
-        }
-#pragma unroll
-        for (int sl = 0; sl < D_SLOTS; ++sl) {
-            const int idx = sl * THREADS + tid;
-            const int tsel = idx >= N_D, id = idx - tsel * N_D;
-            const int x = id & 7, rj = id >> 3;
-            const int s = rj / R, r = rj - s * R;
-            pre_d[sl] = uint4_t{0u, 0u, 0u, 0u};
-            if (idx < 2 * N_D && x < t.nxc && r < t.rows_eff) {
-                const _Float16* src = (tsel ? a.attn : a.dl) + (((long)t.b * a.heads + m) * S + s) * HW + (long)(t.i0 + r) * a.W + t.j0 + 8 * x;
-                pre_d[sl] = *(const uint4_t*)src;
             }
         }
     };
@@ -293,61 +280,77 @@ bwd_dw_kernel(const Args a)
                 *(uint4_t*)(smem + (tsel ? OFF_DO : OFF_Q) + (((wave * CPW + cc) * R + r) * QP + 8 * x) * 2) =
                     bf16x8_to_half(pre_q[sl], in2);
         }
-#pragma unroll
-        for (int sl = 0; sl < D_SLOTS; ++sl) {
-            const int idx = sl * THREADS + tid;
-            if (idx >= 2 * N_D) continue;
-            const int tsel = idx >= N_D, id = idx - tsel * N_D;
-            const int x = id & 7, rj = id >> 3;
-            const int s = rj / R, r = rj - s * R;
-            *(uint4_t*)(smem + (tsel ? OFF_A : OFF_DL) + ((s * R + r) * DP + 8 * x) * 2) = pre_d[sl];
+    };
+
+    // dl and a enter as the B operands straight from global memory: lane (n, g) needs the 8
+    // consecutive pixels 32h + 8g .. +7 of shift n, which are 16 contiguous bytes of the planar
+    // workspace.  All 8 waves of a block read the same addresses (served by the caches).  The
+    // operand of a step is fetched one unit ahead, into the registers that the step has just
+    // used, so nothing of a unit is shared between the waves through LDS and they need not
+    // wait for each other: no block barrier inside the loop.
+    uint4_t Bop[R][2][2];
+    auto load_B = [&](const Unit& t, int r, int h, uint4_t (&dst)[2]) {
+        dst[0] = uint4_t{0u, 0u, 0u, 0u}; dst[1] = uint4_t{0u, 0u, 0u, 0u};
+        if (i < S && r < t.rows_eff && 32 * h + 8 * g < t.cols_eff) {
+            const long at = (((long)t.b * a.heads + m) * S + i) * HW + (long)(t.i0 + r) * a.W + t.j0 + 32 * h + 8 * g;
+            dst[0] = *(const uint4_t*)(a.dl + at);
+            dst[1] = *(const uint4_t*)(a.attn + at);
         }
     };
 
-    if (j < n_units) issue_loads(unit_of(j));
+    __syncthreads();                           // LDS is zeroed
+    if (j < n_units) {
+        const Unit t0 = unit_of(j);
+        issue_loads(t0);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) load_B(t0, r, h, Bop[r][h]);
+    }
     for (int u = j; u < n_units; u += a.NB) {
         const Unit t = unit_of(u);
-        __syncthreads();                       // the previous unit's reads of LDS are done
-        commit_to_lds(t);
-        __syncthreads();
-        if (u + a.NB < n_units) issue_loads(unit_of(u + a.NB));
+        const bool has_next = u + a.NB < n_units;
+        const Unit tn = unit_of(has_next ? u + a.NB : u);
+        commit_to_lds(t);                      // this wave's own regions: its reads of the previous unit are done
+        if (has_next) issue_loads(tn);
         const int rows_eff = t.rows_eff, cols_eff = t.cols_eff;
 
-        // ---- accumulate: for every 32-pixel chunk, one MFMA per channel and side
-        for (int r = 0; r < rows_eff; ++r) {
+        // ---- accumulate: for every 32-pixel chunk, one MFMA per window row and side
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (32 * h >= cols_eff) continue;
-                const int dl_addr = (b_off >= 0) ? OFF_DL + b_off + r * DP * 2 + 64 * h : OFF_ZERO;
-                const int a_addr = (b_off >= 0) ? OFF_A + b_off + r * DP * 2 + 64 * h : OFF_ZERO;
-                const half8_t Bdl = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + dl_addr));
-                const half8_t Ba = __builtin_bit_cast(half8_t, *(const uint4_t*)(smem + a_addr));
-                // q and dO of the row's channel: the same for the three window rows
-                const int qo = (q_off >= 0) ? q_off + r * QP * 2 + 64 * h : -1;
-                const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
-                const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
-                uint32_t kw[3][4], vw[3][4];
-                {
-                    const int ko = kwin_off + r * KP * 2 + 64 * h;
-                    lds_read_windows((uint32_t)(uintptr_t)(smem + OFF_K + ko),
-                                     (uint32_t)(uintptr_t)(smem + OFF_V + ko), kw, vw);
-                }
-#pragma unroll
-                for (int ty = 0; ty < 3; ++ty) {
-                    uint4_t ak, av;
-#pragma unroll
-                    for (int y = 0; y < 4; ++y) {
-                        ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[ty][y]));
-                        av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[ty][y]));
+                if (r < rows_eff && 32 * h < cols_eff) {
+                    const half8_t Bdl = __builtin_bit_cast(half8_t, Bop[r][h][0]);
+                    const half8_t Ba = __builtin_bit_cast(half8_t, Bop[r][h][1]);
+                    // q and dO of the row's channel: the same for the three window rows
+                    const int qo = (q_off >= 0) ? q_off + r * QP * 2 + 64 * h : -1;
+                    const uint4_t qv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_Q + qo : OFF_ZERO));
+                    const uint4_t dv = *(const uint4_t*)(smem + (qo >= 0 ? OFF_DO + qo : OFF_ZERO));
+                    uint32_t kw[3][4], vw[3][4];
+                    {
+                        const int ko = kwin_off + r * KP * 2 + 64 * h;
+                        lds_read_windows((uint32_t)(uintptr_t)(smem + OFF_K + ko),
+                                         (uint32_t)(uintptr_t)(smem + OFF_V + ko), kw, vw);
                     }
-                    if (ty == 0 && wave == 0) {
 #pragma unroll
-                        for (int y = 0; y < 4; ++y) ak[y] = bias_lane ? as_dword(one2) : ak[y];
+                    for (int ty = 0; ty < 3; ++ty) {
+                        uint4_t ak, av;
+#pragma unroll
+                        for (int y = 0; y < 4; ++y) {
+                            ak[y] = as_dword(as_half2(qv[y]) * as_half2(kw[ty][y]));
+                            av[y] = as_dword(as_half2(dv[y]) * as_half2(vw[ty][y]));
+                        }
+                        if (ty == 0 && wave == 0) {
+#pragma unroll
+                            for (int y = 0; y < 4; ++y) ak[y] = bias_lane ? as_dword(one2) : ak[y];
+                        }
+                        acc_k[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[ty], 0, 0, 0);
+                        acc_v[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[ty], 0, 0, 0);
+                        if (ty == 1) __builtin_amdgcn_sched_barrier(0);   // keep two products in flight, not three
                     }
-                    acc_k[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, ak), Bdl, acc_k[ty], 0, 0, 0);
-                    acc_v[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av), Ba, acc_v[ty], 0, 0, 0);
-                    if (ty == 1) __builtin_amdgcn_sched_barrier(0);   // keep two products in flight, not three
                 }
+                if (has_next) load_B(tn, r, h, Bop[r][h]);    // the same step of the next unit
             }
         }
     }
