@@ -289,12 +289,15 @@ bwd_dw_kernel(const Args a)
     // used, so nothing of a unit is shared between the waves through LDS and they need not
     // wait for each other: no block barrier inside the loop.
     uint4_t Bop[R][2][2];
+    // address = one base per (unit, row, half) that is the same for the whole wave + a byte
+    // offset per lane that never changes (9 * H * W halves stay far below 2^31 bytes)
+    const uint32_t b_lane = (uint32_t)(((long)(i < S ? i : 0) * HW + 8 * g) * 2);
     auto load_B = [&](const Unit& t, int r, int h, uint4_t (&dst)[2]) {
         dst[0] = uint4_t{0u, 0u, 0u, 0u}; dst[1] = uint4_t{0u, 0u, 0u, 0u};
+        const long at = ((long)t.b * a.heads + m) * S * HW + (long)(t.i0 + r) * a.W + t.j0 + 32 * h;   // uniform
         if (i < S && r < t.rows_eff && 32 * h + 8 * g < t.cols_eff) {
-            const long at = (((long)t.b * a.heads + m) * S + i) * HW + (long)(t.i0 + r) * a.W + t.j0 + 32 * h + 8 * g;
-            dst[0] = *(const uint4_t*)(a.dl + at);
-            dst[1] = *(const uint4_t*)(a.attn + at);
+            dst[0] = *(const uint4_t*)((const char*)(a.dl + at) + b_lane);
+            dst[1] = *(const uint4_t*)((const char*)(a.attn + at) + b_lane);
         }
     };
 
