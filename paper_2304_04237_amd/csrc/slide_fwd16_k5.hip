@@ -304,7 +304,7 @@ hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, cons
                             float* lse, void* workspace, hipStream_t st)
 {
     using namespace f16k5;
-    const TilePlan t = plan_tiles(p, TILE_BUDGET, 64, 64);
+    const TilePlan t = plan_tiles(p, TILE_BUDGET, 64, 64, 0, WAVES);
     uint32_t* image = (uint32_t*)workspace;
     hipLaunchKernelGGL(prep_weights5_kernel, dim3(S5, (unsigned)p.heads), dim3(256), 0, st,
                        wk, wv, bias, image);

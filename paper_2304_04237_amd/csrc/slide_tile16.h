@@ -256,8 +256,11 @@ inline double queue_makespan(long TA, double cA, long TB, double cB, int G)
 // Tile heights for a kernel that may spend lds_budget bytes on one tile buffer holding two
 // halo tensors of px_bytes per halo pixel each (64 for a staged activation tensor).
 // px_bytes_extra: further LDS bytes per halo pixel that the kernel places after the buffer.
+// pass_waves > 0: the kernel deals the 16-pixel passes of a tile to that many waves and does
+// not overlap the staging of a tile with its passes; a tile then costs the rounds of passes
+// its busiest wave runs plus a staging share, instead of its rows.
 inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int px_bytes_b,
-                           int px_bytes_extra = 0)
+                           int px_bytes_extra = 0, int pass_waves = 0)
 {
     const int r2 = 2 * (p.ksize / 2);
     TilePlan t;
@@ -282,7 +285,12 @@ inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int
                 if ((rem == 0) != (nB == 0)) continue;
                 const int hb = nB ? (rem + nB - 1) / nB : 0;
                 if (nB && (hb < 1 || (long)hb * (nB - 1) >= rem)) continue;
-                const double ms = queue_makespan(planes * nA, th + 1.5, planes * nB, hb + 1.5, NUM_CU);
+                auto cost = [&](int rows) {
+                    if (pass_waves <= 0) return rows + 1.5;
+                    const int passes = (rows * t.tw + 15) / 16;
+                    return (double)((passes + pass_waves - 1) / pass_waves) + 0.35 + 0.035 * (rows + r2);
+                };
+                const double ms = queue_makespan(planes * nA, cost(th), planes * nB, cost(hb), NUM_CU);
                 if (ms < best - 1e-9) { best = ms; t.th = th; t.nA = nA; t.nB = nB; t.hb = hb; }
             }
         }
