@@ -25,17 +25,15 @@ using namespace t16;
 constexpr int WAVES = 4, THREADS = WAVES * 64;
 constexpr int REC_BYTES = 32;                       // 16 halves per halo pixel and tensor
 
-// Per-head image of the MFMA weight operands (dwords), written by prep_dkdv_weights_kernel:
+// Per-head image of the MFMA weight operands (dwords), written by prep_dkdv_weights:
 //   side (K: 0, V: 1) x tap t (9) x channel half j (2) x lane (64) x 2 dwords.
 // Row i of product (t, j) is channel 8*(i/4) + 4j + (i%4); dword y of lane (i, g) holds the
 // merged weights (one-hot shift included) for the shifts of operand slots 4g+2y and 4g+2y+1.
 constexpr int IMG_DWORDS = 2 * S * 2 * 64 * 2;      // 4608
 
-__global__ void __launch_bounds__(256)
-prep_dkdv_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
-                         uint32_t* __restrict__ image)
+__device__ __forceinline__ void prep_dkdv_weights(const float* __restrict__ wk, const float* __restrict__ wv,
+                                                  uint32_t* __restrict__ image, int t, int m)
 {
-    const int t = blockIdx.x, m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
     for (int idx = threadIdx.x; idx < 2 * 2 * 128; idx += 256) {
         const int y = idx & 1, lane = (idx >> 1) & 63, j = (idx >> 7) & 1, side = idx >> 8;
@@ -250,11 +248,10 @@ bwd_dkdv_kernel16(const DkdvArgs a)
 constexpr int PX_A1K = 0, PX_A1V = 2304, PX_A2K = 4608, PX_BIAS = 6912, PX_IMG_DWORDS = 6928;
 constexpr float G_SCALE = 0.0625f, W_SCALE = 16.0f;
 
-__global__ void __launch_bounds__(256)
-prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
-                          const float* __restrict__ bias, uint32_t* __restrict__ image)
+__device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk, const float* __restrict__ wv,
+                                                   const float* __restrict__ bias, uint32_t* __restrict__ image,
+                                                   int t, int m)
 {
-    const int t = blockIdx.x, m = blockIdx.y;
     uint32_t* img = image + (long)m * PX_IMG_DWORDS;
     const int tid = threadIdx.x;
     {
@@ -295,6 +292,17 @@ prep_pixel_weights_kernel(const float* __restrict__ wk, const float* __restrict_
         if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
         img[PX_BIAS + tid] = __float_as_uint(b);
     }
+}
+
+// Both operand images in one launch: blocks (t, m, 0) write tap t of head m of the per-pixel
+// kernel's image, blocks (t, m, 1) that of the dk/dv kernel's.
+__global__ void __launch_bounds__(256)
+prep_bwd_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
+                        const float* __restrict__ bias, uint32_t* __restrict__ pixel_image,
+                        uint32_t* __restrict__ dkdv_image)
+{
+    if (blockIdx.z == 0) prep_pixel_weights(wk, wv, bias, pixel_image, blockIdx.x, blockIdx.y);
+    else                 prep_dkdv_weights(wk, wv, dkdv_image, blockIdx.x, blockIdx.y);
 }
 
 struct PixelArgs {
@@ -534,13 +542,13 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p)
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 hipStream_t st)
+                                 void* dkdv_image_ws, hipStream_t st)
 {
     using namespace b16path;
     const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
     uint32_t* image = (uint32_t*)image_ws;
-    hipLaunchKernelGGL(prep_pixel_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
-                       wk, wv, bias, image);
+    hipLaunchKernelGGL(prep_bwd_weights_kernel, dim3(S, (unsigned)p.heads, 2), dim3(256), 0, st,
+                       wk, wv, bias, image, (uint32_t*)dkdv_image_ws);
     PixelArgs a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q;
     a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
@@ -583,8 +591,8 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
 {
     using namespace b16path;
     const TilePlan t = plan_dkdv(p);
+    (void)wk; (void)wv;                         // the operand image was written by launch_bwd_pixel_mfma
     uint32_t* image = (uint32_t*)image_ws;
-    hipLaunchKernelGGL(prep_dkdv_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st, wk, wv, image);
     DkdvArgs a;
     a.q = (const bf16_bits*)q; a.dout = (const bf16_bits*)dout;
     a.attn = attn_ws; a.dl = dl_ws;

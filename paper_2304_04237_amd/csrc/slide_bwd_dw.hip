@@ -382,19 +382,6 @@ bwd_dw_kernel(const Args a)
     }
 }
 
-// dbias[m,s] = sum_j partial[j][m][s]: one wavefront per entry, lane l adds blocks l, l+64, ...
-// in order, then a fixed butterfly over the lanes
-__global__ void __launch_bounds__(64)
-bwd_dbias_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dbias, int n, int NB)
-{
-    const int e = blockIdx.x, lane = threadIdx.x;
-    float acc = 0.0f;
-    for (int jj = lane; jj < NB; jj += 64) acc += partial[(long)jj * n + e];
-#pragma unroll
-    for (int w = 32; w > 0; w >>= 1) acc += __shfl_xor(acc, w, 64);
-    if (lane == 0) dbias[e] = acc;
-}
-
 static int blocks_per_head(const Problem& p)
 {
     const long units = (long)p.B * ((p.H + R - 1) / R) * ((p.W + TW - 1) / TW);
@@ -441,13 +428,7 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     }
     hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
     const long side = (long)p.C * 81;
-    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, st);
-    if (dbias) {
-        const int nbias = p.heads * 9;
-        hipLaunchKernelGGL(bwd_dbias_reduce_kernel, dim3((unsigned)nbias), dim3(64), 0, st,
-                           a.dbias_partial, dbias, nbias, a.NB);
-    }
-    return hipGetLastError();
+    return launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, a.dbias_partial, dbias, p.heads * 9, st);
 }
 
 }  // namespace slide

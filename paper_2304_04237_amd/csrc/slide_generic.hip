@@ -379,21 +379,46 @@ bwd_dw_partial_kernel(const T* __restrict__ dout, const T* __restrict__ q, const
     }
 }
 
-// Step 4: add the per-chunk partials.  One wavefront per output entry: lane l adds chunks
-// l, l+64, ... in order, then the 64 lane sums are combined by a fixed butterfly, so the
-// result does not depend on timing.  n = 2 * C*S*S entries.
-__global__ void __launch_bounds__(256)
+// Step 4: add the per-chunk partials.  A block handles 64 consecutive output entries (the
+// loads of a wave are 256 contiguous bytes); its 16 waves each add every 16th chunk in order,
+// with 8 loads in flight, and the 16 sums per entry are combined in a fixed order through
+// LDS, so the result does not depend on timing.  n = 2 * C*S*S entries.  Blocks past those
+// entries add the bias-gradient partials [n_chunks][nbias] the same way (nbias may be 0).
+constexpr int RED_GROUPS = 16;
+__global__ void __launch_bounds__(64 * RED_GROUPS)
 bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
-                     float* __restrict__ dwv, long side, int n_chunks)
+                     float* __restrict__ dwv, long side, int n_chunks,
+                     const float* __restrict__ bias_partial, float* __restrict__ dbias, int nbias)
 {
-    const long e = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (e >= 2 * side) return;
+    __shared__ float part[RED_GROUPS][64];
+    const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const long dw_blocks = (2 * side + 63) / 64;
+    const bool bias_job = blockIdx.x >= dw_blocks;
+    const long e = (long)(bias_job ? blockIdx.x - dw_blocks : blockIdx.x) * 64 + el;
+    const long n = bias_job ? nbias : 2 * side;
+    const float* src = bias_job ? bias_partial : partial;
+    const bool live = e < n;
     float acc = 0.0f;
-    for (int ch = lane; ch < n_chunks; ch += 64) acc += partial[(long)ch * 2 * side + e];
+    for (int base = grp; base < n_chunks; base += 8 * RED_GROUPS) {
+        float x[8];
 #pragma unroll
-    for (int w = 32; w > 0; w >>= 1) acc += __shfl_xor(acc, w, 64);
-    if (lane == 0) { if (e < side) dwk[e] = acc; else dwv[e - side] = acc; }
+        for (int u = 0; u < 8; ++u) {
+            const int ch = base + u * RED_GROUPS;
+            x[u] = (live && ch < n_chunks) ? src[(long)ch * n + e] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u];
+    }
+    part[grp][el] = acc;
+    __syncthreads();
+    if (grp == 0 && live) {
+        float sum = part[0][el];
+#pragma unroll
+        for (int g2 = 1; g2 < RED_GROUPS; ++g2) sum += part[g2][el];
+        if (bias_job) dbias[e] = sum;
+        else if (e < side) dwk[e] = sum;
+        else dwv[e - side] = sum;
+    }
 }
 
 // Step 5: dbias[m,s] = sum over batch and pixels of dl; one block per (m,s),
@@ -430,10 +455,12 @@ static int dw_chunks(const Problem& p)
 }
 
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
-                                hipStream_t st)
+                                const float* bias_partial, float* dbias, int nbias, hipStream_t st)
 {
-    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3((unsigned)((2 * side + 3) / 4)), dim3(256),
-                       0, st, partial, dwk, dwv, side, n_chunks);
+    if (!dbias) nbias = 0;
+    const unsigned blocks = (unsigned)((2 * side + 63) / 64 + (nbias + 63) / 64);
+    hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3(blocks), dim3(64 * RED_GROUPS),
+                       0, st, partial, dwk, dwv, side, n_chunks, bias_partial, dbias, nbias);
     return hipGetLastError();
 }
 
@@ -480,7 +507,9 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     const bool half_ws = fast && bwd_dw_mfma_supported(p);
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p) + bwd_dkdv_mfma_image_bytes(p);
-        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws, st);
+        void* dkdv_image_ws = (char*)partial + bwd_partial_bytes(p);
+        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws,
+                                             dkdv_image_ws, st);
         if (e != hipSuccess) return e;
     } else
         hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
@@ -506,7 +535,7 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
                        (const T*)dout, (const T*)q, (const T*)k, (const T*)v, attn_ws, dl_ws,
                        partial, p.B, p.H, p.W, p.C, p.heads, per_chunk);
     const long side = (long)p.C * S * S;
-    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, st);
+    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, nullptr, nullptr, 0, st);
     if (dbias)
         hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
                            dl_ws, dbias, p.B, p.plane(), p.heads, S);

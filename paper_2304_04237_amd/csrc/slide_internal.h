@@ -25,8 +25,10 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
+// adds n_chunks partial sums per entry in a fixed order; bias_partial [n_chunks][nbias] -> dbias
+// in the same launch (dbias may be null)
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
-                                hipStream_t st);
+                                const float* bias_partial, float* dbias, int nbias, hipStream_t st);
 
 // ---- matrix-core kernel/bias gradients (slide_bwd_dw.hip): bf16, d == 32, ksize 3, W % 8 == 0
 bool bwd_dw_mfma_supported(const Problem& p);
@@ -42,7 +44,7 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p);
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 hipStream_t st);
+                                 void* dkdv_image_ws, hipStream_t st);   // also prepares the dk/dv kernel's operand image
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
                                 const void* attn_ws, const void* dl_ws, bool half_ws,
