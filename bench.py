@@ -251,7 +251,7 @@ def main():
     # ---- CPU oracle on this machine's host cores (a reported baseline, not a target)
     if not args.no_cpu_baseline:
         from oracle import slide_oracle as oracle
-        nb, reps = 64, 4                          # bounded sample: the whole workload, four times
+        nb, reps = 64, 8                          # bounded sample: the whole workload, eight times (about 17 core-seconds)
         n = {x: data[x][:nb].double().numpy() for x in ("q", "k", "v")}
         wkm = oracle.reparam(data["wk_learned"].double().numpy(), ksize)
         wvm = oracle.reparam(data["wv_learned"].double().numpy(), ksize)
