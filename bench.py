@@ -219,24 +219,51 @@ def main():
         outs = (torch.empty_like(sets[0]["q"]), torch.empty_like(sets[0]["q"]),
                 torch.empty_like(sets[0]["q"]), torch.empty_like(wk), torch.empty_like(wv),
                 torch.empty_like(bias))
-        n_train = max(3, min(20, args.steps // 10))
+        need_f = sa.slide_attn_workspace_bytes(wl5.B, wl5.H, wl5.W, wl5.C, wl5.heads, wl5.ksize,
+                                               torch.bfloat16, False)
+        ws_f = torch.empty(max(need_f, 1), dtype=torch.uint8, device=dev)
+        n_train = max(4, min(20, args.steps // 10)) // 2 * 2
 
         def train_step(i):
             s = sets[i % 2]
             sa.slide_reparam(wk_l, wk)
             sa.slide_reparam(wv_l, wv)
-            sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, wl5.heads, wl5.ksize, out=s["out"])
+            sa.slide_attn_fwd(s["q"], s["k"], s["v"], wk, wv, bias, wl5.heads, wl5.ksize, out=s["out"],
+                              workspace=ws_f)
             sa.slide_attn_bwd(s["dout"], s["q"], s["k"], s["v"], wk, wv, bias, wl5.heads, wl5.ksize,
                               workspace=ws, outputs=outs)
 
         for i in range(2):
             train_step(i)
         torch.cuda.synchronize()
+        want_dq = outs[0].clone()                       # eager result of set 1, the last one run
+        # two steps (one per input set) captured in a HIP graph and replayed, like the forward;
+        # eager launches if the capture fails or a replay does not reproduce the eager result
+        train_graph = None
+        try:
+            g5 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g5):
+                train_step(0)
+                train_step(1)
+            for _ in range(2):
+                outs[0].zero_()
+                g5.replay()
+                torch.cuda.synchronize()
+                if not torch.equal(outs[0], want_dq):
+                    raise RuntimeError("graph replay differs from the eager step")
+            train_graph = g5
+        except Exception as exc:                        # noqa: BLE001
+            print("bench.py: training steps launched eagerly (%s)" % exc, file=sys.stderr)
+            torch.cuda.synchronize()
         a = torch.cuda.Event(enable_timing=True)
         b = torch.cuda.Event(enable_timing=True)
         a.record()
-        for i in range(n_train):
-            train_step(i)
+        if train_graph is not None:
+            for _ in range(n_train // 2):
+                train_graph.replay()
+        else:
+            for i in range(n_train):
+                train_step(i)
         b.record()
         torch.cuda.synchronize()
         tms = a.elapsed_time(b) / n_train
@@ -244,6 +271,8 @@ def main():
         result["training"] = {"workload": "stage1_bf16_train: B=128 H=W=56 C=64 heads=2 ksize=3, fwd+bwd",
                               "ms_per_step": tms, "steps": n_train,
                               "value": pxh5 / (tms * 1e-3) / 1e9, "unit": "Gpixel*head/s",
+                              "launch": ("hip graph of 2 steps, replayed" if train_graph is not None
+                                         else "eager"),
                               "workspace_bytes": need}
         del sets, ws, outs
         torch.cuda.empty_cache()
