@@ -109,6 +109,33 @@ int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v
                    int B, int H, int W, int C, int heads, int ksize, int dtype,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Training form (Sec. 4.3, Fig. 4(1)): the deformed shifting module with its two parallel
+ * paths, the fixed one-hot shift and the learned depthwise kernel, before they are merged.
+ * These two entry points take the LEARNED kernels wk_learned, wv_learned (float32
+ * [C,S,ksize,ksize]) and add the shift path where the kernels are used,
+ *     Ks[c,s] = k[c, pixel + offset(s)] + sum_t wk_learned[c,s,t] * k[c, pixel + offset(t)],
+ * so a training step needs no slide_reparam call.  Results equal slide_attn_fwd /
+ * slide_attn_bwd on slide_reparam(wk_learned), slide_reparam(wv_learned) up to rounding
+ * (identical where the kernels enter as float32).  All other arguments, the workspace size
+ * and the error behaviour are those of slide_attn_fwd / slide_attn_bwd.
+ * accumulate != 0: dwk, dwv and dbias are added to what the arrays hold instead of
+ * overwriting it (gradient accumulation over micro-batches; the caller zeroes them before
+ * the first one); dq, dk, dv are always overwritten.
+ */
+int slide_attn_fwd_two_branch(const void* q, const void* k, const void* v,
+                              const float* wk_learned, const float* wv_learned, const float* bias,
+                              void* out, float* lse,
+                              int B, int H, int W, int C, int heads, int ksize, int dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+int slide_attn_bwd_two_branch(const void* dout, const void* q, const void* k, const void* v,
+                              const float* wk_learned, const float* wv_learned, const float* bias,
+                              const void* out, const float* lse,
+                              void* dq, void* dk, void* dv,
+                              float* dwk, float* dwv, float* dbias, int accumulate,
+                              int B, int H, int W, int C, int heads, int ksize, int dtype,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* slide_status_string(int status);
 

@@ -10,7 +10,9 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     slide_attn_bwd,
+    slide_attn_bwd_two_branch,
     slide_attn_fwd,
+    slide_attn_fwd_two_branch,
     slide_attn_fwd_path,
     slide_attn_workspace_bytes,
     slide_reparam,

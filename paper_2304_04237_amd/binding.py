@@ -48,6 +48,10 @@ def load_library():
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_bwd.restype = i
     lib.slide_attn_bwd.argtypes = [_vp] * 15 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_fwd_two_branch.restype = i
+    lib.slide_attn_fwd_two_branch.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_bwd_two_branch.restype = i
+    lib.slide_attn_bwd_two_branch.argtypes = [_vp] * 15 + [i] * 8 + [_vp, sz, _vp]
     _lib = lib
     return lib
 
@@ -113,6 +117,17 @@ def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None
 
     lse: optional float32 [B, heads, H, W] tensor that receives the log of the softmax
     denominator per pixel and head."""
+    return _fwd(load_library().slide_attn_fwd, q, k, v, wk, wv, bias, heads, ksize, out, workspace, lse)
+
+
+def slide_attn_fwd_two_branch(q, k, v, wk_learned, wv_learned, bias, heads, ksize, out=None,
+                              workspace=None, lse=None):
+    """The same with the LEARNED kernels of the training form (shift path added inside)."""
+    return _fwd(load_library().slide_attn_fwd_two_branch, q, k, v, wk_learned, wv_learned, bias, heads,
+                ksize, out, workspace, lse)
+
+
+def _fwd(entry, q, k, v, wk, wv, bias, heads, ksize, out, workspace, lse):
     lib = load_library()
     B, C, H, W = q.shape
     code = _dtype_code(q)
@@ -128,11 +143,11 @@ def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib.slide_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
-                              _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
-                              _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
-                              _dev(lse, "lse", torch.float32),
-                              B, H, W, C, heads, ksize, code, ws_ptr, ws_bytes, _stream()))
+    _check(entry(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                 _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                 _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
+                 _dev(lse, "lse", torch.float32),
+                 B, H, W, C, heads, ksize, code, ws_ptr, ws_bytes, _stream()))
     return out
 
 
@@ -141,6 +156,19 @@ def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, ou
     """Returns (dq, dk, dv, dwk, dwv, dbias); dbias is None when bias is None.
 
     out, lse: the forward's results, if the caller kept them (optional; passed through)."""
+    return _bwd(False, False, dout, q, k, v, wk, wv, bias, heads, ksize, workspace, outputs, out, lse)
+
+
+def slide_attn_bwd_two_branch(dout, q, k, v, wk_learned, wv_learned, bias, heads, ksize, workspace=None,
+                              outputs=None, out=None, lse=None, accumulate=False):
+    """Backward of the training form.  accumulate: add dwk, dwv, dbias to what `outputs` holds."""
+    if accumulate and outputs is None:
+        raise SlideAttnError("accumulate needs the gradient tensors in `outputs`")
+    return _bwd(True, accumulate, dout, q, k, v, wk_learned, wv_learned, bias, heads, ksize, workspace,
+                outputs, out, lse)
+
+
+def _bwd(two_branch, accumulate, dout, q, k, v, wk, wv, bias, heads, ksize, workspace, outputs, out, lse):
     lib = load_library()
     B, C, H, W = q.shape
     code = _dtype_code(q)
@@ -156,14 +184,17 @@ def slide_attn_bwd(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, ou
     need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 1)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
-    _check(lib.slide_attn_bwd(_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
-                              _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
-                              _dev(bias, "bias", torch.float32),
-                              _dev(out, "out", q.dtype), _dev(lse, "lse", torch.float32),
-                              _dev(dq, "dq", q.dtype), _dev(dk, "dk", q.dtype), _dev(dv, "dv", q.dtype),
-                              _dev(dwk, "dwk", torch.float32), _dev(dwv, "dwv", torch.float32),
-                              _dev(dbias, "dbias", torch.float32),
-                              B, H, W, C, heads, ksize, code,
-                              workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                              _stream()))
+    ptrs = (_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+            _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+            _dev(bias, "bias", torch.float32),
+            _dev(out, "out", q.dtype), _dev(lse, "lse", torch.float32),
+            _dev(dq, "dq", q.dtype), _dev(dk, "dk", q.dtype), _dev(dv, "dv", q.dtype),
+            _dev(dwk, "dwk", torch.float32), _dev(dwv, "dwv", torch.float32),
+            _dev(dbias, "dbias", torch.float32))
+    tail = (B, H, W, C, heads, ksize, code,
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream())
+    if two_branch:
+        _check(lib.slide_attn_bwd_two_branch(*ptrs, int(bool(accumulate)), *tail))
+    else:
+        _check(lib.slide_attn_bwd(*ptrs, *tail))
     return dq, dk, dv, dwk, dwv, dbias

@@ -59,11 +59,10 @@ extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ks
     return slide::fwd_mfma_supported(p) ? 2 : (slide::fwd_mfma5_supported(p) ? 3 : 1);
 }
 
-extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
-                              const float* wk, const float* wv, const float* bias, void* out,
-                              float* lse,
-                              int B, int H, int W, int C, int heads, int ksize, int dtype,
-                              void* workspace, size_t workspace_bytes, void* stream)
+static int forward(const void* q, const void* k, const void* v,
+                   const float* wk, const float* wv, const float* bias, void* out, float* lse,
+                   int B, int H, int W, int C, int heads, int ksize, int dtype, int two_branch,
+                   void* workspace, size_t workspace_bytes, void* stream)
 {
     int st = check_problem(B, H, W, C, heads, ksize, dtype);
     if (st != SLIDE_OK) return st;
@@ -73,6 +72,7 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
         !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(lse, 4))
         return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, ksize, dtype};
+    p.two_branch = two_branch;
     hipError_t e;
     if (slide::fwd_mfma_supported(p)) {
         if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
@@ -87,12 +87,33 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }
 
-extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
-                              const float* wk, const float* wv, const float* bias,
-                              const void* out, const float* lse,
-                              void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias, void* out,
+                              float* lse,
                               int B, int H, int W, int C, int heads, int ksize, int dtype,
                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    return forward(q, k, v, wk, wv, bias, out, lse, B, H, W, C, heads, ksize, dtype, 0,
+                   workspace, workspace_bytes, stream);
+}
+
+extern "C" int slide_attn_fwd_two_branch(const void* q, const void* k, const void* v,
+                                         const float* wk_learned, const float* wv_learned,
+                                         const float* bias, void* out, float* lse,
+                                         int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    return forward(q, k, v, wk_learned, wv_learned, bias, out, lse, B, H, W, C, heads, ksize, dtype, 1,
+                   workspace, workspace_bytes, stream);
+}
+
+static int backward(const void* dout, const void* q, const void* k, const void* v,
+                    const float* wk, const float* wv, const float* bias,
+                    const void* out, const float* lse,
+                    void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                    int B, int H, int W, int C, int heads, int ksize, int dtype,
+                    int two_branch, int accumulate,
+                    void* workspace, size_t workspace_bytes, void* stream)
 {
     int st = check_problem(B, H, W, C, heads, ksize, dtype);
     if (st != SLIDE_OK) return st;
@@ -107,8 +128,33 @@ extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, co
         !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 4) || !aligned_to(lse, 4))
         return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, ksize, dtype};
+    p.two_branch = two_branch;
+    p.accumulate = accumulate != 0;
     if (!workspace || workspace_bytes < slide::bwd_generic_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
     hipError_t e = slide::launch_bwd_generic(p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv,
                                              dbias, workspace, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
+extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
+                              const float* wk, const float* wv, const float* bias,
+                              const void* out, const float* lse,
+                              void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                              int B, int H, int W, int C, int heads, int ksize, int dtype,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    return backward(dout, q, k, v, wk, wv, bias, out, lse, dq, dk, dv, dwk, dwv, dbias,
+                    B, H, W, C, heads, ksize, dtype, 0, 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int slide_attn_bwd_two_branch(const void* dout, const void* q, const void* k, const void* v,
+                                         const float* wk_learned, const float* wv_learned,
+                                         const float* bias, const void* out, const float* lse,
+                                         void* dq, void* dk, void* dv,
+                                         float* dwk, float* dwv, float* dbias, int accumulate,
+                                         int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    return backward(dout, q, k, v, wk_learned, wv_learned, bias, out, lse, dq, dk, dv, dwk, dwv, dbias,
+                    B, H, W, C, heads, ksize, dtype, 1, accumulate, workspace, workspace_bytes, stream);
 }

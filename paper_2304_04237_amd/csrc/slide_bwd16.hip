@@ -31,8 +31,10 @@ constexpr int REC_BYTES = 32;                       // 16 halves per halo pixel 
 // merged weights (one-hot shift included) for the shifts of operand slots 4g+2y and 4g+2y+1.
 constexpr int IMG_DWORDS = 2 * S * 2 * 64 * 2;      // 4608
 
+// idw = 1: wk, wv are the learned kernels of the two-branch form and the fixed shift path
+// (weight 1 where shift and tap coincide) is added here; 0: merged kernels
 __device__ __forceinline__ void prep_dkdv_weights(const float* __restrict__ wk, const float* __restrict__ wv,
-                                                  uint32_t* __restrict__ image, int t, int m)
+                                                  uint32_t* __restrict__ image, int t, int m, float idw)
 {
     uint32_t* img = image + (long)m * IMG_DWORDS;
     for (int idx = threadIdx.x; idx < 2 * 2 * 128; idx += 256) {
@@ -43,7 +45,7 @@ __device__ __forceinline__ void prep_dkdv_weights(const float* __restrict__ wk, 
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_row(4 * g + 2 * y + h);
-            if (s >= 0) d[h] = w[((long)c * S + s) * S + t];
+            if (s >= 0) d[h] = w[((long)c * S + s) * S + t] + ((s == t) ? idw : 0.0f);
         }
         img[((side * S + t) * 2 + j) * 128 + lane * 2 + y] = pack_half(d[0], d[1]);
     }
@@ -250,7 +252,7 @@ constexpr float G_SCALE = 0.0625f, W_SCALE = 16.0f;
 
 __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk, const float* __restrict__ wv,
                                                    const float* __restrict__ bias, uint32_t* __restrict__ image,
-                                                   int t, int m)
+                                                   int t, int m, float idw)
 {
     uint32_t* img = image + (long)m * PX_IMG_DWORDS;
     const int tid = threadIdx.x;
@@ -263,10 +265,11 @@ __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk,
         float k0 = 0.0f, k1 = 0.0f, v0 = 0.0f, v1 = 0.0f;
         if (s >= 0) {
             const int c = m * D + 8 * g + 2 * y;
-            k0 = wk[((long)c * S + s) * S + t] * W_SCALE;
-            k1 = wk[((long)(c + 1) * S + s) * S + t] * W_SCALE;
-            v0 = wv[((long)c * S + s) * S + t] * W_SCALE;
-            v1 = wv[((long)(c + 1) * S + s) * S + t] * W_SCALE;
+            const float id = (s == t) ? idw : 0.0f;
+            k0 = (wk[((long)c * S + s) * S + t] + id) * W_SCALE;
+            k1 = (wk[((long)(c + 1) * S + s) * S + t] + id) * W_SCALE;
+            v0 = (wv[((long)c * S + s) * S + t] + id) * W_SCALE;
+            v1 = (wv[((long)(c + 1) * S + s) * S + t] + id) * W_SCALE;
         }
         img[PX_A1K + t * 256 + tid] = pack_half(k0, k1);
         img[PX_A1V + t * 256 + tid] = pack_half(v0, v1);
@@ -282,7 +285,7 @@ __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk,
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_row(4 * g + 2 * y + h);
-            if (s >= 0) d[h] = wk[((long)c * S + s) * S + tap];
+            if (s >= 0) d[h] = wk[((long)c * S + s) * S + tap] + ((s == tap) ? idw : 0.0f);
         }
         img[PX_A2K + u * 128 + (tid & 127)] = pack_half(d[0], d[1]);
     }
@@ -299,10 +302,10 @@ __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk,
 __global__ void __launch_bounds__(256)
 prep_bwd_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
                         const float* __restrict__ bias, uint32_t* __restrict__ pixel_image,
-                        uint32_t* __restrict__ dkdv_image)
+                        uint32_t* __restrict__ dkdv_image, float idw)
 {
-    if (blockIdx.z == 0) prep_pixel_weights(wk, wv, bias, pixel_image, blockIdx.x, blockIdx.y);
-    else                 prep_dkdv_weights(wk, wv, dkdv_image, blockIdx.x, blockIdx.y);
+    if (blockIdx.z == 0) prep_pixel_weights(wk, wv, bias, pixel_image, blockIdx.x, blockIdx.y, idw);
+    else                 prep_dkdv_weights(wk, wv, dkdv_image, blockIdx.x, blockIdx.y, idw);
 }
 
 struct PixelArgs {
@@ -548,7 +551,7 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
     const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
     uint32_t* image = (uint32_t*)image_ws;
     hipLaunchKernelGGL(prep_bwd_weights_kernel, dim3(S, (unsigned)p.heads, 2), dim3(256), 0, st,
-                       wk, wv, bias, image, (uint32_t*)dkdv_image_ws);
+                       wk, wv, bias, image, (uint32_t*)dkdv_image_ws, p.two_branch ? 1.0f : 0.0f);
     PixelArgs a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q;
     a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;

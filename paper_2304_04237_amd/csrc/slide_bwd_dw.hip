@@ -428,7 +428,8 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     }
     hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
     const long side = (long)p.C * 81;
-    return launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, a.dbias_partial, dbias, p.heads * 9, st);
+    return launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, a.dbias_partial, dbias, p.heads * 9,
+                                p.accumulate, st);
 }
 
 }  // namespace slide

@@ -46,15 +46,16 @@ constexpr int IMG_A1 = 0, IMG_A2 = 2304, IMG_BIAS = 4608, IMG_DWORDS = 4624;
 
 // ------------------------------------------------------------------ weight preparation
 // Dword idx < IMG_BIAS of a head's operand image is pack_half(f(w[off0]), f(w[off1])) with
-// f(x) = ok ? (x - sub) * scale : 0 and w the merged K (A1 part) or V (A2 part) kernel
-// [C, 9, 3, 3] of float32: the learned part is the merged kernel minus the one-hot.  The
-// loads are unconditional so that a caller can issue many of them before using any.
+// f(x) = ok ? (x - sub) * scale : 0 and w the K (A1 part) or V (A2 part) kernel [C, 9, 3, 3]
+// of float32.  sub is 0 for merged kernels; for the learned kernels of the two-branch form
+// it is -1 where shift and tap coincide (idw = 1: the fixed shift path joins the operand).
+// The loads are unconditional so that a caller can issue many of them before using any.
 struct ImageSource {
     int off0, off1;          // element offsets into the kernel tensor
     float sub0, sub1, scale;
     bool ok0, ok1, from_v;
 };
-__device__ __forceinline__ ImageSource image_source(int m, int idx)
+__device__ __forceinline__ ImageSource image_source(int m, int idx, float idw)
 {
     ImageSource r;
     if (idx < IMG_A2) {
@@ -66,7 +67,7 @@ __device__ __forceinline__ ImageSource image_source(int m, int idx)
         const int c = m * D + 8 * g + 2 * y;
         r.off0 = (c * S + max(s, 0)) * S + t;
         r.off1 = r.off0 + S * S;
-        r.sub0 = r.sub1 = 0.0f;
+        r.sub0 = r.sub1 = (s == t) ? -idw : 0.0f;
         r.ok0 = r.ok1 = s >= 0;
         r.scale = WK_SCALE;
         r.from_v = false;
@@ -83,7 +84,8 @@ __device__ __forceinline__ ImageSource image_source(int m, int idx)
         const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
         r.off0 = (c * S + max(s0, 0)) * S + tap;
         r.off1 = (c * S + max(s1, 0)) * S + tap;
-        r.sub0 = r.sub1 = 0.0f;
+        r.sub0 = (s0 == tap) ? -idw : 0.0f;
+        r.sub1 = (s1 == tap) ? -idw : 0.0f;
         r.ok0 = s0 >= 0;
         r.ok1 = s1 >= 0;
         r.scale = 1.0f;
@@ -107,12 +109,12 @@ __device__ __forceinline__ uint32_t image_bias(const float* __restrict__ bias, i
 // grid = (9, heads), block = 256: the images in global memory, for the one-tile-per-block kernel
 __global__ void __launch_bounds__(256)
 prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
-                    const float* __restrict__ bias, uint32_t* __restrict__ image)
+                    const float* __restrict__ bias, uint32_t* __restrict__ image, float idw)
 {
     const int m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
     for (int idx = blockIdx.x * 256 + threadIdx.x; idx < IMG_BIAS; idx += gridDim.x * 256) {
-        const ImageSource r = image_source(m, idx);
+        const ImageSource r = image_source(m, idx, idw);
         const float* w = r.from_v ? wv : wk;
         img[idx] = image_value(r, w[r.off0], w[r.off1]);
     }
@@ -129,6 +131,7 @@ struct FwdArgs {
     int buf_stride;          // bytes between the two tile buffers (pipelined kernel)
     int a_base;              // byte offset of the per-wave scratch (1 KB per wave)
     float scale_log2e;
+    float idw;               // 1: wk, wv are the learned kernels of the two-branch form; 0: merged
 };
 
 // q of one pixel: 8 channels as bf16 patterns (one per dword) -> halves divided by 16
@@ -440,7 +443,7 @@ constexpr int HEAD_W = D * S * S;                         // floats of one head 
 constexpr int IMG_RAW_BYTES = 2 * HEAD_W * 4;             // 20736
 template <int THREADS>
 __device__ __forceinline__ void build_image(const float* __restrict__ wk, const float* __restrict__ wv,
-                                            const float* __restrict__ bias, int m, uint32_t* dst,
+                                            const float* __restrict__ bias, int m, float idw, uint32_t* dst,
                                             float* raw, int tid)
 {
     constexpr int N = IMG_BIAS / THREADS, CHUNKS = HEAD_W / 4;
@@ -454,7 +457,7 @@ __device__ __forceinline__ void build_image(const float* __restrict__ wk, const 
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < N; ++i) {
-        const ImageSource src = image_source(m, tid + i * THREADS);
+        const ImageSource src = image_source(m, tid + i * THREADS, idw);
         const float* w = raw + (src.from_v ? HEAD_W : 0) - m * HEAD_W;
         dst[tid + i * THREADS] = image_value(src, w[src.off0], w[src.off1]);
     }
@@ -481,7 +484,7 @@ fwd16_pipe_kernel(const FwdArgs a)
     Tile tcur = decode_tile(a.g, cur);
     // The block builds the operand image of its head in the second tile buffer, which is
     // free until the first pass (no separate preparation kernel on this path).
-    build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)(smem + a.buf_stride),
+    build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, a.idw, (uint32_t*)(smem + a.buf_stride),
                          (float*)(smem + a.buf_stride + IMG_RAW_AT), tid);
     // the first tile is staged without overlap, two shares per lane in flight
     {
@@ -531,7 +534,7 @@ fwd16_pipe_kernel(const FwdArgs a)
         __syncthreads();                                // buf is complete, buf_next is free
         if (tcur.m != m_loaded) {
             if (it > 0) {                               // the block moves on to another head
-                build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, (uint32_t*)buf_next,
+                build_image<THREADS>(a.wk, a.wv, a.bias, tcur.m, a.idw, (uint32_t*)buf_next,
                                      (float*)(buf_next + IMG_RAW_AT), tid);
                 __syncthreads();
             }
@@ -653,7 +656,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     uint32_t* image = (uint32_t*)workspace;
     if (!pipelined)
         hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
-                           wk, wv, bias, image);
+                           wk, wv, bias, image, p.two_branch ? 1.0f : 0.0f);
     FwdArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.lse = lse; a.image = image;
@@ -663,6 +666,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     a.buf_stride = t.buf_bytes;
     a.a_base = (pipelined ? 2 : 1) * t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.idw = p.two_branch ? 1.0f : 0.0f;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)fwd16_kernel<FWD_WAVES>,

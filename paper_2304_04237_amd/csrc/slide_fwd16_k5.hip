@@ -46,8 +46,9 @@ __host__ __device__ constexpr int shift_of_slot5(int slot)
 // grid = (25, heads), block = 256
 __global__ void __launch_bounds__(256)
 prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
-                     const float* __restrict__ bias, uint32_t* __restrict__ image)
-{
+                     const float* __restrict__ bias, uint32_t* __restrict__ image, float idw)
+{   // idw = 1: wk, wv are the learned kernels of the two-branch form, the fixed shift path
+    // (weight 1 where shift and tap coincide) is added here; 0: merged kernels
     const int t = blockIdx.x, m = blockIdx.y;
     uint32_t* img = image + (long)m * IMG_DWORDS;
     const int tid = threadIdx.x;
@@ -60,8 +61,9 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
         float d0 = 0.0f, d1 = 0.0f;
         if (s >= 0) {
             const int c = m * D + 8 * g + 2 * y;
-            d0 = wk[((long)c * S5 + s) * S5 + t] * WK_SCALE;
-            d1 = wk[((long)(c + 1) * S5 + s) * S5 + t] * WK_SCALE;
+            const float id = (s == t) ? idw : 0.0f;
+            d0 = (wk[((long)c * S5 + s) * S5 + t] + id) * WK_SCALE;
+            d1 = (wk[((long)(c + 1) * S5 + s) * S5 + t] + id) * WK_SCALE;
         }
         img[IMG_A1 + (t * 2 + tile) * 256 + tid] = pack_half(d0, d1);
     }
@@ -80,7 +82,7 @@ prep_weights5_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
         float d[2] = {0.0f, 0.0f};
         for (int h = 0; h < 2; ++h) {
             const int s = shift_of_slot5(8 * g + 2 * y + h);
-            if (s >= 0) d[h] = wv[((long)c * S5 + s) * S5 + tap];
+            if (s >= 0) d[h] = wv[((long)c * S5 + s) * S5 + tap] + ((s == tap) ? idw : 0.0f);
         }
         img[IMG_A2 + u * 256 + tid] = pack_half(d[0], d[1]);
     }
@@ -307,7 +309,7 @@ hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, cons
     const TilePlan t = plan_tiles(p, TILE_BUDGET, 64, 64, 0, WAVES);
     uint32_t* image = (uint32_t*)workspace;
     hipLaunchKernelGGL(prep_weights5_kernel, dim3(S5, (unsigned)p.heads), dim3(256), 0, st,
-                       wk, wv, bias, image);
+                       wk, wv, bias, image, p.two_branch ? 1.0f : 0.0f);
     Fwd5Args a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.lse = lse; a.image = image;

@@ -60,16 +60,17 @@ __device__ __forceinline__ void load_window(const T* __restrict__ plane, int i, 
     }
 }
 
-// deformed shift of one channel at one pixel: shifted[s] = sum_t w[s][t] * win[t]
+// deformed shift of one channel at one pixel: shifted[s] = sum_t w[s][t] * win[t], plus the
+// fixed shift path idw * win[s] (idw = 1 when w is the learned kernel of the two-branch form)
 template <int KS>
 __device__ __forceinline__ void apply_kernels(const float* __restrict__ w_c,
                                               const float (&win)[KS * KS],
-                                              float (&shifted)[KS * KS])
+                                              float (&shifted)[KS * KS], float idw)
 {
     constexpr int S = KS * KS;
 #pragma unroll
     for (int s = 0; s < S; ++s) {
-        float acc = 0.0f;
+        float acc = idw * win[s];
 #pragma unroll
         for (int t = 0; t < S; ++t) acc = fmaf(w_c[s * S + t], win[t], acc);
         shifted[s] = acc;
@@ -83,7 +84,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
                                                   const float* __restrict__ wk,
                                                   const float* __restrict__ bias,
                                                   int b, int m, int i, int j, int H, int W, int C,
-                                                  int d, float (&a)[KS * KS], float& lse)
+                                                  int d, float idw, float (&a)[KS * KS], float& lse)
 {
     constexpr int S = KS * KS;
     const long HW = (long)H * W;
@@ -96,7 +97,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
         const T* kp = k + ((long)b * C + c) * HW;
         float win[S], ks[S];
         load_window<T, KS>(kp, i, j, H, W, win);
-        apply_kernels<KS>(wk + (long)c * S * S, win, ks);
+        apply_kernels<KS>(wk + (long)c * S * S, win, ks, idw);
         float qc = Elem<T>::load(q + ((long)b * C + c) * HW + pix);
 #pragma unroll
         for (int s = 0; s < S; ++s) dot[s] = fmaf(qc, ks[s], dot[s]);
@@ -123,7 +124,7 @@ __global__ void __launch_bounds__(256)
 fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                    const float* __restrict__ wk, const float* __restrict__ wv,
                    const float* __restrict__ bias, T* __restrict__ out, float* __restrict__ lse,
-                   int H, int W, int C, int heads)
+                   int H, int W, int C, int heads, float idw)
 {
     constexpr int S = KS * KS;
     const int d = C / heads;
@@ -134,7 +135,7 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a, lse_px);
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, idw, a, lse_px);
     if (lse) lse[((long)b * heads + m) * HW + pix] = lse_px;
 
     for (int cc = 0; cc < d; ++cc) {
@@ -142,7 +143,7 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
         const T* vp = v + ((long)b * C + c) * HW;
         float win[S], vs[S];
         load_window<T, KS>(vp, i, j, H, W, win);
-        apply_kernels<KS>(wv + (long)c * S * S, win, vs);
+        apply_kernels<KS>(wv + (long)c * S * S, win, vs, idw);
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(a[s], vs[s], acc);
@@ -158,7 +159,7 @@ static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, c
     dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
     hipLaunchKernelGGL((fwd_generic_kernel<T, KS>), grid, dim3(256), 0, st,
                        (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
-                       p.H, p.W, p.C, p.heads);
+                       p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     return hipGetLastError();
 }
 
@@ -200,7 +201,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
                  const T* __restrict__ v, const float* __restrict__ wk,
                  const float* __restrict__ wv, const float* __restrict__ bias,
                  T* __restrict__ dq, float* __restrict__ attn_ws, float* __restrict__ dl_ws,
-                 int H, int W, int C, int heads)
+                 int H, int W, int C, int heads, float idw)
 {
     constexpr int S = KS * KS;
     const int d = C / heads;
@@ -211,7 +212,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, a, lse_px);
+    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, idw, a, lse_px);
 
     float da[S];
 #pragma unroll
@@ -220,7 +221,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
         int c = m * d + cc;
         float win[S], vs[S];
         load_window<T, KS>(v + ((long)b * C + c) * HW, i, j, H, W, win);
-        apply_kernels<KS>(wv + (long)c * S * S, win, vs);
+        apply_kernels<KS>(wv + (long)c * S * S, win, vs, idw);
         float doc = Elem<T>::load(dout + ((long)b * C + c) * HW + pix);
 #pragma unroll
         for (int s = 0; s < S; ++s) da[s] = fmaf(doc, vs[s], da[s]);
@@ -241,7 +242,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
         int c = m * d + cc;
         float win[S], ks[S];
         load_window<T, KS>(k + ((long)b * C + c) * HW, i, j, H, W, win);
-        apply_kernels<KS>(wk + (long)c * S * S, win, ks);
+        apply_kernels<KS>(wk + (long)c * S * S, win, ks, idw);
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(dl[s], ks[s], acc);
@@ -259,7 +260,7 @@ __global__ void __launch_bounds__(256)
 bwd_dkdv_kernel(const T* __restrict__ dout, const T* __restrict__ q,
                 const float* __restrict__ wk, const float* __restrict__ wv,
                 const float* __restrict__ attn_ws, const float* __restrict__ dl_ws,
-                T* __restrict__ dk, T* __restrict__ dv, int H, int W, int C, int heads)
+                T* __restrict__ dk, T* __restrict__ dv, int H, int W, int C, int heads, float idw)
 {
     constexpr int S = KS * KS, R = KS / 2, CH = 8;
     const int d = C / heads;
@@ -295,7 +296,7 @@ bwd_dkdv_kernel(const T* __restrict__ dout, const T* __restrict__ q,
                         const int c = m * d + c0 + e;
                         const float* wkc = wk + (long)c * S * S + t;
                         const float* wvc = wv + (long)c * S * S + t;
-                        float ck = 0.0f, cv = 0.0f;
+                        float ck = idw * dl[t], cv = idw * a[t];     // the fixed shift path: shift t reads tap t
 #pragma unroll
                         for (int s = 0; s < S; ++s) {
                             ck = fmaf(wkc[s * S], dl[s], ck);
@@ -388,7 +389,8 @@ constexpr int RED_GROUPS = 16;
 __global__ void __launch_bounds__(64 * RED_GROUPS)
 bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
                      float* __restrict__ dwv, long side, int n_chunks,
-                     const float* __restrict__ bias_partial, float* __restrict__ dbias, int nbias)
+                     const float* __restrict__ bias_partial, float* __restrict__ dbias, int nbias,
+                     int accumulate)
 {
     __shared__ float part[RED_GROUPS][64];
     const int el = threadIdx.x & 63, grp = threadIdx.x >> 6;
@@ -415,9 +417,8 @@ bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
         float sum = part[0][el];
 #pragma unroll
         for (int g2 = 1; g2 < RED_GROUPS; ++g2) sum += part[g2][el];
-        if (bias_job) dbias[e] = sum;
-        else if (e < side) dwk[e] = sum;
-        else dwv[e - side] = sum;
+        float* dst = bias_job ? dbias + e : (e < side ? dwk + e : dwv + (e - side));
+        *dst = accumulate ? *dst + sum : sum;
     }
 }
 
@@ -425,7 +426,7 @@ bwd_dw_reduce_kernel(const float* __restrict__ partial, float* __restrict__ dwk,
 // fixed-order tree reduction.
 __global__ void __launch_bounds__(256)
 bwd_dbias_kernel(const float* __restrict__ dl_ws, float* __restrict__ dbias,
-                 int B, long HW, int heads, int S)
+                 int B, long HW, int heads, int S, int accumulate)
 {
     const int m = blockIdx.x / S, s = blockIdx.x % S;
     float acc = 0.0f;
@@ -440,7 +441,7 @@ bwd_dbias_kernel(const float* __restrict__ dl_ws, float* __restrict__ dbias,
         if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) dbias[blockIdx.x] = red[0];
+    if (threadIdx.x == 0) dbias[blockIdx.x] = accumulate ? dbias[blockIdx.x] + red[0] : red[0];
 }
 
 static int dw_chunks(const Problem& p)
@@ -455,12 +456,13 @@ static int dw_chunks(const Problem& p)
 }
 
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
-                                const float* bias_partial, float* dbias, int nbias, hipStream_t st)
+                                const float* bias_partial, float* dbias, int nbias, int accumulate,
+                                hipStream_t st)
 {
     if (!dbias) nbias = 0;
     const unsigned blocks = (unsigned)((2 * side + 63) / 64 + (nbias + 63) / 64);
     hipLaunchKernelGGL(bwd_dw_reduce_kernel, dim3(blocks), dim3(64 * RED_GROUPS),
-                       0, st, partial, dwk, dwv, side, n_chunks, bias_partial, dbias, nbias);
+                       0, st, partial, dwk, dwv, side, n_chunks, bias_partial, dbias, nbias, accumulate);
     return hipGetLastError();
 }
 
@@ -514,7 +516,7 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     } else
         hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
                            (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
-                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads);
+                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
         hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
@@ -522,7 +524,7 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     } else
         hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
                            (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
-                           p.H, p.W, p.C, p.heads);
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     if (half_ws) {
         // kernel and bias gradients on the matrix cores
         return launch_bwd_dw_mfma(p, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias, st);
@@ -535,10 +537,10 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
                        (const T*)dout, (const T*)q, (const T*)k, (const T*)v, attn_ws, dl_ws,
                        partial, p.B, p.H, p.W, p.C, p.heads, per_chunk);
     const long side = (long)p.C * S * S;
-    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, nullptr, nullptr, 0, st);
+    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, nullptr, nullptr, 0, p.accumulate, st);
     if (dbias)
         hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
-                           dl_ws, dbias, p.B, p.plane(), p.heads, S);
+                           dl_ws, dbias, p.B, p.plane(), p.heads, S, p.accumulate);
     return hipGetLastError();
 }
 

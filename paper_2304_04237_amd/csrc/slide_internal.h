@@ -9,6 +9,11 @@ namespace slide {
 
 struct Problem {
     int B, H, W, C, heads, ksize, dtype;
+    // the kernels passed in are the LEARNED ones of the two-branch (training) form: the fixed
+    // shift path is added where they are used (Sec. 4.3, Fig. 4(1)); 0: merged kernels
+    int two_branch = 0;
+    // backward: add the kernel and bias gradients to what dwk, dwv, dbias hold (micro-batches)
+    int accumulate = 0;
     int d() const { return C / heads; }
     int S() const { return ksize * ksize; }
     long plane() const { return (long)H * W; }
@@ -28,7 +33,8 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
 // adds n_chunks partial sums per entry in a fixed order; bias_partial [n_chunks][nbias] -> dbias
 // in the same launch (dbias may be null)
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
-                                const float* bias_partial, float* dbias, int nbias, hipStream_t st);
+                                const float* bias_partial, float* dbias, int nbias, int accumulate,
+                                hipStream_t st);
 
 // ---- matrix-core kernel/bias gradients (slide_bwd_dw.hip): bf16, d == 32, ksize 3, W % 8 == 0
 bool bwd_dw_mfma_supported(const Problem& p);

@@ -29,6 +29,7 @@ def declared_functions():
 def test_header_declares_the_expected_calls():
     names = declared_functions()
     for required in ("slide_reparam", "slide_attn_fwd", "slide_attn_bwd",
+                     "slide_attn_fwd_two_branch", "slide_attn_bwd_two_branch",
                      "slide_attn_workspace_bytes", "slide_status_string"):
         assert required in names
 
@@ -90,6 +91,23 @@ def test_backward_rejects_bad_arguments_on_the_host(lib):
     assert lib.slide_attn_bwd(*given, *shape, p, need, None) == 6             # out given but misaligned
     shape_bad = [1, 14, 14, 64, 5, 3, 0]
     assert lib.slide_attn_bwd(*args13, *shape_bad, p, need, None) == 2
+
+
+def test_two_branch_entry_points_check_arguments_like_the_merged_ones(lib):
+    p = ctypes.c_void_p(0x1000)
+    fwd = lib.slide_attn_fwd_two_branch
+    # none of these may reach a kernel launch: the pointers are not real device memory
+    assert fwd(p, p, p, p, p, p, p, None, 1, 14, 14, 64, 3, 3, 0, None, 0, None) == 2   # C % heads != 0
+    assert fwd(p, p, p, None, p, p, p, None, 1, 14, 14, 64, 2, 3, 0, None, 0, None) == 1  # wk_learned NULL
+    assert fwd(p, p, p, p, p, p, p, None, 64, 56, 56, 64, 2, 3, 1, None, 0, None) == 4    # needs its workspace
+    bwd = lib.slide_attn_bwd_two_branch
+    args = [p] * 7 + [None, None] + [p] * 6
+    shape = [1, 14, 14, 64, 2, 3, 0]
+    need = lib.slide_attn_workspace_bytes(*shape, 1)
+    assert bwd(*args, 1, *shape, None, 0, None) == 4                      # no workspace
+    assert bwd(*args, 0, *[1, 14, 14, 64, 5, 3, 0], p, need, None) == 2   # bad shape
+    bad = list(args); bad[12] = None
+    assert bwd(*bad, 1, *shape, p, need, None) == 1                       # dwk NULL
 
 
 def test_workspace_query(lib):

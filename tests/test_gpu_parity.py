@@ -194,6 +194,70 @@ def test_backward_matches_oracle(shape):
         assert torch.equal(a, b)
 
 
+TWO_BRANCH_SHAPES = [
+    # B, H, W, C, heads, ksize, dtype
+    (1, 14, 14, 64, 2, 3, "f32"),        # general kernels
+    (1, 6, 7, 24, 3, 5, "f32"),
+    (2, 9, 21, 64, 2, 3, "bf16"),        # matrix-core forward, one tile per block; float32 workspace
+    (2, 31, 24, 64, 2, 3, "bf16"),       # all backward kernels on the matrix cores
+    (2, 17, 13, 128, 4, 5, "bf16"),      # 5x5 matrix-core forward, general backward
+]
+
+
+@pytest.mark.parametrize("shape", TWO_BRANCH_SHAPES)
+def test_two_branch_form_matches_oracle(shape):
+    """Training form (Sec. 4.3, Fig. 4(1)): the entry points that take the learned kernels and
+    add the shift path themselves, against the oracle's two-branch forward and (the gradient
+    with respect to the learned kernel being that with respect to the merged one) its backward."""
+    B, H, W, C, heads, ksize, dtype = shape
+    print("two-branch case", shape, flush=True)
+    d, g, n = gpu_problem(B, H, W, C, heads, ksize, dtype, seed=300 + H + W)
+    dev = g["q"].device
+    wk_l, wv_l = d["wk_learned"].to(dev), d["wv_learned"].to(dev)
+    lse = torch.empty((B, heads, H, W), dtype=torch.float32, device=dev)
+    out = sa.slide_attn_fwd_two_branch(g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, ksize, lse=lse)
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], d["wk_learned"].double().numpy(),
+                              d["wv_learned"].double().numpy(), n["bias"], heads, ksize,
+                              two_branch=True, return_lse=True)
+    check("out", dtype, out, ref)
+    check("lse", dtype, lse, ref_lse)
+    grads = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, ksize)
+    ref_g = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, ksize)
+    for name, got, want in zip(GRAD_NAMES, grads, ref_g):
+        check(name, dtype, got, want)
+    # accumulation over micro-batches: a second call adds the same parameter gradients again
+    # (x + x is exact), the activation gradients are overwritten
+    first = [t.clone() for t in grads]
+    again = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, ksize,
+                                         outputs=grads, accumulate=True)
+    for idx in range(3):
+        assert torch.equal(again[idx], first[idx])
+    for idx in range(3, 6):
+        assert torch.equal(again[idx], 2 * first[idx])
+
+
+def test_two_branch_full_size_forward():
+    """Stage-1 workload through the pipelined kernel, learned kernels in: whole planes of the
+    first and last batch item against the oracle's two-branch form."""
+    wl, d = synth.make_config_inputs(1)
+    dev = torch.device("cuda:0")
+    q, k, v = (d[x].to(dev).to(torch.bfloat16) for x in ("q", "k", "v"))
+    wk_l, wv_l, bias = d["wk_learned"].to(dev), d["wv_learned"].to(dev), d["bias"].to(dev)
+    out = sa.slide_attn_fwd_two_branch(q, k, v, wk_l, wv_l, bias, wl.heads, wl.ksize)
+    torch.cuda.synchronize()
+    out = out.float().cpu().numpy()
+    for b in (0, wl.B - 1):
+        sl = slice(b, b + 1)
+        ref = oracle.fwd(d["q"][sl].numpy(), d["k"][sl].numpy(), d["v"][sl].numpy(),
+                         d["wk_learned"].double().numpy(), d["wv_learned"].double().numpy(),
+                         d["bias"].double().numpy(), wl.heads, wl.ksize, two_branch=True)
+        assert np.abs(out[sl] - ref).max() <= 2e-2
+    # and it is the merged form's result up to the last bf16 bit (1 + w is formed in float32
+    # either way; a fused multiply-add in the operand preparation may round it differently)
+    merged = sa.slide_attn_fwd(q, k, v, sa.slide_reparam(wk_l), sa.slide_reparam(wv_l), bias, wl.heads, wl.ksize)
+    assert np.abs(merged.float().cpu().numpy() - out).max() <= 2.0 ** -7
+
+
 def test_forward_unaligned_parameters_and_activations():
     """Pointers that are aligned to their element size only (4 bytes for the kernels, 2 for
     the activations): the forward must not take the paths that need 16-byte alignment."""
