@@ -290,11 +290,20 @@ def main():
         for _ in range(reps):
             oracle.fwd(n["q"], n["k"], n["v"], wkm, wvm, bn, heads, ksize)
         dt = (time.perf_counter() - t1) / reps
+        cores = oracle.num_threads()
+        # the same loops on one thread, on the first four batch items
+        oracle.set_num_threads(1)
+        t1 = time.perf_counter()
+        oracle.fwd(n["q"][:4], n["k"][:4], n["v"][:4], wkm, wvm, bn, heads, ksize)
+        dt1 = time.perf_counter() - t1
+        oracle.set_num_threads(cores)
         result["cpu_baseline"] = {"value": nb * H * W * heads / dt / 1e9, "unit": "Gpixel*head/s",
-                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "cores": cores, "kind": "oracle",
                                   "sample": "forward of all %d batch items of the same workload, %d "
                                             "repetitions, fp64 C loops, OpenMP over (batch, head); "
-                                            "%.2f s wall each" % (nb, reps, dt)}
+                                            "%.2f s wall each" % (nb, reps, dt),
+                                  "value_one_thread": 4 * H * W * heads / dt1 / 1e9,
+                                  "sample_one_thread": "4 batch items, %.2f s" % dt1}
     print(json.dumps(result))
 
 
