@@ -52,7 +52,7 @@ constexpr int KP = 96;                // halves per staged row of k, v: 8 margin
 constexpr float IN_SCALE = 0.0625f;   // q and dO are staged divided by 16
 
 // LDS map (bytes)
-constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 28160
+constexpr int KH_BYTES = D * (R + 2) * KP * 2;            // 30720
 constexpr int QH_BYTES = D * R * QP * 2;                  // 12288
 constexpr int OFF_K = 0, OFF_V = OFF_K + KH_BYTES, OFF_Q = OFF_V + KH_BYTES,
               OFF_DO = OFF_Q + QH_BYTES, OFF_ZERO = OFF_DO + QH_BYTES,
