@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-train", action="store_true")
+    ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5],
+                    help="which bf16 benchmark configuration's forward to time (default 2 = stage 1, "
+                         "the configuration the metric is quoted on; the others are for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (batch items, heads and tiles are "
@@ -53,7 +56,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    wl, data = synth.make_config_inputs(1)
+    wl, data = synth.make_config_inputs(args.config - 1)
     B, H, W, C, heads, ksize = wl.B, wl.H, wl.W, wl.C, wl.heads, wl.ksize
     px_heads = B * H * W * heads
     esz = 2
@@ -172,7 +175,7 @@ def main():
     ms_per_step = total_ms / args.steps
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json" if args.config == 2 else "none")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("bytes_per_launch")
@@ -181,14 +184,17 @@ def main():
     launch_ms = fwd_graph_ms if fwd_graph_ms is not None else fwd_avg_ms
     achieved = alg_bytes / (launch_ms * 1e-3) / 1e9
     result = {
-        "metric": "slide-attn fwd Gpixel*head/s at 56x56 stage-1 (reparam + forward per step)",
+        "metric": ("slide-attn fwd Gpixel*head/s at 56x56 stage-1 (reparam + forward per step)"
+                   if args.config == 2 else
+                   "slide-attn fwd Gpixel*head/s, configuration %d (reparam + forward per step)" % args.config),
         "value": px_heads / (ms_per_step * 1e-3) / 1e9,
         "unit": "Gpixel*head/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "stage1_bf16_fwd: B=64 H=W=56 C=64 heads=2 head_dim=32 ksize=3",
+        "config": {"workload": "%s: B=%d H=%d W=%d C=%d heads=%d head_dim=%d ksize=%d"
+                               % (wl.name, B, H, W, C, heads, C // heads, ksize),
                    "inputs": "seeded N(0,1) q,k,v; N(0,0.02^2) learned kernels and bias",
                    "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path, "launch": launch,
                    "host_wall_ms_per_step": wall_ms / args.steps},
@@ -280,7 +286,7 @@ def main():
     # ---- CPU oracle on this machine's host cores (a reported baseline, not a target)
     if not args.no_cpu_baseline:
         from oracle import slide_oracle as oracle
-        nb, reps = 64, 8                          # bounded sample: the whole workload, eight times (about 17 core-seconds)
+        nb, reps = min(64, B), 8                  # bounded sample: the whole stage-1 workload, eight times (about 17 core-seconds)
         n = {x: data[x][:nb].double().numpy() for x in ("q", "k", "v")}
         wkm = oracle.reparam(data["wk_learned"].double().numpy(), ksize)
         wvm = oracle.reparam(data["wv_learned"].double().numpy(), ksize)
@@ -294,7 +300,8 @@ def main():
         # the same loops on one thread, on the first four batch items
         oracle.set_num_threads(1)
         t1 = time.perf_counter()
-        oracle.fwd(n["q"][:4], n["k"][:4], n["v"][:4], wkm, wvm, bn, heads, ksize)
+        n1 = min(4, nb)
+        oracle.fwd(n["q"][:n1], n["k"][:n1], n["v"][:n1], wkm, wvm, bn, heads, ksize)
         dt1 = time.perf_counter() - t1
         oracle.set_num_threads(cores)
         result["cpu_baseline"] = {"value": nb * H * W * heads / dt / 1e9, "unit": "Gpixel*head/s",
@@ -302,8 +309,8 @@ def main():
                                   "sample": "forward of all %d batch items of the same workload, %d "
                                             "repetitions, fp64 C loops, OpenMP over (batch, head); "
                                             "%.2f s wall each" % (nb, reps, dt),
-                                  "value_one_thread": 4 * H * W * heads / dt1 / 1e9,
-                                  "sample_one_thread": "4 batch items, %.2f s" % dt1}
+                                  "value_one_thread": n1 * H * W * heads / dt1 / 1e9,
+                                  "sample_one_thread": "%d batch items, %.2f s" % (n1, dt1)}
     print(json.dumps(result))
 
 

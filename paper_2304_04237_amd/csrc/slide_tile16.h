@@ -109,9 +109,9 @@ struct Tile {
 // List index -> tile.  Class A (full-height tiles) comes first so that dealing the list
 // round-robin to the blocks balances them (a persistent kernel may ask for class B first: its
 // blocks then start on a small tile, which shortens the part of the run where nothing
-// overlaps the first staging); inside a class tiles are ordered head, batch, column tile, row tile,
+// overlaps the first staging); inside a class tiles are ordered head, batch, row tile, column tile,
 // and consecutive queue indices are dealt to the 8 XCDs (blocks are dealt round-robin over
-// XCDs too), so vertically adjacent tiles are staged through the same L2 at about the same
+// XCDs too), so tiles adjacent in a plane are staged through the same L2 at about the same
 // time and a block rarely changes head.
 __device__ __forceinline__ Tile decode_tile(const TileGrid& a, int i)
 {
@@ -119,11 +119,13 @@ __device__ __forceinline__ Tile decode_tile(const TileGrid& a, int i)
     const bool cls_a = a.small_first ? i >= a.TB : i < a.TA;
     if (cls_a) { k = a.small_first ? i - a.TB : i; n_r = a.nA; hgt = a.th; row_base = 0; cnt = a.TA; }
     else       { k = a.small_first ? i : i - a.TA; n_r = a.nB; hgt = a.hb; row_base = a.nA * a.th; cnt = a.TB; }
-    if ((cnt & 7) == 0) k = (k & 7) * (cnt >> 3) + (k >> 3);
+    // (the last cnt % 8 tiles of a class keep their place)
+    const int per_xcd = cnt >> 3;
+    if (k < 8 * per_xcd) k = (k & 7) * per_xcd + (k >> 3);
     const int per_plane = a.n_tc * n_r;
     const int plane = k / per_plane;
     const int rem = k - plane * per_plane;
-    const int tcx = rem / n_r, tr = rem - tcx * n_r;
+    const int tr = rem / a.n_tc, tcx = rem - tr * a.n_tc;
     Tile t;
     t.m = plane / a.B;
     const int b = plane - t.m * a.B;
