@@ -302,18 +302,23 @@ bwd_dw_kernel(const Args a)
     };
 
     __syncthreads();                           // LDS is zeroed
-    if (j < n_units) {
-        const Unit t0 = unit_of(j);
+    // A block walks through consecutive units (down the strips of a plane): the k/v halo rows
+    // that two neighbouring strips share are then read again by the same compute unit one unit
+    // later, out of the caches instead of from HBM.
+    const int per_block = (n_units + a.NB - 1) / a.NB;
+    const int u_begin = j * per_block, u_end = min(u_begin + per_block, n_units);
+    if (u_begin < u_end) {
+        const Unit t0 = unit_of(u_begin);
         issue_loads(t0);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int h = 0; h < 2; ++h) load_B(t0, r, h, Bop[r][h]);
     }
-    for (int u = j; u < n_units; u += a.NB) {
+    for (int u = u_begin; u < u_end; ++u) {
         const Unit t = unit_of(u);
-        const bool has_next = u + a.NB < n_units;
-        const Unit tn = unit_of(has_next ? u + a.NB : u);
+        const bool has_next = u + 1 < u_end;
+        const Unit tn = unit_of(has_next ? u + 1 : u);
         commit_to_lds(t);                      // this wave's own regions: its reads of the previous unit are done
         if (has_next) issue_loads(tn);
         const int rows_eff = t.rows_eff, cols_eff = t.cols_eff;
