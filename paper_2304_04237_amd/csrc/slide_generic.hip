@@ -77,14 +77,25 @@ __device__ __forceinline__ void apply_kernels(const float* __restrict__ w_c,
     }
 }
 
+// sum of x over the LPP adjacent lanes that share a pixel (every one of them gets the sum)
+template <int LPP>
+__device__ __forceinline__ float pixel_lanes_sum(float x)
+{
+#pragma unroll
+    for (int w = 1; w < LPP; w <<= 1) x += __shfl_xor(x, w, 64);
+    return x;
+}
+
 // logits over the S shifts for one pixel of one head, then softmax in place; lse receives
-// the log of the softmax denominator, log sum_s exp(logit[s])
-template <typename T, int KS>
+// the log of the softmax denominator, log sum_s exp(logit[s]).  LPP adjacent lanes share the
+// pixel: lane cg takes the head's channels cg, cg + LPP, ... and the partial logits are
+// added across the lanes (small problems get LPP = 8 so that they fill more of the chip).
+template <typename T, int KS, int LPP>
 __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const T* __restrict__ k,
                                                   const float* __restrict__ wk,
                                                   const float* __restrict__ bias,
                                                   int b, int m, int i, int j, int H, int W, int C,
-                                                  int d, float idw, float (&a)[KS * KS], float& lse)
+                                                  int d, int cg, float idw, float (&a)[KS * KS], float& lse)
 {
     constexpr int S = KS * KS;
     const long HW = (long)H * W;
@@ -92,7 +103,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
     float dot[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) dot[s] = 0.0f;
-    for (int cc = 0; cc < d; ++cc) {
+    for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
         const T* kp = k + ((long)b * C + c) * HW;
         float win[S], ks[S];
@@ -106,6 +117,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
     float mx = -INFINITY;
 #pragma unroll
     for (int s = 0; s < S; ++s) {
+        dot[s] = pixel_lanes_sum<LPP>(dot[s]);
         a[s] = fmaf(scale, dot[s], bias ? bias[m * S + s] : 0.0f);
         mx = fmaxf(mx, a[s]);
     }
@@ -119,7 +131,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
 }
 
 // ------------------------------------------------------------------ forward
-template <typename T, int KS>
+template <typename T, int KS, int LPP>
 __global__ void __launch_bounds__(256)
 fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                    const float* __restrict__ wk, const float* __restrict__ wv,
@@ -130,15 +142,18 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
     const int d = C / heads;
     const int m = blockIdx.y, b = blockIdx.z;
     const long HW = (long)H * W;
-    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pix >= HW) return;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int cg = (int)(gid % LPP);
+    // lanes past the last pixel work on the last one (they take part in the lane sums) and store nothing
+    const bool live = gid / LPP < HW;
+    const long pix = live ? gid / LPP : HW - 1;
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, idw, a, lse_px);
-    if (lse) lse[((long)b * heads + m) * HW + pix] = lse_px;
+    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px);
+    if (lse && live && cg == 0) lse[((long)b * heads + m) * HW + pix] = lse_px;
 
-    for (int cc = 0; cc < d; ++cc) {
+    for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
         const T* vp = v + ((long)b * C + c) * HW;
         float win[S], vs[S];
@@ -147,19 +162,28 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(a[s], vs[s], acc);
-        Elem<T>::store(out + ((long)b * C + c) * HW + pix, acc);
+        if (live) Elem<T>::store(out + ((long)b * C + c) * HW + pix, acc);
     }
 }
+
+// small problems: 8 lanes per pixel and head
+static bool few_pixels(const Problem& p) { return (long)p.B * p.heads * p.plane() < 262144; }
 
 template <typename T, int KS>
 static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, const void* v,
                                const float* wk, const float* wv, const float* bias, void* out,
                                float* lse, hipStream_t st)
 {
-    dim3 grid((unsigned)((p.plane() + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
-    hipLaunchKernelGGL((fwd_generic_kernel<T, KS>), grid, dim3(256), 0, st,
-                       (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
-                       p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+    const int lpp = few_pixels(p) ? 8 : 1;
+    dim3 grid((unsigned)((p.plane() * lpp + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+    if (lpp == 8)
+        hipLaunchKernelGGL((fwd_generic_kernel<T, KS, 8>), grid, dim3(256), 0, st,
+                           (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+    else
+        hipLaunchKernelGGL((fwd_generic_kernel<T, KS, 1>), grid, dim3(256), 0, st,
+                           (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     return hipGetLastError();
 }
 
@@ -195,7 +219,7 @@ hipError_t launch_fwd_generic(const Problem& p, const void* q, const void* k, co
 // weights a[s]; da[s] = sum_c dO[c] Vs[c,s]; dl[s] = a[s] (da[s] - sum a da);
 // dq[c] = scale * sum_s dl[s] Ks[c,s].  a and dl go to scratch as
 // [B, heads, S, H, W] float32 for the gather steps below.
-template <typename T, int KS>
+template <typename T, int KS, int LPP>
 __global__ void __launch_bounds__(256)
 bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* __restrict__ k,
                  const T* __restrict__ v, const float* __restrict__ wk,
@@ -207,17 +231,19 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
     const int d = C / heads;
     const int m = blockIdx.y, b = blockIdx.z;
     const long HW = (long)H * W;
-    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (pix >= HW) return;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int cg = (int)(gid % LPP);
+    const bool live = gid / LPP < HW;          // see fwd_generic_kernel
+    const long pix = live ? gid / LPP : HW - 1;
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS>(q, k, wk, bias, b, m, i, j, H, W, C, d, idw, a, lse_px);
+    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px);
 
     float da[S];
 #pragma unroll
     for (int s = 0; s < S; ++s) da[s] = 0.0f;
-    for (int cc = 0; cc < d; ++cc) {
+    for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
         float win[S], vs[S];
         load_window<T, KS>(v + ((long)b * C + c) * HW, i, j, H, W, win);
@@ -228,17 +254,22 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
     }
     float dsum = 0.0f;
 #pragma unroll
-    for (int s = 0; s < S; ++s) dsum = fmaf(a[s], da[s], dsum);
+    for (int s = 0; s < S; ++s) {
+        da[s] = pixel_lanes_sum<LPP>(da[s]);
+        dsum = fmaf(a[s], da[s], dsum);
+    }
     float dl[S];
     const long ws_base = ((long)b * heads + m) * S * HW + pix;
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         dl[s] = a[s] * (da[s] - dsum);
-        attn_ws[ws_base + (long)s * HW] = a[s];
-        dl_ws[ws_base + (long)s * HW] = dl[s];
+        if (live && cg == 0) {
+            attn_ws[ws_base + (long)s * HW] = a[s];
+            dl_ws[ws_base + (long)s * HW] = dl[s];
+        }
     }
     const float scale = 1.0f / sqrtf((float)d);
-    for (int cc = 0; cc < d; ++cc) {
+    for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
         float win[S], ks[S];
         load_window<T, KS>(k + ((long)b * C + c) * HW, i, j, H, W, win);
@@ -246,7 +277,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(dl[s], ks[s], acc);
-        Elem<T>::store(dq + ((long)b * C + c) * HW + pix, scale * acc);
+        if (live) Elem<T>::store(dq + ((long)b * C + c) * HW + pix, scale * acc);
     }
 }
 
@@ -254,25 +285,28 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
 // (pixel y, head, batch item):
 //   dk[c,y] = scale * sum_t q[c, y - off(t)] * sum_s wk[c,s,t] dl[s, y - off(t)]
 //   dv[c,y] =         sum_t dO[c, y - off(t)] * sum_s wv[c,s,t] a[s, y - off(t)]
-// over the taps t whose source pixel y - off(t) lies inside the map.
-template <typename T, int KS>
+// over the taps t whose source pixel y - off(t) lies inside the map.  LPP adjacent lanes share
+// the pixel and take every LPP-th group of CH channels (small problems: more lanes in flight).
+template <typename T, int KS, int CH, int LPP>
 __global__ void __launch_bounds__(256)
 bwd_dkdv_kernel(const T* __restrict__ dout, const T* __restrict__ q,
                 const float* __restrict__ wk, const float* __restrict__ wv,
                 const float* __restrict__ attn_ws, const float* __restrict__ dl_ws,
                 T* __restrict__ dk, T* __restrict__ dv, int H, int W, int C, int heads, float idw)
 {
-    constexpr int S = KS * KS, R = KS / 2, CH = 8;
+    constexpr int S = KS * KS, R = KS / 2;
     const int d = C / heads;
     const int m = blockIdx.y, b = blockIdx.z;
     const long HW = (long)H * W;
-    const long pix = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long pix = gid / LPP;
+    const int cg = (int)(gid % LPP);
     if (pix >= HW) return;
     const int i = (int)(pix / W), j = (int)(pix % W);
     const float scale = 1.0f / sqrtf((float)d);
     const long ws_head = ((long)b * heads + m) * S * HW;
 
-    for (int c0 = 0; c0 < d; c0 += CH) {
+    for (int c0 = cg * CH; c0 < d; c0 += LPP * CH) {
         float acc_k[CH], acc_v[CH];
 #pragma unroll
         for (int e = 0; e < CH; ++e) { acc_k[e] = 0.0f; acc_v[e] = 0.0f; }
@@ -513,16 +547,26 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
         hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws,
                                              dkdv_image_ws, st);
         if (e != hipSuccess) return e;
+    } else if (few_pixels(p)) {
+        dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 8>), grid8, dim3(256), 0, st,
+                           (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
+                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     } else
-        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS>), grid, dim3(256), 0, st,
+        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 1>), grid, dim3(256), 0, st,
                            (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
                            (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
         hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
         if (e != hipSuccess) return e;
+    } else if (few_pixels(p)) {
+        dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 4, 8>), grid8, dim3(256), 0, st,
+                           (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     } else
-        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS>), grid, dim3(256), 0, st,
+        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 8, 1>), grid, dim3(256), 0, st,
                            (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
                            p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
     if (half_ws) {
