@@ -51,18 +51,7 @@ __device__ __forceinline__ uint32_t pack_half_rtz(float lo, float hi)
 }
 
 // ------------------------------------------------------------------ cross-group reductions
-// lanes l and l+32:  returns a[l] + a[l+32] in lanes 0..31 and b[l-32] + b[l] in lanes 32..63
-__device__ __forceinline__ float fold32(float a, float b)
-{
-    uint2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// rows of 16 lanes: returns (a.r0+a.r1, b.r0+b.r1, a.r2+a.r3, b.r2+b.r3)
-__device__ __forceinline__ float fold16(float a, float b)
-{
-    uint2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
+// maximum / sum of x over the four lane groups (lanes l, l+16, l+32, l+48); every lane gets it
 __device__ __forceinline__ float allmax_groups(float x)
 {
     uint2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
