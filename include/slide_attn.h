@@ -12,6 +12,17 @@
  *   - Activations are contiguous NCHW [B, C, H, W]; `dtype` gives their element
  *     type (SLIDE_F32 or SLIDE_BF16).  Kernels, bias and all parameter gradients
  *     are always float32.  Arithmetic accumulates in float32.
+ *   - Number format of the SLIDE_BF16 matrix-core paths (head size 32, ksize 3 or 5):
+ *     inside the kernels the bf16 activations (q, k, v, dout) and the kernels wk, wv are held
+ *     as IEEE half precision (11 significant bits, more than bf16's 8), products are formed
+ *     in half precision from q/16 (dout/16), and every sum is accumulated in float32.  The
+ *     conversion is exact for 2^-17 <= |x| <= 65504.  CONTRACT: finite inputs with
+ *     |q|, |k|, |v|, |dout| <= 2^15 and |q*k|, |dout*v| < 2^20 per element, |wk|, |wv| < 2^11.
+ *     Inside it results meet the bf16 tolerance (2e-2 relative to max(1, |result|)).
+ *     Outside it nothing is rejected: magnitudes above 65504 saturate to +-65504
+ *     (conversion rounds toward zero, never to infinity), magnitudes below 2^-24 become
+ *     zero and those below 2^-17 lose low bits; NaN and infinity propagate.  SLIDE_F32
+ *     problems and all other shapes compute in float32 throughout and have no such limits.
  *   - S = ksize*ksize.  Shift index s = (u+r)*ksize + (v+r) for u,v in [-r, r],
  *     r = ksize/2, reads the neighbour at offset (u, v) (row, column).  Tap index
  *     t = p*ksize + q reads offset (p-r, q-r): depthwise cross-correlation, no
@@ -99,7 +110,8 @@ int slide_attn_fwd(const void* q, const void* k, const void* v,
  * through them.
  * Parameter gradients are accumulated in float32 in a fixed order (results are
  * reproducible run to run).
- * workspace: at least slide_attn_workspace_bytes(..., 1) bytes of device scratch.
+ * workspace: at least slide_attn_workspace_bytes(..., 1) bytes of device scratch, 16-byte
+ * aligned (SLIDE_ERR_ALIGN otherwise).
  */
 int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,
                    const float* wk, const float* wv, const float* bias,
@@ -147,6 +159,18 @@ const char* slide_status_string(int status);
  * tests and benchmarks.
  */
 int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype);
+
+/*
+ * The kernel inside that implementation, for tests that must know which code ran:
+ * 0 = invalid arguments, 10 = general kernel, 20 = ksize-3 matrix-core kernel with one tile
+ * per block, 21 / 22 / 23 = pipelined ksize-3 kernel (persistent blocks, next tile staged
+ * during the passes of the current one) with the tile width taken from its arguments /
+ * fixed at 56 / fixed at 64, 30 = ksize-5 matrix-core kernel.  aligned16: whether
+ * q, k, v, out, wk, wv are all 16-byte aligned (the pipelined kernel needs that).  Launches
+ * nothing; reads the compute-unit count of the current device (256 if there is none).
+ */
+int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,
+                           int aligned16);
 
 #ifdef __cplusplus
 }

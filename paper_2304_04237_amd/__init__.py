@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     slide_attn_fwd,
     slide_attn_fwd_two_branch,
     slide_attn_fwd_path,
+    slide_attn_fwd_variant,
     slide_attn_workspace_bytes,
     slide_reparam,
     slide_status_string,

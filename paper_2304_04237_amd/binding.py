@@ -44,6 +44,8 @@ def load_library():
     lib.slide_attn_workspace_bytes.argtypes = [i] * 8
     lib.slide_attn_fwd_path.restype = i
     lib.slide_attn_fwd_path.argtypes = [i] * 7
+    lib.slide_attn_fwd_variant.restype = i
+    lib.slide_attn_fwd_variant.argtypes = [i] * 8
     lib.slide_attn_fwd.restype = i
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_bwd.restype = i
@@ -99,6 +101,25 @@ def slide_attn_fwd_path(B, H, W, C, heads, ksize, dtype):
     return int(load_library().slide_attn_fwd_path(B, H, W, C, heads, ksize, code))
 
 
+def slide_attn_fwd_variant(B, H, W, C, heads, ksize, dtype, aligned16=True):
+    code = dtype if isinstance(dtype, int) else (SLIDE_F32 if dtype == torch.float32 else SLIDE_BF16)
+    return int(load_library().slide_attn_fwd_variant(B, H, W, C, heads, ksize, code, int(bool(aligned16))))
+
+
+def _check_params(q, wk, wv, bias, heads, ksize):
+    """Shapes of the kernels and the bias against the activations (a mismatch must not
+    reach a kernel as an out-of-bounds access)."""
+    if q.dim() != 4:
+        raise SlideAttnError("activations must be [B, C, H, W]")
+    C = q.shape[1]
+    S = ksize * ksize
+    for t, n in ((wk, "wk"), (wv, "wv")):
+        if tuple(t.shape) != (C, S, ksize, ksize):
+            raise SlideAttnError("%s must be [C, k*k, k, k] = %s, got %s" % (n, (C, S, ksize, ksize), tuple(t.shape)))
+    if bias is not None and tuple(bias.shape) != (heads, S):
+        raise SlideAttnError("bias must be [heads, k*k] = %s, got %s" % ((heads, S), tuple(bias.shape)))
+
+
 def slide_reparam(w_learned, w_merged=None):
     """w_merged = one-hot shift kernels + w_learned, float32 [C, k*k, k, k]."""
     lib = load_library()
@@ -107,6 +128,8 @@ def slide_reparam(w_learned, w_merged=None):
         raise SlideAttnError("kernel must be [C, k*k, k, k]")
     if w_merged is None:
         w_merged = torch.empty_like(w_learned)
+    elif w_merged.shape != w_learned.shape:
+        raise SlideAttnError("w_merged must have the shape of w_learned")
     _check(lib.slide_reparam(_dev(w_learned, "w_learned", torch.float32),
                              _dev(w_merged, "w_merged", torch.float32), C, kh, _stream()))
     return w_merged
@@ -129,6 +152,7 @@ def slide_attn_fwd_two_branch(q, k, v, wk_learned, wv_learned, bias, heads, ksiz
 
 def _fwd(entry, q, k, v, wk, wv, bias, heads, ksize, out, workspace, lse):
     lib = load_library()
+    _check_params(q, wk, wv, bias, heads, ksize)
     B, C, H, W = q.shape
     code = _dtype_code(q)
     for t, n in ((k, "k"), (v, "v")):
@@ -136,11 +160,15 @@ def _fwd(entry, q, k, v, wk, wv, bias, heads, ksize, out, workspace, lse):
             raise SlideAttnError("%s must match q in shape and dtype" % n)
     if out is None:
         out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype:
+        raise SlideAttnError("out must match q in shape and dtype")
     if lse is not None and tuple(lse.shape) != (B, heads, H, W):
         raise SlideAttnError("lse must be [B, heads, H, W]")
     need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 0)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if workspace is not None and not workspace.is_cuda:
+        raise SlideAttnError("workspace must live on the GPU")
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(entry(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
@@ -170,6 +198,7 @@ def slide_attn_bwd_two_branch(dout, q, k, v, wk_learned, wv_learned, bias, heads
 
 def _bwd(two_branch, accumulate, dout, q, k, v, wk, wv, bias, heads, ksize, workspace, outputs, out, lse):
     lib = load_library()
+    _check_params(q, wk, wv, bias, heads, ksize)
     B, C, H, W = q.shape
     code = _dtype_code(q)
     for t, n in ((k, "k"), (v, "v"), (dout, "dout")):
@@ -181,9 +210,22 @@ def _bwd(two_branch, accumulate, dout, q, k, v, wk, wv, bias, heads, ksize, work
         dbias = torch.empty_like(bias) if bias is not None else None
     else:
         dq, dk, dv, dwk, dwv, dbias = outputs
+        for t, n in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
+            if t.shape != q.shape or t.dtype != q.dtype:
+                raise SlideAttnError("%s must match q in shape and dtype" % n)
+        for t, n, like in ((dwk, "dwk", wk), (dwv, "dwv", wv), (dbias, "dbias", bias)):
+            if (t is None) != (like is None) or (t is not None and t.shape != like.shape):
+                raise SlideAttnError("%s must have the shape of the parameter it is the gradient of" % n)
+    for t, n in ((out, "out"), ):
+        if t is not None and (t.shape != q.shape or t.dtype != q.dtype):
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if lse is not None and tuple(lse.shape) != (B, heads, H, W):
+        raise SlideAttnError("lse must be [B, heads, H, W]")
     need = lib.slide_attn_workspace_bytes(B, H, W, C, heads, ksize, code, 1)
     if workspace is None:
         workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    elif not workspace.is_cuda:
+        raise SlideAttnError("workspace must live on the GPU")
     ptrs = (_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
             _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
             _dev(bias, "bias", torch.float32),

@@ -5,6 +5,28 @@
 
 using slide::Problem;
 
+int slide::device_cu_count()
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static int cached[MAX_DEV];                 // 0 = not read yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) {
+        (void)hipGetLastError();
+        return MAX_CU_PLANNED;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+            (void)hipGetLastError();
+            n = MAX_CU_PLANNED;
+        }
+        cached[dev] = n > MAX_CU_PLANNED ? MAX_CU_PLANNED : n;
+    }
+    return cached[dev];
+}
+
 static bool ksize_supported(int ksize) { return ksize == 1 || ksize == 3 || ksize == 5 || ksize == 7; }
 
 // Validate the shape arguments common to forward and backward.
@@ -30,7 +52,7 @@ extern "C" const char* slide_status_string(int status)
         case SLIDE_ERR_DTYPE: return "SLIDE_ERR_DTYPE: dtype must be SLIDE_F32 or SLIDE_BF16";
         case SLIDE_ERR_WORKSPACE: return "SLIDE_ERR_WORKSPACE: workspace missing or too small";
         case SLIDE_ERR_HIP: return "SLIDE_ERR_HIP: kernel launch failed";
-        case SLIDE_ERR_ALIGN: return "SLIDE_ERR_ALIGN: activation pointer not aligned to its element size";
+        case SLIDE_ERR_ALIGN: return "SLIDE_ERR_ALIGN: a pointer is not aligned to its element size (workspace: 16 bytes)";
         default: return "SLIDE_ERR_UNKNOWN";
     }
 }
@@ -57,6 +79,15 @@ extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ks
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
     return slide::fwd_mfma_supported(p) ? 2 : (slide::fwd_mfma5_supported(p) ? 3 : 1);
+}
+
+extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                      int aligned16)
+{
+    if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    if (slide::fwd_mfma_supported(p)) return slide::fwd_mfma_variant(p, aligned16 != 0);
+    return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
 static int forward(const void* q, const void* k, const void* v,
@@ -125,7 +156,7 @@ static int backward(const void* dout, const void* q, const void* k, const void* 
     for (const void* a : acts)
         if (!aligned_to(a, esz)) return SLIDE_ERR_ALIGN;
     if (!aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(dwk, 4) ||
-        !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 4) || !aligned_to(lse, 4))
+        !aligned_to(dwv, 4) || !aligned_to(dbias, 4) || !aligned_to(workspace, 16) || !aligned_to(lse, 4))
         return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, ksize, dtype};
     p.two_branch = two_branch;

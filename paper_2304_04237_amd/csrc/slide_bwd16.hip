@@ -559,16 +559,9 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
     fill_grid(a.g, p, t, k, v);
     a.scale = 1.0f / sqrtf((float)D);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)bwd_pixel_kernel16<true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)bwd_pixel_kernel16<false>, (const void*)bwd_pixel_kernel16<true>}, LDS_LIMIT);
+    if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((long)t.TA + t.TB);
     if (half_ws) hipLaunchKernelGGL(bwd_pixel_kernel16<true>, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
     else         hipLaunchKernelGGL(bwd_pixel_kernel16<false>, dim3(grid), dim3(THREADS), (size_t)t.buf_bytes, st, a);
@@ -606,16 +599,9 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
     a.rec_a = t.buf_bytes + t.halo_px * REC_BYTES;
     a.scale = 1.0f / sqrtf((float)D);
     const int lds_bytes = t.buf_bytes + 2 * t.halo_px * REC_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute((const void*)bwd_dkdv_kernel16<true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)bwd_dkdv_kernel16<false>, (const void*)bwd_dkdv_kernel16<true>}, LDS_LIMIT);
+    if (e != hipSuccess) return e;
     const unsigned grid = (unsigned)((long)t.TA + t.TB);
     if (half_ws) hipLaunchKernelGGL(bwd_dkdv_kernel16<true>, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
     else         hipLaunchKernelGGL(bwd_dkdv_kernel16<false>, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);

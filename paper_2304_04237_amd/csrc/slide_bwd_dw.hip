@@ -387,10 +387,11 @@ bwd_dw_kernel(const Args a)
     }
 }
 
-static int blocks_per_head(const Problem& p)
+// n_cu: compute units to fill (the workspace query passes the upper bound MAX_CU_PLANNED)
+static int blocks_per_head(const Problem& p, int n_cu)
 {
     const long units = (long)p.B * ((p.H + R - 1) / R) * ((p.W + TW - 1) / TW);
-    long nb = 256 / p.heads;                 // one block per compute unit
+    long nb = n_cu / p.heads;                // one block per compute unit
     if (nb < 1) nb = 1;
     if (nb > units) nb = units;
     return (int)nb;
@@ -406,7 +407,7 @@ bool bwd_dw_mfma_supported(const Problem& p)
 // floats: per-block kernel-gradient partials, then per-block bias partials
 size_t bwd_dw_mfma_partial_floats(const Problem& p)
 {
-    const size_t nb = (size_t)dwpath::blocks_per_head(p);
+    const size_t nb = (size_t)dwpath::blocks_per_head(p, MAX_CU_PLANNED);
     return nb * 2 * (size_t)p.C * 81 + nb * (size_t)p.heads * 9;
 }
 
@@ -418,19 +419,15 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     Args a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.attn = (const _Float16*)attn_ws; a.dl = (const _Float16*)dl_ws;
-    a.NB = blocks_per_head(p);
+    a.NB = blocks_per_head(p, device_cu_count());
     a.partial = partial;
     a.dbias_partial = partial + (size_t)a.NB * 2 * p.C * 81;
     a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
     a.n_strips = (p.H + R - 1) / R; a.n_ct = (p.W + TW - 1) / TW;
     a.scale = 1.0f / sqrtf((float)D);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)bwd_dw_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)bwd_dw_kernel}, LDS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
     const long side = (long)p.C * 81;
     return launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, a.dbias_partial, dbias, p.heads * 9,

@@ -641,18 +641,40 @@ size_t fwd_mfma_workspace_bytes(const Problem& p)
     return fwd_mfma_supported(p) ? (size_t)p.heads * f16path::IMG_DWORDS * sizeof(uint32_t) : 0;
 }
 
+namespace f16path {
+// Which 3x3 kernel serves a problem.  The pipelined kernel needs 16-byte aligned rows and
+// pointers, at least two tiles per persistent block, and a tile buffer large enough to hold a
+// head's operand image plus the raw kernels it is gathered from (the block builds the image in
+// the tile buffer that is free at that moment).
+static bool choose_pipelined(const Problem& p, bool aligned16, TilePlan& t)
+{
+    t = plan_fwd(p, true);
+    const bool pipelined = aligned16 && (p.W % 8 == 0) &&
+                           ((long)t.TA + t.TB >= 2L * device_cu_count()) &&
+                           t.buf_bytes >= IMG_RAW_AT + IMG_RAW_BYTES;
+    if (!pipelined) t = plan_fwd(p, false);
+    return pipelined;
+}
+
+}  // namespace f16path
+
+int fwd_mfma_variant(const Problem& p, bool aligned16)
+{
+    using namespace f16path;
+    TilePlan t;
+    if (!choose_pipelined(p, aligned16, t)) return 20;
+    return t.tw == 56 ? 22 : (t.tw == 64 ? 23 : 21);
+}
+
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, void* workspace, hipStream_t st)
 {
     using namespace f16path;
-    // the pipelined kernel needs 16-byte aligned rows everywhere and enough tiles per block
-    const bool aligned = (p.W % 8 == 0) &&
-                         (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out |
+    const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out |
                            (uintptr_t)wk | (uintptr_t)wv) % 16 == 0);
-    TilePlan t = plan_fwd(p, true);
-    const bool pipelined = aligned && ((long)t.TA + t.TB >= 2L * NUM_CU);
-    if (!pipelined) t = plan_fwd(p, false);
+    TilePlan t;
+    const bool pipelined = choose_pipelined(p, aligned, t);
     uint32_t* image = (uint32_t*)workspace;
     if (!pipelined)
         hipLaunchKernelGGL(prep_weights_kernel, dim3(S, (unsigned)p.heads), dim3(256), 0, st,
@@ -667,24 +689,17 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     a.a_base = (pipelined ? 2 : 1) * t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)fwd16_kernel<FWD_WAVES>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        const void* pipes[6] = {(const void*)fwd16_pipe_kernel<0, false>, (const void*)fwd16_pipe_kernel<56, false>,
-                                (const void*)fwd16_pipe_kernel<64, false>, (const void*)fwd16_pipe_kernel<0, true>,
-                                (const void*)fwd16_pipe_kernel<56, true>, (const void*)fwd16_pipe_kernel<64, true>};
-        for (const void* f : pipes) {
-            e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-            if (e != hipSuccess) return e;
-        }
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)fwd16_kernel<FWD_WAVES>,
+                                  (const void*)fwd16_pipe_kernel<0, false>, (const void*)fwd16_pipe_kernel<56, false>,
+                                  (const void*)fwd16_pipe_kernel<64, false>, (const void*)fwd16_pipe_kernel<0, true>,
+                                  (const void*)fwd16_pipe_kernel<56, true>, (const void*)fwd16_pipe_kernel<64, true>},
+                                 LDS_LIMIT);
+    if (e != hipSuccess) return e;
     const long n_tiles = (long)t.TA + t.TB;
     if (pipelined) {
         const int lds_bytes = a.a_base + PIPE_WAVES * WAVE_SCRATCH;
-        const dim3 grid(NUM_CU), block(PIPE_WAVES * 64);
+        const dim3 grid((unsigned)device_cu_count()), block(PIPE_WAVES * 64);
 #define SLIDE_PIPE(TWV)                                                                                      \
         do {                                                                                                 \
             if (lse) hipLaunchKernelGGL((fwd16_pipe_kernel<TWV, true>), grid, block, (size_t)lds_bytes, st, a);  \

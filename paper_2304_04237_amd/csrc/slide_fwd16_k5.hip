@@ -317,15 +317,12 @@ hipError_t launch_fwd_mfma5(const Problem& p, const void* q, const void* k, cons
     a.w_base = t.buf_bytes;
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     const int lds_bytes = t.buf_bytes + IMG_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)fwd16_k5_kernel,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)fwd16_k5_kernel}, LDS_LIMIT);
+    if (e != hipSuccess) return e;
     const long n_tiles = (long)t.TA + t.TB;
-    const unsigned grid = (unsigned)(n_tiles > NUM_CU ? NUM_CU : n_tiles);
+    const int n_cu = device_cu_count();
+    const unsigned grid = (unsigned)(n_tiles > n_cu ? n_cu : n_tiles);
     hipLaunchKernelGGL(fwd16_k5_kernel, dim3(grid), dim3(THREADS), (size_t)lds_bytes, st, a);
     return hipGetLastError();
 }

@@ -541,34 +541,41 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     // when all three kernels are matrix-core kernels a and dl cross the workspace as halves
     // (in the first half of the same two regions)
     const bool half_ws = fast && bwd_dw_mfma_supported(p);
+    hipError_t e;
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p) + bwd_dkdv_mfma_image_bytes(p);
         void* dkdv_image_ws = (char*)partial + bwd_partial_bytes(p);
-        hipError_t e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws,
-                                             dkdv_image_ws, st);
-        if (e != hipSuccess) return e;
-    } else if (few_pixels(p)) {
-        dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
-        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 8>), grid8, dim3(256), 0, st,
-                           (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
-                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
-    } else
-        hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 1>), grid, dim3(256), 0, st,
-                           (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
-                           (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws,
+                                  dkdv_image_ws, st);
+    } else {
+        if (few_pixels(p)) {
+            dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+            hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 8>), grid8, dim3(256), 0, st,
+                               (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
+                               (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        } else
+            hipLaunchKernelGGL((bwd_pixel_kernel<T, KS, 1>), grid, dim3(256), 0, st,
+                               (const T*)dout, (const T*)q, (const T*)k, (const T*)v, wk, wv, bias,
+                               (T*)dq, attn_ws, dl_ws, p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
-        hipError_t e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
-        if (e != hipSuccess) return e;
-    } else if (few_pixels(p)) {
-        dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
-        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 4, 8>), grid8, dim3(256), 0, st,
-                           (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
-                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
-    } else
-        hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 8, 1>), grid, dim3(256), 0, st,
-                           (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
-                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
+    } else {
+        if (few_pixels(p)) {
+            dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+            hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 4, 8>), grid8, dim3(256), 0, st,
+                               (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
+                               p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        } else
+            hipLaunchKernelGGL((bwd_dkdv_kernel<T, KS, 8, 1>), grid, dim3(256), 0, st,
+                               (const T*)dout, (const T*)q, wk, wv, attn_ws, dl_ws, (T*)dk, (T*)dv,
+                               p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) return e;
     if (half_ws) {
         // kernel and bias gradients on the matrix cores
         return launch_bwd_dw_mfma(p, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias, st);
@@ -580,8 +587,11 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
                        dim3(256), 0, st,
                        (const T*)dout, (const T*)q, (const T*)k, (const T*)v, attn_ws, dl_ws,
                        partial, p.B, p.H, p.W, p.C, p.heads, per_chunk);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
     const long side = (long)p.C * S * S;
-    (void)launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, nullptr, nullptr, 0, p.accumulate, st);
+    e = launch_bwd_dw_reduce(partial, dwk, dwv, side, n_chunks, nullptr, nullptr, 0, p.accumulate, st);
+    if (e != hipSuccess) return e;
     if (dbias)
         hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
                            dl_ws, dbias, p.B, p.plane(), p.heads, S, p.accumulate);

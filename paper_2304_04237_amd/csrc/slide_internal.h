@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <initializer_list>
+#include <mutex>
 
 namespace slide {
 
@@ -17,6 +19,29 @@ struct Problem {
     int d() const { return C / heads; }
     int S() const { return ksize * ksize; }
     long plane() const { return (long)H * W; }
+};
+
+// Compute units of the current device, read from the runtime once per device and process
+// (thread-safe).  MAX_CU_PLANNED when the query fails; never more than MAX_CU_PLANNED, which is
+// what the host-only workspace query sizes per-block partial results for.
+constexpr int MAX_CU_PLANNED = 256;
+int device_cu_count();
+
+// Opt-in of a set of kernels to `bytes` of dynamic LDS: done once per process, safe when
+// several host threads call into the library at the same time; the first error sticks.
+struct LdsOptIn {
+    std::once_flag once;
+    hipError_t err = hipSuccess;
+    hipError_t ensure(std::initializer_list<const void*> kernels, int bytes)
+    {
+        std::call_once(once, [&] {
+            for (const void* f : kernels) {
+                err = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+                if (err != hipSuccess) return;
+            }
+        });
+        return err;
+    }
 };
 
 // ---- general kernels (slide_generic.hip): any supported ksize / head size / dtype
@@ -59,6 +84,9 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
 // ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
+// 20: one tile per block; 21, 22, 23: pipelined kernel with the tile width read from its
+// arguments / fixed at 56 / fixed at 64.  aligned16: every pointer is 16-byte aligned.
+int fwd_mfma_variant(const Problem& p, bool aligned16);
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, void* workspace, hipStream_t st);

@@ -216,7 +216,6 @@ __device__ __forceinline__ void zero_pad_columns(const TileGrid& a, const Tile& 
 }
 
 // ------------------------------------------------------------------ host side
-constexpr int NUM_CU = 256;
 constexpr int LDS_LIMIT = 160 * 1024;
 
 struct TilePlan {
@@ -254,6 +253,7 @@ inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int
                            int px_bytes_extra = 0, int pass_waves = 0)
 {
     const int r2 = 2 * (p.ksize / 2);
+    const int n_cu = device_cu_count();
     TilePlan t;
     t.tw = p.W <= 64 ? p.W : 64;
     t.n_tc = (p.W + t.tw - 1) / t.tw;
@@ -281,7 +281,7 @@ inline TilePlan plan_tiles(const Problem& p, int lds_budget, int px_bytes_a, int
                     const int passes = (rows * t.tw + 15) / 16;
                     return (double)((passes + pass_waves - 1) / pass_waves) + 0.35 + 0.035 * (rows + r2);
                 };
-                const double ms = queue_makespan(planes * nA, cost(th), planes * nB, cost(hb), NUM_CU);
+                const double ms = queue_makespan(planes * nA, cost(th), planes * nB, cost(hb), n_cu);
                 if (ms < best - 1e-9) { best = ms; t.th = th; t.nA = nA; t.nB = nB; t.hb = hb; }
             }
         }

@@ -91,6 +91,9 @@ def test_backward_rejects_bad_arguments_on_the_host(lib):
     assert lib.slide_attn_bwd(*given, *shape, p, need, None) == 6             # out given but misaligned
     shape_bad = [1, 14, 14, 64, 5, 3, 0]
     assert lib.slide_attn_bwd(*args13, *shape_bad, p, need, None) == 2
+    # the workspace must be 16-byte aligned, as the header says (no silent slow path)
+    assert lib.slide_attn_bwd(*args13, *shape, ctypes.c_void_p(0x1004), need + 16, None) == 6
+    assert lib.slide_attn_bwd(*args13, *shape, ctypes.c_void_p(0x1008), need + 16, None) == 6
 
 
 def test_two_branch_entry_points_check_arguments_like_the_merged_ones(lib):
@@ -134,3 +137,47 @@ def test_forward_path_selection(lib):
     p = ctypes.c_void_p(0x1000)
     # the matrix-core forward needs its workspace
     assert lib.slide_attn_fwd(p, p, p, p, p, p, p, None, 64, 56, 56, 64, 2, 3, 1, None, 0, None) == 4
+
+
+def test_forward_variant_selection(lib):
+    """Which kernel inside the matrix-core forward serves a problem (256 compute units
+    assumed when there is no device)."""
+    v = lib.slide_attn_fwd_variant
+    assert v(1, 14, 14, 64, 3, 3, 0, 1) == 0                       # invalid
+    assert v(1, 14, 14, 64, 2, 3, 0, 1) == 10                      # float32: general kernel
+    assert v(64, 28, 28, 128, 4, 5, 1, 1) == 30                    # 5x5
+    assert v(64, 56, 56, 64, 2, 3, 1, 1) == 22                     # stage 1: pipelined, width 56
+    assert v(64, 56, 56, 64, 2, 3, 1, 0) == 20                     # unaligned pointers: one tile per block
+    assert v(2, 200, 304, 96, 3, 3, 1, 1) == 23                    # 200x304: pipelined, width 64
+    assert v(96, 40, 40, 64, 2, 3, 1, 1) == 21                     # pipelined, width from the arguments
+    assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0
+    assert v(40, 40, 40, 64, 2, 3, 1, 1) == 20                     # too few tiles
+    # many small planes: enough tiles, but a tile buffer too small to build the operand image in
+    assert v(128, 8, 8, 128, 4, 3, 1, 1) == 20
+    assert v(256, 2, 64, 64, 2, 3, 1, 1) == 20
+
+
+def test_binding_rejects_mismatched_parameter_shapes(lib):
+    """Shape mistakes are reported by the binding; they must not reach a kernel."""
+    import torch
+    q = torch.zeros(1, 64, 6, 6)
+    w3 = torch.zeros(64, 9, 3, 3)
+    w5 = torch.zeros(64, 25, 5, 5)
+    bias = torch.zeros(2, 9)
+    with pytest.raises(sa.SlideAttnError, match="wk must be"):
+        sa.slide_attn_fwd(q, q, q, w3, w3, bias, 2, 5)             # ksize 5 with 3x3 kernels
+    with pytest.raises(sa.SlideAttnError, match="wv must be"):
+        sa.slide_attn_fwd(q, q, q, w5, w3, None, 2, 5)
+    with pytest.raises(sa.SlideAttnError, match="bias must be"):
+        sa.slide_attn_fwd(q, q, q, w3, w3, torch.zeros(4, 9), 2, 3)
+    with pytest.raises(sa.SlideAttnError, match="out must match"):
+        sa.slide_attn_fwd(q, q, q, w3, w3, bias, 2, 3, out=torch.zeros(1, 64, 6, 5))
+    with pytest.raises(sa.SlideAttnError, match="dq must match"):
+        sa.slide_attn_bwd(q, q, q, q, w3, w3, bias, 2, 3,
+                          outputs=(torch.zeros(1, 64, 6, 5), q, q, w3, w3, bias))
+    with pytest.raises(sa.SlideAttnError, match="dwk must have"):
+        sa.slide_attn_bwd(q, q, q, q, w3, w3, bias, 2, 3, outputs=(q, q, q, w5, w3, bias))
+    with pytest.raises(sa.SlideAttnError, match="dbias must have"):
+        sa.slide_attn_bwd(q, q, q, q, w3, w3, bias, 2, 3, outputs=(q, q, q, w3, w3, None))
+    with pytest.raises(sa.SlideAttnError, match="w_merged"):
+        sa.slide_reparam(w3, w5)

@@ -168,6 +168,12 @@ BWD_SHAPES = [
     (1, 5, 8, 32, 1, 3, "bf16"),         # tiny
     (1, 1, 16, 32, 1, 3, "bf16"),        # single row
     (2, 31, 24, 64, 2, 3, "bf16"),       # rows not a multiple of the strip height
+    # the kernel-gradient kernel gives a block several work units (strips of 3 rows x 56
+    # columns, 128 blocks per head): next-unit prefetch, reuse of its LDS slots
+    (40, 10, 56, 64, 2, 3, "bf16"),      # 160 units: two per block for some, a one-row last strip
+    (20, 10, 112, 64, 2, 3, "bf16"),     # two column tiles, 160 units
+    (24, 17, 48, 32, 1, 3, "bf16"),      # one head: 256 blocks; 144 units of width 48
+    (50, 20, 40, 96, 3, 3, "bf16"),      # three heads: 85 blocks per head, 350 units, 4-5 per block
 ]
 
 
@@ -280,8 +286,45 @@ def test_forward_unaligned_parameters_and_activations():
     check("out (activations at 2-byte alignment)", "bf16", out, ref)
 
 
+PIPELINED_SHAPES = [
+    # B, H, W, C, heads, expected variant: pipelined kernel with the tile width from its arguments
+    (90, 33, 48, 64, 2, 21),             # ragged last row tile
+    (100, 30, 40, 64, 2, 21),
+    (180, 24, 40, 32, 1, 21),            # one head
+    (64, 24, 56, 64, 2, 22),             # width fixed at 56, short planes
+    (12, 64, 72, 64, 2, 23),             # width fixed at 64, ragged second column tile
+    # enough tiles for the pipelined kernel, but tile buffers too small to build a head's
+    # operand image in: must take the one-tile-per-block kernel
+    (128, 8, 8, 128, 4, 20),
+    (256, 2, 64, 64, 2, 20),
+]
+
+
+@pytest.mark.parametrize("shape", PIPELINED_SHAPES)
+def test_forward_kernel_variants_match_oracle(shape):
+    """Every instantiation of the 3x3 matrix-core forward, asserted by the variant query, whole
+    output and lse against the oracle."""
+    B, H, W, C, heads, variant = shape
+    print("variant case", shape, flush=True)
+    assert sa.slide_attn_fwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True) == variant
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=400 + H + W)
+    for t in (g["q"], g["k"], g["v"], g["wk"], g["wv"]):
+        assert t.data_ptr() % 16 == 0
+    lse = torch.full((B, heads, H, W), float("nan"), dtype=torch.float32, device=g["q"].device)
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, lse=lse)
+    out_nl = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_nl)
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3, return_lse=True)
+    check("out", "bf16", out, ref)
+    check("lse", "bf16", lse, ref_lse)
+
+
 def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
+    assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 22
+    assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, False) == 20
+    assert sa.slide_attn_fwd_variant(2, 200, 304, 96, 3, 3, torch.bfloat16, True) == 23
     assert sa.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, torch.bfloat16) == 2
     assert sa.slide_attn_fwd_path(64, 28, 28, 128, 4, 5, torch.bfloat16) == 3
     assert sa.slide_attn_fwd_path(1, 14, 14, 64, 2, 3, torch.float32) == 1
@@ -366,6 +409,15 @@ def test_training_config_full_size():
         ref = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], wkn, wvn, bn, wl.heads, wl.ksize)
         for name, got, want in zip(GRAD_NAMES[:3], full[:3], ref[:3]):
             check(name, "bf16", got[sl], want)
+    # parameter gradients of the whole batch against the oracle (every block of the
+    # kernel-gradient kernel walks through 19 work units here)
+    nall = {x: d[x].double().numpy() for x in ("q", "k", "v", "dout")}
+    ref_all = oracle.bwd(nall["dout"], nall["q"], nall["k"], nall["v"], wkn, wvn, bn, wl.heads, wl.ksize)
+    del nall
+    for name, got, want in zip(GRAD_NAMES[3:], full[3:], ref_all[3:]):
+        err = check(name, "bf16", got, want)
+        print("config 5 %s: strict max abs err %.3e, max |oracle| %.3e" % (name, err, np.abs(want).max()), flush=True)
+    del ref_all
     half = wl.B // 2
     parts = []
     for sl in (slice(0, half), slice(half, wl.B)):
