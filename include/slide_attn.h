@@ -95,6 +95,26 @@ int slide_attn_fwd(const void* q, const void* k, const void* v,
                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * slide_attn_fwd for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and errors as slide_attn_fwd, minus the workspace: the kernels' scratch
+ * (the per-head matrix-core operand images) lives in a fixed array of
+ * SLIDE_NOALLOC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.
+ * This call allocates and frees nothing.  A problem whose forward scratch
+ * (slide_attn_workspace_bytes(..., 0)) exceeds that size returns SLIDE_ERR_WORKSPACE and
+ * launches nothing (at head size 32: more than 113 heads at ksize 3, 20 heads at ksize 5).
+ * All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ * streams or host threads) race on it; calls on the same stream are safe.  Nothing in it has
+ * to start at zero (every call rewrites what it reads).
+ */
+#define SLIDE_NOALLOC_SCRATCH_BYTES (2u << 20)
+int slide_attn_fwd_noalloc(const void* q, const void* k, const void* v,
+                           const float* wk, const float* wv, const float* bias,
+                           void* out, float* lse,
+                           int B, int H, int W, int C, int heads, int ksize, int dtype,
+                           void* stream);
+
+/*
  * Backward of slide_attn_fwd (chain rule through the definition above; the
  * attention weights are recomputed from q and k):
  *     dq, dk, dv : [B,C,H,W] of `dtype`   (overwritten)

@@ -48,6 +48,8 @@ def load_library():
     lib.slide_attn_fwd_variant.argtypes = [i] * 8
     lib.slide_attn_fwd.restype = i
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
+    lib.slide_attn_fwd_noalloc.restype = i
+    lib.slide_attn_fwd_noalloc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
     lib.slide_attn_bwd.restype = i
     lib.slide_attn_bwd.argtypes = [_vp] * 15 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_fwd_two_branch.restype = i
@@ -141,6 +143,26 @@ def slide_attn_fwd(q, k, v, wk, wv, bias, heads, ksize, out=None, workspace=None
     lse: optional float32 [B, heads, H, W] tensor that receives the log of the softmax
     denominator per pixel and head."""
     return _fwd(load_library().slide_attn_fwd, q, k, v, wk, wv, bias, heads, ksize, out, workspace, lse)
+
+
+def slide_attn_fwd_noalloc(q, k, v, wk, wv, bias, heads, ksize, out, lse=None):
+    """slide_attn_fwd through the entry point that allocates nothing: `out` must be given,
+    the kernels' scratch is the library's own fixed array."""
+    lib = load_library()
+    _check_params(q, wk, wv, bias, heads, ksize)
+    B, C, H, W = q.shape
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v"), (out, "out")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if lse is not None and tuple(lse.shape) != (B, heads, H, W):
+        raise SlideAttnError("lse must be [B, heads, H, W]")
+    _check(lib.slide_attn_fwd_noalloc(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                      _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                                      _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
+                                      _dev(lse, "lse", torch.float32),
+                                      B, H, W, C, heads, ksize, code, _stream()))
+    return out
 
 
 def slide_attn_fwd_two_branch(q, k, v, wk_learned, wv_learned, bias, heads, ksize, out=None,

@@ -50,7 +50,7 @@ extern "C" const char* slide_status_string(int status)
         case SLIDE_ERR_NULL: return "SLIDE_ERR_NULL: a required pointer is NULL";
         case SLIDE_ERR_SHAPE: return "SLIDE_ERR_SHAPE: bad dimension, C % heads != 0, or unsupported ksize";
         case SLIDE_ERR_DTYPE: return "SLIDE_ERR_DTYPE: dtype must be SLIDE_F32 or SLIDE_BF16";
-        case SLIDE_ERR_WORKSPACE: return "SLIDE_ERR_WORKSPACE: workspace missing or too small";
+        case SLIDE_ERR_WORKSPACE: return "SLIDE_ERR_WORKSPACE: workspace missing or too small (or the problem needs more scratch than slide_attn_fwd_noalloc has)";
         case SLIDE_ERR_HIP: return "SLIDE_ERR_HIP: kernel launch failed";
         case SLIDE_ERR_ALIGN: return "SLIDE_ERR_ALIGN: a pointer is not aligned to its element size (workspace: 16 bytes)";
         default: return "SLIDE_ERR_UNKNOWN";
@@ -90,6 +90,35 @@ extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int
     return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
+// ---- scratch of the entry point that allocates nothing ---------------------------------
+// One array per GPU (every device that loads the library holds its own copy until the process
+// ends).  In host code the array's name is only a handle for hipGetSymbolAddress: kernels and
+// copies get the device address looked up below, never the name.
+constexpr size_t NOALLOC_SCRATCH_BYTES = SLIDE_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+// Device address of `scratch` on the current device, looked up once per device.
+static hipError_t noalloc_scratch(void** ptr)
+{
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void* addr[MAX_DEV];                 // null = not looked up yet
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return hipSuccess;
+}
+
 static int forward(const void* q, const void* k, const void* v,
                    const float* wk, const float* wv, const float* bias, void* out, float* lse,
                    int B, int H, int W, int C, int heads, int ksize, int dtype, int two_branch,
@@ -126,6 +155,27 @@ extern "C" int slide_attn_fwd(const void* q, const void* k, const void* v,
 {
     return forward(q, k, v, wk, wv, bias, out, lse, B, H, W, C, heads, ksize, dtype, 0,
                    workspace, workspace_bytes, stream);
+}
+
+extern "C" int slide_attn_fwd_noalloc(const void* q, const void* k, const void* v,
+                                      const float* wk, const float* wv, const float* bias, void* out,
+                                      float* lse,
+                                      int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                      void* stream)
+{
+    // argument errors first, as in slide_attn_fwd, before the device is touched
+    int st = check_problem(B, H, W, C, heads, ksize, dtype);
+    if (st != SLIDE_OK) return st;
+    if (!q || !k || !v || !wk || !wv || !out) return SLIDE_ERR_NULL;
+    const size_t need = slide_attn_workspace_bytes(B, H, W, C, heads, ksize, dtype, 0);
+    if (need > NOALLOC_SCRATCH_BYTES) return SLIDE_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (noalloc_scratch(&ws) != hipSuccess) {
+        (void)hipGetLastError();
+        return SLIDE_ERR_HIP;
+    }
+    return forward(q, k, v, wk, wv, bias, out, lse, B, H, W, C, heads, ksize, dtype, 0,
+                   ws, NOALLOC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int slide_attn_fwd_two_branch(const void* q, const void* k, const void* v,
