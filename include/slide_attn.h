@@ -183,10 +183,11 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
 /*
  * The kernel inside that implementation, for tests that must know which code ran:
  * 0 = invalid arguments, 10 = general kernel, 20 = ksize-3 matrix-core kernel with one tile
- * per block, 21 / 22 / 23 = pipelined ksize-3 kernel (persistent blocks, next tile staged
- * during the passes of the current one) with the tile width taken from its arguments /
- * fixed at 56 / fixed at 64, 30 = ksize-5 matrix-core kernel.  aligned16: whether
- * q, k, v, out, wk, wv are all 16-byte aligned (the pipelined kernel needs that).  Launches
+ * per block, 21 / 23 = pipelined ksize-3 tile kernel (persistent blocks, next tile staged
+ * during the passes of the current one) with the tile width taken from its arguments / fixed
+ * at 64, 24 = streaming ksize-3 kernel (a block walks down a band of rows, K/V rows in an LDS
+ * ring; maps 32..64 columns wide), 30 = ksize-5 matrix-core kernel.  aligned16: whether
+ * q, k, v, out, wk, wv are all 16-byte aligned (kernels 21, 23, 24 need that).  Launches
  * nothing; reads the compute-unit count of the current device (256 if there is none).
  */
 int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,

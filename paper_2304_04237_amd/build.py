@@ -11,20 +11,21 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslide_attn.so")
-SOURCES = ["slide_api.hip", "slide_generic.hip", "slide_fwd16.hip", "slide_bwd_dw.hip", "slide_bwd16.hip", "slide_fwd16_k5.hip"]
+SOURCES = ["slide_api.hip", "slide_generic.hip", "slide_fwd16.hip", "slide_fwd16_ring.hip", "slide_bwd_dw.hip", "slide_bwd16.hip", "slide_fwd16_k5.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
 def build(verbose=False):
+    flags = FLAGS + os.environ.get("SLIDE_ATTN_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -D switches of development builds
     objs = []
     build_dir = os.path.join(HERE, "_build")
     os.makedirs(build_dir, exist_ok=True)
     procs = []
     for src in SOURCES:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
-        cmd = ["hipcc"] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ["hipcc"] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

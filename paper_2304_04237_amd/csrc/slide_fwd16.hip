@@ -26,86 +26,17 @@
 // the B-operand layout of v_mfma_f32_16x16x32_f16 with the channel as K index, and the
 // D layout of v_mfma_f32_16x16x16_f16 with the pixel as column, so no data moves
 // between lanes except two small cross-group reductions (v_permlane{16,32}_swap).
-#include "slide_tile16.h"
+#include "slide_fwd16_ops.h"
+#include <stdlib.h>
 
 namespace slide {
 namespace f16path {
 using namespace t16;
+using namespace f16ops;
 
 constexpr int WAVE_SCRATCH = 1152;                 // per wave (pipelined kernel): 32 channels x 16 pixels of bf16
 // byte offset of channel c's 16 pixels in the wave scratch (octets 64 banks apart would collide)
 __device__ __forceinline__ int chan_row(int c) { return (c + (c >> 3)) * 32; }
-constexpr float G_SCALE = 0.0625f;                 // q is divided by 16 for the MFMA products ...
-constexpr float WK_SCALE = 16.0f;                  // ... and the learned K kernel multiplied by 16
-
-// Per-head image of the MFMA weight operands, written by prep_weights_kernel (dwords):
-//   [0, 2304)      A1: tap t (9) x lane (64) x 4 dwords       -- learned K kernel (times 16)
-//   [2304, 4608)   A2: product u (18) x lane (64) x 2 dwords  -- learned V kernel
-//   [4608, 4624)   bias row r (16) as float, times log2(e); -inf on unused rows
-constexpr int IMG_A1 = 0, IMG_A2 = 2304, IMG_BIAS = 4608, IMG_DWORDS = 4624;
-
-// ------------------------------------------------------------------ weight preparation
-// Dword idx < IMG_BIAS of a head's operand image is pack_half(f(w[off0]), f(w[off1])) with
-// f(x) = ok ? (x - sub) * scale : 0 and w the K (A1 part) or V (A2 part) kernel [C, 9, 3, 3]
-// of float32.  sub is 0 for merged kernels; for the learned kernels of the two-branch form
-// it is -1 where shift and tap coincide (idw = 1: the fixed shift path joins the operand).
-// The loads are unconditional so that a caller can issue many of them before using any.
-struct ImageSource {
-    int off0, off1;          // element offsets into the kernel tensor
-    float sub0, sub1, scale;
-    bool ok0, ok1, from_v;
-};
-__device__ __forceinline__ ImageSource image_source(int m, int idx, float idw)
-{
-    ImageSource r;
-    if (idx < IMG_A2) {
-        // A1, tap t: dword y of lane (i, g) = learned K weights of channels 8g+2y, 8g+2y+1
-        // for the shift of logit row i.
-        const int t = idx >> 8, y = idx & 3, lane = (idx >> 2) & 63;
-        const int i = lane & 15, g = lane >> 4;
-        const int s = shift_of_row(i);
-        const int c = m * D + 8 * g + 2 * y;
-        r.off0 = (c * S + max(s, 0)) * S + t;
-        r.off1 = r.off0 + S * S;
-        r.sub0 = r.sub1 = (s == t) ? -idw : 0.0f;
-        r.ok0 = r.ok1 = s >= 0;
-        r.scale = WK_SCALE;
-        r.from_v = false;
-    } else {
-        // A2, product u.  u < 16: channel slot e = u & 7, tap quad tq = u >> 3; row i of the
-        // product is channel 8*(i/4) + e at tap 4*tq + (i%4).  Products 16, 17 (j = u - 16):
-        // row i is channel 8*(i/4) + 4j + (i%4) at tap 8.  Dword y of lane (i, g) holds the
-        // learned V weights for the shifts of logit rows 4g+2y and 4g+2y+1.
-        const int q = idx - IMG_A2;
-        const int u = q >> 7, y = q & 1, lane = (q >> 1) & 63;
-        const int i = lane & 15, g = lane >> 4;
-        const int c = m * D + 8 * (i >> 2) + (u < 16 ? (u & 7) : 4 * (u - 16) + (i & 3));
-        const int tap = u < 16 ? 4 * (u >> 3) + (i & 3) : 8;
-        const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
-        r.off0 = (c * S + max(s0, 0)) * S + tap;
-        r.off1 = (c * S + max(s1, 0)) * S + tap;
-        r.sub0 = (s0 == tap) ? -idw : 0.0f;
-        r.sub1 = (s1 == tap) ? -idw : 0.0f;
-        r.ok0 = s0 >= 0;
-        r.ok1 = s1 >= 0;
-        r.scale = 1.0f;
-        r.from_v = true;
-    }
-    return r;
-}
-__device__ __forceinline__ uint32_t image_value(const ImageSource& r, float w0, float w1)
-{
-    return pack_half(r.ok0 ? (w0 - r.sub0) * r.scale : 0.0f, r.ok1 ? (w1 - r.sub1) * r.scale : 0.0f);
-}
-// dwords IMG_BIAS .. IMG_DWORDS-1: bias of logit row r times log2(e); -inf on unused rows
-__device__ __forceinline__ uint32_t image_bias(const float* __restrict__ bias, int m, int row)
-{
-    const int s = shift_of_row(row);
-    float b = -INFINITY;
-    if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
-    return __float_as_uint(b);
-}
-
 // grid = (9, heads), block = 256: the images in global memory, for the one-tile-per-block kernel
 __global__ void __launch_bounds__(256)
 prep_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
@@ -223,20 +154,6 @@ __device__ __forceinline__ void slide_pass(const unsigned char* kl, int RS, int 
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-}
-
-// MFMA weight operands of one head (coalesced reads of the prepared image)
-__device__ __forceinline__ void load_operands(const uint32_t* img, int lane, int g, half8_t (&A1)[S],
-                                              half4_t (&A2)[2 * S], float (&bias2)[3])
-{
-#pragma unroll
-    for (int t = 0; t < S; ++t)
-        A1[t] = __builtin_bit_cast(half8_t, *(const uint4_t*)(img + IMG_A1 + (t * 64 + lane) * 4));
-#pragma unroll
-    for (int u = 0; u < 2 * S; ++u)
-        A2[u] = __builtin_bit_cast(half4_t, *(const uint2_t*)(img + IMG_A2 + (u * 64 + lane) * 2));
-#pragma unroll
-    for (int r = 0; r < 3; ++r) bias2[r] = __uint_as_float(img[IMG_BIAS + 4 * g + r]);
 }
 
 // ------------------------------------------------------------------ forward, one tile per block
@@ -433,37 +350,6 @@ __device__ __forceinline__ void pipe_zero_pad(const TileGrid& a, const Tile& t, 
     }
 }
 
-// One block builds a head's operand image in LDS (THREADS threads, every weight load issued
-// before the first use).
-// The head's kernels (2 x 32 x 81 floats, contiguous) come in as coalesced 16-byte loads and
-// are gathered from LDS: `raw` is IMG_RAW_BYTES of LDS that does not overlap dst.  Contains a
-// block barrier; every thread of the block must call it.
-constexpr int IMG_RAW_AT = 20480;                         // byte offset of `raw` behind an image (IMG_DWORDS * 4 = 18496)
-constexpr int HEAD_W = D * S * S;                         // floats of one head in a kernel tensor
-constexpr int IMG_RAW_BYTES = 2 * HEAD_W * 4;             // 20736
-template <int THREADS>
-__device__ __forceinline__ void build_image(const float* __restrict__ wk, const float* __restrict__ wv,
-                                            const float* __restrict__ bias, int m, float idw, uint32_t* dst,
-                                            float* raw, int tid)
-{
-    constexpr int N = IMG_BIAS / THREADS, CHUNKS = HEAD_W / 4;
-    static_assert(N * THREADS == IMG_BIAS, "whole rounds");
-    static_assert(CHUNKS * 4 == HEAD_W, "16-byte chunks");
-    for (int i = tid; i < 2 * CHUNKS; i += THREADS) {
-        const bool is_v = i >= CHUNKS;
-        const float* src = (is_v ? wv : wk) + (long)m * HEAD_W;               // 16-byte aligned: HEAD_W % 4 == 0
-        *(float4_t*)(raw + 4 * i) = *(const float4_t*)(src + 4 * (i - (is_v ? CHUNKS : 0)));
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const ImageSource src = image_source(m, tid + i * THREADS, idw);
-        const float* w = raw + (src.from_v ? HEAD_W : 0) - m * HEAD_W;
-        dst[tid + i * THREADS] = image_value(src, w[src.off0], w[src.off1]);
-    }
-    if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
-}
-
 template <int TW, bool LSE>
 __global__ void __launch_bounds__(PIPE_WAVES * 64, 2)
 fwd16_pipe_kernel(const FwdArgs a)
@@ -658,12 +544,24 @@ static bool choose_pipelined(const Problem& p, bool aligned16, TilePlan& t)
 
 }  // namespace f16path
 
+// SLIDE_ATTN_DISABLE_RING=1 in the environment keeps the streaming kernel out of the dispatch
+// (for side-by-side measurements of the tiled kernels); read once.
+static bool ring_enabled()
+{
+    static const bool on = [] {
+        const char* e = getenv("SLIDE_ATTN_DISABLE_RING");
+        return !(e && e[0] == '1');
+    }();
+    return on;
+}
+
 int fwd_mfma_variant(const Problem& p, bool aligned16)
 {
     using namespace f16path;
+    if (ring_enabled() && fwd_ring_supported(p, aligned16)) return 24;
     TilePlan t;
     if (!choose_pipelined(p, aligned16, t)) return 20;
-    return t.tw == 56 ? 22 : (t.tw == 64 ? 23 : 21);
+    return t.tw == 64 ? 23 : 21;
 }
 
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
@@ -673,6 +571,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     using namespace f16path;
     const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out |
                            (uintptr_t)wk | (uintptr_t)wv) % 16 == 0);
+    if (ring_enabled() && fwd_ring_supported(p, aligned))
+        return launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, st);
     TilePlan t;
     const bool pipelined = choose_pipelined(p, aligned, t);
     uint32_t* image = (uint32_t*)workspace;
@@ -691,9 +591,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     a.idw = p.two_branch ? 1.0f : 0.0f;
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)fwd16_kernel<FWD_WAVES>,
-                                  (const void*)fwd16_pipe_kernel<0, false>, (const void*)fwd16_pipe_kernel<56, false>,
-                                  (const void*)fwd16_pipe_kernel<64, false>, (const void*)fwd16_pipe_kernel<0, true>,
-                                  (const void*)fwd16_pipe_kernel<56, true>, (const void*)fwd16_pipe_kernel<64, true>},
+                                  (const void*)fwd16_pipe_kernel<0, false>, (const void*)fwd16_pipe_kernel<64, false>,
+                                  (const void*)fwd16_pipe_kernel<0, true>, (const void*)fwd16_pipe_kernel<64, true>},
                                  LDS_LIMIT);
     if (e != hipSuccess) return e;
     const long n_tiles = (long)t.TA + t.TB;
@@ -705,9 +604,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
             if (lse) hipLaunchKernelGGL((fwd16_pipe_kernel<TWV, true>), grid, block, (size_t)lds_bytes, st, a);  \
             else     hipLaunchKernelGGL((fwd16_pipe_kernel<TWV, false>), grid, block, (size_t)lds_bytes, st, a); \
         } while (0)
-        if (t.tw == 56)      SLIDE_PIPE(56);
-        else if (t.tw == 64) SLIDE_PIPE(64);
-        else                 SLIDE_PIPE(0);
+        if (t.tw == 64) SLIDE_PIPE(64);
+        else            SLIDE_PIPE(0);
 #undef SLIDE_PIPE
     } else {
         const int lds_bytes = a.a_base + FWD_WAVES * WAVE_SCRATCH;

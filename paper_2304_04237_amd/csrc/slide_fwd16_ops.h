@@ -1,0 +1,142 @@
+// Pieces shared by the 3x3 matrix-core forward kernels (bf16, head size 32): the per-head
+// image of MFMA weight operands (layout, how it is built from the float32 kernels, how a
+// wavefront loads it into registers).
+//
+// Arithmetic the image serves (the operator of Sec. 4.1-4.3, re-associated), with the merged
+// kernel W~ = one-hot shift + learned part (Sec. 4.3, Fig. 4):
+//     logit[s] = scale * sum_{c,t} (q[c] k[c, p+t]) W~k[c,s,t]       <- 288 x 9 contraction
+//     out[c]   = sum_t v[c, p+t] * g[c,t],  g[c,t] = sum_s a[s] W~v[c,s,t]   <- 9 x 288
+#pragma once
+#include "slide_tile16.h"
+
+namespace slide {
+namespace f16ops {
+using namespace t16;
+
+constexpr float G_SCALE = 0.0625f;                 // q is divided by 16 for the MFMA products ...
+constexpr float WK_SCALE = 16.0f;                  // ... and the learned K kernel multiplied by 16
+
+// Per-head image of the MFMA weight operands, written by prep_weights_kernel (dwords):
+//   [0, 2304)      A1: tap t (9) x lane (64) x 4 dwords       -- learned K kernel (times 16)
+//   [2304, 4608)   A2: product u (18) x lane (64) x 2 dwords  -- learned V kernel
+//   [4608, 4624)   bias row r (16) as float, times log2(e); -inf on unused rows
+constexpr int IMG_A1 = 0, IMG_A2 = 2304, IMG_BIAS = 4608, IMG_DWORDS = 4624;
+
+// ------------------------------------------------------------------ weight preparation
+// Dword idx < IMG_BIAS of a head's operand image is pack_half(f(w[off0]), f(w[off1])) with
+// f(x) = ok ? (x - sub) * scale : 0 and w the K (A1 part) or V (A2 part) kernel [C, 9, 3, 3]
+// of float32.  sub is 0 for merged kernels; for the learned kernels of the two-branch form
+// it is -1 where shift and tap coincide (idw = 1: the fixed shift path joins the operand).
+// The loads are unconditional so that a caller can issue many of them before using any.
+struct ImageSource {
+    int off0, off1;          // element offsets into the kernel tensor
+    float sub0, sub1, scale;
+    bool ok0, ok1, from_v;
+};
+__device__ __forceinline__ ImageSource image_source(int m, int idx, float idw)
+{
+    ImageSource r;
+    if (idx < IMG_A2) {
+        // A1, tap t: dword y of lane (i, g) = learned K weights of channels 8g+2y, 8g+2y+1
+        // for the shift of logit row i.
+        const int t = idx >> 8, y = idx & 3, lane = (idx >> 2) & 63;
+        const int i = lane & 15, g = lane >> 4;
+        const int s = shift_of_row(i);
+        const int c = m * D + 8 * g + 2 * y;
+        r.off0 = (c * S + max(s, 0)) * S + t;
+        r.off1 = r.off0 + S * S;
+        r.sub0 = r.sub1 = (s == t) ? -idw : 0.0f;
+        r.ok0 = r.ok1 = s >= 0;
+        r.scale = WK_SCALE;
+        r.from_v = false;
+    } else {
+        // A2, product u.  u < 16: channel slot e = u & 7, tap quad tq = u >> 3; row i of the
+        // product is channel 8*(i/4) + e at tap 4*tq + (i%4).  Products 16, 17 (j = u - 16):
+        // row i is channel 8*(i/4) + 4j + (i%4) at tap 8.  Dword y of lane (i, g) holds the
+        // learned V weights for the shifts of logit rows 4g+2y and 4g+2y+1.
+        const int q = idx - IMG_A2;
+        const int u = q >> 7, y = q & 1, lane = (q >> 1) & 63;
+        const int i = lane & 15, g = lane >> 4;
+        const int c = m * D + 8 * (i >> 2) + (u < 16 ? (u & 7) : 4 * (u - 16) + (i & 3));
+        const int tap = u < 16 ? 4 * (u >> 3) + (i & 3) : 8;
+        const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
+        r.off0 = (c * S + max(s0, 0)) * S + tap;
+        r.off1 = (c * S + max(s1, 0)) * S + tap;
+        r.sub0 = (s0 == tap) ? -idw : 0.0f;
+        r.sub1 = (s1 == tap) ? -idw : 0.0f;
+        r.ok0 = s0 >= 0;
+        r.ok1 = s1 >= 0;
+        r.scale = 1.0f;
+        r.from_v = true;
+    }
+    return r;
+}
+__device__ __forceinline__ uint32_t image_value(const ImageSource& r, float w0, float w1)
+{
+    return pack_half(r.ok0 ? (w0 - r.sub0) * r.scale : 0.0f, r.ok1 ? (w1 - r.sub1) * r.scale : 0.0f);
+}
+// dwords IMG_BIAS .. IMG_DWORDS-1: bias of logit row r times log2(e); -inf on unused rows
+__device__ __forceinline__ uint32_t image_bias(const float* __restrict__ bias, int m, int row)
+{
+    const int s = shift_of_row(row);
+    float b = -INFINITY;
+    if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
+    return __float_as_uint(b);
+}
+
+// MFMA weight operands of one head (coalesced reads of the prepared image)
+__device__ __forceinline__ void load_operands(const uint32_t* img, int lane, int g, half8_t (&A1)[S],
+                                              half4_t (&A2)[2 * S], float (&bias2)[3])
+{
+#pragma unroll
+    for (int t = 0; t < S; ++t)
+        A1[t] = __builtin_bit_cast(half8_t, *(const uint4_t*)(img + IMG_A1 + (t * 64 + lane) * 4));
+#pragma unroll
+    for (int u = 0; u < 2 * S; ++u)
+        A2[u] = __builtin_bit_cast(half4_t, *(const uint2_t*)(img + IMG_A2 + (u * 64 + lane) * 2));
+#pragma unroll
+    for (int r = 0; r < 3; ++r) bias2[r] = __uint_as_float(img[IMG_BIAS + 4 * g + r]);
+}
+
+// One block builds a head's operand image in LDS (THREADS threads, every weight load issued
+// before the first use).
+// The head's kernels (2 x 32 x 81 floats, contiguous) come in as coalesced 16-byte loads and
+// are gathered from LDS: `raw` is IMG_RAW_BYTES of LDS that does not overlap dst.  Contains a
+// block barrier; every thread of the block must call it.
+constexpr int IMG_RAW_AT = 20480;                         // byte offset of `raw` behind an image (IMG_DWORDS * 4 = 18496)
+constexpr int HEAD_W = D * S * S;                         // floats of one head in a kernel tensor
+constexpr int IMG_RAW_BYTES = 2 * HEAD_W * 4;             // 20736
+// the gather: raw (the head's K kernels, then its V kernels, as float32 in LDS) -> operand image
+template <int THREADS>
+__device__ __forceinline__ void image_from_raw(const float* raw, const float* __restrict__ bias, int m, float idw,
+                                               uint32_t* dst, int tid)
+{
+    constexpr int N = IMG_BIAS / THREADS;
+    static_assert(N * THREADS == IMG_BIAS, "whole rounds");
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const ImageSource src = image_source(m, tid + i * THREADS, idw);
+        const float* w = raw + (src.from_v ? HEAD_W : 0) - m * HEAD_W;
+        dst[tid + i * THREADS] = image_value(src, w[src.off0], w[src.off1]);
+    }
+    if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
+}
+
+template <int THREADS>
+__device__ __forceinline__ void build_image(const float* __restrict__ wk, const float* __restrict__ wv,
+                                            const float* __restrict__ bias, int m, float idw, uint32_t* dst,
+                                            float* raw, int tid)
+{
+    constexpr int CHUNKS = HEAD_W / 4;
+    static_assert(CHUNKS * 4 == HEAD_W, "16-byte chunks");
+    for (int i = tid; i < 2 * CHUNKS; i += THREADS) {
+        const bool is_v = i >= CHUNKS;
+        const float* src = (is_v ? wv : wk) + (long)m * HEAD_W;               // 16-byte aligned: HEAD_W % 4 == 0
+        *(float4_t*)(raw + 4 * i) = *(const float4_t*)(src + 4 * (i - (is_v ? CHUNKS : 0)));
+    }
+    __syncthreads();
+    image_from_raw<THREADS>(raw, bias, m, idw, dst, tid);
+}
+
+}  // namespace f16ops
+}  // namespace slide

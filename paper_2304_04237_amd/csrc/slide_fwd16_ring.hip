@@ -1,0 +1,590 @@
+// Streaming matrix-core forward of Slide Attention for gfx950: bf16 activations, head size
+// 32, 3x3 window, maps of 32..64 columns (a multiple of 8) whose rows and pointers are
+// 16-byte aligned.  Same arithmetic as the tiled kernels (operator of Sec. 4.1-4.3 with the
+// merged kernel W~ of Sec. 4.3 / Fig. 4 as matrix-core operands, see slide_fwd16_ops.h); what
+// differs is how data moves:
+//
+//   - A block (8 waves) owns a band of consecutive rows of one (batch, head) plane and walks
+//     down it.  K and V rows live in LDS in a ring of R rows, pixel-major ([column][32
+//     channels] as halves, 64 B per pixel, the 16-byte channel octets swizzled by the column),
+//     each row staged exactly once per block; the zero padding left and right of the map are
+//     two ring columns that are cleared once, the rows above and below the map are staged as
+//     zeros (Fig. 2).
+//   - Global memory is read with 16-byte loads that write straight into LDS
+//     (global_load_lds_dwordx4): the raw bf16 rows land channel-major in per-wave landing
+//     slots and use no registers while in flight.  One epoch later the same wave reads its
+//     slots back with the transposing LDS read (ds_read_b64_tr_b16: a lane gets four
+//     channels of one pixel), converts bf16 -> half and writes the ring row.
+//   - q is private to the pass that uses it: one direct-to-LDS load per pass into a per-wave
+//     slot, read back transposed.  Results leave the same way in reverse: a lane writes its
+//     pixel's 8 channels to a per-wave slot, reads 8 pixels of one channel back transposed
+//     and stores 16 bytes.
+//   - Work is cut into epochs of 128 pixels (one 16-pixel pass per wave).  At the start of
+//     epoch e a wave fetches the landed raw rows that epoch e + 1 will read first (loaded two
+//     epochs earlier) into registers and re-issues loads into their slots for epoch e + 3;
+//     it converts the fetched rows and writes them to the ring in the shadow of its pass.
+//     One block barrier ends the epoch.  The ring is deep enough that rows written during an
+//     epoch are never among those read during it.
+//
+// Vector-memory waits are placed by hand: the direct-to-LDS loads are issued from inline
+// assembly (the compiler would otherwise make every LDS read wait for them), and the code
+// below counts the operations in flight itself.
+#include "slide_fwd16_ops.h"
+#include <stdlib.h>
+
+namespace slide {
+namespace f16ring {
+using namespace t16;
+using namespace f16ops;
+
+constexpr int MIN_W = 32, MAX_W = 64;
+constexpr int WAVES = 8, THREADS = WAVES * 64;
+constexpr int PX_EPOCH = WAVES * 16;           // pixels per epoch
+constexpr int SLOT = 1024;                     // bytes of a landing slot: 8 channels x 64 pixels or 32 channels x 16 pixels
+
+struct RingArgs {
+    const bf16_bits* q; const bf16_bits* k; const bf16_bits* v; bf16_bits* out;
+    float* lse;                                // [B, heads, H, W] or null
+    const float* wk; const float* wv; const float* bias;
+    int B, H, W, C, heads;
+    int nbp, rows_pb, n_blocks;                // bands per plane, rows per band, blocks
+    int R, RS, PS;                             // ring rows, bytes per ring row = (W + 2) * 16, bytes per unit plane = (R + 1) * RS
+    int off_raw, off_dummy, off_q, off_out;    // LDS byte offsets: K/V landing slots, dump slot, q slots, result slots
+    uint32_t magic_w, magic_r;                 // ceil(2^32 / W), ceil(2^32 / R): x / W == umulhi(x, magic_w) for x < 2^26
+    float scale_log2e, idw;
+    unsigned long long* ts;                    // development builds: time stamps
+};
+
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+// 16 bytes per active lane from global memory (uniform base + per-lane byte offset) straight
+// into LDS: lane l's bytes land at lds_base + 16 l.  Counts as one vector-memory operation.
+__device__ __forceinline__ void load_to_lds(const void* base, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %0"
+                 :: "s"(base), "v"(voff), "s"(lds_base) : "memory");
+}
+
+// the same with a full 64-bit address per lane
+__device__ __forceinline__ void load_to_lds_addr(const void* vaddr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off"
+                 :: "v"(vaddr), "s"(lds_base) : "memory");
+}
+
+// wait until at most n vector-memory operations of this wave are in flight (n uniform;
+// above 12 the wait is for 12, which is stricter)
+__device__ __forceinline__ void wait_vmem(int n)
+{
+    switch (n) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+        case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+        case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+        case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+        case 11: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    }
+}
+
+// all LDS operations of this wave are done, then the block barrier; memory operations are not
+// moved across it by the compiler
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane n receives element (n % 4) of the
+// 8-byte pieces addressed by lanes n / 4, n / 4 + 4, n / 4 + 8, n / 4 + 12.  With lane s
+// addressing four consecutive pixels 4 (s % 4) .. + 3 of row s / 4 of a [row][pixel] array,
+// lane n gets pixel n of rows 0..3 (and vice versa with rows and pixels exchanged).
+__device__ __forceinline__ uint2_t lds_read_tr(const unsigned char* p)
+{
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
+    return __builtin_bit_cast(uint2_t, r);
+}
+
+// two bf16 in a dword -> two halves in a dword (exact for 2^-17 <= |x| <= 65504, round toward
+// zero below, saturating above)
+__device__ __forceinline__ uint32_t bf16x2_to_half2(uint32_t d)
+{
+    return pack_half_rtz(__uint_as_float(d << 16), __uint_as_float(d & 0xffff0000u));
+}
+
+// RPG: most rows a group of new K/V rows can have (rows that one epoch is the first to read).
+// The epoch loop has no data-dependent control flow beyond "this wave has a pass": every epoch
+// issues exactly RPG + 1 loads per wave (rows a group does not have, rows outside the map and
+// passes past the end of the band are loaded from a valid address into a dump slot), so the
+// wait for "everything but the latest round has landed" is a constant, and rows that are not
+// there are converted into a dump row of the ring.
+template <int RPG, bool LSE>
+__global__ void __launch_bounds__(THREADS, 2)
+fwd16_ring_kernel(const RingArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p = lane & 15, g = lane >> 4;
+    const int W = a.W, H = a.H, R = a.R;
+    const int RS = a.RS, PS = a.PS;
+    const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;                 // LDS address of the dynamic region
+#ifdef SLIDE_RING_STAMPS
+    int ts_n = 0;
+    auto stamp = [&]() {
+        if (a.ts && (blockIdx.x == 0 || blockIdx.x == 100) && (wave == 0 || wave == 5)) {
+            const unsigned long long t = __builtin_amdgcn_s_memrealtime();
+            if (lane == 0 && ts_n < 128) a.ts[(((blockIdx.x ? 1 : 0) * 2 + (wave ? 1 : 0)) * 128) + ts_n] = t;
+            ++ts_n;
+        }
+    };
+#else
+    auto stamp = [&]() {};
+#endif
+    stamp();
+
+    // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
+    // the XCDs by the hardware; the bands of a plane (which share two halo rows) get indices
+    // 8 apart, so they run on the same XCD and the shared rows come out of its L2.
+    int u = blockIdx.x;
+    {
+        const int per = a.n_blocks >> 3;
+        if (u < 8 * per) u = (u & 7) * per + (u >> 3);
+    }
+    const int plane = u / a.nbp, part = u - plane * a.nbp;
+    const int b = plane / a.heads, m = plane - b * a.heads;
+    const int y0 = part * a.rows_pb;
+    const int nr = min(a.rows_pb, H - y0);
+    const long HW = (long)H * W;
+    const long head_base = ((long)b * a.C + (long)m * D) * HW;       // element offset of channel 0 of the head
+    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
+
+    // Stage row sr = 0 .. nr + 1 is map row y0 - 1 + sr of K and V and lives in ring row
+    // sr % R; output row ry reads stage rows ry, ry + 1, ry + 2.  srn(j): the last stage row
+    // that epoch j reads; group j = stage rows srn(j - 1) + 1 .. srn(j), the rows that epoch j
+    // is the first to read (group 0: everything the first epoch reads).  Uniform integer
+    // arithmetic; divisions by W and R are multiplications by their reciprocals.
+    auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
+    auto mod_r = [&](int x) { return x - (int)__umulhi((uint32_t)x, a.magic_r) * R; };
+    auto srn = [&](int j) {
+        const int rb = min(div_w(PX_EPOCH * j + PX_EPOCH - 1), nr - 1);
+        return j >= E ? nr + 1 : min(rb + 2, nr + 1);
+    };
+
+    // ---- K/V staging.  Wave w stages unit w = tensor * 4 + channel octet for every new row.  A
+    // unit's rows live in LDS plane `unit` of the ring: [ring row 0 .. R][column 0 .. W + 1][8
+    // channels as halves], 16 B per pixel, columns 0 and W + 1 zero, ring row R a dump row.
+    // Landing slots of a wave: two sets of RPG (group j uses set j % 2); at start-up also the
+    // third q slot and the result slot; one dump slot for the whole block.
+    const bf16_bits* kv_src = ((wave >> 2) ? a.v : a.k) + head_base + (long)(8 * (wave & 3)) * HW;
+    const int NXC = W >> 3;                                            // 16-byte chunks per row
+    const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;           // lane l loads chunk x of channel 8 oct + cc
+    const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
+    const int raw_off = a.off_raw + wave * (2 * RPG * SLOT);
+    const int q_slots = a.off_q + wave * (3 * SLOT);
+    const int o_off = a.off_out + wave * SLOT;
+    auto slot_off = [&](int s) {                                       // s < 2 RPG: the two sets; then the two start-up extras
+        return s < 2 * RPG ? raw_off + s * SLOT : (s == 2 * RPG ? q_slots + 2 * SLOT : o_off);
+    };
+    // load map row gy (must be inside the map) of this wave's unit into the landing slot at LDS offset off
+    auto load_row = [&](int gy, int off) {
+        if (lane < W) load_to_lds(kv_src, kv_lane_off + (uint32_t)(gy * W) * 2u, lds0 + off);
+    };
+    // read a landed row back, transposed
+    const int cv_src_off = ((lane & 15) >> 2) * (W * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
+    struct RawRow { uint2_t lo, hi; };
+    auto read_row = [&](int off) {
+        RawRow r;
+        const unsigned char* src = smem + off + cv_src_off;
+        r.lo = lds_read_tr(src);
+        r.hi = lds_read_tr(src + 4 * (W * 2));
+        return r;
+    };
+    // convert a fetched row (zeros if !in_map) and write it to ring row ri of this wave's plane
+    unsigned char* cv_dst = smem + wave * PS + (lane + 1) * 16;
+    auto write_row = [&](int ri, bool in_map, const RawRow& r) {
+        uint4_t h4;
+        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
+        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
+#pragma unroll
+        for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
+        if (lane < W) *(uint4_t*)(cv_dst + ri * RS) = h4;
+    };
+
+    // ---- q: one direct load per pass into one of the wave's three slots, two epochs ahead
+    const bf16_bits* q_src = a.q + head_base + (long)y0 * W;
+    const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (uint32_t)(lane & 1) * 16u;
+    // n_first: first pixel of the pass (a multiple of 16; passes past the band go to the dump slot)
+    auto load_q = [&](int n_first, int qo) {
+        const bool real = n_first < npix;
+        const int nf = real ? n_first : 0;
+        const int off = real ? q_slots + qo : a.off_dummy;
+        // (npix is a multiple of 8: a 16-byte chunk is inside the band or outside it)
+        if (nf + 8 * (lane & 1) < npix) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
+    };
+
+    // ---- start-up: every load that has a slot first: the head's kernels, group 0, q of the
+    // first two epochs, group 1
+    int v0 = srn(0), v1 = srn(1), v2 = srn(2), v3 = 0;                 // srn(e), srn(e+1), srn(e+2), srn(e+3) with e = 0
+    int nb = 16 * wave;                                                // first pixel of this wave's pass of the current epoch
+    int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
+    int n_after_w = 0;                                                 // loads issued after the kernels'
+    {
+        // 2 x 32 x 81 floats = 1296 chunks of 16 bytes, K kernels then V kernels, to smem + IMG_RAW_AT
+        constexpr int CHUNKS = HEAD_W / 4;
+        for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
+            const int c = L * 64 + lane;
+            const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
+            if (c < 2 * CHUNKS) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
+        }
+    }
+    for (int k = 0; k <= v0; ++k) {                                    // group 0 (at most RPG + 2 rows)
+        const int gy = y0 - 1 + k;
+        if (gy >= 0 && gy < H) { load_row(gy, slot_off(k < RPG ? k : 2 * RPG + (k - RPG))); ++n_after_w; }
+    }
+    const int n_after_g0_mark = n_after_w;
+    load_q(nb, qo_cur);
+    load_q(nb + PX_EPOCH, qo_1);
+    n_after_w += 2;
+    for (int k = 0; k < v1 - v0; ++k) {                                // group 1 into set 1
+        const int gy = y0 + v0 + k;
+        if (gy >= 0 && gy < H) { load_row(gy, slot_off(RPG + k)); ++n_after_w; }
+    }
+    stamp();
+    wait_vmem(n_after_w);                                              // the kernels have landed
+    block_barrier();
+    image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
+    block_barrier();
+    stamp();
+    half8_t A1[S];
+    half4_t A2[2 * S];
+    float bias2[3];
+    load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
+    block_barrier();
+    stamp();
+    // the two padding columns of every ring row stay zero for the whole kernel
+    for (int idx = tid; idx < R * 16; idx += THREADS) {
+        const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
+        *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
+    }
+    wait_vmem(n_after_w - n_after_g0_mark);                            // group 0 has landed
+    stamp();
+    {                                                                  // group 0 -> ring rows 0 .. v0
+        RawRow r0[RPG + 2];
+#pragma unroll
+        for (int k = 0; k < RPG + 2; ++k)
+            if (k <= v0) r0[k] = read_row(slot_off(k < RPG ? k : 2 * RPG + (k - RPG)));
+#pragma unroll
+        for (int k = 0; k < RPG + 2; ++k)
+            if (k <= v0) write_row(k, y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[k]);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                 // set 0 has been read before it is loaded again
+    // group 2 into set 0, as a full round of RPG + 1 loads
+#pragma unroll
+    for (int k = 0; k < RPG; ++k) {
+        const int gy = y0 + v1 + k;
+        const bool real = k < v2 - v1 && gy >= 0 && gy < H;
+        load_row(min(max(gy, 0), H - 1), real ? raw_off + k * SLOT : a.off_dummy);
+    }
+    load_q(npix, 0);                                                   // (a dump load that completes the round)
+    stamp();
+    block_barrier();
+    stamp();
+
+    unsigned char* o_slot = smem + o_off;
+    const int VD = 4 * PS;
+    // results of the previous epoch's pass, ready to be stored (16 bytes: 8 pixels of one channel)
+    uint4_t st_val = {0u, 0u, 0u, 0u};
+    float st_lse = 0.0f;
+    int st_nb = npix;                                                  // first pixel of that pass (npix: nothing to store)
+    const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
+    char* out_base = (char*)(a.out + head_base + (long)y0 * W);
+    auto store_results = [&]() {
+        const int n0 = st_nb + 8 * st_hh;
+        if (n0 < npix) *(uint4_t*)(out_base + ((uint32_t)st_c * hw2 + (uint32_t)n0 * 2u)) = st_val;
+        if (LSE && g == 0 && st_nb + p < npix)
+            a.lse[head_base / D + (long)y0 * W + st_nb + p] = st_lse;
+    };
+
+    int set_rd = RPG * SLOT;                                           // offset of the set that holds group e + 1
+    for (int e = 0; e < E; ++e) {
+        const bool valid = nb < npix;                                  // uniform per wave
+        v3 = srn(e + 3);
+        // ---- A: what this wave issued two epochs ago has landed: group e + 1 and q(e) (only the
+        // latest round of RPG + 1 loads may still be in flight).  Fetch the landed rows into
+        // registers and reuse their slots for group e + 3.
+        if (RPG == 2) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if (RPG == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+        const int cnt = v1 - v0;                                       // rows of group e + 1
+        RawRow raw[RPG];
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) raw[k] = read_row(k < cnt ? raw_off + set_rd + k * SLOT : a.off_dummy);
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + v2 + k;                                // map row of stage row v2 + 1 + k
+            const bool real = k < v3 - v2 && gy >= 0 && gy < H;
+            load_row(min(max(gy, 0), H - 1), real ? raw_off + set_rd + k * SLOT : a.off_dummy);
+        }
+        load_q(nb + 2 * PX_EPOCH, qo_2);
+        store_results();
+        stamp();
+
+        // ---- B: the pass, with the conversion of the fetched rows in its shadow
+        const int ring0 = mod_r(v0 + 1);                               // ring row of the group's first stage row
+        auto convert_group = [&]() {
+#pragma unroll
+            for (int k = 0; k < RPG; ++k) {
+                int ri = ring0 + k;
+                ri = ri >= R ? ri - R : ri;
+                const int gy = y0 + v0 + k;
+                write_row(k < cnt ? ri : R, gy >= 0 && gy < H, raw[k]);
+            }
+        };
+        st_nb = npix;
+        if (valid) {
+            // the pass's 16 pixels start at column c0 of band row ra (ring row rm) and may run into the next row
+            const int ra = div_w(nb), c0 = nb - ra * W, rm = mod_r(ra);
+            int cx = c0 + p, dr = 0;
+            if (cx >= W) { cx -= W; dr = 1; }
+            if (nb + p >= npix) { cx = 0; dr = 0; }                    // lanes past the band: any valid pixel
+            // tap (ty, tx) of the lane's pixel: plane g, ring row of stage row ry + ty, column cx + tx
+            const unsigned char* kb[KS];
+#pragma unroll
+            for (int ty = 0; ty < KS; ++ty) {
+                int ri = rm + dr + ty;                                 // < R + 3
+                ri = ri >= R ? ri - R : ri;
+                kb[ty] = smem + g * PS + ri * RS + cx * 16;
+            }
+            const unsigned char* qsrc = smem + q_slots + qo_cur + (8 * g + (p >> 2)) * 32 + (p & 3) * 8;
+            const uint2_t q0 = lds_read_tr(qsrc), q1 = lds_read_tr(qsrc + 4 * 32);
+            uint4_t kd[S];
+#pragma unroll
+            for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
+            // conversion of the rows fetched above: vector work while the tap reads are in flight
+            convert_group();
+            // q: 8 channels of the lane's pixel as halves divided by 16
+            half2_t qs[4];
+            {
+                const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
+                qs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; qs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
+                qs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; qs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
+            }
+            // ---- K side: the nine logits, row 4g+r of the product in acc1[r] of lane group g
+            float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int t = 0; t < S; ++t) {
+                uint4_t bb;
+#pragma unroll
+                for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
+            }
+            // V taps: issue the LDS reads now, they land while the softmax runs
+            uint4_t vd[S];
+#pragma unroll
+            for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+
+            // ---- softmax over the 9 shifts (3 per lane, 4 lane groups; unused rows have bias -inf)
+            float l[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
+            const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
+            float pr[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
+            const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
+            const float inv = __builtin_amdgcn_rcpf(den);
+            if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
+            uint2_t b2;
+            b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
+            b2[1] = pack_half(pr[2] * inv, 0.0f);
+            const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+
+            // ---- V side: out[c] = sum_t v[c, p+t] * g[c,t] with g = W~v^T a from the matrix core.
+            // Product u < 16 gives, in its four result registers, the weights of channel u & 7 for
+            // taps 4(u >> 3) .. +3; products 16, 17 those of channels 0..3, 4..7 for tap 8.  Two
+            // products stay in flight ahead of the multiply-adds that consume them.
+            const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            float4_t w[2 * S];
+            float o[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) o[x] = 0.0f;
+            constexpr int AHEAD = 2;
+#pragma unroll
+            for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
+#pragma unroll
+            for (int uu = 0; uu < 2 * S; ++uu) {
+                if (uu + AHEAD < 2 * S)
+                    w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
+                // scheduling fence: without it the compiler issues all products first and keeps all
+                // 72 results live
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
+                    const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
+                    o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // results: pixel-major into the wave's slot, back as 8 pixels of one channel
+            uint4_t ov;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                typedef float float2_t __attribute__((ext_vector_type(2)));
+                const float2_t f2 = {o[2 * y], o[2 * y + 1]};
+                ov[y] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));
+            }
+            *(uint4_t*)(o_slot + p * 64 + ((g ^ ((p >> 2) & 3)) << 4)) = ov;
+            const int grp = lane >> 4, nn = lane & 15;
+            const int sa = nn & 3, sj = nn >> 2;                       // as address supplier: pixel sj of the four, channel quad sa
+            const int oct_s = 2 * (grp & 1) + (sa >> 1);
+            const int P0 = 8 * st_hh + sj, P1 = P0 + 4;
+            const uint2_t ra2 = lds_read_tr(o_slot + P0 * 64 + ((oct_s ^ ((P0 >> 2) & 3)) << 4) + (sa & 1) * 8);
+            const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
+            st_val = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
+            st_nb = nb;
+        } else {
+            convert_group();
+        }
+        stamp();
+
+        set_rd = RPG * SLOT - set_rd;
+        v0 = v1; v1 = v2; v2 = v3;
+        { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
+        nb += PX_EPOCH;
+        block_barrier();
+        stamp();
+    }
+    store_results();
+    wait_vmem(0);                                                      // no load into this block's LDS outlives it
+}
+
+// ------------------------------------------------------------------ host side
+struct RingPlan {
+    int rpg, nbp, rows_pb, n_blocks, R, RS, PS, off_raw, off_dummy, off_q, off_out, lds_bytes;
+    bool ok;
+};
+
+static RingPlan plan_ring(const Problem& p)
+{
+    RingPlan r{};
+    r.ok = false;
+    const int W = p.W, H = p.H;
+    if (W < MIN_W || W > MAX_W || (W % 8) != 0) return r;
+    const long planes = (long)p.B * p.heads;
+    const int n_cu = device_cu_count();
+    // bands per plane: fewest rounds of blocks over the compute units, each round costing a
+    // band's rows plus a start-up share
+    double best = 1e300;
+    int best_nbp = 1;
+    for (int nbp = 1; nbp <= H; ++nbp) {
+        const int rows = (H + nbp - 1) / nbp;
+        if ((long)rows * (nbp - 1) >= H) continue;                      // every band has rows
+        if (rows < 4 && nbp > 1) break;
+        const long blocks = planes * nbp;
+        const long rounds = (blocks + n_cu - 1) / n_cu;
+        const double cost = (double)rounds * (rows + 6.0);
+        if (cost < best - 1e-9) { best = cost; best_nbp = nbp; }
+    }
+    r.nbp = best_nbp;
+    r.rows_pb = (H + r.nbp - 1) / r.nbp;
+    if (planes * r.nbp >= (1L << 30)) return r;
+    r.n_blocks = (int)(planes * r.nbp);
+    // Ring depth: the rows read during epoch e and the rows written during it (group e + 1)
+    // must be distinct ring rows: R >= (last row epoch e + 1 reads) - (first row epoch e reads) + 1.
+    const int nr = r.rows_pb;
+    const int E = ((nr * W + 15) / 16 + WAVES - 1) / WAVES;
+    auto srn = [&](int e) {
+        if (e < 0) return -1;
+        if (e >= E) return nr + 1;
+        int rb = (PX_EPOCH * e + PX_EPOCH - 1) / W;
+        if (rb > nr - 1) rb = nr - 1;
+        return rb + 2 < nr + 1 ? rb + 2 : nr + 1;
+    };
+    int need = 3, rpg = 2;
+    for (int e = 0; e < E; ++e) {
+        const int first = (PX_EPOCH * e) / W;
+        const int cnt = srn(e + 1) - first + 1;
+        if (cnt > need) need = cnt;
+        if (e >= 1 && srn(e) - srn(e - 1) > rpg) rpg = srn(e) - srn(e - 1);
+    }
+    if (rpg < srn(0) - 1) rpg = srn(0) - 1;                             // group 0 (srn(0) + 1 rows) fits the rpg + 2 start-up slots
+    if (rpg > 4) return r;
+    if (need < srn(0) + 2) need = srn(0) + 2;
+    r.rpg = rpg;
+    r.R = need;
+    r.RS = (W + 2) * 16;
+    r.PS = (r.R + 1) * r.RS;                                            // ring row R is the dump row
+    int ring_bytes = 8 * r.PS;
+    if (ring_bytes < IMG_RAW_AT + 21 * 1024) ring_bytes = IMG_RAW_AT + 21 * 1024;   // the raw kernels land in whole 1 KB loads
+    r.off_raw = (ring_bytes + 1023) & ~1023;
+    r.off_dummy = r.off_raw + WAVES * 2 * rpg * SLOT;
+    r.off_q = r.off_dummy + SLOT;
+    r.off_out = r.off_q + WAVES * 3 * SLOT;
+    r.lds_bytes = r.off_out + WAVES * SLOT;
+    if (4 * r.PS > 65535 - 64) return r;                                // V taps are read at an immediate offset
+    r.ok = r.lds_bytes <= LDS_LIMIT;
+    return r;
+}
+
+}  // namespace f16ring
+
+bool fwd_ring_supported(const Problem& p, bool aligned16)
+{
+    if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16ring::D) return false;
+    if ((long)p.H * p.W * 2 * f16ring::D >= (1L << 31)) return false;  // 32-bit byte offsets inside a head
+    return f16ring::plan_ring(p).ok;
+}
+
+hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
+                           const float* wk, const float* wv, const float* bias, void* out,
+                           float* lse, hipStream_t st)
+{
+    using namespace f16ring;
+    const RingPlan r = plan_ring(p);
+    if (!r.ok) return hipErrorInvalidValue;
+    RingArgs a;
+    a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.out = (bf16_bits*)out; a.lse = lse;
+    a.wk = wk; a.wv = wv; a.bias = bias;
+    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
+    a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out;
+    a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
+    a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
+    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.idw = p.two_branch ? 1.0f : 0.0f;
+    { const char* e = getenv("SLIDE_RING_TS"); a.ts = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)fwd16_ring_kernel<2, false>, (const void*)fwd16_ring_kernel<2, true>,
+                                  (const void*)fwd16_ring_kernel<3, false>, (const void*)fwd16_ring_kernel<3, true>,
+                                  (const void*)fwd16_ring_kernel<4, false>, (const void*)fwd16_ring_kernel<4, true>}, LDS_LIMIT);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)r.n_blocks), block(THREADS);
+#define SLIDE_RING_LAUNCH(RPGV)                                                                                     \
+    do {                                                                                                            \
+        if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true>), grid, block, (size_t)r.lds_bytes, st, a);      \
+        else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false>), grid, block, (size_t)r.lds_bytes, st, a);     \
+    } while (0)
+    if (r.rpg == 2) SLIDE_RING_LAUNCH(2);
+    else if (r.rpg == 3) SLIDE_RING_LAUNCH(3);
+    else SLIDE_RING_LAUNCH(4);
+#undef SLIDE_RING_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace slide

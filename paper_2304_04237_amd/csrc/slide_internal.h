@@ -84,12 +84,19 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
 // ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
-// 20: one tile per block; 21, 22, 23: pipelined kernel with the tile width read from its
-// arguments / fixed at 56 / fixed at 64.  aligned16: every pointer is 16-byte aligned.
+// 20: one tile per block; 21, 23: pipelined tile kernel with the tile width read from its
+// arguments / fixed at 64; 24: streaming kernel.  aligned16: every pointer is 16-byte aligned.
 int fwd_mfma_variant(const Problem& p, bool aligned16);
 hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, void* workspace, hipStream_t st);
+
+// ---- streaming matrix-core forward (slide_fwd16_ring.hip): bf16, d == 32, ksize 3, 32 <= W <= 64,
+// W % 8 == 0, every pointer 16-byte aligned; needs no workspace
+bool fwd_ring_supported(const Problem& p, bool aligned16);
+hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
+                           const float* wk, const float* wv, const float* bias, void* out,
+                           float* lse, hipStream_t st);
 
 // ---- matrix-core forward, 5x5 window (slide_fwd16_k5.hip): bf16, d == 32, ksize 5
 bool fwd_mfma5_supported(const Problem& p);

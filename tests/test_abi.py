@@ -146,15 +146,16 @@ def test_forward_variant_selection(lib):
     assert v(1, 14, 14, 64, 3, 3, 0, 1) == 0                       # invalid
     assert v(1, 14, 14, 64, 2, 3, 0, 1) == 10                      # float32: general kernel
     assert v(64, 28, 28, 128, 4, 5, 1, 1) == 30                    # 5x5
-    assert v(64, 56, 56, 64, 2, 3, 1, 1) == 22                     # stage 1: pipelined, width 56
+    assert v(64, 56, 56, 64, 2, 3, 1, 1) == 24                     # stage 1: streaming kernel
     assert v(64, 56, 56, 64, 2, 3, 1, 0) == 20                     # unaligned pointers: one tile per block
-    assert v(2, 200, 304, 96, 3, 3, 1, 1) == 23                    # 200x304: pipelined, width 64
-    assert v(96, 40, 40, 64, 2, 3, 1, 1) == 21                     # pipelined, width from the arguments
+    assert v(2, 200, 304, 96, 3, 3, 1, 1) == 23                    # 200x304: pipelined tiles, width 64
+    assert v(96, 40, 40, 64, 2, 3, 1, 1) == 24                     # streaming kernel, 40 columns
+    assert v(300, 24, 24, 64, 2, 3, 1, 1) == 21                    # narrower than 32: pipelined tiles, width from the arguments
     assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0
-    assert v(40, 40, 40, 64, 2, 3, 1, 1) == 20                     # too few tiles
+    assert v(8, 100, 128, 32, 1, 3, 1, 1) == 20                    # wider than 64 and too few tiles to pipeline
     # many small planes: enough tiles, but a tile buffer too small to build the operand image in
     assert v(128, 8, 8, 128, 4, 3, 1, 1) == 20
-    assert v(256, 2, 64, 64, 2, 3, 1, 1) == 20
+    assert v(256, 2, 64, 64, 2, 3, 1, 1) == 24                     # two-row planes: streaming kernel
 
 
 def test_binding_rejects_mismatched_parameter_shapes(lib):

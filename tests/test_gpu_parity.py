@@ -287,23 +287,28 @@ def test_forward_unaligned_parameters_and_activations():
 
 
 PIPELINED_SHAPES = [
-    # B, H, W, C, heads, expected variant: pipelined kernel with the tile width from its arguments
-    (90, 33, 48, 64, 2, 21),             # ragged last row tile
-    (100, 30, 40, 64, 2, 21),
-    (180, 24, 40, 32, 1, 21),            # one head
-    (64, 24, 56, 64, 2, 22),             # width fixed at 56, short planes
-    (12, 64, 72, 64, 2, 23),             # width fixed at 64, ragged second column tile
+    # B, H, W, C, heads, expected variant
+    (90, 33, 48, 64, 2, 24),             # streaming kernel: ragged band split, 48 columns
+    (100, 30, 40, 64, 2, 24),            # 40 columns (groups of up to four new rows per epoch)
+    (180, 24, 32, 32, 1, 24),            # one head, 32 columns
+    (64, 24, 56, 64, 2, 24),             # stage-1 width, short planes
+    (5, 9, 64, 96, 3, 24),               # 64 columns, three heads, one band per plane
+    (3, 61, 56, 64, 2, 24),              # tall planes cut into many bands
+    (256, 2, 64, 64, 2, 24),             # two-row planes: a band shorter than the window's reach
+    (1, 1, 56, 32, 1, 24),               # a single row
+    (12, 64, 72, 64, 2, 23),             # pipelined tiles of width 64, ragged second column tile
+    (300, 24, 24, 64, 2, 21),            # pipelined tiles, width from the arguments
+    (700, 16, 16, 32, 1, 21),
     # enough tiles for the pipelined kernel, but tile buffers too small to build a head's
     # operand image in: must take the one-tile-per-block kernel
     (128, 8, 8, 128, 4, 20),
-    (256, 2, 64, 64, 2, 20),
 ]
 
 
 @pytest.mark.parametrize("shape", PIPELINED_SHAPES)
 def test_forward_kernel_variants_match_oracle(shape):
-    """Every instantiation of the 3x3 matrix-core forward, asserted by the variant query, whole
-    output and lse against the oracle."""
+    """Every kernel of the 3x3 matrix-core forward, asserted by the variant query, whole output
+    and lse against the oracle."""
     B, H, W, C, heads, variant = shape
     print("variant case", shape, flush=True)
     assert sa.slide_attn_fwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True) == variant
@@ -322,7 +327,7 @@ def test_forward_kernel_variants_match_oracle(shape):
 
 def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
-    assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 22
+    assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 24
     assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, False) == 20
     assert sa.slide_attn_fwd_variant(2, 200, 304, 96, 3, 3, torch.bfloat16, True) == 23
     assert sa.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, torch.bfloat16) == 2
