@@ -158,6 +158,30 @@ def main():
             fwd_graph_ms = e0.elapsed_time(e1) / (n_rep * POOL_SETS)
         except Exception:
             fwd_graph_ms = None
+    # what the memory system gives for the forward's bytes without its arithmetic (context for
+    # the roofline): a flat copy-like kernel and the streaming kernel's access pattern
+    probes = {}
+    variant = sa.slide_attn_fwd_variant(B, H, W, C, heads, ksize, torch.bfloat16, True)
+    for mode, name in ((0, "flat_copy_us"), (1, "streaming_pattern_us")):
+        if mode == 1 and variant != 24:
+            continue
+        try:
+            for i in range(POOL_SETS):
+                s_ = pool[i]
+                sa.slide_attn_fwd_traffic_probe(s_["q"], s_["k"], s_["v"], s_["out"], heads, mode)
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            n_p = 40
+            e0.record()
+            for i in range(n_p):
+                s_ = pool[i % POOL_SETS]
+                sa.slide_attn_fwd_traffic_probe(s_["q"], s_["k"], s_["v"], s_["out"], heads, mode)
+            e1.record()
+            torch.cuda.synchronize()
+            probes[name] = e0.elapsed_time(e1) / n_p * 1e3
+        except Exception as exc:                  # noqa: BLE001
+            probes[name] = "failed: %s" % exc
     n_replay, n_tail = (args.steps // POOL_SETS, args.steps % POOL_SETS) if graph is not None else (0, args.steps)
     t0 = time.perf_counter()
     start = torch.cuda.Event(enable_timing=True)
@@ -192,11 +216,12 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16 storage; f16 products and MFMA operands, f32 accumulation", "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d W=%d C=%d heads=%d head_dim=%d ksize=%d"
                                % (wl.name, B, H, W, C, heads, C // heads, ksize),
                    "inputs": "seeded N(0,1) q,k,v; N(0,0.02^2) learned kernels and bias",
-                   "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path, "launch": launch,
+                   "buffer_pool_sets": POOL_SETS, "fwd_kernel_path": path, "fwd_kernel_variant": variant,
+                   "launch": launch,
                    "host_wall_ms_per_step": wall_ms / args.steps},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
@@ -205,7 +230,8 @@ def main():
                      "timing": ("HIP events around back-to-back launches replayed from a graph"
                                 if fwd_graph_ms is not None else "HIP events around each eager call"),
                      "eager_call_avg_ms": fwd_avg_ms, "eager_call_median_ms": fwd_med_ms,
-                     "eager_call_min_ms": fwd_ms[0]},
+                     "eager_call_min_ms": fwd_ms[0],
+                     "same_bytes_no_arithmetic": probes},
     }
 
     # ---- training workload (B=128 forward + backward), extra context
@@ -274,12 +300,20 @@ def main():
         torch.cuda.synchronize()
         tms = a.elapsed_time(b) / n_train
         pxh5 = wl5.B * wl5.H * wl5.W * wl5.heads
+        # algorithmic bytes of one step: forward reads q, k, v and writes out; backward reads
+        # q, k, v, dout and writes dq, dk, dv (11 tensor passes of B*C*H*W bf16 elements)
+        alg5 = 11 * wl5.B * wl5.C * wl5.H * wl5.W * 2
+        ach5 = alg5 / (tms * 1e-3) / 1e9
         result["training"] = {"workload": "stage1_bf16_train: B=128 H=W=56 C=64 heads=2 ksize=3, fwd+bwd",
                               "ms_per_step": tms, "steps": n_train,
                               "value": pxh5 / (tms * 1e-3) / 1e9, "unit": "Gpixel*head/s",
                               "launch": ("hip graph of 2 steps, replayed" if train_graph is not None
                                          else "eager"),
-                              "workspace_bytes": need}
+                              "workspace_bytes": need,
+                              "roofline": {"bound": "hbm", "achieved": ach5, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                           "frac": ach5 / HBM_PEAK_GBS, "algorithmic_bytes": alg5,
+                                           "note": "whole step (reparam x2 + forward + backward, 7 launches) "
+                                                   "against the bytes of one forward and one backward"}}
         del sets, ws, outs
         torch.cuda.empty_cache()
 

@@ -193,6 +193,20 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
 int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,
                            int aligned16);
 
+/*
+ * Measurement aid for benchmarks: moves the bytes of slide_attn_fwd on a SLIDE_BF16 problem
+ * (reads q, k, v once, writes out once; ksize 3) with no arithmetic, so that the forward can be
+ * held against what the memory system gives for its traffic.  out receives the bitwise XOR
+ * of the data read (contents are meaningless).
+ *   mode 0: flat copy-like access (every wave reads and writes contiguous kilobytes);
+ *   mode 1: the blocks, bands, per-instruction address shapes and barriers of the streaming
+ *           forward kernel (only where slide_attn_fwd_variant says 24; SLIDE_ERR_SHAPE
+ *           otherwise).
+ * All four pointers 16-byte aligned device pointers of B*C*H*W bf16 elements.
+ */
+int slide_attn_fwd_traffic_probe(const void* q, const void* k, const void* v, void* out,
+                                 int B, int H, int W, int C, int heads, int mode, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,8 @@ def load_library():
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_fwd_noalloc.restype = i
     lib.slide_attn_fwd_noalloc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
+    lib.slide_attn_fwd_traffic_probe.restype = i
+    lib.slide_attn_fwd_traffic_probe.argtypes = [_vp] * 4 + [i] * 6 + [_vp]
     lib.slide_attn_bwd.restype = i
     lib.slide_attn_bwd.argtypes = [_vp] * 15 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_fwd_two_branch.restype = i
@@ -162,6 +164,17 @@ def slide_attn_fwd_noalloc(q, k, v, wk, wv, bias, heads, ksize, out, lse=None):
                                       _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
                                       _dev(lse, "lse", torch.float32),
                                       B, H, W, C, heads, ksize, code, _stream()))
+    return out
+
+
+def slide_attn_fwd_traffic_probe(q, k, v, out, heads, mode):
+    """The forward's bytes without its arithmetic (mode 0: flat copy, 1: the streaming kernel's pattern)."""
+    B, C, H, W = q.shape
+    for t, n in ((q, "q"), (k, "k"), (v, "v"), (out, "out")):
+        if t.shape != q.shape or t.dtype != torch.bfloat16:
+            raise SlideAttnError("%s must be bfloat16 [B, C, H, W]" % n)
+    _check(load_library().slide_attn_fwd_traffic_probe(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"),
+                                                       B, H, W, C, heads, int(mode), _stream()))
     return out
 
 

@@ -188,6 +188,21 @@ extern "C" int slide_attn_fwd_two_branch(const void* q, const void* k, const voi
                    workspace, workspace_bytes, stream);
 }
 
+extern "C" int slide_attn_fwd_traffic_probe(const void* q, const void* k, const void* v, void* out,
+                                           int B, int H, int W, int C, int heads, int mode, void* stream)
+{
+    int st = check_problem(B, H, W, C, heads, 3, SLIDE_BF16);
+    if (st != SLIDE_OK) return st;
+    if (!q || !k || !v || !out) return SLIDE_ERR_NULL;
+    if (mode != 0 && mode != 1) return SLIDE_ERR_SHAPE;
+    if (!aligned_to(q, 16) || !aligned_to(k, 16) || !aligned_to(v, 16) || !aligned_to(out, 16)) return SLIDE_ERR_ALIGN;
+    Problem p{B, H, W, C, heads, 3, SLIDE_BF16};
+    if (((long)B * C * H * W) % 8 != 0) return SLIDE_ERR_SHAPE;
+    if (mode == 1 && !slide::fwd_ring_supported(p, true)) return SLIDE_ERR_SHAPE;
+    hipError_t e = slide::launch_fwd_traffic_probe(p, q, k, v, out, mode, (hipStream_t)stream);
+    return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
 static int backward(const void* dout, const void* q, const void* k, const void* v,
                     const float* wk, const float* wv, const float* bias,
                     const void* out, const float* lse,

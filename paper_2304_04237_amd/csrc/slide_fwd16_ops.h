@@ -106,18 +106,48 @@ __device__ __forceinline__ void load_operands(const uint32_t* img, int lane, int
 constexpr int IMG_RAW_AT = 20480;                         // byte offset of `raw` behind an image (IMG_DWORDS * 4 = 18496)
 constexpr int HEAD_W = D * S * S;                         // floats of one head in a kernel tensor
 constexpr int IMG_RAW_BYTES = 2 * HEAD_W * 4;             // 20736
-// the gather: raw (the head's K kernels, then its V kernels, as float32 in LDS) -> operand image
+// the gather: raw (the head's K kernels, then its V kernels, as float32 in LDS) -> operand image.
+// 512 threads; the same dwords as image_source() / image_value() describe, with a thread's
+// part of the index arithmetic taken out of its loop: thread (lane, y, th) writes dwords y of
+// that lane for every second tap (A1 part) and for every fourth product (A2 part).
 template <int THREADS>
 __device__ __forceinline__ void image_from_raw(const float* raw, const float* __restrict__ bias, int m, float idw,
                                                uint32_t* dst, int tid)
 {
-    constexpr int N = IMG_BIAS / THREADS;
-    static_assert(N * THREADS == IMG_BIAS, "whole rounds");
+    static_assert(THREADS == 512, "thread-to-dword mapping below");
+    const int lane = tid & 63, i = lane & 15, g = lane >> 4;
+    {
+        // A1: dword (t * 64 + lane) * 4 + y = K weights of channels 8g + 2y, 8g + 2y + 1 for the shift of logit row i at tap t
+        const int y = (tid >> 6) & 3, th = tid >> 8;
+        const int s = shift_of_row(i);
+        const bool ok = s >= 0;
+        const float* w = raw + ((8 * g + 2 * y) * S + max(s, 0)) * S;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        const ImageSource src = image_source(m, tid + i * THREADS, idw);
-        const float* w = raw + (src.from_v ? HEAD_W : 0) - m * HEAD_W;
-        dst[tid + i * THREADS] = image_value(src, w[src.off0], w[src.off1]);
+        for (int k = 0; k < 5; ++k) {
+            const int t = th + 2 * k;
+            if (t < S) {
+                const float sub = (s == t) ? -idw : 0.0f;
+                const float w0 = w[t], w1 = w[t + S * S];
+                dst[IMG_A1 + (t * 64 + lane) * 4 + y] = ok ? pack_half((w0 - sub) * WK_SCALE, (w1 - sub) * WK_SCALE) : 0u;
+            }
+        }
+    }
+    {
+        // A2: dword (u * 64 + lane) * 2 + y = V weights of the product's row i (a channel and a tap) for the shifts of logit rows 4g + 2y, 4g + 2y + 1
+        const int y = (tid >> 6) & 1, uh = tid >> 7;
+        const int s0 = shift_of_row(4 * g + 2 * y), s1 = shift_of_row(4 * g + 2 * y + 1);
+        const float* wv = raw + HEAD_W;
+#pragma unroll
+        for (int k = 0; k < 5; ++k) {
+            const int u = uh + 4 * k;
+            if (k < 4 || uh < 2) {
+                const int c = 8 * (i >> 2) + (k < 4 ? uh + 4 * (k & 1) : 4 * uh + (i & 3));
+                const int tap = k < 4 ? 4 * (k >> 1) + (i & 3) : 8;
+                const float w0 = wv[(c * S + max(s0, 0)) * S + tap], w1 = wv[(c * S + max(s1, 0)) * S + tap];
+                const float sub0 = (s0 == tap) ? -idw : 0.0f, sub1 = (s1 == tap) ? -idw : 0.0f;
+                dst[IMG_A2 + (u * 64 + lane) * 2 + y] = pack_half(s0 >= 0 ? w0 - sub0 : 0.0f, s1 >= 0 ? w1 - sub1 : 0.0f);
+            }
+        }
     }
     if (tid < IMG_DWORDS - IMG_BIAS) dst[IMG_BIAS + tid] = image_bias(bias, m, tid);
 }

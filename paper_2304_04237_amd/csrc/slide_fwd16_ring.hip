@@ -5,20 +5,23 @@
 // differs is how data moves:
 //
 //   - A block (8 waves) owns a band of consecutive rows of one (batch, head) plane and walks
-//     down it.  K and V rows live in LDS in a ring of R rows, pixel-major ([column][32
-//     channels] as halves, 64 B per pixel, the 16-byte channel octets swizzled by the column),
-//     each row staged exactly once per block; the zero padding left and right of the map are
-//     two ring columns that are cleared once, the rows above and below the map are staged as
-//     zeros (Fig. 2).
+//     down it.  K and V rows live in LDS in a ring of R rows: eight planes (tensor x channel
+//     octet), each [ring row][column][8 channels as halves], 16 B per pixel, so the nine taps
+//     of a pixel are three row addresses plus constant offsets and neighbouring lanes read
+//     neighbouring 16-byte slots.  Every row is staged exactly once per block; the zero
+//     padding left and right of the map are two ring columns that are cleared once, the rows
+//     above and below the map are staged as zeros (Fig. 2).
 //   - Global memory is read with 16-byte loads that write straight into LDS
 //     (global_load_lds_dwordx4): the raw bf16 rows land channel-major in per-wave landing
-//     slots and use no registers while in flight.  One epoch later the same wave reads its
+//     slots and use no registers while in flight.  Two epochs later the same wave reads its
 //     slots back with the transposing LDS read (ds_read_b64_tr_b16: a lane gets four
-//     channels of one pixel), converts bf16 -> half and writes the ring row.
+//     channels of one pixel), converts bf16 -> half and writes the ring row.  The head's
+//     kernels arrive the same way and are turned into the operand image in LDS.
 //   - q is private to the pass that uses it: one direct-to-LDS load per pass into a per-wave
-//     slot, read back transposed.  Results leave the same way in reverse: a lane writes its
-//     pixel's 8 channels to a per-wave slot, reads 8 pixels of one channel back transposed
-//     and stores 16 bytes.
+//     slot, read back transposed.  Results go the other way: a lane writes its pixel's 8
+//     channels to a per-wave slot, reads 8 pixels of one channel back transposed, and puts
+//     them into a buffer of the block from which, one barrier later, every wave stores four
+//     channels x 256 contiguous bytes.
 //   - Work is cut into epochs of 128 pixels (one 16-pixel pass per wave).  At the start of
 //     epoch e a wave fetches the landed raw rows that epoch e + 1 will read first (loaded two
 //     epochs earlier) into registers and re-issues loads into their slots for epoch e + 3;
@@ -27,10 +30,10 @@
 //     epoch are never among those read during it.
 //
 // Vector-memory waits are placed by hand: the direct-to-LDS loads are issued from inline
-// assembly (the compiler would otherwise make every LDS read wait for them), and the code
-// below counts the operations in flight itself.
+// assembly (the compiler would otherwise make every LDS read wait for them), and every epoch
+// issues the same number of them, so "all but the latest round have landed" is one constant
+// wait.
 #include "slide_fwd16_ops.h"
-#include <stdlib.h>
 
 namespace slide {
 namespace f16ring {
@@ -48,11 +51,10 @@ struct RingArgs {
     const float* wk; const float* wv; const float* bias;
     int B, H, W, C, heads;
     int nbp, rows_pb, n_blocks;                // bands per plane, rows per band, blocks
-    int R, RS, PS;                             // ring rows, bytes per ring row = (W + 2) * 16, bytes per unit plane = (R + 1) * RS
-    int off_raw, off_dummy, off_q, off_out;    // LDS byte offsets: K/V landing slots, dump slot, q slots, result slots
+    int R, RS, PS;                             // ring rows, bytes per ring row = (W + 2) * 16, bytes per unit plane = R * RS
+    int off_raw, off_dummy, off_q, off_out, off_out2;   // LDS byte offsets: K/V landing slots, dump slot, q slots, per-wave result slots, the block's two result buffers
     uint32_t magic_w, magic_r;                 // ceil(2^32 / W), ceil(2^32 / R): x / W == umulhi(x, magic_w) for x < 2^26
     float scale_log2e, idw;
-    unsigned long long* ts;                    // development builds: time stamps
 };
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
@@ -125,8 +127,7 @@ __device__ __forceinline__ uint32_t bf16x2_to_half2(uint32_t d)
 // The epoch loop has no data-dependent control flow beyond "this wave has a pass": every epoch
 // issues exactly RPG + 1 loads per wave (rows a group does not have, rows outside the map and
 // passes past the end of the band are loaded from a valid address into a dump slot), so the
-// wait for "everything but the latest round has landed" is a constant, and rows that are not
-// there are converted into a dump row of the ring.
+// wait for "everything but the latest round has landed" is a constant.
 template <int RPG, bool LSE>
 __global__ void __launch_bounds__(THREADS, 2)
 fwd16_ring_kernel(const RingArgs a)
@@ -140,19 +141,6 @@ fwd16_ring_kernel(const RingArgs a)
     const int RS = a.RS, PS = a.PS;
     const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;                 // LDS address of the dynamic region
-#ifdef SLIDE_RING_STAMPS
-    int ts_n = 0;
-    auto stamp = [&]() {
-        if (a.ts && (blockIdx.x == 0 || blockIdx.x == 100) && (wave == 0 || wave == 5)) {
-            const unsigned long long t = __builtin_amdgcn_s_memrealtime();
-            if (lane == 0 && ts_n < 128) a.ts[(((blockIdx.x ? 1 : 0) * 2 + (wave ? 1 : 0)) * 128) + ts_n] = t;
-            ++ts_n;
-        }
-    };
-#else
-    auto stamp = [&]() {};
-#endif
-    stamp();
 
     // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
     // the XCDs by the hardware; the bands of a plane (which share two halo rows) get indices
@@ -184,7 +172,7 @@ fwd16_ring_kernel(const RingArgs a)
 
     // ---- K/V staging.  Wave w stages unit w = tensor * 4 + channel octet for every new row.  A
     // unit's rows live in LDS plane `unit` of the ring: [ring row 0 .. R][column 0 .. W + 1][8
-    // channels as halves], 16 B per pixel, columns 0 and W + 1 zero, ring row R a dump row.
+    // channels as halves], 16 B per pixel, columns 0 and W + 1 zero.
     // Landing slots of a wave: two sets of RPG (group j uses set j % 2); at start-up also the
     // third q slot and the result slot; one dump slot for the whole block.
     const bf16_bits* kv_src = ((wave >> 2) ? a.v : a.k) + head_base + (long)(8 * (wave & 3)) * HW;
@@ -261,25 +249,21 @@ fwd16_ring_kernel(const RingArgs a)
         const int gy = y0 + v0 + k;
         if (gy >= 0 && gy < H) { load_row(gy, slot_off(RPG + k)); ++n_after_w; }
     }
-    stamp();
     wait_vmem(n_after_w);                                              // the kernels have landed
     block_barrier();
     image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
     block_barrier();
-    stamp();
     half8_t A1[S];
     half4_t A2[2 * S];
     float bias2[3];
     load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
     block_barrier();
-    stamp();
     // the two padding columns of every ring row stay zero for the whole kernel
     for (int idx = tid; idx < R * 16; idx += THREADS) {
         const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
         *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
     }
     wait_vmem(n_after_w - n_after_g0_mark);                            // group 0 has landed
-    stamp();
     {                                                                  // group 0 -> ring rows 0 .. v0
         RawRow r0[RPG + 2];
 #pragma unroll
@@ -298,21 +282,28 @@ fwd16_ring_kernel(const RingArgs a)
         load_row(min(max(gy, 0), H - 1), real ? raw_off + k * SLOT : a.off_dummy);
     }
     load_q(npix, 0);                                                   // (a dump load that completes the round)
-    stamp();
     block_barrier();
-    stamp();
 
     unsigned char* o_slot = smem + o_off;
     const int VD = 4 * PS;
-    // results of the previous epoch's pass, ready to be stored (16 bytes: 8 pixels of one channel)
-    uint4_t st_val = {0u, 0u, 0u, 0u};
+    // Results leave in two steps: a pass writes its 16 pixels x 32 channels pixel-major into the
+    // wave's slot, reads them back transposed (8 pixels of one channel per lane) and puts them
+    // into the block's buffer of the epoch, [channel][128 pixels] with rows of OUT_ROW bytes;
+    // one barrier later wave w stores channels 4 w .. 4 w + 3 of that buffer, 256 contiguous
+    // bytes per channel.
+    constexpr int OUT_ROW = 2 * PX_EPOCH + 16;                         // 16 bytes of padding: 16 channel rows hit 16 different bank groups
     float st_lse = 0.0f;
-    int st_nb = npix;                                                  // first pixel of that pass (npix: nothing to store)
+    int st_nb = npix;                                                  // first pixel of this wave's previous pass (npix: none)
+    int st_e0 = npix;                                                  // first pixel of the previous epoch (npix: none)
+    int out2_wr = a.off_out2, out2_rd = a.off_out2 + 32 * OUT_ROW;     // buffer written this epoch / stored this epoch
     const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
     char* out_base = (char*)(a.out + head_base + (long)y0 * W);
     auto store_results = [&]() {
-        const int n0 = st_nb + 8 * st_hh;
-        if (n0 < npix) *(uint4_t*)(out_base + ((uint32_t)st_c * hw2 + (uint32_t)n0 * 2u)) = st_val;
+        const int c = 4 * wave + (lane >> 4), n0 = st_e0 + 8 * (lane & 15);
+        if (n0 < npix) {
+            const uint4_t val = *(const uint4_t*)(smem + out2_rd + c * OUT_ROW + (lane & 15) * 16);
+            *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val;
+        }
         if (LSE && g == 0 && st_nb + p < npix)
             a.lse[head_base / D + (long)y0 * W + st_nb + p] = st_lse;
     };
@@ -340,7 +331,6 @@ fwd16_ring_kernel(const RingArgs a)
         }
         load_q(nb + 2 * PX_EPOCH, qo_2);
         store_results();
-        stamp();
 
         // ---- B: the pass, with the conversion of the fetched rows in its shadow
         const int ring0 = mod_r(v0 + 1);                               // ring row of the group's first stage row
@@ -350,7 +340,7 @@ fwd16_ring_kernel(const RingArgs a)
                 int ri = ring0 + k;
                 ri = ri >= R ? ri - R : ri;
                 const int gy = y0 + v0 + k;
-                write_row(k < cnt ? ri : R, gy >= 0 && gy < H, raw[k]);
+                if (k < cnt) write_row(ri, gy >= 0 && gy < H, raw[k]);
             }
         };
         st_nb = npix;
@@ -455,19 +445,19 @@ fwd16_ring_kernel(const RingArgs a)
             const int P0 = 8 * st_hh + sj, P1 = P0 + 4;
             const uint2_t ra2 = lds_read_tr(o_slot + P0 * 64 + ((oct_s ^ ((P0 >> 2) & 3)) << 4) + (sa & 1) * 8);
             const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
-            st_val = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
+            *(uint4_t*)(smem + out2_wr + st_c * OUT_ROW + (16 * wave + 8 * st_hh) * 2) = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
             st_nb = nb;
         } else {
             convert_group();
         }
-        stamp();
 
         set_rd = RPG * SLOT - set_rd;
+        { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
+        st_e0 = nb - 16 * wave;
         v0 = v1; v1 = v2; v2 = v3;
         { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
         nb += PX_EPOCH;
         block_barrier();
-        stamp();
     }
     store_results();
     wait_vmem(0);                                                      // no load into this block's LDS outlives it
@@ -475,7 +465,7 @@ fwd16_ring_kernel(const RingArgs a)
 
 // ------------------------------------------------------------------ host side
 struct RingPlan {
-    int rpg, nbp, rows_pb, n_blocks, R, RS, PS, off_raw, off_dummy, off_q, off_out, lds_bytes;
+    int rpg, nbp, rows_pb, n_blocks, R, RS, PS, off_raw, off_dummy, off_q, off_out, off_out2, lds_bytes;
     bool ok;
 };
 
@@ -528,17 +518,94 @@ static RingPlan plan_ring(const Problem& p)
     r.rpg = rpg;
     r.R = need;
     r.RS = (W + 2) * 16;
-    r.PS = (r.R + 1) * r.RS;                                            // ring row R is the dump row
+    r.PS = r.R * r.RS;
     int ring_bytes = 8 * r.PS;
     if (ring_bytes < IMG_RAW_AT + 21 * 1024) ring_bytes = IMG_RAW_AT + 21 * 1024;   // the raw kernels land in whole 1 KB loads
     r.off_raw = (ring_bytes + 1023) & ~1023;
     r.off_dummy = r.off_raw + WAVES * 2 * rpg * SLOT;
     r.off_q = r.off_dummy + SLOT;
     r.off_out = r.off_q + WAVES * 3 * SLOT;
-    r.lds_bytes = r.off_out + WAVES * SLOT;
+    r.off_out2 = r.off_out + WAVES * SLOT;
+    r.lds_bytes = r.off_out2 + 2 * 32 * (2 * PX_EPOCH + 16);
     if (4 * r.PS > 65535 - 64) return r;                                // V taps are read at an immediate offset
     r.ok = r.lds_bytes <= LDS_LIMIT;
     return r;
+}
+
+// ------------------------------------------------------------------ traffic probes
+// The bytes of the forward without its arithmetic, to measure what the memory system gives
+// for them.  Results are the bitwise XOR of what was read (so nothing is optimised away).
+typedef __attribute__((ext_vector_type(4))) uint32_t probe_u4;
+
+// flat: every thread reads 16 bytes of q, k, v and writes 16 bytes of out, consecutive lanes
+// consecutive addresses, persistent blocks striding over the tensors
+__global__ void __launch_bounds__(512)
+probe_flat_kernel(const probe_u4* __restrict__ q, const probe_u4* __restrict__ k, const probe_u4* __restrict__ v,
+                  probe_u4* __restrict__ out, long n16)
+{
+    for (long i = (long)blockIdx.x * 512 + threadIdx.x; i < n16; i += (long)gridDim.x * 512)
+        out[i] = q[i] ^ k[i] ^ v[i];
+}
+
+// streaming pattern: the blocks, bands, epochs and per-instruction address shapes of
+// fwd16_ring_kernel (a wave loads the new rows of its K/V unit as 8 channels x one row, its
+// pass's q as 32 channels x 32 bytes, and stores 4 channels x 256 bytes of the previous
+// epoch's pixels), one block barrier per epoch, loads consumed one epoch after their issue
+__global__ void __launch_bounds__(THREADS)
+probe_stream_kernel(const RingArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int W = a.W, H = a.H;
+    const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;
+    int u = blockIdx.x;
+    {
+        const int per = a.n_blocks >> 3;
+        if (u < 8 * per) u = (u & 7) * per + (u >> 3);
+    }
+    const int plane = u / a.nbp, part = u - plane * a.nbp;
+    const int b = plane / a.heads, m = plane - b * a.heads;
+    const int y0 = part * a.rows_pb;
+    const int nr = min(a.rows_pb, H - y0);
+    const long HW = (long)H * W;
+    const long head_base = ((long)b * a.C + (long)m * D) * HW;
+    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
+    auto srn = [&](int j) {
+        if (j < 0) return -1;
+        const int rb = min((int)__umulhi((uint32_t)(PX_EPOCH * j + PX_EPOCH - 1), a.magic_w), nr - 1);
+        return j >= E ? nr + 1 : min(rb + 2, nr + 1);
+    };
+    const char* kv_src = (const char*)(((wave >> 2) ? a.v : a.k) + head_base + (long)(8 * (wave & 3)) * HW);
+    const int NXC = W >> 3;
+    const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;
+    const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
+    const char* q_src = (const char*)(a.q + head_base + (long)y0 * W);
+    char* out_base = (char*)(a.out + head_base + (long)y0 * W);
+    probe_u4 acc = {0u, 0u, 0u, 0u};
+    probe_u4 pend[5];
+#pragma unroll
+    for (int j = 0; j < 5; ++j) pend[j] = probe_u4{0u, 0u, 0u, 0u};
+    for (int e = -1; e < E; ++e) {
+#pragma unroll
+        for (int j = 0; j < 5; ++j) { acc ^= pend[j]; pend[j] = probe_u4{0u, 0u, 0u, 0u}; }
+        // rows that epoch e + 1 is the first to read
+        const int lo = srn(e), hi = srn(e + 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gy = y0 + lo + j;
+            if (lo + 1 + j <= hi && gy >= 0 && gy < H && lane < W)
+                pend[j] = *(const probe_u4*)(kv_src + kv_lane_off + (uint32_t)(gy * W) * 2u);
+        }
+        for (int sr = lo + 5; sr <= hi; ++sr) {                        // (start-up group: more than four rows)
+            const int gy = y0 - 1 + sr;
+            if (gy >= 0 && gy < H && lane < W) acc ^= *(const probe_u4*)(kv_src + kv_lane_off + (uint32_t)(gy * W) * 2u);
+        }
+        const int nq = PX_EPOCH * (e + 1) + 16 * wave + 8 * (lane & 1);
+        if (nq < npix) pend[4] = *(const probe_u4*)(q_src + (uint32_t)(lane >> 1) * hw2 + (uint32_t)nq * 2u);
+        const int no = PX_EPOCH * e + 8 * (lane & 15);
+        if (e >= 0 && no < npix)
+            *(probe_u4*)(out_base + (uint32_t)(4 * wave + (lane >> 4)) * hw2 + (uint32_t)no * 2u) = acc;
+        __builtin_amdgcn_s_barrier();
+    }
 }
 
 }  // namespace f16ring
@@ -563,12 +630,11 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.wk = wk; a.wv = wv; a.bias = bias;
     a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
     a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
-    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out; a.off_out2 = r.off_out2;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    { const char* e = getenv("SLIDE_RING_TS"); a.ts = e ? (unsigned long long*)strtoull(e, nullptr, 0) : nullptr; }
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)fwd16_ring_kernel<2, false>, (const void*)fwd16_ring_kernel<2, true>,
                                   (const void*)fwd16_ring_kernel<3, false>, (const void*)fwd16_ring_kernel<3, true>,
@@ -584,6 +650,27 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     else if (r.rpg == 3) SLIDE_RING_LAUNCH(3);
     else SLIDE_RING_LAUNCH(4);
 #undef SLIDE_RING_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_traffic_probe(const Problem& p, const void* q, const void* k, const void* v, void* out,
+                                    int mode, hipStream_t st)
+{
+    using namespace f16ring;
+    if (mode == 0) {
+        const long n16 = (long)p.B * p.C * p.H * p.W * 2 / 16;
+        hipLaunchKernelGGL(probe_flat_kernel, dim3((unsigned)(8 * device_cu_count())), dim3(512), 0, st,
+                           (const probe_u4*)q, (const probe_u4*)k, (const probe_u4*)v, (probe_u4*)out, n16);
+        return hipGetLastError();
+    }
+    const RingPlan r = plan_ring(p);
+    if (!r.ok) return hipErrorInvalidValue;
+    RingArgs a{};
+    a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v; a.out = (bf16_bits*)out;
+    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
+    a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
+    a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
+    hipLaunchKernelGGL(probe_stream_kernel, dim3((unsigned)r.n_blocks), dim3(THREADS), 0, st, a);
     return hipGetLastError();
 }
 

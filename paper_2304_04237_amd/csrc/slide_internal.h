@@ -98,6 +98,11 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, hipStream_t st);
 
+// the forward's bytes without its arithmetic: mode 0 flat copy-like, mode 1 the streaming
+// kernel's access pattern (needs fwd_ring_supported)
+hipError_t launch_fwd_traffic_probe(const Problem& p, const void* q, const void* k, const void* v, void* out,
+                                    int mode, hipStream_t st);
+
 // ---- matrix-core forward, 5x5 window (slide_fwd16_k5.hip): bf16, d == 32, ksize 5
 bool fwd_mfma5_supported(const Problem& p);
 size_t fwd_mfma5_workspace_bytes(const Problem& p);

@@ -149,7 +149,8 @@ def test_forward_variant_selection(lib):
     assert v(64, 56, 56, 64, 2, 3, 1, 1) == 24                     # stage 1: streaming kernel
     assert v(64, 56, 56, 64, 2, 3, 1, 0) == 20                     # unaligned pointers: one tile per block
     assert v(2, 200, 304, 96, 3, 3, 1, 1) == 23                    # 200x304: pipelined tiles, width 64
-    assert v(96, 40, 40, 64, 2, 3, 1, 1) == 24                     # streaming kernel, 40 columns
+    assert v(96, 48, 48, 64, 2, 3, 1, 1) == 24                     # streaming kernel, 48 columns
+    assert v(96, 40, 40, 64, 2, 3, 1, 1) == 21                     # 40 columns need too much LDS there: pipelined tiles
     assert v(300, 24, 24, 64, 2, 3, 1, 1) == 21                    # narrower than 32: pipelined tiles, width from the arguments
     assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0
     assert v(8, 100, 128, 32, 1, 3, 1, 1) == 20                    # wider than 64 and too few tiles to pipeline

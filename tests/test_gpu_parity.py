@@ -289,7 +289,8 @@ def test_forward_unaligned_parameters_and_activations():
 PIPELINED_SHAPES = [
     # B, H, W, C, heads, expected variant
     (90, 33, 48, 64, 2, 24),             # streaming kernel: ragged band split, 48 columns
-    (100, 30, 40, 64, 2, 24),            # 40 columns (groups of up to four new rows per epoch)
+    (100, 30, 40, 64, 2, 21),            # 40 columns: too much LDS for the streaming kernel, pipelined tiles
+    (90, 31, 32, 64, 2, 24),             # 32 columns (groups of up to four new rows per epoch)
     (180, 24, 32, 32, 1, 24),            # one head, 32 columns
     (64, 24, 56, 64, 2, 24),             # stage-1 width, short planes
     (5, 9, 64, 96, 3, 24),               # 64 columns, three heads, one band per plane
