@@ -194,6 +194,23 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
                            int aligned16);
 
 /*
+ * Plain-shift forward: local attention over the ksize x ksize window whose keys and values
+ * are the fixed shifts alone (Sec. 4.2: Eq. 9 rewritten as one-hot depthwise kernels in
+ * Eq. 10-13; the "without deformed shifting" stage of Fig. 1 and Fig. 5).  Computes what
+ * slide_attn_fwd computes for wk = wv = slide_reparam(0), i.e.
+ *     Ks[c,s] = k[c, pixel + offset(s)],  Vs[c,s] = v[c, pixel + offset(s)]
+ * (zero outside the map; those positions stay in the softmax), without reading any kernel
+ * and with k*k instead of k^4 multiply-adds per pixel and channel.
+ * q, k, v, bias, out, lse, the shape arguments, dtype, the number-format contract and the
+ * error codes are those of slide_attn_fwd; there is no workspace.  Where
+ * slide_attn_fwd_variant(...) says 24 the streaming matrix-core kernel runs in its plain
+ * form; every other problem runs on the general kernel.
+ */
+int slide_attn_fwd_shift(const void* q, const void* k, const void* v, const float* bias,
+                         void* out, float* lse,
+                         int B, int H, int W, int C, int heads, int ksize, int dtype, void* stream);
+
+/*
  * Measurement aid for benchmarks: moves the bytes of slide_attn_fwd on a SLIDE_BF16 problem
  * (reads q, k, v once, writes out once; ksize 3) with no arithmetic, so that the forward can be
  * held against what the memory system gives for its traffic.  out receives the bitwise XOR

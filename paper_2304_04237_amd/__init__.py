@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     slide_attn_fwd_noalloc,
     slide_attn_fwd_two_branch,
     slide_attn_fwd_path,
+    slide_attn_fwd_shift,
     slide_attn_fwd_traffic_probe,
     slide_attn_fwd_variant,
     slide_attn_workspace_bytes,

@@ -50,6 +50,8 @@ def load_library():
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_fwd_noalloc.restype = i
     lib.slide_attn_fwd_noalloc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
+    lib.slide_attn_fwd_shift.restype = i
+    lib.slide_attn_fwd_shift.argtypes = [_vp] * 6 + [i] * 7 + [_vp]
     lib.slide_attn_fwd_traffic_probe.restype = i
     lib.slide_attn_fwd_traffic_probe.argtypes = [_vp] * 4 + [i] * 6 + [_vp]
     lib.slide_attn_bwd.restype = i
@@ -164,6 +166,30 @@ def slide_attn_fwd_noalloc(q, k, v, wk, wv, bias, heads, ksize, out, lse=None):
                                       _dev(bias, "bias", torch.float32), _dev(out, "out", q.dtype),
                                       _dev(lse, "lse", torch.float32),
                                       B, H, W, C, heads, ksize, code, _stream()))
+    return out
+
+
+def slide_attn_fwd_shift(q, k, v, bias, heads, ksize, out=None, lse=None):
+    """Plain-shift forward: local attention over the window with no learned kernels."""
+    if q.dim() != 4:
+        raise SlideAttnError("activations must be [B, C, H, W]")
+    B, C, H, W = q.shape
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if bias is not None and tuple(bias.shape) != (heads, ksize * ksize):
+        raise SlideAttnError("bias must be [heads, k*k] = %s, got %s" % ((heads, ksize * ksize), tuple(bias.shape)))
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype:
+        raise SlideAttnError("out must match q in shape and dtype")
+    if lse is not None and tuple(lse.shape) != (B, heads, H, W):
+        raise SlideAttnError("lse must be [B, heads, H, W]")
+    _check(load_library().slide_attn_fwd_shift(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                               _dev(bias, "bias", torch.float32), _dev(out, "out"),
+                                               _dev(lse, "lse", torch.float32),
+                                               B, H, W, C, heads, ksize, code, _stream()))
     return out
 
 

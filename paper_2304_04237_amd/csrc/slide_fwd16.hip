@@ -546,7 +546,7 @@ static bool choose_pipelined(const Problem& p, bool aligned16, TilePlan& t)
 
 // SLIDE_ATTN_DISABLE_RING=1 in the environment keeps the streaming kernel out of the dispatch
 // (for side-by-side measurements of the tiled kernels); read once.
-static bool ring_enabled()
+bool fwd_ring_enabled()
 {
     static const bool on = [] {
         const char* e = getenv("SLIDE_ATTN_DISABLE_RING");
@@ -558,7 +558,7 @@ static bool ring_enabled()
 int fwd_mfma_variant(const Problem& p, bool aligned16)
 {
     using namespace f16path;
-    if (ring_enabled() && fwd_ring_supported(p, aligned16)) return 24;
+    if (fwd_ring_enabled() && fwd_ring_supported(p, aligned16)) return 24;
     TilePlan t;
     if (!choose_pipelined(p, aligned16, t)) return 20;
     return t.tw == 64 ? 23 : 21;
@@ -571,8 +571,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     using namespace f16path;
     const bool aligned = (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out |
                            (uintptr_t)wk | (uintptr_t)wv) % 16 == 0);
-    if (ring_enabled() && fwd_ring_supported(p, aligned))
-        return launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, st);
+    if (fwd_ring_enabled() && fwd_ring_supported(p, aligned))
+        return launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, false, st);
     TilePlan t;
     const bool pipelined = choose_pipelined(p, aligned, t);
     uint32_t* image = (uint32_t*)workspace;

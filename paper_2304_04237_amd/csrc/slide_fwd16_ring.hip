@@ -128,7 +128,12 @@ __device__ __forceinline__ uint32_t bf16x2_to_half2(uint32_t d)
 // issues exactly RPG + 1 loads per wave (rows a group does not have, rows outside the map and
 // passes past the end of the band are loaded from a valid address into a dump slot), so the
 // wait for "everything but the latest round has landed" is a constant.
-template <int RPG, bool LSE>
+//
+// PLAIN: the shift without learned kernels (Sec. 4.2, Eq. 10-13: every shift is a one-hot
+// depthwise kernel, so the shifted keys and values are the taps themselves).  No kernels are
+// read and no operand image is built; the matrix core only adds the 32 channel products of a
+// tap, and every lane holds all nine logits of its pixel.
+template <int RPG, bool LSE, bool PLAIN>
 __global__ void __launch_bounds__(THREADS, 2)
 fwd16_ring_kernel(const RingArgs a)
 {
@@ -228,7 +233,7 @@ fwd16_ring_kernel(const RingArgs a)
     int nb = 16 * wave;                                                // first pixel of this wave's pass of the current epoch
     int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
     int n_after_w = 0;                                                 // loads issued after the kernels'
-    {
+    if (!PLAIN) {
         // 2 x 32 x 81 floats = 1296 chunks of 16 bytes, K kernels then V kernels, to smem + IMG_RAW_AT
         constexpr int CHUNKS = HEAD_W / 4;
         for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
@@ -249,15 +254,21 @@ fwd16_ring_kernel(const RingArgs a)
         const int gy = y0 + v0 + k;
         if (gy >= 0 && gy < H) { load_row(gy, slot_off(RPG + k)); ++n_after_w; }
     }
-    wait_vmem(n_after_w);                                              // the kernels have landed
-    block_barrier();
-    image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
-    block_barrier();
     half8_t A1[S];
     half4_t A2[2 * S];
     float bias2[3];
-    load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
-    block_barrier();
+    float bias9[S];                                                    // PLAIN: the head's biases times log2(e), uniform
+    if (!PLAIN) {
+        wait_vmem(n_after_w);                                          // the kernels have landed
+        block_barrier();
+        image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
+        block_barrier();
+        load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
+        block_barrier();
+    } else {
+#pragma unroll
+        for (int t = 0; t < S; ++t) bias9[t] = a.bias ? a.bias[m * S + t] * 1.44269504088896341f : 0.0f;
+    }
     // the two padding columns of every ring row stay zero for the whole kernel
     for (int idx = tid; idx < R * 16; idx += THREADS) {
         const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
@@ -372,62 +383,99 @@ fwd16_ring_kernel(const RingArgs a)
                 qs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; qs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
                 qs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; qs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
             }
-            // ---- K side: the nine logits, row 4g+r of the product in acc1[r] of lane group g
-            float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int t = 0; t < S; ++t) {
-                uint4_t bb;
-#pragma unroll
-                for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
-                acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
-            }
-            // V taps: issue the LDS reads now, they land while the softmax runs
-            uint4_t vd[S];
-#pragma unroll
-            for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
-
-            // ---- softmax over the 9 shifts (3 per lane, 4 lane groups; unused rows have bias -inf)
-            float l[3];
-#pragma unroll
-            for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
-            const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
-            float pr[3];
-#pragma unroll
-            for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
-            const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
-            const float inv = __builtin_amdgcn_rcpf(den);
-            if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
-            uint2_t b2;
-            b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
-            b2[1] = pack_half(pr[2] * inv, 0.0f);
-            const half4_t B2 = __builtin_bit_cast(half4_t, b2);
-
-            // ---- V side: out[c] = sum_t v[c, p+t] * g[c,t] with g = W~v^T a from the matrix core.
-            // Product u < 16 gives, in its four result registers, the weights of channel u & 7 for
-            // taps 4(u >> 3) .. +3; products 16, 17 those of channels 0..3, 4..7 for tap 8.  Two
-            // products stay in flight ahead of the multiply-adds that consume them.
-            const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-            float4_t w[2 * S];
             float o[8];
 #pragma unroll
             for (int x = 0; x < 8; ++x) o[x] = 0.0f;
-            constexpr int AHEAD = 2;
+            if (PLAIN) {
+                // ---- logits: the matrix core adds a tap's 32 channel products (every row of the
+                // left operand is sixteen, which undoes q's division), so each of the four lanes of
+                // a pixel gets the full sum
+                const uint32_t c16 = 0x4c004c00u;
+                const half8_t ones = __builtin_bit_cast(half8_t, uint4_t{c16, c16, c16, c16});
+                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                float l[S];
 #pragma unroll
-            for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
+                for (int t = 0; t < S; ++t) {
+                    uint4_t bb;
 #pragma unroll
-            for (int uu = 0; uu < 2 * S; ++uu) {
-                if (uu + AHEAD < 2 * S)
-                    w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
-                // scheduling fence: without it the compiler issues all products first and keeps all
-                // 72 results live
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
-                    const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
-                    o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
+                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                    const float4_t dsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(half8_t, bb), zero4, 0, 0, 0);
+                    l[t] = dsum[0];
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                uint4_t vd[S];
+#pragma unroll
+                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+                // ---- softmax over the nine shifts, all in this lane
+                float mx = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < S; ++t) { l[t] = fmaf(l[t], a.scale_log2e, bias9[t]); mx = fmaxf(mx, l[t]); }
+                float den = 0.0f;
+#pragma unroll
+                for (int t = 0; t < S; ++t) { l[t] = __builtin_amdgcn_exp2f(l[t] - mx); den += l[t]; }
+                const float inv = __builtin_amdgcn_rcpf(den);
+                if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
+                // ---- out[c] = sum_t a[t] v[c, p + t]
+#pragma unroll
+                for (int t = 0; t < S; ++t)
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) o[x] = fmaf(l[t], (float)as_half2(vd[t][x >> 1])[x & 1], o[x]);
+#pragma unroll
+                for (int x = 0; x < 8; ++x) o[x] *= inv;
+            } else {
+                // ---- K side: the nine logits, row 4g+r of the product in acc1[r] of lane group g
+                float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+    #pragma unroll
+                for (int t = 0; t < S; ++t) {
+                    uint4_t bb;
+    #pragma unroll
+                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
+                }
+                // V taps: issue the LDS reads now, they land while the softmax runs
+                uint4_t vd[S];
+    #pragma unroll
+                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+
+                // ---- softmax over the 9 shifts (3 per lane, 4 lane groups; unused rows have bias -inf)
+                float l[3];
+    #pragma unroll
+                for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
+                const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
+                float pr[3];
+    #pragma unroll
+                for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
+                const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
+                const float inv = __builtin_amdgcn_rcpf(den);
+                if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
+                uint2_t b2;
+                b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
+                b2[1] = pack_half(pr[2] * inv, 0.0f);
+                const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+
+                // ---- V side: out[c] = sum_t v[c, p+t] * g[c,t] with g = W~v^T a from the matrix core.
+                // Product u < 16 gives, in its four result registers, the weights of channel u & 7 for
+                // taps 4(u >> 3) .. +3; products 16, 17 those of channels 0..3, 4..7 for tap 8.  Two
+                // products stay in flight ahead of the multiply-adds that consume them.
+                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                float4_t w[2 * S];
+                constexpr int AHEAD = 2;
+    #pragma unroll
+                for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
+    #pragma unroll
+                for (int uu = 0; uu < 2 * S; ++uu) {
+                    if (uu + AHEAD < 2 * S)
+                        w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
+                    // scheduling fence: without it the compiler issues all products first and keeps all
+                    // 72 results live
+                    __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
+                        const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
+                        o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             // results: pixel-major into the wave's slot, back as 8 pixels of one channel
             uint4_t ov;
@@ -619,7 +667,7 @@ bool fwd_ring_supported(const Problem& p, bool aligned16)
 
 hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
-                           float* lse, hipStream_t st)
+                           float* lse, bool plain, hipStream_t st)
 {
     using namespace f16ring;
     const RingPlan r = plan_ring(p);
@@ -636,19 +684,27 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
     static LdsOptIn opt_in;
-    hipError_t e = opt_in.ensure({(const void*)fwd16_ring_kernel<2, false>, (const void*)fwd16_ring_kernel<2, true>,
-                                  (const void*)fwd16_ring_kernel<3, false>, (const void*)fwd16_ring_kernel<3, true>,
-                                  (const void*)fwd16_ring_kernel<4, false>, (const void*)fwd16_ring_kernel<4, true>}, LDS_LIMIT);
+#define SLIDE_RING_KERNELS(RPGV)                                                                                    \
+    (const void*)fwd16_ring_kernel<RPGV, false, false>, (const void*)fwd16_ring_kernel<RPGV, true, false>,          \
+    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>
+    hipError_t e = opt_in.ensure({SLIDE_RING_KERNELS(2), SLIDE_RING_KERNELS(3), SLIDE_RING_KERNELS(4)}, LDS_LIMIT);
+#undef SLIDE_RING_KERNELS
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)r.n_blocks), block(THREADS);
+#define SLIDE_RING_LAUNCH2(RPGV, LSEV)                                                                              \
+    do {                                                                                                            \
+        if (plain) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, true>), grid, block, (size_t)r.lds_bytes, st, a);   \
+        else       hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, false>), grid, block, (size_t)r.lds_bytes, st, a);  \
+    } while (0)
 #define SLIDE_RING_LAUNCH(RPGV)                                                                                     \
     do {                                                                                                            \
-        if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true>), grid, block, (size_t)r.lds_bytes, st, a);      \
-        else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false>), grid, block, (size_t)r.lds_bytes, st, a);     \
+        if (lse) SLIDE_RING_LAUNCH2(RPGV, true);                                                                    \
+        else     SLIDE_RING_LAUNCH2(RPGV, false);                                                                   \
     } while (0)
     if (r.rpg == 2) SLIDE_RING_LAUNCH(2);
     else if (r.rpg == 3) SLIDE_RING_LAUNCH(3);
     else SLIDE_RING_LAUNCH(4);
+#undef SLIDE_RING_LAUNCH2
 #undef SLIDE_RING_LAUNCH
     return hipGetLastError();
 }

@@ -61,13 +61,19 @@ __device__ __forceinline__ void load_window(const T* __restrict__ plane, int i, 
 }
 
 // deformed shift of one channel at one pixel: shifted[s] = sum_t w[s][t] * win[t], plus the
-// fixed shift path idw * win[s] (idw = 1 when w is the learned kernel of the two-branch form)
+// fixed shift path idw * win[s] (idw = 1 when w is the learned kernel of the two-branch form).
+// w_c null: the plain shift (one-hot kernels, Eq. 10-13), shifted[s] = win[s].
 template <int KS>
 __device__ __forceinline__ void apply_kernels(const float* __restrict__ w_c,
                                               const float (&win)[KS * KS],
                                               float (&shifted)[KS * KS], float idw)
 {
     constexpr int S = KS * KS;
+    if (!w_c) {
+#pragma unroll
+        for (int s = 0; s < S; ++s) shifted[s] = win[s];
+        return;
+    }
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         float acc = idw * win[s];
@@ -108,7 +114,7 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
         const T* kp = k + ((long)b * C + c) * HW;
         float win[S], ks[S];
         load_window<T, KS>(kp, i, j, H, W, win);
-        apply_kernels<KS>(wk + (long)c * S * S, win, ks, idw);
+        apply_kernels<KS>(wk ? wk + (long)c * S * S : nullptr, win, ks, idw);
         float qc = Elem<T>::load(q + ((long)b * C + c) * HW + pix);
 #pragma unroll
         for (int s = 0; s < S; ++s) dot[s] = fmaf(qc, ks[s], dot[s]);
@@ -158,7 +164,7 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
         const T* vp = v + ((long)b * C + c) * HW;
         float win[S], vs[S];
         load_window<T, KS>(vp, i, j, H, W, win);
-        apply_kernels<KS>(wv + (long)c * S * S, win, vs, idw);
+        apply_kernels<KS>(wv ? wv + (long)c * S * S : nullptr, win, vs, idw);
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(a[s], vs[s], acc);

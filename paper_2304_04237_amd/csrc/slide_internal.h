@@ -92,11 +92,13 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
                            float* lse, void* workspace, hipStream_t st);
 
 // ---- streaming matrix-core forward (slide_fwd16_ring.hip): bf16, d == 32, ksize 3, 32 <= W <= 64,
-// W % 8 == 0, every pointer 16-byte aligned; needs no workspace
+// W % 8 == 0, every pointer 16-byte aligned; needs no workspace.  plain: the shift without
+// learned kernels (Sec. 4.2, Eq. 10-13); wk and wv are not read then.
 bool fwd_ring_supported(const Problem& p, bool aligned16);
+bool fwd_ring_enabled();                               // false if the environment switches the streaming kernel off
 hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
-                           float* lse, hipStream_t st);
+                           float* lse, bool plain, hipStream_t st);
 
 // the forward's bytes without its arithmetic: mode 0 flat copy-like, mode 1 the streaming
 // kernel's access pattern (needs fwd_ring_supported)

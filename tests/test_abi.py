@@ -72,6 +72,24 @@ def test_forward_rejects_bad_arguments_on_the_host(lib):
     assert call_fwd(lib, lse=ctypes.c_void_p(0x1002)) == 6            # lse not 4-byte aligned
 
 
+def test_shift_forward_rejects_bad_arguments_on_the_host(lib):
+    lib.slide_attn_fwd_shift.restype = ctypes.c_int
+    lib.slide_attn_fwd_shift.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 7 + [ctypes.c_void_p]
+
+    def call(ptr=0x1000, **kw):
+        a = dict(FWD_OK); a.update(kw)
+        p = ctypes.c_void_p(ptr)
+        return lib.slide_attn_fwd_shift(p, p, p, p, p, None, a["B"], a["H"], a["W"], a["C"], a["heads"],
+                                        a["ksize"], a["dtype"], None)
+    assert call(heads=3) == 2
+    assert call(ksize=2) == 2
+    assert call(W=0) == 2
+    assert call(dtype=2) == 3
+    assert call(ptr=0) == 1
+    assert call(ptr=0x1002) == 6
+    assert call(ptr=0x1001, dtype=1) == 6
+
+
 def test_backward_rejects_bad_arguments_on_the_host(lib):
     p = ctypes.c_void_p(0x1000)
     # dout q k v wk wv bias | out lse (optional) | dq dk dv dwk dwv dbias
