@@ -168,5 +168,72 @@ __device__ __forceinline__ void build_image(const float* __restrict__ wk, const 
     image_from_raw<THREADS>(raw, bias, m, idw, dst, tid);
 }
 
+// ------------------------------------------------------------------ data movement of the streaming kernels
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+// 16 bytes per active lane from global memory (uniform base + per-lane byte offset) straight
+// into LDS: lane l's bytes land at lds_base + 16 l.  Counts as one vector-memory operation.
+__device__ __forceinline__ void load_to_lds(const void* base, uint32_t voff, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %1, %0"
+                 :: "s"(base), "v"(voff), "s"(lds_base) : "memory");
+}
+
+// the same with a full 64-bit address per lane
+__device__ __forceinline__ void load_to_lds_addr(const void* vaddr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off"
+                 :: "v"(vaddr), "s"(lds_base) : "memory");
+}
+
+// wait until at most n vector-memory operations of this wave are in flight (n uniform;
+// above 12 the wait is for 12, which is stricter)
+__device__ __forceinline__ void wait_vmem(int n)
+{
+    switch (n) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+        case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+        case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+        case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+        case 11: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    }
+}
+
+// all LDS operations of this wave are done, then the block barrier; memory operations are not
+// moved across it by the compiler
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Transposing LDS read: within each group of 16 lanes, lane n receives element (n % 4) of the
+// 8-byte pieces addressed by lanes n / 4, n / 4 + 4, n / 4 + 8, n / 4 + 12.  With lane s
+// addressing four consecutive pixels 4 (s % 4) .. + 3 of row s / 4 of a [row][pixel] array,
+// lane n gets pixel n of rows 0..3 (and vice versa with rows and pixels exchanged).
+__device__ __forceinline__ uint2_t lds_read_tr(const unsigned char* p)
+{
+    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
+    return __builtin_bit_cast(uint2_t, r);
+}
+
+// two bf16 in a dword -> two halves in a dword (exact for 2^-17 <= |x| <= 65504, round toward
+// zero below, saturating above)
+__device__ __forceinline__ uint32_t bf16x2_to_half2(uint32_t d)
+{
+    return pack_half_rtz(__uint_as_float(d << 16), __uint_as_float(d & 0xffff0000u));
+}
+
 }  // namespace f16ops
 }  // namespace slide

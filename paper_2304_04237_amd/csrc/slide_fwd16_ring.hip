@@ -57,72 +57,6 @@ struct RingArgs {
     float scale_log2e, idw;
 };
 
-typedef short short4_t __attribute__((ext_vector_type(4)));
-
-// 16 bytes per active lane from global memory (uniform base + per-lane byte offset) straight
-// into LDS: lane l's bytes land at lds_base + 16 l.  Counts as one vector-memory operation.
-__device__ __forceinline__ void load_to_lds(const void* base, uint32_t voff, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %2\n\t"
-                 "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %1, %0"
-                 :: "s"(base), "v"(voff), "s"(lds_base) : "memory");
-}
-
-// the same with a full 64-bit address per lane
-__device__ __forceinline__ void load_to_lds_addr(const void* vaddr, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\t"
-                 "s_nop 0\n\t"
-                 "global_load_lds_dwordx4 %0, off"
-                 :: "v"(vaddr), "s"(lds_base) : "memory");
-}
-
-// wait until at most n vector-memory operations of this wave are in flight (n uniform;
-// above 12 the wait is for 12, which is stricter)
-__device__ __forceinline__ void wait_vmem(int n)
-{
-    switch (n) {
-        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
-        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
-        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
-        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
-        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
-        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
-        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
-        case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
-        case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
-        case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
-        case 11: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
-        default: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
-    }
-}
-
-// all LDS operations of this wave are done, then the block barrier; memory operations are not
-// moved across it by the compiler
-__device__ __forceinline__ void block_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
-// Transposing LDS read: within each group of 16 lanes, lane n receives element (n % 4) of the
-// 8-byte pieces addressed by lanes n / 4, n / 4 + 4, n / 4 + 8, n / 4 + 12.  With lane s
-// addressing four consecutive pixels 4 (s % 4) .. + 3 of row s / 4 of a [row][pixel] array,
-// lane n gets pixel n of rows 0..3 (and vice versa with rows and pixels exchanged).
-__device__ __forceinline__ uint2_t lds_read_tr(const unsigned char* p)
-{
-    const short4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
-    return __builtin_bit_cast(uint2_t, r);
-}
-
-// two bf16 in a dword -> two halves in a dword (exact for 2^-17 <= |x| <= 65504, round toward
-// zero below, saturating above)
-__device__ __forceinline__ uint32_t bf16x2_to_half2(uint32_t d)
-{
-    return pack_half_rtz(__uint_as_float(d << 16), __uint_as_float(d & 0xffff0000u));
-}
-
 // RPG: most rows a group of new K/V rows can have (rows that one epoch is the first to read).
 // The epoch loop has no data-dependent control flow beyond "this wave has a pass": every epoch
 // issues exactly RPG + 1 loads per wave (rows a group does not have, rows outside the map and
@@ -145,7 +79,7 @@ fwd16_ring_kernel(const RingArgs a)
     const int W = a.W, H = a.H, R = a.R;
     const int RS = a.RS, PS = a.PS;
     const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;                 // LDS address of the dynamic region
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS address of the dynamic region
 
     // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
     // the XCDs by the hardware; the bands of a plane (which share two halo rows) get indices
@@ -206,13 +140,20 @@ fwd16_ring_kernel(const RingArgs a)
     };
     // convert a fetched row (zeros if !in_map) and write it to ring row ri of this wave's plane
     unsigned char* cv_dst = smem + wave * PS + (lane + 1) * 16;
-    auto write_row = [&](int ri, bool in_map, const RawRow& r) {
+    // (ring_off: byte offset of the ring row inside a plane)
+    auto write_row = [&](uint32_t ring_off, bool in_map, const RawRow& r) {
         uint4_t h4;
         h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
         h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
 #pragma unroll
         for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
-        if (lane < W) *(uint4_t*)(cv_dst + ri * RS) = h4;
+        if (lane < W) *(uint4_t*)(cv_dst + ring_off) = h4;
+    };
+    auto write_row_in_map = [&](uint32_t ring_off, const RawRow& r) {
+        uint4_t h4;
+        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
+        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
+        if (lane < W) *(uint4_t*)(cv_dst + ring_off) = h4;
     };
 
     // ---- q: one direct load per pass into one of the wave's three slots, two epochs ahead
@@ -229,7 +170,7 @@ fwd16_ring_kernel(const RingArgs a)
 
     // ---- start-up: every load that has a slot first: the head's kernels, group 0, q of the
     // first two epochs, group 1
-    int v0 = srn(0), v1 = srn(1), v2 = srn(2), v3 = 0;                 // srn(e), srn(e+1), srn(e+2), srn(e+3) with e = 0
+    const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int nb = 16 * wave;                                                // first pixel of this wave's pass of the current epoch
     int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
     int n_after_w = 0;                                                 // loads issued after the kernels'
@@ -282,7 +223,7 @@ fwd16_ring_kernel(const RingArgs a)
             if (k <= v0) r0[k] = read_row(slot_off(k < RPG ? k : 2 * RPG + (k - RPG)));
 #pragma unroll
         for (int k = 0; k < RPG + 2; ++k)
-            if (k <= v0) write_row(k, y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[k]);
+            if (k <= v0) write_row((uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[k]);
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                 // set 0 has been read before it is loaded again
     // group 2 into set 0, as a full round of RPG + 1 loads
@@ -319,56 +260,92 @@ fwd16_ring_kernel(const RingArgs a)
             a.lse[head_base / D + (long)y0 * W + st_nb + p] = st_lse;
     };
 
+    // ---- the schedule: everything uniform that an epoch needs, worked out once, lane e of the
+    // table registers holding epoch e (E <= 64).  Ring positions are in 16-byte units (10 bits).
+    //   t_cvA, t_cvB: ring positions of the rows of group e + 1 (converted during epoch e), their
+    //                 number, which of them lie outside the map (written as zeros), and which
+    //                 loads of group e + 3 are real
+    //   t_ld:         byte offset of the first row of group e + 3 inside a channel plane
+    //   t_p0, t_p1:   ring positions of the three tap rows of this wave's pass, for lanes that stay
+    //                 in the pass's first row / that run into the next row
+    //   t_p2:         column of the pass's first pixel; bit 8: the wave has a pass
+    uint32_t t_cvA, t_cvB, t_ld, t_p0, t_p1, t_p2;
+    {
+        const int e = lane;
+        const int s0 = srn(e), s1 = srn(e + 1), s2 = srn(e + 2), s3 = srn(e + 3);
+        const int RW = W + 2;
+        auto ring_of = [&](int sr) { return (uint32_t)(mod_r(sr) * RW); };
+        t_cvA = ring_of(s0 + 1) | ring_of(s0 + 2) << 10 | ring_of(s0 + 3) << 20;
+        uint32_t outside = 0, ldm = 0;
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + s0 + k, gl = y0 + s2 + k;
+            outside |= (gy < 0 || gy >= H) ? 1u << k : 0u;
+            ldm |= (k < s3 - s2 && gl >= 0 && gl < H) ? 1u << k : 0u;
+        }
+        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13 | ldm << 17;
+        t_ld = (uint32_t)(min(max(y0 + s2, 0), H - 1) * W) * 2u;
+        const int nbe = PX_EPOCH * e + 16 * wave;
+        const int ra = div_w(nbe), c0 = nbe - ra * W;
+        t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
+        t_p1 = ring_of(ra + 1) | ring_of(ra + 2) << 10 | ring_of(ra + 3) << 20;
+        t_p2 = (uint32_t)c0 | (nbe < npix ? 256u : 0u);
+    }
+    const uint32_t w2 = (uint32_t)W * 2u;
+    const unsigned char* tap_base = smem + g * PS;                     // plane g of the ring
+
     int set_rd = RPG * SLOT;                                           // offset of the set that holds group e + 1
     for (int e = 0; e < E; ++e) {
-        const bool valid = nb < npix;                                  // uniform per wave
-        v3 = srn(e + 3);
+        const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
+        const uint32_t ldo = __builtin_amdgcn_readlane(t_ld, e);
         // ---- A: what this wave issued two epochs ago has landed: group e + 1 and q(e) (only the
         // latest round of RPG + 1 loads may still be in flight).  Fetch the landed rows into
         // registers and reuse their slots for group e + 3.
         if (RPG == 2) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
         else if (RPG == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        const int cnt = v1 - v0;                                       // rows of group e + 1
         RawRow raw[RPG];
 #pragma unroll
-        for (int k = 0; k < RPG; ++k) raw[k] = read_row(k < cnt ? raw_off + set_rd + k * SLOT : a.off_dummy);
+        for (int k = 0; k < RPG; ++k) raw[k] = read_row(raw_off + set_rd + k * SLOT);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
         for (int k = 0; k < RPG; ++k) {
-            const int gy = y0 + v2 + k;                                // map row of stage row v2 + 1 + k
-            const bool real = k < v3 - v2 && gy >= 0 && gy < H;
-            load_row(min(max(gy, 0), H - 1), real ? raw_off + set_rd + k * SLOT : a.off_dummy);
+            const bool real = (cvB >> (17 + k)) & 1u;
+            if (lane < W)
+                load_to_lds(kv_src, kv_lane_off + (real ? ldo + (uint32_t)k * w2 : ldo),
+                            lds0 + (real ? raw_off + set_rd + k * SLOT : a.off_dummy));
         }
         load_q(nb + 2 * PX_EPOCH, qo_2);
         store_results();
 
         // ---- B: the pass, with the conversion of the fetched rows in its shadow
-        const int ring0 = mod_r(v0 + 1);                               // ring row of the group's first stage row
+        const int cnt = (cvB >> 10) & 7;
         auto convert_group = [&]() {
+            if (((cvB >> 13) & 15u) == 0) {                            // every row inside the map: the usual case
 #pragma unroll
-            for (int k = 0; k < RPG; ++k) {
-                int ri = ring0 + k;
-                ri = ri >= R ? ri - R : ri;
-                const int gy = y0 + v0 + k;
-                if (k < cnt) write_row(ri, gy >= 0 && gy < H, raw[k]);
+                for (int k = 0; k < RPG; ++k)
+                    if (k < cnt) write_row_in_map((k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16, raw[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < RPG; ++k)
+                    if (k < cnt) write_row((k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16, !((cvB >> (13 + k)) & 1u), raw[k]);
             }
         };
+        const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
+        const bool valid = (p2 & 256u) != 0;                           // uniform per wave
         st_nb = npix;
         if (valid) {
-            // the pass's 16 pixels start at column c0 of band row ra (ring row rm) and may run into the next row
-            const int ra = div_w(nb), c0 = nb - ra * W, rm = mod_r(ra);
-            int cx = c0 + p, dr = 0;
-            if (cx >= W) { cx -= W; dr = 1; }
-            if (nb + p >= npix) { cx = 0; dr = 0; }                    // lanes past the band: any valid pixel
-            // tap (ty, tx) of the lane's pixel: plane g, ring row of stage row ry + ty, column cx + tx
+            // the pass's 16 pixels start at column c0 of a band row and may run into the next row;
+            // tap (ty, tx) of the lane's pixel: plane g, ring position of tap row ty, column cx + tx
+            // (lanes past the band read some staged pixel; nothing of theirs is stored)
+            const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
+            const int cx0 = (int)(p2 & 255u) + p;
+            const bool next_row = cx0 >= W;
+            const uint32_t cx = next_row ? cx0 - W : cx0;
+            const uint32_t rows = next_row ? p1 : p0;
             const unsigned char* kb[KS];
 #pragma unroll
-            for (int ty = 0; ty < KS; ++ty) {
-                int ri = rm + dr + ty;                                 // < R + 3
-                ri = ri >= R ? ri - R : ri;
-                kb[ty] = smem + g * PS + ri * RS + cx * 16;
-            }
+            for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
             const unsigned char* qsrc = smem + q_slots + qo_cur + (8 * g + (p >> 2)) * 32 + (p & 3) * 8;
             const uint2_t q0 = lds_read_tr(qsrc), q1 = lds_read_tr(qsrc + 4 * 32);
             uint4_t kd[S];
@@ -502,7 +479,6 @@ fwd16_ring_kernel(const RingArgs a)
         set_rd = RPG * SLOT - set_rd;
         { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
         st_e0 = nb - 16 * wave;
-        v0 = v1; v1 = v2; v2 = v3;
         { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
         nb += PX_EPOCH;
         block_barrier();
@@ -533,6 +509,7 @@ static RingPlan plan_ring(const Problem& p)
         const int rows = (H + nbp - 1) / nbp;
         if ((long)rows * (nbp - 1) >= H) continue;                      // every band has rows
         if (rows < 4 && nbp > 1) break;
+        if (((rows * W + 15) / 16 + WAVES - 1) / WAVES > 64) continue;  // the kernel's schedule table holds 64 epochs
         const long blocks = planes * nbp;
         const long rounds = (blocks + n_cu - 1) / n_cu;
         const double cost = (double)rounds * (rows + 6.0);
@@ -546,6 +523,7 @@ static RingPlan plan_ring(const Problem& p)
     // must be distinct ring rows: R >= (last row epoch e + 1 reads) - (first row epoch e reads) + 1.
     const int nr = r.rows_pb;
     const int E = ((nr * W + 15) / 16 + WAVES - 1) / WAVES;
+    if (E > 64) return r;
     auto srn = [&](int e) {
         if (e < 0) return -1;
         if (e >= E) return nr + 1;
