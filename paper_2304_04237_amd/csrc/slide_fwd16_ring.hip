@@ -487,6 +487,394 @@ fwd16_ring_kernel(const RingArgs a)
     wait_vmem(0);                                                      // no load into this block's LDS outlives it
 }
 
+// ------------------------------------------------------------------ the same with mover waves
+// Twelve waves per block: waves 0 .. 7 only run passes; waves 8 .. 11 ("movers") do all of the
+// data movement around them.  Mover j stages octet j of K and of V (fetch of the landed rows,
+// conversion, ring rows, loads of later groups), issues the q loads of passes 2j and 2j + 1
+// and stores channels 8j .. 8j + 7 of the previous epoch's results.  A pass wave issues 280
+// instead of 470 instructions per epoch, and three waves instead of two share a SIMD (the
+// kernel stays under 168 registers); LDS is laid out as for fwd16_ring_kernel.
+// A mover waits at the END of an epoch until only the loads it issued during that epoch are in
+// flight (stores go out before the loads of an epoch, every epoch issues the same number of
+// loads), so what the next epoch reads -- q in the pass waves, rows in the mover -- has landed
+// before the barrier.
+constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
+
+template <int RPG, bool LSE, bool PLAIN>
+__global__ void __launch_bounds__(THREADS12)
+fwd16_ring12_kernel(const RingArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool mover = wave >= WAVES;
+    const int mv = wave - WAVES;                                       // mover index 0 .. 3
+    const int p = lane & 15, g = lane >> 4;
+    const int W = a.W, H = a.H, R = a.R;
+    const int RS = a.RS, PS = a.PS;
+    const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
+    const uint32_t w2 = (uint32_t)W * 2u;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+    int u = blockIdx.x;                                                // block -> band, as in fwd16_ring_kernel
+    {
+        const int per = a.n_blocks >> 3;
+        if (u < 8 * per) u = (u & 7) * per + (u >> 3);
+    }
+    const int plane = u / a.nbp, part = u - plane * a.nbp;
+    const int b = plane / a.heads, m = plane - b * a.heads;
+    const int y0 = part * a.rows_pb;
+    const int nr = min(a.rows_pb, H - y0);
+    const long HW = (long)H * W;
+    const long head_base = ((long)b * a.C + (long)m * D) * HW;
+    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
+
+    auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
+    auto mod_r = [&](int x) { return x - (int)__umulhi((uint32_t)x, a.magic_r) * R; };
+    auto srn = [&](int j) {
+        const int rb = min(div_w(PX_EPOCH * j + PX_EPOCH - 1), nr - 1);
+        return j >= E ? nr + 1 : min(rb + 2, nr + 1);
+    };
+
+    // ---- mover: K/V staging of units j = 0 (K), 1 (V), octet mv
+    const int oct = mover ? mv : 0;
+    const bf16_bits* kv_src[2] = {a.k + head_base + (long)(8 * oct) * HW, a.v + head_base + (long)(8 * oct) * HW};
+    const int NXC = W >> 3;
+    const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;
+    const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
+    // landing slots of unit j: two sets of RPG; at start-up also the third q slot and the result
+    // slot of pass wave 2 mv + j
+    auto slot_off = [&](int j, int s) {
+        const int raw = a.off_raw + (4 * j + oct) * (2 * RPG * SLOT);
+        const int pw = 2 * oct + j;
+        return s < 2 * RPG ? raw + s * SLOT : (s == 2 * RPG ? a.off_q + pw * (3 * SLOT) + 2 * SLOT : a.off_out + pw * SLOT);
+    };
+    auto load_row = [&](int j, uint32_t row_off, int off) {
+        if (lane < W) load_to_lds(kv_src[j], kv_lane_off + row_off, lds0 + off);
+    };
+    const int cv_src_off = ((lane & 15) >> 2) * (W * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
+    struct RawRow { uint2_t lo, hi; };
+    auto read_row = [&](int off) {
+        RawRow r;
+        const unsigned char* src = smem + off + cv_src_off;
+        r.lo = lds_read_tr(src);
+        r.hi = lds_read_tr(src + 4 * (W * 2));
+        return r;
+    };
+    auto write_row = [&](int j, uint32_t ring_off, bool in_map, const RawRow& r) {
+        uint4_t h4;
+        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
+        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
+#pragma unroll
+        for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
+        if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
+    };
+    // q of pass wave pw, pass starting at band pixel n_first, into slot offset qo of that wave
+    const bf16_bits* q_src = a.q + head_base + (long)y0 * W;
+    const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (uint32_t)(lane & 1) * 16u;
+    auto load_q = [&](int pw, int n_first, int qo) {
+        const bool real = n_first < npix;
+        const int nf = real ? n_first : 0;
+        const int off = real ? a.off_q + pw * (3 * SLOT) + qo : a.off_dummy;
+        if (nf + 8 * (lane & 1) < npix) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
+    };
+
+    // ---- start-up
+    const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
+    int n_after_g0 = 0;                                                // mover: loads issued after group 0
+    if (!PLAIN && !mover) {
+        constexpr int CHUNKS = HEAD_W / 4;
+        for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
+            const int c = L * 64 + lane;
+            const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
+            if (c < 2 * CHUNKS) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
+        }
+    }
+    if (mover) {
+        for (int k = 0; k <= v0; ++k) {                                // group 0 (at most RPG + 2 rows)
+            const int gy = y0 - 1 + k;
+            if (gy >= 0 && gy < H)
+                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+        }
+        for (int i = 0; i < 2; ++i) {
+            load_q(2 * mv + i, 16 * (2 * mv + i), 0);
+            load_q(2 * mv + i, 16 * (2 * mv + i) + PX_EPOCH, SLOT);
+        }
+        n_after_g0 = 4;
+        for (int k = 0; k < v1 - v0; ++k) {                            // group 1 into set 1
+            const int gy = y0 + v0 + k;
+            if (gy >= 0 && gy < H) {
+                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
+                n_after_g0 += 2;
+            }
+        }
+    }
+    half8_t A1[S];
+    half4_t A2[2 * S];
+    float bias2[3];
+    float bias9[S];
+    if (!PLAIN) {
+        if (!mover) wait_vmem(0);                                      // the kernels have landed
+        block_barrier();
+        if (tid < THREADS) image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
+        block_barrier();
+        if (!mover) load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
+        block_barrier();
+    } else if (!mover) {
+#pragma unroll
+        for (int t = 0; t < S; ++t) bias9[t] = a.bias ? a.bias[m * S + t] * 1.44269504088896341f : 0.0f;
+    }
+    for (int idx = tid; idx < R * 16; idx += THREADS12) {              // the padding columns of the ring stay zero
+        const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
+        *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
+    }
+    constexpr int NL = 2 * RPG + 2;                                    // loads of a mover per epoch
+    if (mover) {
+        wait_vmem(n_after_g0);                                         // group 0 has landed
+        for (int k = 0; k <= v0; ++k) {                                // group 0 -> ring rows 0 .. v0
+            RawRow r0[2];
+            for (int j = 0; j < 2; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+            for (int j = 0; j < 2; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
+        // group 2 into set 0, as a full round of NL loads
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + v1 + k;
+            const bool real = k < v2 - v1 && gy >= 0 && gy < H;
+            for (int j = 0; j < 2; ++j)
+                load_row(j, (uint32_t)min(max(gy, 0), H - 1) * w2, real ? slot_off(j, k) : a.off_dummy);
+        }
+        load_q(0, npix, 0);
+        load_q(0, npix, 0);                                            // (two dump loads complete the round)
+        wait_vmem(NL);                                                 // everything but that round: group 1, q of epochs 0 and 1
+    }
+    block_barrier();
+
+    // ---- the schedule (see fwd16_ring_kernel), lane e of the table registers holding epoch e
+    uint32_t t_cvA, t_cvB, t_ld, t_p0, t_p1, t_p2;
+    {
+        const int e = lane;
+        const int s0 = srn(e), s1 = srn(e + 1), s2 = srn(e + 2), s3 = srn(e + 3);
+        const int RW = W + 2;
+        auto ring_of = [&](int sr) { return (uint32_t)(mod_r(sr) * RW); };
+        t_cvA = ring_of(s0 + 1) | ring_of(s0 + 2) << 10 | ring_of(s0 + 3) << 20;
+        uint32_t outside = 0, ldm = 0;
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + s0 + k, gl = y0 + s2 + k;
+            outside |= (gy < 0 || gy >= H) ? 1u << k : 0u;
+            ldm |= (k < s3 - s2 && gl >= 0 && gl < H) ? 1u << k : 0u;
+        }
+        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13 | ldm << 17;
+        t_ld = (uint32_t)(min(max(y0 + s2, 0), H - 1) * W) * 2u;
+        const int nbe = PX_EPOCH * e + 16 * (mover ? 0 : wave);
+        const int ra = div_w(nbe), c0 = nbe - ra * W;
+        t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
+        t_p1 = ring_of(ra + 1) | ring_of(ra + 2) << 10 | ring_of(ra + 3) << 20;
+        t_p2 = (uint32_t)c0 | (nbe < npix ? 256u : 0u);
+    }
+
+    constexpr int OUT_ROW = 2 * PX_EPOCH + 16;
+    char* out_base = (char*)(a.out + head_base + (long)y0 * W);
+    int out2_wr = a.off_out2, out2_rd = a.off_out2 + 32 * OUT_ROW;     // buffer written this epoch / stored this epoch
+    int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
+    // mover: store channels 8 mv .. 8 mv + 7 of the epoch whose first pixel is e0 from buffer rd
+    auto store_results = [&](int e0, int rd) {
+        uint4_t val[2];
+        const int n0 = e0 + 8 * (lane & 15);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = 8 * mv + 4 * i + (lane >> 4);
+            if (n0 < npix) val[i] = *(const uint4_t*)(smem + rd + c * OUT_ROW + (lane & 15) * 16);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = 8 * mv + 4 * i + (lane >> 4);
+            if (n0 < npix) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
+        }
+    };
+
+    if (mover) {
+        int set_rd = RPG * SLOT;                                       // offset of the set that holds group e + 1
+        for (int e = 0; e < E; ++e) {
+            const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
+            const uint32_t ldo = __builtin_amdgcn_readlane(t_ld, e);
+            // group e + 1 has landed (waited for at the end of the previous epoch): fetch it
+            RawRow raw[2][RPG];
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int k = 0; k < RPG; ++k) raw[j][k] = read_row(slot_off(j, 0) + set_rd + k * SLOT);
+            if (e > 0) store_results(PX_EPOCH * (e - 1), out2_rd);       // (contains the wait for its LDS reads)
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            // the epoch's round of loads: group e + 3 into the slots just read, q(e + 2) of two pass waves
+#pragma unroll
+            for (int k = 0; k < RPG; ++k) {
+                const bool real = (cvB >> (17 + k)) & 1u;
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    load_row(j, real ? ldo + (uint32_t)k * w2 : ldo, real ? slot_off(j, 0) + set_rd + k * SLOT : a.off_dummy);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) load_q(2 * mv + i, PX_EPOCH * (e + 2) + 16 * (2 * mv + i), qo_2);
+            // conversion of group e + 1 into the ring
+            const int cnt = (cvB >> 10) & 7;
+            const bool any_outside = ((cvB >> 13) & 15u) != 0;
+#pragma unroll
+            for (int k = 0; k < RPG; ++k) {
+                const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
+                if (k < cnt) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) write_row(j, pos, !any_outside || !((cvB >> (13 + k)) & 1u), raw[j][k]);
+                }
+            }
+            set_rd = RPG * SLOT - set_rd;
+            { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
+            { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
+            if (NL == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else if (NL == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
+            block_barrier();
+        }
+        store_results(PX_EPOCH * (E - 1), out2_rd);
+        wait_vmem(0);                                                  // no load into this block's LDS outlives it
+        return;
+    }
+
+    // ---- pass waves
+    const int q_slots = a.off_q + wave * (3 * SLOT);
+    unsigned char* o_slot = smem + a.off_out + wave * SLOT;
+    const int VD = 4 * PS;
+    const unsigned char* tap_base = smem + g * PS;
+    const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
+    int nb = 16 * wave;
+    float* lse_ptr = LSE ? a.lse + head_base / D + (long)y0 * W : nullptr;
+    for (int e = 0; e < E; ++e) {
+        const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
+        if (p2 & 256u) {
+            const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
+            const int cx0 = (int)(p2 & 255u) + p;
+            const bool next_row = cx0 >= W;
+            const uint32_t cx = next_row ? cx0 - W : cx0;
+            const uint32_t rows = next_row ? p1 : p0;
+            const unsigned char* kb[KS];
+#pragma unroll
+            for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
+            const unsigned char* qsrc = smem + q_slots + qo_cur + (8 * g + (p >> 2)) * 32 + (p & 3) * 8;
+            const uint2_t q0 = lds_read_tr(qsrc), q1 = lds_read_tr(qsrc + 4 * 32);
+            uint4_t kd[S];
+#pragma unroll
+            for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
+            half2_t qs[4];
+            {
+                const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
+                qs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; qs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
+                qs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; qs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
+            }
+            float o[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) o[x] = 0.0f;
+            if (PLAIN) {
+                const uint32_t c16 = 0x4c004c00u;
+                const half8_t ones = __builtin_bit_cast(half8_t, uint4_t{c16, c16, c16, c16});
+                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                float l[S];
+#pragma unroll
+                for (int t = 0; t < S; ++t) {
+                    uint4_t bb;
+#pragma unroll
+                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                    const float4_t dsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(half8_t, bb), zero4, 0, 0, 0);
+                    l[t] = dsum[0];
+                }
+                uint4_t vd[S];
+#pragma unroll
+                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+                float mx = -INFINITY;
+#pragma unroll
+                for (int t = 0; t < S; ++t) { l[t] = fmaf(l[t], a.scale_log2e, bias9[t]); mx = fmaxf(mx, l[t]); }
+                float den = 0.0f;
+#pragma unroll
+                for (int t = 0; t < S; ++t) { l[t] = __builtin_amdgcn_exp2f(l[t] - mx); den += l[t]; }
+                const float inv = __builtin_amdgcn_rcpf(den);
+                if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+#pragma unroll
+                for (int t = 0; t < S; ++t)
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) o[x] = fmaf(l[t], (float)as_half2(vd[t][x >> 1])[x & 1], o[x]);
+#pragma unroll
+                for (int x = 0; x < 8; ++x) o[x] *= inv;
+            } else {
+                float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+                for (int t = 0; t < S; ++t) {
+                    uint4_t bb;
+#pragma unroll
+                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
+                }
+                uint4_t vd[S];
+#pragma unroll
+                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+                float l[3];
+#pragma unroll
+                for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
+                const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
+                float pr[3];
+#pragma unroll
+                for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
+                const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
+                const float inv = __builtin_amdgcn_rcpf(den);
+                if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+                uint2_t b2;
+                b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
+                b2[1] = pack_half(pr[2] * inv, 0.0f);
+                const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+                float4_t w[2 * S];
+                constexpr int AHEAD = 2;
+#pragma unroll
+                for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
+#pragma unroll
+                for (int uu = 0; uu < 2 * S; ++uu) {
+                    if (uu + AHEAD < 2 * S)
+                        w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
+                        const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
+                        o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            uint4_t ov;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                typedef float float2_t __attribute__((ext_vector_type(2)));
+                const float2_t f2 = {o[2 * y], o[2 * y + 1]};
+                ov[y] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));
+            }
+            *(uint4_t*)(o_slot + p * 64 + ((g ^ ((p >> 2) & 3)) << 4)) = ov;
+            const int grp = lane >> 4, nn = lane & 15;
+            const int sa = nn & 3, sj = nn >> 2;
+            const int oct_s = 2 * (grp & 1) + (sa >> 1);
+            const int P0 = 8 * st_hh + sj, P1 = P0 + 4;
+            const uint2_t ra2 = lds_read_tr(o_slot + P0 * 64 + ((oct_s ^ ((P0 >> 2) & 3)) << 4) + (sa & 1) * 8);
+            const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
+            *(uint4_t*)(smem + out2_wr + st_c * OUT_ROW + (16 * wave + 8 * st_hh) * 2) = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
+        }
+        { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
+        { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
+        nb += PX_EPOCH;
+        block_barrier();
+    }
+}
+
 // ------------------------------------------------------------------ host side
 struct RingPlan {
     int rpg, nbp, rows_pb, n_blocks, R, RS, PS, off_raw, off_dummy, off_q, off_out, off_out2, lds_bytes;
@@ -661,18 +1049,30 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
+    // SLIDE_ATTN_RING_WAVES=8 in the environment (read once) selects the kernel without mover waves
+    static const bool twelve = [] {
+        const char* e = getenv("SLIDE_ATTN_RING_WAVES");
+        return !(e && e[0] == '8');
+    }();
     static LdsOptIn opt_in;
 #define SLIDE_RING_KERNELS(RPGV)                                                                                    \
     (const void*)fwd16_ring_kernel<RPGV, false, false>, (const void*)fwd16_ring_kernel<RPGV, true, false>,          \
-    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>
+    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>,            \
+    (const void*)fwd16_ring12_kernel<RPGV, false, false>, (const void*)fwd16_ring12_kernel<RPGV, true, false>,      \
+    (const void*)fwd16_ring12_kernel<RPGV, false, true>, (const void*)fwd16_ring12_kernel<RPGV, true, true>
     hipError_t e = opt_in.ensure({SLIDE_RING_KERNELS(2), SLIDE_RING_KERNELS(3), SLIDE_RING_KERNELS(4)}, LDS_LIMIT);
 #undef SLIDE_RING_KERNELS
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)r.n_blocks), block(THREADS);
+    const dim3 grid((unsigned)r.n_blocks), block(THREADS), block12(THREADS12);
+#define SLIDE_RING_LAUNCH3(RPGV, LSEV, PLAINV)                                                                      \
+    do {                                                                                                            \
+        if (twelve) hipLaunchKernelGGL((fwd16_ring12_kernel<RPGV, LSEV, PLAINV>), grid, block12, (size_t)r.lds_bytes, st, a); \
+        else        hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, PLAINV>), grid, block, (size_t)r.lds_bytes, st, a);     \
+    } while (0)
 #define SLIDE_RING_LAUNCH2(RPGV, LSEV)                                                                              \
     do {                                                                                                            \
-        if (plain) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, true>), grid, block, (size_t)r.lds_bytes, st, a);   \
-        else       hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, false>), grid, block, (size_t)r.lds_bytes, st, a);  \
+        if (plain) SLIDE_RING_LAUNCH3(RPGV, LSEV, true);                                                            \
+        else       SLIDE_RING_LAUNCH3(RPGV, LSEV, false);                                                           \
     } while (0)
 #define SLIDE_RING_LAUNCH(RPGV)                                                                                     \
     do {                                                                                                            \
@@ -683,6 +1083,7 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     else if (r.rpg == 3) SLIDE_RING_LAUNCH(3);
     else SLIDE_RING_LAUNCH(4);
 #undef SLIDE_RING_LAUNCH2
+#undef SLIDE_RING_LAUNCH3
 #undef SLIDE_RING_LAUNCH
     return hipGetLastError();
 }
