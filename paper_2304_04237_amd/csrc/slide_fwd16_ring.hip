@@ -4,35 +4,35 @@
 // merged kernel W~ of Sec. 4.3 / Fig. 4 as matrix-core operands, see slide_fwd16_ops.h); what
 // differs is how data moves:
 //
-//   - A block (8 waves) owns a band of consecutive rows of one (batch, head) plane and walks
-//     down it.  K and V rows live in LDS in a ring of R rows: eight planes (tensor x channel
-//     octet), each [ring row][column][8 channels as halves], 16 B per pixel, so the nine taps
-//     of a pixel are three row addresses plus constant offsets and neighbouring lanes read
+//   - A block owns a band of consecutive rows of one (batch, head) plane and walks down it.
+//     K and V rows live in LDS in a ring of R rows: eight planes (tensor x channel octet),
+//     each [ring row][column][8 channels as halves], 16 B per pixel, so the nine taps of a
+//     pixel are three row addresses plus constant offsets and neighbouring lanes read
 //     neighbouring 16-byte slots.  Every row is staged exactly once per block; the zero
 //     padding left and right of the map are two ring columns that are cleared once, the rows
 //     above and below the map are staged as zeros (Fig. 2).
+//   - Work is cut into epochs of 128 pixels: eight pass waves run one 16-pixel pass each, four
+//     mover waves do the data movement around them.  One block barrier ends the epoch.  The
+//     ring is deep enough that rows written during an epoch are never among those read
+//     during it.
 //   - Global memory is read with 16-byte loads that write straight into LDS
-//     (global_load_lds_dwordx4): the raw bf16 rows land channel-major in per-wave landing
-//     slots and use no registers while in flight.  Two epochs later the same wave reads its
-//     slots back with the transposing LDS read (ds_read_b64_tr_b16: a lane gets four
-//     channels of one pixel), converts bf16 -> half and writes the ring row.  The head's
-//     kernels arrive the same way and are turned into the operand image in LDS.
-//   - q is private to the pass that uses it: one direct-to-LDS load per pass into a per-wave
-//     slot, read back transposed.  Results go the other way: a lane writes its pixel's 8
-//     channels to a per-wave slot, reads 8 pixels of one channel back transposed, and puts
-//     them into a buffer of the block from which, one barrier later, every wave stores four
-//     channels x 256 contiguous bytes.
-//   - Work is cut into epochs of 128 pixels (one 16-pixel pass per wave).  At the start of
-//     epoch e a wave fetches the landed raw rows that epoch e + 1 will read first (loaded two
-//     epochs earlier) into registers and re-issues loads into their slots for epoch e + 3;
-//     it converts the fetched rows and writes them to the ring in the shadow of its pass.
-//     One block barrier ends the epoch.  The ring is deep enough that rows written during an
-//     epoch are never among those read during it.
+//     (global_load_lds_dwordx4): the raw bf16 rows of a K/V unit (tensor x channel octet) land
+//     channel-major in the landing slots of the mover that owns the unit and use no registers
+//     while in flight.  Two epochs later the mover reads the slots back with the transposing
+//     LDS read (ds_read_b64_tr_b16: a lane gets four channels of one pixel), converts
+//     bf16 -> half, writes the ring rows that the next epoch reads first, and re-issues loads
+//     into the slots for the epoch after that.  The head's kernels arrive the same way and
+//     are turned into the operand image in LDS.
+//   - q is private to the pass that uses it: one direct-to-LDS load per pass (issued by a
+//     mover two epochs ahead) into a slot of the pass wave, read back transposed.  Results go
+//     the other way: a lane writes its pixel's 8 channels to a per-wave slot, reads 8 pixels
+//     of one channel back transposed, and puts them into a buffer of the block from which,
+//     one barrier later, the movers store 256 contiguous bytes per channel.
 //
 // Vector-memory waits are placed by hand: the direct-to-LDS loads are issued from inline
 // assembly (the compiler would otherwise make every LDS read wait for them), and every epoch
-// issues the same number of them, so "all but the latest round have landed" is one constant
-// wait.
+// issues the same number of them per mover, so "all but the latest round have landed" is one
+// constant wait.
 #include "slide_fwd16_ops.h"
 
 namespace slide {
@@ -58,451 +58,27 @@ struct RingArgs {
 };
 
 // RPG: most rows a group of new K/V rows can have (rows that one epoch is the first to read).
-// The epoch loop has no data-dependent control flow beyond "this wave has a pass": every epoch
-// issues exactly RPG + 1 loads per wave (rows a group does not have, rows outside the map and
-// passes past the end of the band are loaded from a valid address into a dump slot), so the
-// wait for "everything but the latest round has landed" is a constant.
+// Twelve waves per block: waves 0 .. 7 ("pass waves") only run passes; waves 8 .. 11 ("movers")
+// do all of the data movement around them.  Mover j stages octet j of K and of V (fetch of the
+// landed rows, conversion, ring rows, loads of later groups), issues the q loads of pass waves
+// 2j and 2j + 1 and stores channels 8j .. 8j + 7 of the previous epoch's results.  A pass wave
+// issues about 280 instructions per epoch, and three waves share a SIMD (under 168 registers).
+// The epoch loops have no data-dependent control flow beyond "this wave has a pass": a mover
+// issues exactly 2 RPG + 2 loads per epoch (rows a group does not have, rows outside the map
+// and passes past the end of the band are loaded from a valid address into a dump slot), its
+// stores go out before them, and it waits at the END of an epoch until only the loads of that
+// epoch are in flight: what the next epoch reads -- q in the pass waves, rows in the mover --
+// has landed before the barrier.
 //
 // PLAIN: the shift without learned kernels (Sec. 4.2, Eq. 10-13: every shift is a one-hot
 // depthwise kernel, so the shifted keys and values are the taps themselves).  No kernels are
 // read and no operand image is built; the matrix core only adds the 32 channel products of a
 // tap, and every lane holds all nine logits of its pixel.
-template <int RPG, bool LSE, bool PLAIN>
-__global__ void __launch_bounds__(THREADS, 2)
-fwd16_ring_kernel(const RingArgs a)
-{
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int p = lane & 15, g = lane >> 4;
-    const int W = a.W, H = a.H, R = a.R;
-    const int RS = a.RS, PS = a.PS;
-    const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;   // LDS address of the dynamic region
-
-    // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
-    // the XCDs by the hardware; the bands of a plane (which share two halo rows) get indices
-    // 8 apart, so they run on the same XCD and the shared rows come out of its L2.
-    int u = blockIdx.x;
-    {
-        const int per = a.n_blocks >> 3;
-        if (u < 8 * per) u = (u & 7) * per + (u >> 3);
-    }
-    const int plane = u / a.nbp, part = u - plane * a.nbp;
-    const int b = plane / a.heads, m = plane - b * a.heads;
-    const int y0 = part * a.rows_pb;
-    const int nr = min(a.rows_pb, H - y0);
-    const long HW = (long)H * W;
-    const long head_base = ((long)b * a.C + (long)m * D) * HW;       // element offset of channel 0 of the head
-    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
-
-    // Stage row sr = 0 .. nr + 1 is map row y0 - 1 + sr of K and V and lives in ring row
-    // sr % R; output row ry reads stage rows ry, ry + 1, ry + 2.  srn(j): the last stage row
-    // that epoch j reads; group j = stage rows srn(j - 1) + 1 .. srn(j), the rows that epoch j
-    // is the first to read (group 0: everything the first epoch reads).  Uniform integer
-    // arithmetic; divisions by W and R are multiplications by their reciprocals.
-    auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
-    auto mod_r = [&](int x) { return x - (int)__umulhi((uint32_t)x, a.magic_r) * R; };
-    auto srn = [&](int j) {
-        const int rb = min(div_w(PX_EPOCH * j + PX_EPOCH - 1), nr - 1);
-        return j >= E ? nr + 1 : min(rb + 2, nr + 1);
-    };
-
-    // ---- K/V staging.  Wave w stages unit w = tensor * 4 + channel octet for every new row.  A
-    // unit's rows live in LDS plane `unit` of the ring: [ring row 0 .. R][column 0 .. W + 1][8
-    // channels as halves], 16 B per pixel, columns 0 and W + 1 zero.
-    // Landing slots of a wave: two sets of RPG (group j uses set j % 2); at start-up also the
-    // third q slot and the result slot; one dump slot for the whole block.
-    const bf16_bits* kv_src = ((wave >> 2) ? a.v : a.k) + head_base + (long)(8 * (wave & 3)) * HW;
-    const int NXC = W >> 3;                                            // 16-byte chunks per row
-    const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;           // lane l loads chunk x of channel 8 oct + cc
-    const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
-    const int raw_off = a.off_raw + wave * (2 * RPG * SLOT);
-    const int q_slots = a.off_q + wave * (3 * SLOT);
-    const int o_off = a.off_out + wave * SLOT;
-    auto slot_off = [&](int s) {                                       // s < 2 RPG: the two sets; then the two start-up extras
-        return s < 2 * RPG ? raw_off + s * SLOT : (s == 2 * RPG ? q_slots + 2 * SLOT : o_off);
-    };
-    // load map row gy (must be inside the map) of this wave's unit into the landing slot at LDS offset off
-    auto load_row = [&](int gy, int off) {
-        if (lane < W) load_to_lds(kv_src, kv_lane_off + (uint32_t)(gy * W) * 2u, lds0 + off);
-    };
-    // read a landed row back, transposed
-    const int cv_src_off = ((lane & 15) >> 2) * (W * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
-    struct RawRow { uint2_t lo, hi; };
-    auto read_row = [&](int off) {
-        RawRow r;
-        const unsigned char* src = smem + off + cv_src_off;
-        r.lo = lds_read_tr(src);
-        r.hi = lds_read_tr(src + 4 * (W * 2));
-        return r;
-    };
-    // convert a fetched row (zeros if !in_map) and write it to ring row ri of this wave's plane
-    unsigned char* cv_dst = smem + wave * PS + (lane + 1) * 16;
-    // (ring_off: byte offset of the ring row inside a plane)
-    auto write_row = [&](uint32_t ring_off, bool in_map, const RawRow& r) {
-        uint4_t h4;
-        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
-        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
-#pragma unroll
-        for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
-        if (lane < W) *(uint4_t*)(cv_dst + ring_off) = h4;
-    };
-    auto write_row_in_map = [&](uint32_t ring_off, const RawRow& r) {
-        uint4_t h4;
-        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
-        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
-        if (lane < W) *(uint4_t*)(cv_dst + ring_off) = h4;
-    };
-
-    // ---- q: one direct load per pass into one of the wave's three slots, two epochs ahead
-    const bf16_bits* q_src = a.q + head_base + (long)y0 * W;
-    const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (uint32_t)(lane & 1) * 16u;
-    // n_first: first pixel of the pass (a multiple of 16; passes past the band go to the dump slot)
-    auto load_q = [&](int n_first, int qo) {
-        const bool real = n_first < npix;
-        const int nf = real ? n_first : 0;
-        const int off = real ? q_slots + qo : a.off_dummy;
-        // (npix is a multiple of 8: a 16-byte chunk is inside the band or outside it)
-        if (nf + 8 * (lane & 1) < npix) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
-    };
-
-    // ---- start-up: every load that has a slot first: the head's kernels, group 0, q of the
-    // first two epochs, group 1
-    const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
-    int nb = 16 * wave;                                                // first pixel of this wave's pass of the current epoch
-    int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
-    int n_after_w = 0;                                                 // loads issued after the kernels'
-    if (!PLAIN) {
-        // 2 x 32 x 81 floats = 1296 chunks of 16 bytes, K kernels then V kernels, to smem + IMG_RAW_AT
-        constexpr int CHUNKS = HEAD_W / 4;
-        for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
-            const int c = L * 64 + lane;
-            const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
-            if (c < 2 * CHUNKS) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
-        }
-    }
-    for (int k = 0; k <= v0; ++k) {                                    // group 0 (at most RPG + 2 rows)
-        const int gy = y0 - 1 + k;
-        if (gy >= 0 && gy < H) { load_row(gy, slot_off(k < RPG ? k : 2 * RPG + (k - RPG))); ++n_after_w; }
-    }
-    const int n_after_g0_mark = n_after_w;
-    load_q(nb, qo_cur);
-    load_q(nb + PX_EPOCH, qo_1);
-    n_after_w += 2;
-    for (int k = 0; k < v1 - v0; ++k) {                                // group 1 into set 1
-        const int gy = y0 + v0 + k;
-        if (gy >= 0 && gy < H) { load_row(gy, slot_off(RPG + k)); ++n_after_w; }
-    }
-    half8_t A1[S];
-    half4_t A2[2 * S];
-    float bias2[3];
-    float bias9[S];                                                    // PLAIN: the head's biases times log2(e), uniform
-    if (!PLAIN) {
-        wait_vmem(n_after_w);                                          // the kernels have landed
-        block_barrier();
-        image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
-        block_barrier();
-        load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
-        block_barrier();
-    } else {
-#pragma unroll
-        for (int t = 0; t < S; ++t) bias9[t] = a.bias ? a.bias[m * S + t] * 1.44269504088896341f : 0.0f;
-    }
-    // the two padding columns of every ring row stay zero for the whole kernel
-    for (int idx = tid; idx < R * 16; idx += THREADS) {
-        const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
-        *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
-    }
-    wait_vmem(n_after_w - n_after_g0_mark);                            // group 0 has landed
-    {                                                                  // group 0 -> ring rows 0 .. v0
-        RawRow r0[RPG + 2];
-#pragma unroll
-        for (int k = 0; k < RPG + 2; ++k)
-            if (k <= v0) r0[k] = read_row(slot_off(k < RPG ? k : 2 * RPG + (k - RPG)));
-#pragma unroll
-        for (int k = 0; k < RPG + 2; ++k)
-            if (k <= v0) write_row((uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[k]);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                 // set 0 has been read before it is loaded again
-    // group 2 into set 0, as a full round of RPG + 1 loads
-#pragma unroll
-    for (int k = 0; k < RPG; ++k) {
-        const int gy = y0 + v1 + k;
-        const bool real = k < v2 - v1 && gy >= 0 && gy < H;
-        load_row(min(max(gy, 0), H - 1), real ? raw_off + k * SLOT : a.off_dummy);
-    }
-    load_q(npix, 0);                                                   // (a dump load that completes the round)
-    block_barrier();
-
-    unsigned char* o_slot = smem + o_off;
-    const int VD = 4 * PS;
-    // Results leave in two steps: a pass writes its 16 pixels x 32 channels pixel-major into the
-    // wave's slot, reads them back transposed (8 pixels of one channel per lane) and puts them
-    // into the block's buffer of the epoch, [channel][128 pixels] with rows of OUT_ROW bytes;
-    // one barrier later wave w stores channels 4 w .. 4 w + 3 of that buffer, 256 contiguous
-    // bytes per channel.
-    constexpr int OUT_ROW = 2 * PX_EPOCH + 16;                         // 16 bytes of padding: 16 channel rows hit 16 different bank groups
-    float st_lse = 0.0f;
-    int st_nb = npix;                                                  // first pixel of this wave's previous pass (npix: none)
-    int st_e0 = npix;                                                  // first pixel of the previous epoch (npix: none)
-    int out2_wr = a.off_out2, out2_rd = a.off_out2 + 32 * OUT_ROW;     // buffer written this epoch / stored this epoch
-    const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
-    char* out_base = (char*)(a.out + head_base + (long)y0 * W);
-    auto store_results = [&]() {
-        const int c = 4 * wave + (lane >> 4), n0 = st_e0 + 8 * (lane & 15);
-        if (n0 < npix) {
-            const uint4_t val = *(const uint4_t*)(smem + out2_rd + c * OUT_ROW + (lane & 15) * 16);
-            *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val;
-        }
-        if (LSE && g == 0 && st_nb + p < npix)
-            a.lse[head_base / D + (long)y0 * W + st_nb + p] = st_lse;
-    };
-
-    // ---- the schedule: everything uniform that an epoch needs, worked out once, lane e of the
-    // table registers holding epoch e (E <= 64).  Ring positions are in 16-byte units (10 bits).
-    //   t_cvA, t_cvB: ring positions of the rows of group e + 1 (converted during epoch e), their
-    //                 number, which of them lie outside the map (written as zeros), and which
-    //                 loads of group e + 3 are real
-    //   t_ld:         byte offset of the first row of group e + 3 inside a channel plane
-    //   t_p0, t_p1:   ring positions of the three tap rows of this wave's pass, for lanes that stay
-    //                 in the pass's first row / that run into the next row
-    //   t_p2:         column of the pass's first pixel; bit 8: the wave has a pass
-    uint32_t t_cvA, t_cvB, t_ld, t_p0, t_p1, t_p2;
-    {
-        const int e = lane;
-        const int s0 = srn(e), s1 = srn(e + 1), s2 = srn(e + 2), s3 = srn(e + 3);
-        const int RW = W + 2;
-        auto ring_of = [&](int sr) { return (uint32_t)(mod_r(sr) * RW); };
-        t_cvA = ring_of(s0 + 1) | ring_of(s0 + 2) << 10 | ring_of(s0 + 3) << 20;
-        uint32_t outside = 0, ldm = 0;
-#pragma unroll
-        for (int k = 0; k < RPG; ++k) {
-            const int gy = y0 + s0 + k, gl = y0 + s2 + k;
-            outside |= (gy < 0 || gy >= H) ? 1u << k : 0u;
-            ldm |= (k < s3 - s2 && gl >= 0 && gl < H) ? 1u << k : 0u;
-        }
-        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13 | ldm << 17;
-        t_ld = (uint32_t)(min(max(y0 + s2, 0), H - 1) * W) * 2u;
-        const int nbe = PX_EPOCH * e + 16 * wave;
-        const int ra = div_w(nbe), c0 = nbe - ra * W;
-        t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
-        t_p1 = ring_of(ra + 1) | ring_of(ra + 2) << 10 | ring_of(ra + 3) << 20;
-        t_p2 = (uint32_t)c0 | (nbe < npix ? 256u : 0u);
-    }
-    const uint32_t w2 = (uint32_t)W * 2u;
-    const unsigned char* tap_base = smem + g * PS;                     // plane g of the ring
-
-    int set_rd = RPG * SLOT;                                           // offset of the set that holds group e + 1
-    for (int e = 0; e < E; ++e) {
-        const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
-        const uint32_t ldo = __builtin_amdgcn_readlane(t_ld, e);
-        // ---- A: what this wave issued two epochs ago has landed: group e + 1 and q(e) (only the
-        // latest round of RPG + 1 loads may still be in flight).  Fetch the landed rows into
-        // registers and reuse their slots for group e + 3.
-        if (RPG == 2) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else if (RPG == 3) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
-        RawRow raw[RPG];
-#pragma unroll
-        for (int k = 0; k < RPG; ++k) raw[k] = read_row(raw_off + set_rd + k * SLOT);
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int k = 0; k < RPG; ++k) {
-            const bool real = (cvB >> (17 + k)) & 1u;
-            if (lane < W)
-                load_to_lds(kv_src, kv_lane_off + (real ? ldo + (uint32_t)k * w2 : ldo),
-                            lds0 + (real ? raw_off + set_rd + k * SLOT : a.off_dummy));
-        }
-        load_q(nb + 2 * PX_EPOCH, qo_2);
-        store_results();
-
-        // ---- B: the pass, with the conversion of the fetched rows in its shadow
-        const int cnt = (cvB >> 10) & 7;
-        auto convert_group = [&]() {
-            if (((cvB >> 13) & 15u) == 0) {                            // every row inside the map: the usual case
-#pragma unroll
-                for (int k = 0; k < RPG; ++k)
-                    if (k < cnt) write_row_in_map((k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16, raw[k]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < RPG; ++k)
-                    if (k < cnt) write_row((k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16, !((cvB >> (13 + k)) & 1u), raw[k]);
-            }
-        };
-        const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
-        const bool valid = (p2 & 256u) != 0;                           // uniform per wave
-        st_nb = npix;
-        if (valid) {
-            // the pass's 16 pixels start at column c0 of a band row and may run into the next row;
-            // tap (ty, tx) of the lane's pixel: plane g, ring position of tap row ty, column cx + tx
-            // (lanes past the band read some staged pixel; nothing of theirs is stored)
-            const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
-            const int cx0 = (int)(p2 & 255u) + p;
-            const bool next_row = cx0 >= W;
-            const uint32_t cx = next_row ? cx0 - W : cx0;
-            const uint32_t rows = next_row ? p1 : p0;
-            const unsigned char* kb[KS];
-#pragma unroll
-            for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
-            const unsigned char* qsrc = smem + q_slots + qo_cur + (8 * g + (p >> 2)) * 32 + (p & 3) * 8;
-            const uint2_t q0 = lds_read_tr(qsrc), q1 = lds_read_tr(qsrc + 4 * 32);
-            uint4_t kd[S];
-#pragma unroll
-            for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
-            // conversion of the rows fetched above: vector work while the tap reads are in flight
-            convert_group();
-            // q: 8 channels of the lane's pixel as halves divided by 16
-            half2_t qs[4];
-            {
-                const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
-                qs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; qs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
-                qs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; qs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
-            }
-            float o[8];
-#pragma unroll
-            for (int x = 0; x < 8; ++x) o[x] = 0.0f;
-            if (PLAIN) {
-                // ---- logits: the matrix core adds a tap's 32 channel products (every row of the
-                // left operand is sixteen, which undoes q's division), so each of the four lanes of
-                // a pixel gets the full sum
-                const uint32_t c16 = 0x4c004c00u;
-                const half8_t ones = __builtin_bit_cast(half8_t, uint4_t{c16, c16, c16, c16});
-                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                float l[S];
-#pragma unroll
-                for (int t = 0; t < S; ++t) {
-                    uint4_t bb;
-#pragma unroll
-                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
-                    const float4_t dsum = __builtin_amdgcn_mfma_f32_16x16x32_f16(ones, __builtin_bit_cast(half8_t, bb), zero4, 0, 0, 0);
-                    l[t] = dsum[0];
-                }
-                uint4_t vd[S];
-#pragma unroll
-                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
-                // ---- softmax over the nine shifts, all in this lane
-                float mx = -INFINITY;
-#pragma unroll
-                for (int t = 0; t < S; ++t) { l[t] = fmaf(l[t], a.scale_log2e, bias9[t]); mx = fmaxf(mx, l[t]); }
-                float den = 0.0f;
-#pragma unroll
-                for (int t = 0; t < S; ++t) { l[t] = __builtin_amdgcn_exp2f(l[t] - mx); den += l[t]; }
-                const float inv = __builtin_amdgcn_rcpf(den);
-                if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
-                // ---- out[c] = sum_t a[t] v[c, p + t]
-#pragma unroll
-                for (int t = 0; t < S; ++t)
-#pragma unroll
-                    for (int x = 0; x < 8; ++x) o[x] = fmaf(l[t], (float)as_half2(vd[t][x >> 1])[x & 1], o[x]);
-#pragma unroll
-                for (int x = 0; x < 8; ++x) o[x] *= inv;
-            } else {
-                // ---- K side: the nine logits, row 4g+r of the product in acc1[r] of lane group g
-                float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
-    #pragma unroll
-                for (int t = 0; t < S; ++t) {
-                    uint4_t bb;
-    #pragma unroll
-                    for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
-                }
-                // V taps: issue the LDS reads now, they land while the softmax runs
-                uint4_t vd[S];
-    #pragma unroll
-                for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
-
-                // ---- softmax over the 9 shifts (3 per lane, 4 lane groups; unused rows have bias -inf)
-                float l[3];
-    #pragma unroll
-                for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
-                const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
-                float pr[3];
-    #pragma unroll
-                for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
-                const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
-                const float inv = __builtin_amdgcn_rcpf(den);
-                if (LSE) st_lse = LN2 * (mx + __builtin_amdgcn_logf(den));
-                uint2_t b2;
-                b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
-                b2[1] = pack_half(pr[2] * inv, 0.0f);
-                const half4_t B2 = __builtin_bit_cast(half4_t, b2);
-
-                // ---- V side: out[c] = sum_t v[c, p+t] * g[c,t] with g = W~v^T a from the matrix core.
-                // Product u < 16 gives, in its four result registers, the weights of channel u & 7 for
-                // taps 4(u >> 3) .. +3; products 16, 17 those of channels 0..3, 4..7 for tap 8.  Two
-                // products stay in flight ahead of the multiply-adds that consume them.
-                const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
-                float4_t w[2 * S];
-                constexpr int AHEAD = 2;
-    #pragma unroll
-                for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
-    #pragma unroll
-                for (int uu = 0; uu < 2 * S; ++uu) {
-                    if (uu + AHEAD < 2 * S)
-                        w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
-                    // scheduling fence: without it the compiler issues all products first and keeps all
-                    // 72 results live
-                    __builtin_amdgcn_sched_barrier(0);
-    #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
-                        const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
-                        o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            // results: pixel-major into the wave's slot, back as 8 pixels of one channel
-            uint4_t ov;
-#pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-                typedef float float2_t __attribute__((ext_vector_type(2)));
-                const float2_t f2 = {o[2 * y], o[2 * y + 1]};
-                ov[y] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));
-            }
-            *(uint4_t*)(o_slot + p * 64 + ((g ^ ((p >> 2) & 3)) << 4)) = ov;
-            const int grp = lane >> 4, nn = lane & 15;
-            const int sa = nn & 3, sj = nn >> 2;                       // as address supplier: pixel sj of the four, channel quad sa
-            const int oct_s = 2 * (grp & 1) + (sa >> 1);
-            const int P0 = 8 * st_hh + sj, P1 = P0 + 4;
-            const uint2_t ra2 = lds_read_tr(o_slot + P0 * 64 + ((oct_s ^ ((P0 >> 2) & 3)) << 4) + (sa & 1) * 8);
-            const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
-            *(uint4_t*)(smem + out2_wr + st_c * OUT_ROW + (16 * wave + 8 * st_hh) * 2) = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
-            st_nb = nb;
-        } else {
-            convert_group();
-        }
-
-        set_rd = RPG * SLOT - set_rd;
-        { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
-        st_e0 = nb - 16 * wave;
-        { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
-        nb += PX_EPOCH;
-        block_barrier();
-    }
-    store_results();
-    wait_vmem(0);                                                      // no load into this block's LDS outlives it
-}
-
-// ------------------------------------------------------------------ the same with mover waves
-// Twelve waves per block: waves 0 .. 7 only run passes; waves 8 .. 11 ("movers") do all of the
-// data movement around them.  Mover j stages octet j of K and of V (fetch of the landed rows,
-// conversion, ring rows, loads of later groups), issues the q loads of passes 2j and 2j + 1
-// and stores channels 8j .. 8j + 7 of the previous epoch's results.  A pass wave issues 280
-// instead of 470 instructions per epoch, and three waves instead of two share a SIMD (the
-// kernel stays under 168 registers); LDS is laid out as for fwd16_ring_kernel.
-// A mover waits at the END of an epoch until only the loads it issued during that epoch are in
-// flight (stores go out before the loads of an epoch, every epoch issues the same number of
-// loads), so what the next epoch reads -- q in the pass waves, rows in the mover -- has landed
-// before the barrier.
 constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
 
 template <int RPG, bool LSE, bool PLAIN>
 __global__ void __launch_bounds__(THREADS12)
-fwd16_ring12_kernel(const RingArgs a)
+fwd16_ring_kernel(const RingArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
@@ -517,7 +93,10 @@ fwd16_ring12_kernel(const RingArgs a)
     const uint32_t w2 = (uint32_t)W * 2u;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    int u = blockIdx.x;                                                // block -> band, as in fwd16_ring_kernel
+    // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
+    // the XCDs by the hardware; the bands of a plane (which share two halo rows) get indices
+    // 8 apart, so they run on the same XCD and the shared rows come out of its L2.
+    int u = blockIdx.x;
     {
         const int per = a.n_blocks >> 3;
         if (u < 8 * per) u = (u & 7) * per + (u >> 3);
@@ -570,6 +149,12 @@ fwd16_ring12_kernel(const RingArgs a)
         for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
         if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
     };
+    auto write_row_in_map = [&](int j, uint32_t ring_off, const RawRow& r) {
+        uint4_t h4;
+        h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
+        h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
+        if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
+    };
     // q of pass wave pw, pass starting at band pixel n_first, into slot offset qo of that wave
     const bf16_bits* q_src = a.q + head_base + (long)y0 * W;
     const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (uint32_t)(lane & 1) * 16u;
@@ -580,7 +165,13 @@ fwd16_ring12_kernel(const RingArgs a)
         if (nf + 8 * (lane & 1) < npix) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
     };
 
-    // ---- start-up
+    // ---- start-up.  The first access to a tensor takes microseconds (cold translation): the
+    // bias is fetched first thing, next to the kernels, not where it is used.
+    float bias_early = 0.0f;                                           // PLAIN: bias of shift `lane`; else the image's bias word of logit row `tid`
+    if (a.bias && !mover) {
+        if (PLAIN) { if (lane < S) bias_early = a.bias[m * S + lane]; }
+        else if (tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[m * S + shift_of_row(tid)];
+    }
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;                                                // mover: loads issued after group 0
     if (!PLAIN && !mover) {
@@ -617,13 +208,17 @@ fwd16_ring12_kernel(const RingArgs a)
     if (!PLAIN) {
         if (!mover) wait_vmem(0);                                      // the kernels have landed
         block_barrier();
-        if (tid < THREADS) image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), a.bias, m, a.idw, (uint32_t*)smem, tid);
+        if (tid < THREADS) {
+            image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), nullptr, m, a.idw, (uint32_t*)smem, tid);
+            if (tid < IMG_DWORDS - IMG_BIAS)                           // (overwrites the zero-bias words that image_from_raw wrote)
+                ((uint32_t*)smem)[IMG_BIAS + tid] = __float_as_uint(shift_of_row(tid) >= 0 ? bias_early * 1.44269504088896341f : -INFINITY);
+        }
         block_barrier();
         if (!mover) load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
         block_barrier();
     } else if (!mover) {
 #pragma unroll
-        for (int t = 0; t < S; ++t) bias9[t] = a.bias ? a.bias[m * S + t] * 1.44269504088896341f : 0.0f;
+        for (int t = 0; t < S; ++t) bias9[t] = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(bias_early), t)) * 1.44269504088896341f;
     }
     for (int idx = tid; idx < R * 16; idx += THREADS12) {              // the padding columns of the ring stay zero
         const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
@@ -652,7 +247,15 @@ fwd16_ring12_kernel(const RingArgs a)
     }
     block_barrier();
 
-    // ---- the schedule (see fwd16_ring_kernel), lane e of the table registers holding epoch e
+    // ---- the schedule: everything uniform that an epoch needs, worked out once, lane e of the
+    // table registers holding epoch e (E <= 64).  Ring positions are in 16-byte units (10 bits).
+    //   t_cvA, t_cvB: ring positions of the rows of group e + 1 (converted during epoch e), their
+    //                 number, which of them lie outside the map (written as zeros), and which
+    //                 loads of group e + 3 are real
+    //   t_ld:         byte offset of the first row of group e + 3 inside a channel plane
+    //   t_p0, t_p1:   ring positions of the three tap rows of this wave's pass, for lanes that stay
+    //                 in the pass's first row / that run into the next row
+    //   t_p2:         column of the pass's first pixel; bit 8: the wave has a pass
     uint32_t t_cvA, t_cvB, t_ld, t_p0, t_p1, t_p2;
     {
         const int e = lane;
@@ -721,13 +324,23 @@ fwd16_ring12_kernel(const RingArgs a)
             for (int i = 0; i < 2; ++i) load_q(2 * mv + i, PX_EPOCH * (e + 2) + 16 * (2 * mv + i), qo_2);
             // conversion of group e + 1 into the ring
             const int cnt = (cvB >> 10) & 7;
-            const bool any_outside = ((cvB >> 13) & 15u) != 0;
+            if (((cvB >> 13) & 15u) == 0) {                            // every row inside the map: the usual case
 #pragma unroll
-            for (int k = 0; k < RPG; ++k) {
-                const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
-                if (k < cnt) {
+                for (int k = 0; k < RPG; ++k) {
+                    const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
+                    if (k < cnt) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) write_row(j, pos, !any_outside || !((cvB >> (13 + k)) & 1u), raw[j][k]);
+                        for (int j = 0; j < 2; ++j) write_row_in_map(j, pos, raw[j][k]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < RPG; ++k) {
+                    const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
+                    if (k < cnt) {
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) write_row(j, pos, !((cvB >> (13 + k)) & 1u), raw[j][k]);
+                    }
                 }
             }
             set_rd = RPG * SLOT - set_rd;
@@ -807,14 +420,17 @@ fwd16_ring12_kernel(const RingArgs a)
 #pragma unroll
                 for (int x = 0; x < 8; ++x) o[x] *= inv;
             } else {
-                float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+                // (two accumulation chains, even and odd taps: a product does not wait for the one before it)
+                float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1b = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int t = 0; t < S; ++t) {
                     uint4_t bb;
 #pragma unroll
                     for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
-                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
+                    if (t & 1) acc1b = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1b, 0, 0, 0);
+                    else       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
                 }
+                acc1 += acc1b;
                 uint4_t vd[S];
 #pragma unroll
                 for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
@@ -1049,26 +665,16 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    // SLIDE_ATTN_RING_WAVES=8 in the environment (read once) selects the kernel without mover waves
-    static const bool twelve = [] {
-        const char* e = getenv("SLIDE_ATTN_RING_WAVES");
-        return !(e && e[0] == '8');
-    }();
     static LdsOptIn opt_in;
 #define SLIDE_RING_KERNELS(RPGV)                                                                                    \
     (const void*)fwd16_ring_kernel<RPGV, false, false>, (const void*)fwd16_ring_kernel<RPGV, true, false>,          \
-    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>,            \
-    (const void*)fwd16_ring12_kernel<RPGV, false, false>, (const void*)fwd16_ring12_kernel<RPGV, true, false>,      \
-    (const void*)fwd16_ring12_kernel<RPGV, false, true>, (const void*)fwd16_ring12_kernel<RPGV, true, true>
+    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>
     hipError_t e = opt_in.ensure({SLIDE_RING_KERNELS(2), SLIDE_RING_KERNELS(3), SLIDE_RING_KERNELS(4)}, LDS_LIMIT);
 #undef SLIDE_RING_KERNELS
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)r.n_blocks), block(THREADS), block12(THREADS12);
+    const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
 #define SLIDE_RING_LAUNCH3(RPGV, LSEV, PLAINV)                                                                      \
-    do {                                                                                                            \
-        if (twelve) hipLaunchKernelGGL((fwd16_ring12_kernel<RPGV, LSEV, PLAINV>), grid, block12, (size_t)r.lds_bytes, st, a); \
-        else        hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, PLAINV>), grid, block, (size_t)r.lds_bytes, st, a);     \
-    } while (0)
+    hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, PLAINV>), grid, block12, (size_t)r.lds_bytes, st, a)
 #define SLIDE_RING_LAUNCH2(RPGV, LSEV)                                                                              \
     do {                                                                                                            \
         if (plain) SLIDE_RING_LAUNCH3(RPGV, LSEV, true);                                                            \
