@@ -130,3 +130,23 @@ def test_shift_forward_stage1_full_size():
                                    wl.ksize, return_lse=True)
         assert np.abs(out[sl] - refp).max() <= 2e-2
         assert np.abs(lse[sl].cpu().numpy() - ref_lse).max() <= 2e-2
+
+
+def test_traffic_probe_runs_and_rejects_what_it_cannot_do():
+    """The measurement aid: both modes run on the stage-1 shape (out = XOR of the inputs in mode
+    0), mode 1 is refused where the streaming kernel does not run, bad modes are refused."""
+    dev = torch.device("cuda:0")
+    B, C, H, W, heads = 2, 64, 56, 56, 2
+    q, k, v = (torch.randn(B, C, H, W, device=dev).bfloat16() for _ in range(3))
+    out = torch.zeros_like(q)
+    sa.slide_attn_fwd_traffic_probe(q, k, v, out, heads, 0)
+    torch.cuda.synchronize()
+    want = q.view(torch.int16) ^ k.view(torch.int16) ^ v.view(torch.int16)
+    assert torch.equal(out.view(torch.int16), want)
+    sa.slide_attn_fwd_traffic_probe(q, k, v, out, heads, 1)
+    torch.cuda.synchronize()
+    with pytest.raises(sa.SlideAttnError):
+        sa.slide_attn_fwd_traffic_probe(q, k, v, out, heads, 2)
+    wide = torch.zeros(1, 64, 8, 304, device=dev, dtype=torch.bfloat16)
+    with pytest.raises(sa.SlideAttnError):
+        sa.slide_attn_fwd_traffic_probe(wide, wide, wide, torch.empty_like(wide), heads, 1)
