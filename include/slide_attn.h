@@ -12,7 +12,8 @@
  *   - Activations are contiguous NCHW [B, C, H, W]; `dtype` gives their element
  *     type (SLIDE_F32 or SLIDE_BF16).  Kernels, bias and all parameter gradients
  *     are always float32.  Arithmetic accumulates in float32.
- *   - Number format of the SLIDE_BF16 matrix-core paths (head size 32, ksize 3 or 5):
+ *   - Number format of the SLIDE_BF16 matrix-core paths (head size 32 with ksize 3 or 5; head
+ *     size 24 with ksize 3 where slide_attn_fwd_variant says 24):
  *     inside the kernels the bf16 activations (q, k, v, dout) and the kernels wk, wv are held
  *     as IEEE half precision (11 significant bits, more than bf16's 8), products are formed
  *     in half precision from q/16 (dout/16), and every sum is accumulated in float32.  The
@@ -186,7 +187,8 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
  * per block, 21 / 23 = pipelined ksize-3 tile kernel (persistent blocks, next tile staged
  * during the passes of the current one) with the tile width taken from its arguments / fixed
  * at 64, 24 = streaming ksize-3 kernel (a block walks down a band of rows, K/V rows in an LDS
- * ring; maps 32..64 columns wide), 30 = ksize-5 matrix-core kernel.  aligned16: whether
+ * ring; maps 32..64 columns wide; head size 32, or 24 with the fourth channel octet of every
+ * head left empty), 30 = ksize-5 matrix-core kernel.  aligned16: whether
  * q, k, v, out, wk, wv are all 16-byte aligned (kernels 21, 23, 24 need that).  Launches
  * nothing; reads the compute-unit count of the current device (256 if there is none).
  */

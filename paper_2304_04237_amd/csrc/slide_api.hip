@@ -87,6 +87,7 @@ extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
     if (slide::fwd_mfma_supported(p)) return slide::fwd_mfma_variant(p, aligned16 != 0);
+    if (C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16 != 0)) return 24;
     return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
@@ -134,7 +135,13 @@ static int forward(const void* q, const void* k, const void* v,
     Problem p{B, H, W, C, heads, ksize, dtype};
     p.two_branch = two_branch;
     hipError_t e;
-    if (slide::fwd_mfma_supported(p)) {
+    const bool aligned16 = aligned_to(q, 16) && aligned_to(k, 16) && aligned_to(v, 16) && aligned_to(out, 16) &&
+                           aligned_to(wk, 16) && aligned_to(wv, 16);
+    if (C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16)) {
+        // head size 24 on the streaming matrix-core kernel (no workspace); every other problem of
+        // that head size runs on the general kernel below
+        e = slide::launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, false, (hipStream_t)stream);
+    } else if (slide::fwd_mfma_supported(p)) {
         if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
         e = slide::launch_fwd_mfma(p, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
@@ -202,7 +209,7 @@ extern "C" int slide_attn_fwd_shift(const void* q, const void* k, const void* v,
     Problem p{B, H, W, C, heads, ksize, dtype};
     const bool aligned16 = aligned_to(q, 16) && aligned_to(k, 16) && aligned_to(v, 16) && aligned_to(out, 16);
     hipError_t e;
-    if (slide::fwd_mfma_supported(p) && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16))
+    if ((slide::fwd_mfma_supported(p) || C == heads * 24) && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16))
         e = slide::launch_fwd_ring(p, q, k, v, nullptr, nullptr, bias, out, lse, true, (hipStream_t)stream);
     else
         e = slide::launch_fwd_generic(p, q, k, v, nullptr, nullptr, bias, out, lse, (hipStream_t)stream);
@@ -219,7 +226,7 @@ extern "C" int slide_attn_fwd_traffic_probe(const void* q, const void* k, const 
     if (!aligned_to(q, 16) || !aligned_to(k, 16) || !aligned_to(v, 16) || !aligned_to(out, 16)) return SLIDE_ERR_ALIGN;
     Problem p{B, H, W, C, heads, 3, SLIDE_BF16};
     if (((long)B * C * H * W) % 8 != 0) return SLIDE_ERR_SHAPE;
-    if (mode == 1 && !slide::fwd_ring_supported(p, true)) return SLIDE_ERR_SHAPE;
+    if (mode == 1 && (C != heads * 32 || !slide::fwd_ring_supported(p, true))) return SLIDE_ERR_SHAPE;
     hipError_t e = slide::launch_fwd_traffic_probe(p, q, k, v, out, mode, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }

@@ -50,6 +50,7 @@ struct RingArgs {
     float* lse;                                // [B, heads, H, W] or null
     const float* wk; const float* wv; const float* bias;
     int B, H, W, C, heads;
+    int d;                                     // channels per head: 32, or 24 (the fourth octet of every unit is then empty: zeros in, nothing out)
     int nbp, rows_pb, n_blocks;                // bands per plane, rows per band, blocks
     int R, RS, PS;                             // ring rows, bytes per ring row = (W + 2) * 16, bytes per unit plane = R * RS
     int off_raw, off_dummy, off_q, off_out, off_out2;   // LDS byte offsets: K/V landing slots, dump slot, q slots, per-wave result slots, the block's two result buffers
@@ -106,7 +107,8 @@ fwd16_ring_kernel(const RingArgs a)
     const int y0 = part * a.rows_pb;
     const int nr = min(a.rows_pb, H - y0);
     const long HW = (long)H * W;
-    const long head_base = ((long)b * a.C + (long)m * D) * HW;
+    const long head_base = ((long)b * a.C + (long)m * a.d) * HW;   // element offset of channel 0 of the head
+    const bool oct_empty = mover && 8 * mv >= a.d;                   // this mover's octet does not exist
     const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
 
     auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
@@ -118,7 +120,8 @@ fwd16_ring_kernel(const RingArgs a)
 
     // ---- mover: K/V staging of units j = 0 (K), 1 (V), octet mv
     const int oct = mover ? mv : 0;
-    const bf16_bits* kv_src[2] = {a.k + head_base + (long)(8 * oct) * HW, a.v + head_base + (long)(8 * oct) * HW};
+    const int src_oct = oct_empty ? 0 : oct;
+    const bf16_bits* kv_src[2] = {a.k + head_base + (long)(8 * src_oct) * HW, a.v + head_base + (long)(8 * src_oct) * HW};
     const int NXC = W >> 3;
     const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;
     const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
@@ -129,8 +132,9 @@ fwd16_ring_kernel(const RingArgs a)
         const int pw = 2 * oct + j;
         return s < 2 * RPG ? raw + s * SLOT : (s == 2 * RPG ? a.off_q + pw * (3 * SLOT) + 2 * SLOT : a.off_out + pw * SLOT);
     };
+    // (an empty octet reads channel 0 of the head's first octet into the dump slot)
     auto load_row = [&](int j, uint32_t row_off, int off) {
-        if (lane < W) load_to_lds(kv_src[j], kv_lane_off + row_off, lds0 + off);
+        if (lane < W) load_to_lds(kv_src[j], kv_lane_off + row_off, lds0 + (oct_empty ? a.off_dummy : off));
     };
     const int cv_src_off = ((lane & 15) >> 2) * (W * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
     struct RawRow { uint2_t lo, hi; };
@@ -146,7 +150,7 @@ fwd16_ring_kernel(const RingArgs a)
         h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
         h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
 #pragma unroll
-        for (int y = 0; y < 4; ++y) h4[y] = in_map ? h4[y] : 0u;
+        for (int y = 0; y < 4; ++y) h4[y] = (in_map && !oct_empty) ? h4[y] : 0u;
         if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
     };
     auto write_row_in_map = [&](int j, uint32_t ring_off, const RawRow& r) {
@@ -162,7 +166,7 @@ fwd16_ring_kernel(const RingArgs a)
         const bool real = n_first < npix;
         const int nf = real ? n_first : 0;
         const int off = real ? a.off_q + pw * (3 * SLOT) + qo : a.off_dummy;
-        if (nf + 8 * (lane & 1) < npix) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
+        if (nf + 8 * (lane & 1) < npix && (lane >> 1) < a.d) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
     };
 
     // ---- start-up.  The first access to a tensor takes microseconds (cold translation): the
@@ -175,11 +179,18 @@ fwd16_ring_kernel(const RingArgs a)
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;                                                // mover: loads issued after group 0
     if (!PLAIN && !mover) {
+        // 2 x 32 x 81 floats = 1296 chunks of 16 bytes, K kernels then V kernels; with 24 channels
+        // per head the chunks of channels 24 .. 31 are zeros
         constexpr int CHUNKS = HEAD_W / 4;
+        const int head_w = a.d * S * S, chunks_d = head_w / 4;
         for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
             const int c = L * 64 + lane;
-            const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
-            if (c < 2 * CHUNKS) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
+            const int cc = c >= CHUNKS ? c - CHUNKS : c;
+            const float* src = (c >= CHUNKS ? a.wv : a.wk) + (long)m * head_w + 4 * cc;
+            if (c < 2 * CHUNKS) {
+                if (cc < chunks_d) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
+                else *(uint4_t*)(smem + IMG_RAW_AT + c * 16) = uint4_t{0u, 0u, 0u, 0u};
+            }
         }
     }
     if (mover) {
@@ -224,6 +235,17 @@ fwd16_ring_kernel(const RingArgs a)
         const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
         *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
     }
+    // q slots: the rows of channels the head does not have stay zero (the first two slots of every
+    // pass wave here; the third, which holds start-up rows first, by its mover below)
+    auto zero_q_rows = [&](int idx0, int n, int stride, int slot_lo, int slots_per_wave) {
+        const int per_slot = (D - a.d) * 2;                            // 16-byte chunks per slot
+        for (int idx = idx0; idx < n * per_slot; idx += stride) {
+            const int sl = idx / per_slot, ch = idx - sl * per_slot;
+            const int pw = sl / slots_per_wave, s3 = slot_lo + sl % slots_per_wave;
+            *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + s3 * SLOT + a.d * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
+        }
+    };
+    if (a.d < D) zero_q_rows(tid, 2 * WAVES, THREADS12, 0, 2);
     constexpr int NL = 2 * RPG + 2;                                    // loads of a mover per epoch
     if (mover) {
         wait_vmem(n_after_g0);                                         // group 0 has landed
@@ -233,6 +255,13 @@ fwd16_ring_kernel(const RingArgs a)
             for (int j = 0; j < 2; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
+        if (a.d < D) {                                                 // third q slots of pass waves 2 mv, 2 mv + 1
+            const int per_slot = (D - a.d) * 2;
+            if (lane < 2 * per_slot) {
+                const int pw = 2 * mv + lane / per_slot, ch = lane % per_slot;
+                *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + 2 * SLOT + a.d * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
+            }
+        }
         // group 2 into set 0, as a full round of NL loads
 #pragma unroll
         for (int k = 0; k < RPG; ++k) {
@@ -290,12 +319,12 @@ fwd16_ring_kernel(const RingArgs a)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = 8 * mv + 4 * i + (lane >> 4);
-            if (n0 < npix) val[i] = *(const uint4_t*)(smem + rd + c * OUT_ROW + (lane & 15) * 16);
+            if (n0 < npix && c < a.d) val[i] = *(const uint4_t*)(smem + rd + c * OUT_ROW + (lane & 15) * 16);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = 8 * mv + 4 * i + (lane >> 4);
-            if (n0 < npix) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
+            if (n0 < npix && c < a.d) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
         }
     };
 
@@ -324,7 +353,7 @@ fwd16_ring_kernel(const RingArgs a)
             for (int i = 0; i < 2; ++i) load_q(2 * mv + i, PX_EPOCH * (e + 2) + 16 * (2 * mv + i), qo_2);
             // conversion of group e + 1 into the ring
             const int cnt = (cvB >> 10) & 7;
-            if (((cvB >> 13) & 15u) == 0) {                            // every row inside the map: the usual case
+            if (((cvB >> 13) & 15u) == 0 && !oct_empty) {              // every row inside the map: the usual case
 #pragma unroll
                 for (int k = 0; k < RPG; ++k) {
                     const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
@@ -363,7 +392,7 @@ fwd16_ring_kernel(const RingArgs a)
     const unsigned char* tap_base = smem + g * PS;
     const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
     int nb = 16 * wave;
-    float* lse_ptr = LSE ? a.lse + head_base / D + (long)y0 * W : nullptr;
+    float* lse_ptr = LSE ? a.lse + ((long)plane * H + y0) * W : nullptr;
     for (int e = 0; e < E; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
         if (p2 & 256u) {
@@ -642,7 +671,8 @@ probe_stream_kernel(const RingArgs a)
 
 bool fwd_ring_supported(const Problem& p, bool aligned16)
 {
-    if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16ring::D) return false;
+    if (!aligned16 || p.dtype != 1 || p.ksize != 3) return false;
+    if (p.C != p.heads * f16ring::D && p.C != p.heads * 24) return false;   // head size 32 or 24
     if ((long)p.H * p.W * 2 * f16ring::D >= (1L << 31)) return false;  // 32-bit byte offsets inside a head
     return f16ring::plan_ring(p).ok;
 }
@@ -658,12 +688,12 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.lse = lse;
     a.wk = wk; a.wv = wv; a.bias = bias;
-    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
+    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads; a.d = p.C / p.heads;
     a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
     a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out; a.off_out2 = r.off_out2;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
-    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.scale_log2e = 1.44269504088896341f / sqrtf((float)a.d);
     a.idw = p.two_branch ? 1.0f : 0.0f;
     static LdsOptIn opt_in;
 #define SLIDE_RING_KERNELS(RPGV)                                                                                    \

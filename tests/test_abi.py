@@ -72,6 +72,15 @@ def test_forward_rejects_bad_arguments_on_the_host(lib):
     assert call_fwd(lib, lse=ctypes.c_void_p(0x1002)) == 6            # lse not 4-byte aligned
 
 
+def test_variant_query_knows_head_size_24():
+    # head size 24 runs on the streaming kernel where the map fits it, else on the general kernel
+    assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, True) == 24
+    assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, False) == 10
+    assert sa.slide_attn_fwd_variant(2, 56, 72, 48, 2, 3, 1, True) == 10      # wider than the ring takes
+    assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 5, 1, True) == 10      # 5x5 window
+    assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 0, True) == 10      # float32
+
+
 def test_shift_forward_rejects_bad_arguments_on_the_host(lib):
     lib.slide_attn_fwd_shift.restype = ctypes.c_int
     lib.slide_attn_fwd_shift.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 7 + [ctypes.c_void_p]

@@ -150,3 +150,54 @@ def test_traffic_probe_runs_and_rejects_what_it_cannot_do():
     wide = torch.zeros(1, 64, 8, 304, device=dev, dtype=torch.bfloat16)
     with pytest.raises(sa.SlideAttnError):
         sa.slide_attn_fwd_traffic_probe(wide, wide, wide, torch.empty_like(wide), heads, 1)
+
+
+HEAD24_SHAPES = [
+    # B, H, W, C, heads: head size 24 (Slide-CSwin-B, App. A) on the streaming matrix-core kernel
+    (2, 20, 56, 48, 2),
+    (3, 33, 32, 72, 3),
+    (1, 9, 64, 24, 1),
+    (4, 56, 56, 48, 2),
+]
+
+
+@pytest.mark.parametrize("shape", HEAD24_SHAPES)
+def test_head_size_24_on_the_streaming_kernel(shape):
+    """Merged-kernel forward (with lse), training form and plain shift at 24 channels per head."""
+    B, H, W, C, heads = shape
+    ksize, dtype = 3, "bf16"
+    print("head size 24 case", shape, flush=True)
+    assert sa.slide_attn_fwd_variant(B, H, W, C, heads, ksize, 1) == 24
+    assert sa.slide_attn_fwd_variant(B, H, W, C, heads, ksize, 1, aligned16=False) == 10
+    d = synth.make_inputs(B, H, W, C, heads, ksize, dtype, seed=700 + H + W)
+    dev = torch.device("cuda:0")
+    g = {n: d[n].to(dev).to(torch.bfloat16) for n in ("q", "k", "v")}
+    wk_l, wv_l = d["wk_learned"].to(dev), d["wv_learned"].to(dev)
+    wk, wv = sa.slide_reparam(wk_l), sa.slide_reparam(wv_l)
+    bias = d["bias"].to(dev)
+    n = {x: d[x].double().numpy() for x in ("q", "k", "v", "bias")}
+    lse = torch.full((B, heads, H, W), float("nan"), dtype=torch.float32, device=dev)
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], wk, wv, bias, heads, ksize, lse=lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], wk.double().cpu().numpy(), wv.double().cpu().numpy(),
+                              n["bias"], heads, ksize, return_lse=True)
+    check("out", dtype, out, ref)
+    check("lse", dtype, lse, ref_lse)
+    out_nolse = sa.slide_attn_fwd(g["q"], g["k"], g["v"], wk, wv, bias, heads, ksize)
+    assert torch.equal(out_nolse, out)
+    out_tb = sa.slide_attn_fwd_two_branch(g["q"], g["k"], g["v"], wk_l, wv_l, bias, heads, ksize)
+    ref_tb = oracle.fwd(n["q"], n["k"], n["v"], d["wk_learned"].double().numpy(), d["wv_learned"].double().numpy(),
+                        n["bias"], heads, ksize, two_branch=True)
+    check("out(two-branch)", dtype, out_tb, ref_tb)
+    w1 = oracle.reparam(np.zeros((C, 9, 3, 3)), 3)
+    out_s = sa.slide_attn_fwd_shift(g["q"], g["k"], g["v"], bias, heads, ksize)
+    check("out(shift)", dtype, out_s, oracle.fwd(n["q"], n["k"], n["v"], w1, w1, n["bias"], heads, ksize))
+    # the general kernel on the same problem (unaligned views) agrees with the oracle as well
+    numel = B * C * H * W
+    views = {}
+    for name in ("q", "k", "v"):
+        buf = torch.empty(numel + 8, dtype=torch.bfloat16, device=dev)
+        views[name] = buf[1:1 + numel].view(B, C, H, W)
+        views[name].copy_(g[name])
+    out_g = sa.slide_attn_fwd(views["q"], views["k"], views["v"], wk, wv, bias, heads, ksize)
+    check("out(general kernel)", dtype, out_g, ref)
