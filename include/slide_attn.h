@@ -213,6 +213,22 @@ int slide_attn_fwd_shift(const void* q, const void* k, const void* v, const floa
                          int B, int H, int W, int C, int heads, int ksize, int dtype, void* stream);
 
 /*
+ * Forward for channels-last activations: q, k, v, out are [B, H, W, C] (the layout of the
+ * [B, H*W, C] token tensors of window-attention backbones such as Slide-Swin, App. A), C
+ * contiguous, head m owning channels [m*d, (m+1)*d) of every pixel.  Everything else -- the
+ * operator (Sec. 3.1 Eq. 2, Sec. 4.1-4.3), the merged kernels wk, wv [C,S,ksize,ksize], bias,
+ * lse [B,heads,H,W] (planar in either layout), dtype, the number-format contract, the error
+ * codes -- is as for slide_attn_fwd; there is no workspace.  SLIDE_BF16 problems with head size
+ * 32, ksize 3, 32 <= W <= 64, W % 8 == 0 and 16-byte aligned pointers run on the streaming
+ * matrix-core kernel (the 8 channels a lane works on are 16 contiguous bytes in this layout:
+ * nothing is transposed); every other problem runs on the general kernel.
+ */
+int slide_attn_fwd_nhwc(const void* q, const void* k, const void* v,
+                        const float* wk, const float* wv, const float* bias,
+                        void* out, float* lse,
+                        int B, int H, int W, int C, int heads, int ksize, int dtype, void* stream);
+
+/*
  * Measurement aid for benchmarks: moves the bytes of slide_attn_fwd on a SLIDE_BF16 problem
  * (reads q, k, v once, writes out once; ksize 3) with no arithmetic, so that the forward can be
  * held against what the memory system gives for its traffic.  out receives the bitwise XOR

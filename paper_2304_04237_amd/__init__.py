@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     slide_attn_bwd,
     slide_attn_bwd_two_branch,
     slide_attn_fwd,
+    slide_attn_fwd_nhwc,
     slide_attn_fwd_noalloc,
     slide_attn_fwd_two_branch,
     slide_attn_fwd_path,

@@ -52,6 +52,8 @@ def load_library():
     lib.slide_attn_fwd_noalloc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
     lib.slide_attn_fwd_shift.restype = i
     lib.slide_attn_fwd_shift.argtypes = [_vp] * 6 + [i] * 7 + [_vp]
+    lib.slide_attn_fwd_nhwc.restype = i
+    lib.slide_attn_fwd_nhwc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
     lib.slide_attn_fwd_traffic_probe.restype = i
     lib.slide_attn_fwd_traffic_probe.argtypes = [_vp] * 4 + [i] * 6 + [_vp]
     lib.slide_attn_bwd.restype = i
@@ -190,6 +192,35 @@ def slide_attn_fwd_shift(q, k, v, bias, heads, ksize, out=None, lse=None):
                                                _dev(bias, "bias", torch.float32), _dev(out, "out"),
                                                _dev(lse, "lse", torch.float32),
                                                B, H, W, C, heads, ksize, code, _stream()))
+    return out
+
+
+def slide_attn_fwd_nhwc(q, k, v, wk, wv, bias, heads, ksize, out=None, lse=None):
+    """Forward for channels-last activations [B, H, W, C]; lse, if given, is [B, heads, H, W]."""
+    if q.dim() != 4:
+        raise SlideAttnError("activations must be [B, H, W, C]")
+    B, H, W, C = q.shape
+    S = ksize * ksize
+    for t, n in ((wk, "wk"), (wv, "wv")):
+        if tuple(t.shape) != (C, S, ksize, ksize):
+            raise SlideAttnError("%s must be [C, k*k, k, k] = %s, got %s" % (n, (C, S, ksize, ksize), tuple(t.shape)))
+    if bias is not None and tuple(bias.shape) != (heads, S):
+        raise SlideAttnError("bias must be [heads, k*k] = %s, got %s" % ((heads, S), tuple(bias.shape)))
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype:
+        raise SlideAttnError("out must match q in shape and dtype")
+    if lse is not None and tuple(lse.shape) != (B, heads, H, W):
+        raise SlideAttnError("lse must be [B, heads, H, W]")
+    _check(load_library().slide_attn_fwd_nhwc(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                              _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                                              _dev(bias, "bias", torch.float32), _dev(out, "out"),
+                                              _dev(lse, "lse", torch.float32),
+                                              B, H, W, C, heads, ksize, code, _stream()))
     return out
 
 

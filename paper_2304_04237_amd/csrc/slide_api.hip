@@ -216,6 +216,29 @@ extern "C" int slide_attn_fwd_shift(const void* q, const void* k, const void* v,
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }
 
+extern "C" int slide_attn_fwd_nhwc(const void* q, const void* k, const void* v,
+                                   const float* wk, const float* wv, const float* bias, void* out, float* lse,
+                                   int B, int H, int W, int C, int heads, int ksize, int dtype, void* stream)
+{
+    int st = check_problem(B, H, W, C, heads, ksize, dtype);
+    if (st != SLIDE_OK) return st;
+    if (!q || !k || !v || !wk || !wv || !out) return SLIDE_ERR_NULL;
+    const size_t esz = dtype == SLIDE_F32 ? 4 : 2;
+    if (!aligned_to(q, esz) || !aligned_to(k, esz) || !aligned_to(v, esz) || !aligned_to(out, esz) ||
+        !aligned_to(wk, 4) || !aligned_to(wv, 4) || !aligned_to(bias, 4) || !aligned_to(lse, 4))
+        return SLIDE_ERR_ALIGN;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    p.nhwc = 1;
+    const bool aligned16 = aligned_to(q, 16) && aligned_to(k, 16) && aligned_to(v, 16) && aligned_to(out, 16) &&
+                           aligned_to(wk, 16) && aligned_to(wv, 16);
+    hipError_t e;
+    if (slide::fwd_ring_enabled() && slide::fwd_ring_nhwc_supported(p, aligned16))
+        e = slide::launch_fwd_ring_nhwc(p, q, k, v, wk, wv, bias, out, lse, (hipStream_t)stream);
+    else
+        e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, lse, (hipStream_t)stream);
+    return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
 extern "C" int slide_attn_fwd_traffic_probe(const void* q, const void* k, const void* v, void* out,
                                            int B, int H, int W, int C, int heads, int mode, void* stream)
 {

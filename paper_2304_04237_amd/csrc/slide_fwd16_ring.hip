@@ -520,6 +520,294 @@ fwd16_ring_kernel(const RingArgs a)
     }
 }
 
+// ------------------------------------------------------------------ channels-last activations
+// The same kernel for q, k, v, out stored [B, H, W, C] (NHWC, the layout of [B, HW, C] token
+// tensors): the 8 channels of a pixel that a lane works on are 16 contiguous bytes, so nothing
+// is transposed.  A mover loads the K/V rows of its 16-column group (lane = pixel x channel
+// octet, 64 contiguous bytes per pixel and head) and a quarter of every epoch's q into
+// registers two epochs ahead; it converts the rows into the ring and passes q on through a
+// small LDS buffer in the order the pass waves read it (16 bytes per lane, no transposition).
+// A pass wave stores its results straight from its registers.  LDS holds the ring and the q
+// buffer only.  All loads are ordinary loads whose waits the compiler places; the movers'
+// epoch loop is unrolled by two so that the two register sets in flight alternate by name.
+template <int RPG, bool LSE>
+__global__ void __launch_bounds__(THREADS12)
+fwd16_ring_nhwc_kernel(const RingArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool mover = wave >= WAVES;
+    const int mv = wave - WAVES;                                       // mover index 0 .. 3 = its 16-column group
+    const int p = lane & 15, g = lane >> 4;
+    const int W = a.W, H = a.H, R = a.R, C = a.C;
+    const int RS = a.RS, PS = a.PS;
+
+    int u = blockIdx.x;                                                // block -> band of a plane, as above
+    {
+        const int per = a.n_blocks >> 3;
+        if (u < 8 * per) u = (u & 7) * per + (u >> 3);
+    }
+    const int plane = u / a.nbp, part = u - plane * a.nbp;
+    const int b = plane / a.heads, m = plane - b * a.heads;
+    const int y0 = part * a.rows_pb;
+    const int nr = min(a.rows_pb, H - y0);
+    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
+    // byte offset of channel 0 of the head at pixel 0 of batch item b; a pixel is 2 C bytes on
+    const size_t img_base = ((size_t)b * H * W * C + (size_t)m * D) * 2;
+    const uint32_t px2 = (uint32_t)C * 2u, row2 = (uint32_t)W * px2;
+
+    auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
+    auto mod_r = [&](int x) { return x - (int)__umulhi((uint32_t)x, a.magic_r) * R; };
+    auto srn = [&](int j) {
+        const int rb = min(div_w(PX_EPOCH * j + PX_EPOCH - 1), nr - 1);
+        return j >= E ? nr + 1 : min(rb + 2, nr + 1);
+    };
+
+    // ---- the schedule, lane e of the table registers holding epoch e (see fwd16_ring_kernel)
+    uint32_t t_cvA, t_cvB, t_ld, t_p0, t_p1, t_p2;
+    {
+        const int e = lane;
+        const int s0 = srn(e), s1 = srn(e + 1), s2 = srn(e + 2);
+        const int RW = W + 2;
+        auto ring_of = [&](int sr) { return (uint32_t)(mod_r(sr) * RW); };
+        t_cvA = ring_of(s0 + 1) | ring_of(s0 + 2) << 10 | ring_of(s0 + 3) << 20;
+        uint32_t outside = 0;
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + s0 + k;
+            outside |= (gy < 0 || gy >= H) ? 1u << k : 0u;
+        }
+        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13;
+        t_ld = (uint32_t)max(y0 + s2, 0);                              // map row of the first row of group e + 3
+        const int nbe = PX_EPOCH * e + 16 * (mover ? 0 : wave);
+        const int ra = div_w(nbe), c0 = nbe - ra * W;
+        t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
+        t_p1 = ring_of(ra + 1) | ring_of(ra + 2) << 10 | ring_of(ra + 3) << 20;
+        t_p2 = (uint32_t)c0 | (nbe < npix ? 256u : 0u);
+    }
+    const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
+    const int E2 = (E + 1) & ~1;                                       // both loops run an even number of epochs (the last may be empty)
+
+    // The two kinds of waves part here for good (their registers never coexist); both pass the same
+    // four start-up barriers and one barrier per epoch.
+    if (mover) {
+        // columns 16 mv .. 16 mv + 15, lane = pixel (lane / 4) x octet (lane % 4)
+        // Every load is unconditional (lanes and rows that have nothing to fetch read a valid
+        // address and get zeros afterwards): straight-line code, in which the compiler counts the
+        // loads in flight exactly and waits only for the ones it uses.
+        const int m_px = 16 * mv + (lane >> 2), m_oct = lane & 3;
+        const bool m_lane = m_px < W;
+        const int m_pxc = min(m_px, W - 1);
+        const char* kv_base[2] = {(const char*)a.k + img_base + (size_t)m_pxc * px2 + m_oct * 16,
+                                  (const char*)a.v + img_base + (size_t)m_pxc * px2 + m_oct * 16};
+        // map row gy (clamped into the map) of tensor j: the lane's 8 channels.  Nothing is done to
+        // the value here: whatever touches it would wait for the load.
+        auto load_item = [&](int j, int gy) {
+            return *(const uint4_t*)(kv_base[j] + (size_t)min(max(gy, 0), H - 1) * row2);
+        };
+        // (in_map false: the row lies above or below the map and is written as zeros, Fig. 2)
+        auto write_item = [&](int j, uint32_t ring_off, bool in_map, const uint4_t& r) {
+            uint4_t h4;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) h4[y] = in_map ? bf16x2_to_half2(r[y]) : 0u;
+            if (m_lane) *(uint4_t*)(smem + (4 * j + m_oct) * PS + (m_px + 1) * 16 + ring_off) = h4;
+        };
+        // q: pixels 32 mv .. 32 mv + 31 of every epoch, two items per lane
+        const char* q_base = (const char*)a.q + img_base + (size_t)y0 * row2 + m_oct * 16;
+        auto load_q = [&](int e, int i) {                              // (zeros past the band)
+            const int n = PX_EPOCH * e + 32 * mv + 16 * i + (lane >> 2);
+            return *(const uint4_t*)(q_base + (size_t)min(n, npix - 1) * px2);   // (past the band: some pixel; nothing of it is stored)
+        };
+        auto write_q = [&](int e, int i, const uint4_t& r) {
+            *(uint4_t*)(smem + a.off_q + (e & 1) * (PX_EPOCH * 64) + ((32 * mv + 16 * i) * 4 + lane) * 16) = r;
+        };
+        // q of epochs 0 .. 2, group 0 (at most RPG + 2 rows), groups 1 and 2, all issued before anything is used
+        uint4_t q0[2], qa[2], qb[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) { q0[i] = load_q(0, i); qa[i] = load_q(1, i); qb[i] = load_q(2, i); }
+        uint4_t g0[RPG + 2][2], ga[RPG][2], gb[RPG][2];
+#pragma unroll
+        for (int k = 0; k < RPG + 2; ++k) {
+            const int gy = y0 - 1 + k;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) g0[k][j] = load_item(j, gy);
+        }
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + v0 + k;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) ga[k][j] = load_item(j, gy);
+        }
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + v1 + k;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) gb[k][j] = load_item(j, gy);
+        }
+        block_barrier();                                               // (the head's kernels are in LDS)
+        block_barrier();                                               // (the operand image is built)
+        block_barrier();                                               // (the operands are in registers: the ring's memory is free)
+#pragma unroll
+        for (int k = 0; k < RPG + 2; ++k)
+            if (k <= v0) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) write_item(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, g0[k][j]);
+            }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) write_q(0, i, q0[i]);
+        block_barrier();
+        // epoch e: the rows of group e + 1 and q of epoch e + 1 (loaded two epochs ago) go into LDS,
+        // the loads of group e + 3 and of q of epoch e + 3 take their registers
+        auto mover_epoch = [&](int e, uint4_t (&cur)[RPG][2], uint4_t (&qcur)[2]) {
+            const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
+            const int gy0 = (int)__builtin_amdgcn_readlane(t_ld, e);
+            const int cnt = (cvB >> 10) & 7;
+#pragma unroll
+            for (int k = 0; k < RPG; ++k) {
+                const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
+                if (k < cnt) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) write_item(j, pos, !((cvB >> (13 + k)) & 1u), cur[k][j]);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < RPG; ++k)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) cur[k][j] = load_item(j, gy0 + k);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) { write_q(e + 1, i, qcur[i]); qcur[i] = load_q(e + 3, i); }
+            block_barrier();
+        };
+        for (int e = 0; e < E2; e += 2) {
+            mover_epoch(e, ga, qa);
+            mover_epoch(e + 1, gb, qb);
+        }
+        return;
+    }
+
+    // ---- pass waves: the bias and q of the first two epochs first (the first access to a tensor
+    // takes microseconds), then the head's kernels into LDS (behind where the operand image
+    // goes), the image, the operands
+    float bias_early = 0.0f;                                           // the image's bias word of logit row `tid`
+    if (a.bias && tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[m * S + shift_of_row(tid)];
+    char* o_base = (char*)a.out + img_base + (size_t)y0 * row2 + g * 16;
+    {
+        constexpr int CHUNKS = HEAD_W / 4;
+        for (int c = tid; c < 2 * CHUNKS; c += THREADS) {
+            const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
+            *(float4_t*)(smem + IMG_RAW_AT + c * 16) = *(const float4_t*)src;
+        }
+    }
+    block_barrier();
+    image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), nullptr, m, a.idw, (uint32_t*)smem, tid);
+    if (tid < IMG_DWORDS - IMG_BIAS)
+        ((uint32_t*)smem)[IMG_BIAS + tid] = __float_as_uint(shift_of_row(tid) >= 0 ? bias_early * 1.44269504088896341f : -INFINITY);
+    block_barrier();
+    half8_t A1[S];
+    half4_t A2[2 * S];
+    float bias2[3];
+    load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
+    block_barrier();
+    for (int idx = tid; idx < R * 16; idx += THREADS) {                // the padding columns of the ring stay zero
+        const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
+        *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
+    }
+    block_barrier();
+
+    // ---- pass waves
+    const int VD = 4 * PS;
+    const unsigned char* tap_base = smem + g * PS;
+    float* lse_ptr = LSE ? a.lse + ((long)plane * H + y0) * W : nullptr;
+    const unsigned char* q_lds = smem + a.off_q + ((16 * wave + p) * 4 + g) * 16;
+    for (int e = 0; e < E2; ++e) {
+        const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
+        const int nb = PX_EPOCH * e + 16 * wave;
+        if (p2 & 256u) {
+            const uint4_t qraw = *(const uint4_t*)(q_lds + (e & 1) * (PX_EPOCH * 64));
+            const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
+            const int cx0 = (int)(p2 & 255u) + p;
+            const bool next_row = cx0 >= W;
+            const uint32_t cx = next_row ? cx0 - W : cx0;
+            const uint32_t rows = next_row ? p1 : p0;
+            const unsigned char* kb[KS];
+#pragma unroll
+            for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
+            uint4_t kd[S];
+#pragma unroll
+            for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
+            half2_t qs[4];
+            {
+                const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
+#pragma unroll
+                for (int y = 0; y < 4; ++y) qs[y] = as_half2(bf16x2_to_half2(qraw[y])) * sc;
+            }
+            float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1b = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int t = 0; t < S; ++t) {
+                uint4_t bb;
+#pragma unroll
+                for (int y = 0; y < 4; ++y) bb[y] = as_dword(qs[y] * as_half2(kd[t][y]));
+                if (t & 1) acc1b = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1b, 0, 0, 0);
+                else       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
+            }
+            acc1 += acc1b;
+            uint4_t vd[S];
+#pragma unroll
+            for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+            float l[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
+            const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
+            float pr[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
+            const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
+            const float inv = __builtin_amdgcn_rcpf(den);
+            if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+            uint2_t b2;
+            b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
+            b2[1] = pack_half(pr[2] * inv, 0.0f);
+            const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+            const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+            float4_t w[2 * S];
+            float o[8];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) o[x] = 0.0f;
+            constexpr int AHEAD = 2;
+#pragma unroll
+            for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu], B2, zero4, 0, 0, 0);
+#pragma unroll
+            for (int uu = 0; uu < 2 * S; ++uu) {
+                if (uu + AHEAD < 2 * S)
+                    w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2[uu + AHEAD], B2, zero4, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int x = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
+                    const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
+                    o[x] = fmaf(w[uu][r], (float)as_half2(vd[tap][x >> 1])[x & 1], o[x]);
+                }
+                // (pins the multiply-adds here: otherwise they sink below all the products, whose 72 results then live at once)
+                if (uu < 16) asm volatile("" : "+v"(o[uu & 7]));
+                else asm volatile("" : "+v"(o[4 * (uu - 16)]), "+v"(o[4 * (uu - 16) + 1]), "+v"(o[4 * (uu - 16) + 2]), "+v"(o[4 * (uu - 16) + 3]));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            uint4_t ov;
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+                typedef float float2_t __attribute__((ext_vector_type(2)));
+                const float2_t f2 = {o[2 * y], o[2 * y + 1]};
+                ov[y] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f2, bf16x2_t));
+            }
+            if (nb + p < npix) *(uint4_t*)(o_base + (size_t)(nb + p) * px2) = ov;
+        }
+        block_barrier();
+    }
+}
+
 // ------------------------------------------------------------------ host side
 struct RingPlan {
     int rpg, nbp, rows_pb, n_blocks, R, RS, PS, off_raw, off_dummy, off_q, off_out, off_out2, lds_bytes;
@@ -721,6 +1009,53 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
 #undef SLIDE_RING_LAUNCH2
 #undef SLIDE_RING_LAUNCH3
 #undef SLIDE_RING_LAUNCH
+    return hipGetLastError();
+}
+
+bool fwd_ring_nhwc_supported(const Problem& p, bool aligned16)
+{
+    if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16ring::D) return false;
+    if ((long)p.H * p.W * p.C * 2 >= (1L << 31)) return false;        // 32-bit byte offsets inside a batch item
+    return f16ring::plan_ring(p).ok;
+}
+
+hipError_t launch_fwd_ring_nhwc(const Problem& p, const void* q, const void* k, const void* v,
+                                const float* wk, const float* wv, const float* bias, void* out,
+                                float* lse, hipStream_t st)
+{
+    using namespace f16ring;
+    const RingPlan r = plan_ring(p);
+    if (!r.ok) return hipErrorInvalidValue;
+    RingArgs a{};
+    a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.out = (bf16_bits*)out; a.lse = lse;
+    a.wk = wk; a.wv = wv; a.bias = bias;
+    a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads; a.d = D;
+    a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS;
+    a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
+    a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
+    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.idw = p.two_branch ? 1.0f : 0.0f;
+    int lds_bytes = 8 * r.PS;                                          // the ring (at start-up the operand image and the raw kernels) ...
+    if (lds_bytes < IMG_RAW_AT + IMG_RAW_BYTES) lds_bytes = IMG_RAW_AT + IMG_RAW_BYTES;
+    a.off_q = (lds_bytes + 255) & ~255;                                // ... and two q buffers of 128 pixels x 64 bytes
+    lds_bytes = a.off_q + 2 * PX_EPOCH * 64;
+    static LdsOptIn opt_in;
+    hipError_t e = opt_in.ensure({(const void*)fwd16_ring_nhwc_kernel<2, false>, (const void*)fwd16_ring_nhwc_kernel<2, true>,
+                                  (const void*)fwd16_ring_nhwc_kernel<3, false>, (const void*)fwd16_ring_nhwc_kernel<3, true>,
+                                  (const void*)fwd16_ring_nhwc_kernel<4, false>, (const void*)fwd16_ring_nhwc_kernel<4, true>}, LDS_LIMIT);
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
+#define SLIDE_NHWC_LAUNCH(RPGV)                                                                                      \
+    do {                                                                                                             \
+        if (lse) hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, true>), grid, block12, (size_t)lds_bytes, st, a);  \
+        else     hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, false>), grid, block12, (size_t)lds_bytes, st, a); \
+    } while (0)
+    if (r.rpg == 2) SLIDE_NHWC_LAUNCH(2);
+    else if (r.rpg == 3) SLIDE_NHWC_LAUNCH(3);
+    else SLIDE_NHWC_LAUNCH(4);
+#undef SLIDE_NHWC_LAUNCH
     return hipGetLastError();
 }
 

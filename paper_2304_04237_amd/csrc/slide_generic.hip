@@ -45,7 +45,7 @@ hipError_t launch_reparam(const float* w_learned, float* w_merged, int C, int ks
 // zero-padded k*k window of one channel plane around pixel (i, j)
 template <typename T, int KS>
 __device__ __forceinline__ void load_window(const T* __restrict__ plane, int i, int j, int H, int W,
-                                            float (&win)[KS * KS])
+                                            float (&win)[KS * KS], long sp = 1)
 {
     constexpr int R = KS / 2;
 #pragma unroll
@@ -55,7 +55,7 @@ __device__ __forceinline__ void load_window(const T* __restrict__ plane, int i, 
         for (int qq = 0; qq < KS; ++qq) {
             int x = j + qq - R;
             bool in = (y >= 0) && (y < H) && (x >= 0) && (x < W);
-            win[p * KS + qq] = in ? Elem<T>::load(plane + (long)y * W + x) : 0.0f;
+            win[p * KS + qq] = in ? Elem<T>::load(plane + ((long)y * W + x) * sp) : 0.0f;
         }
     }
 }
@@ -101,7 +101,8 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
                                                   const float* __restrict__ wk,
                                                   const float* __restrict__ bias,
                                                   int b, int m, int i, int j, int H, int W, int C,
-                                                  int d, int cg, float idw, float (&a)[KS * KS], float& lse)
+                                                  int d, int cg, float idw, float (&a)[KS * KS], float& lse,
+                                                  long sc, long sp)
 {
     constexpr int S = KS * KS;
     const long HW = (long)H * W;
@@ -111,11 +112,11 @@ __device__ __forceinline__ void attention_weights(const T* __restrict__ q, const
     for (int s = 0; s < S; ++s) dot[s] = 0.0f;
     for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
-        const T* kp = k + ((long)b * C + c) * HW;
+        const T* kp = k + (long)b * C * HW + (long)c * sc;
         float win[S], ks[S];
-        load_window<T, KS>(kp, i, j, H, W, win);
+        load_window<T, KS>(kp, i, j, H, W, win, sp);
         apply_kernels<KS>(wk ? wk + (long)c * S * S : nullptr, win, ks, idw);
-        float qc = Elem<T>::load(q + ((long)b * C + c) * HW + pix);
+        float qc = Elem<T>::load(q + (long)b * C * HW + (long)c * sc + pix * sp);
 #pragma unroll
         for (int s = 0; s < S; ++s) dot[s] = fmaf(qc, ks[s], dot[s]);
     }
@@ -142,8 +143,9 @@ __global__ void __launch_bounds__(256)
 fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v,
                    const float* __restrict__ wk, const float* __restrict__ wv,
                    const float* __restrict__ bias, T* __restrict__ out, float* __restrict__ lse,
-                   int H, int W, int C, int heads, float idw)
-{
+                   int H, int W, int C, int heads, float idw, long sc, long sp)
+{   // element (b, c, pixel) of an activation tensor is at b*C*H*W + c*sc + pixel*sp: sc = H*W,
+    // sp = 1 for [B,C,H,W]; sc = 1, sp = C for [B,H,W,C]
     constexpr int S = KS * KS;
     const int d = C / heads;
     const int m = blockIdx.y, b = blockIdx.z;
@@ -156,19 +158,19 @@ fwd_generic_kernel(const T* __restrict__ q, const T* __restrict__ k, const T* __
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px);
+    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px, sc, sp);
     if (lse && live && cg == 0) lse[((long)b * heads + m) * HW + pix] = lse_px;
 
     for (int cc = cg; cc < d; cc += LPP) {
         int c = m * d + cc;
-        const T* vp = v + ((long)b * C + c) * HW;
+        const T* vp = v + (long)b * C * HW + (long)c * sc;
         float win[S], vs[S];
-        load_window<T, KS>(vp, i, j, H, W, win);
+        load_window<T, KS>(vp, i, j, H, W, win, sp);
         apply_kernels<KS>(wv ? wv + (long)c * S * S : nullptr, win, vs, idw);
         float acc = 0.0f;
 #pragma unroll
         for (int s = 0; s < S; ++s) acc = fmaf(a[s], vs[s], acc);
-        if (live) Elem<T>::store(out + ((long)b * C + c) * HW + pix, acc);
+        if (live) Elem<T>::store(out + (long)b * C * HW + (long)c * sc + pix * sp, acc);
     }
 }
 
@@ -182,14 +184,15 @@ static hipError_t launch_fwd_t(const Problem& p, const void* q, const void* k, c
 {
     const int lpp = few_pixels(p) ? 8 : 1;
     dim3 grid((unsigned)((p.plane() * lpp + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
+    const long sc = p.nhwc ? 1 : p.plane(), sp = p.nhwc ? p.C : 1;
     if (lpp == 8)
         hipLaunchKernelGGL((fwd_generic_kernel<T, KS, 8>), grid, dim3(256), 0, st,
                            (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
-                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f, sc, sp);
     else
         hipLaunchKernelGGL((fwd_generic_kernel<T, KS, 1>), grid, dim3(256), 0, st,
                            (const T*)q, (const T*)k, (const T*)v, wk, wv, bias, (T*)out, lse,
-                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f);
+                           p.H, p.W, p.C, p.heads, p.two_branch ? 1.0f : 0.0f, sc, sp);
     return hipGetLastError();
 }
 
@@ -244,7 +247,7 @@ bwd_pixel_kernel(const T* __restrict__ dout, const T* __restrict__ q, const T* _
     const int i = (int)(pix / W), j = (int)(pix % W);
 
     float a[S], lse_px;
-    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px);
+    attention_weights<T, KS, LPP>(q, k, wk, bias, b, m, i, j, H, W, C, d, cg, idw, a, lse_px, (long)H * W, 1);
 
     float da[S];
 #pragma unroll

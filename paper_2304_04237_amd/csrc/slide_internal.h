@@ -16,6 +16,8 @@ struct Problem {
     int two_branch = 0;
     // backward: add the kernel and bias gradients to what dwk, dwv, dbias hold (micro-batches)
     int accumulate = 0;
+    // activations are stored [B, H, W, C] (channels last) instead of [B, C, H, W]; forward only
+    int nhwc = 0;
     int d() const { return C / heads; }
     int S() const { return ksize * ksize; }
     long plane() const { return (long)H * W; }
@@ -99,6 +101,13 @@ bool fwd_ring_enabled();                               // false if the environme
 hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, bool plain, hipStream_t st);
+
+// the streaming kernel for channels-last activations (Problem::nhwc): bf16, d == 32, ksize 3,
+// 32 <= W <= 64, W % 8 == 0, every pointer 16-byte aligned; needs no workspace
+bool fwd_ring_nhwc_supported(const Problem& p, bool aligned16);
+hipError_t launch_fwd_ring_nhwc(const Problem& p, const void* q, const void* k, const void* v,
+                                const float* wk, const float* wv, const float* bias, void* out,
+                                float* lse, hipStream_t st);
 
 // the forward's bytes without its arithmetic: mode 0 flat copy-like, mode 1 the streaming
 // kernel's access pattern (needs fwd_ring_supported)
