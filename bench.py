@@ -196,6 +196,25 @@ def main():
         probes["plain_shift_forward_us"] = e0.elapsed_time(e1) / 40 * 1e3
     except Exception as exc:                      # noqa: BLE001
         probes["plain_shift_forward_us"] = "failed: %s" % exc
+    # the same workload with channels-last activations ([B,H,W,C], slide_attn_fwd_nhwc)
+    try:
+        nh = [[torch.randn(B, H, W, C, device=dev).to(torch.bfloat16) for _ in range(3)] +
+              [torch.empty(B, H, W, C, device=dev, dtype=torch.bfloat16)] for _ in range(POOL_SETS)]
+        for s_ in nh:
+            sa.slide_attn_fwd_nhwc(s_[0], s_[1], s_[2], wk, wv, bias, heads, ksize, out=s_[3])
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(40):
+            s_ = nh[i % POOL_SETS]
+            sa.slide_attn_fwd_nhwc(s_[0], s_[1], s_[2], wk, wv, bias, heads, ksize, out=s_[3])
+        e1.record()
+        torch.cuda.synchronize()
+        probes["channels_last_forward_us"] = e0.elapsed_time(e1) / 40 * 1e3
+        del nh
+    except Exception as exc:                      # noqa: BLE001
+        probes["channels_last_forward_us"] = "failed: %s" % exc
     n_replay, n_tail = (args.steps // POOL_SETS, args.steps % POOL_SETS) if graph is not None else (0, args.steps)
     t0 = time.perf_counter()
     start = torch.cuda.Event(enable_timing=True)

@@ -530,16 +530,23 @@ fwd16_ring_kernel(const RingArgs a)
 // A pass wave stores its results straight from its registers.  LDS holds the ring and the q
 // buffer only.  All loads are ordinary loads whose waits the compiler places; the movers'
 // epoch loop is unrolled by two so that the two register sets in flight alternate by name.
-template <int RPG, bool LSE>
-__global__ void __launch_bounds__(THREADS12)
+// NW pass waves and NM movers per block.  8 + 4 is what is launched (one block per compute unit,
+// epochs of 128 pixels); 4 + 2 with two blocks per compute unit and epochs of 64 pixels was
+// measured slower (39 against 30 us at stage 1: twice the epochs, barriers and halo rows).
+template <int RPG, bool LSE, int NW, int NM>
+__global__ void __launch_bounds__((NW + NM) * 64, 3)
 fwd16_ring_nhwc_kernel(const RingArgs a)
 {
+    constexpr int PXE = 16 * NW;                                       // pixels per epoch
+    constexpr int CG = 4 / NM;                                         // 16-column groups per mover
+    constexpr int NTH = (NW + NM) * 64, PTH = NW * 64;                 // threads of the block, of its pass waves
+    static_assert(NW == 2 * NM && (NM == 4 || NM == 2), "q is dealt two items per mover lane and epoch");
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool mover = wave >= WAVES;
-    const int mv = wave - WAVES;                                       // mover index 0 .. 3 = its 16-column group
+    const bool mover = wave >= NW;
+    const int mv = wave - NW;                                          // mover index
     const int p = lane & 15, g = lane >> 4;
     const int W = a.W, H = a.H, R = a.R, C = a.C;
     const int RS = a.RS, PS = a.PS;
@@ -553,7 +560,7 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     const int b = plane / a.heads, m = plane - b * a.heads;
     const int y0 = part * a.rows_pb;
     const int nr = min(a.rows_pb, H - y0);
-    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
+    const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + NW - 1) / NW;
     // byte offset of channel 0 of the head at pixel 0 of batch item b; a pixel is 2 C bytes on
     const size_t img_base = ((size_t)b * H * W * C + (size_t)m * D) * 2;
     const uint32_t px2 = (uint32_t)C * 2u, row2 = (uint32_t)W * px2;
@@ -561,7 +568,7 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
     auto mod_r = [&](int x) { return x - (int)__umulhi((uint32_t)x, a.magic_r) * R; };
     auto srn = [&](int j) {
-        const int rb = min(div_w(PX_EPOCH * j + PX_EPOCH - 1), nr - 1);
+        const int rb = min(div_w(PXE * j + PXE - 1), nr - 1);
         return j >= E ? nr + 1 : min(rb + 2, nr + 1);
     };
 
@@ -579,9 +586,9 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
             const int gy = y0 + s0 + k;
             outside |= (gy < 0 || gy >= H) ? 1u << k : 0u;
         }
-        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13;
+        t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13 | (uint32_t)(srn(e + 3) - s2) << 17;
         t_ld = (uint32_t)max(y0 + s2, 0);                              // map row of the first row of group e + 3
-        const int nbe = PX_EPOCH * e + 16 * (mover ? 0 : wave);
+        const int nbe = PXE * e + 16 * (mover ? 0 : wave);
         const int ra = div_w(nbe), c0 = nbe - ra * W;
         t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
         t_p1 = ring_of(ra + 1) | ring_of(ra + 2) << 10 | ring_of(ra + 3) << 20;
@@ -597,54 +604,50 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
         // Every load is unconditional (lanes and rows that have nothing to fetch read a valid
         // address and get zeros afterwards): straight-line code, in which the compiler counts the
         // loads in flight exactly and waits only for the ones it uses.
-        const int m_px = 16 * mv + (lane >> 2), m_oct = lane & 3;
-        const bool m_lane = m_px < W;
-        const int m_pxc = min(m_px, W - 1);
-        const char* kv_base[2] = {(const char*)a.k + img_base + (size_t)m_pxc * px2 + m_oct * 16,
-                                  (const char*)a.v + img_base + (size_t)m_pxc * px2 + m_oct * 16};
-        // map row gy (clamped into the map) of tensor j: the lane's 8 channels.  Nothing is done to
+        // (a mover owns CG groups of 16 columns; item (j, c): tensor j, its c-th group)
+        const int m_oct = lane & 3;
+        const int m_px0 = 16 * CG * mv + (lane >> 2);                  // the lane's column in the mover's first group
+        const char* kv_base[2] = {(const char*)a.k + img_base + m_oct * 16, (const char*)a.v + img_base + m_oct * 16};
+        // map row gy (clamped into the map) of item (j, c): the lane's 8 channels.  Nothing is done to
         // the value here: whatever touches it would wait for the load.
-        auto load_item = [&](int j, int gy) {
-            return *(const uint4_t*)(kv_base[j] + (size_t)min(max(gy, 0), H - 1) * row2);
+        auto load_item = [&](int jc, int gy) {
+            const int px = min(m_px0 + 16 * (jc % CG), W - 1);
+            return *(const uint4_t*)(kv_base[jc / CG] + (size_t)min(max(gy, 0), H - 1) * row2 + (size_t)px * px2);
         };
         // (in_map false: the row lies above or below the map and is written as zeros, Fig. 2)
-        auto write_item = [&](int j, uint32_t ring_off, bool in_map, const uint4_t& r) {
+        auto write_item = [&](int jc, uint32_t ring_off, bool in_map, const uint4_t& r) {
+            const int px = m_px0 + 16 * (jc % CG);
             uint4_t h4;
 #pragma unroll
             for (int y = 0; y < 4; ++y) h4[y] = in_map ? bf16x2_to_half2(r[y]) : 0u;
-            if (m_lane) *(uint4_t*)(smem + (4 * j + m_oct) * PS + (m_px + 1) * 16 + ring_off) = h4;
+            if (px < W) *(uint4_t*)(smem + (4 * (jc / CG) + m_oct) * PS + (px + 1) * 16 + ring_off) = h4;
         };
         // q: pixels 32 mv .. 32 mv + 31 of every epoch, two items per lane
         const char* q_base = (const char*)a.q + img_base + (size_t)y0 * row2 + m_oct * 16;
         auto load_q = [&](int e, int i) {                              // (zeros past the band)
-            const int n = PX_EPOCH * e + 32 * mv + 16 * i + (lane >> 2);
+            const int n = PXE * e + 32 * mv + 16 * i + (lane >> 2);
             return *(const uint4_t*)(q_base + (size_t)min(n, npix - 1) * px2);   // (past the band: some pixel; nothing of it is stored)
         };
         auto write_q = [&](int e, int i, const uint4_t& r) {
-            *(uint4_t*)(smem + a.off_q + (e & 1) * (PX_EPOCH * 64) + ((32 * mv + 16 * i) * 4 + lane) * 16) = r;
+            *(uint4_t*)(smem + a.off_q + (e & 1) * (PXE * 64) + ((32 * mv + 16 * i) * 4 + lane) * 16) = r;
         };
-        // q of epochs 0 .. 2, group 0 (at most RPG + 2 rows), groups 1 and 2, all issued before anything is used
+        // q of epochs 0 and 1, group 0 (at most RPG + 2 rows) and group 1 are issued before anything is
+        // used; q of epoch 2 and group 2 take the place of what the start-up has consumed
         uint4_t q0[2], qa[2], qb[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) { q0[i] = load_q(0, i); qa[i] = load_q(1, i); qb[i] = load_q(2, i); }
-        uint4_t g0[RPG + 2][2], ga[RPG][2], gb[RPG][2];
+        for (int i = 0; i < 2; ++i) { q0[i] = load_q(0, i); qa[i] = load_q(1, i); }
+        uint4_t g0[RPG + 2][2 * CG], ga[RPG][2 * CG], gb[RPG][2 * CG];
 #pragma unroll
         for (int k = 0; k < RPG + 2; ++k) {
             const int gy = y0 - 1 + k;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) g0[k][j] = load_item(j, gy);
+            for (int j = 0; j < 2 * CG; ++j) g0[k][j] = load_item(j, gy);
         }
 #pragma unroll
         for (int k = 0; k < RPG; ++k) {
             const int gy = y0 + v0 + k;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) ga[k][j] = load_item(j, gy);
-        }
-#pragma unroll
-        for (int k = 0; k < RPG; ++k) {
-            const int gy = y0 + v1 + k;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) gb[k][j] = load_item(j, gy);
+            for (int j = 0; j < 2 * CG; ++j) ga[k][j] = load_item(j, gy);
         }
         block_barrier();                                               // (the head's kernels are in LDS)
         block_barrier();                                               // (the operand image is built)
@@ -653,14 +656,22 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
         for (int k = 0; k < RPG + 2; ++k)
             if (k <= v0) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) write_item(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, g0[k][j]);
+                for (int j = 0; j < 2 * CG; ++j) write_item(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, g0[k][j]);
             }
 #pragma unroll
         for (int i = 0; i < 2; ++i) write_q(0, i, q0[i]);
+#pragma unroll
+        for (int k = 0; k < RPG; ++k) {
+            const int gy = y0 + v1 + k;
+#pragma unroll
+            for (int j = 0; j < 2 * CG; ++j) gb[k][j] = load_item(j, gy);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) qb[i] = load_q(2, i);
         block_barrier();
         // epoch e: the rows of group e + 1 and q of epoch e + 1 (loaded two epochs ago) go into LDS,
         // the loads of group e + 3 and of q of epoch e + 3 take their registers
-        auto mover_epoch = [&](int e, uint4_t (&cur)[RPG][2], uint4_t (&qcur)[2]) {
+        auto mover_epoch = [&](int e, uint4_t (&cur)[RPG][2 * CG], uint4_t (&qcur)[2]) {
             const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
             const int gy0 = (int)__builtin_amdgcn_readlane(t_ld, e);
             const int cnt = (cvB >> 10) & 7;
@@ -669,13 +680,14 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
                 const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
                 if (k < cnt) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) write_item(j, pos, !((cvB >> (13 + k)) & 1u), cur[k][j]);
+                    for (int j = 0; j < 2 * CG; ++j) write_item(j, pos, !((cvB >> (13 + k)) & 1u), cur[k][j]);
                 }
             }
+            const int n_new = (int)((cvB >> 17) & 7u);                 // rows of group e + 3; loads beyond it read its first row again (cache hits)
 #pragma unroll
             for (int k = 0; k < RPG; ++k)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) cur[k][j] = load_item(j, gy0 + k);
+                for (int j = 0; j < 2 * CG; ++j) cur[k][j] = load_item(j, gy0 + (k < n_new ? k : 0));
 #pragma unroll
             for (int i = 0; i < 2; ++i) { write_q(e + 1, i, qcur[i]); qcur[i] = load_q(e + 3, i); }
             block_barrier();
@@ -695,13 +707,15 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     char* o_base = (char*)a.out + img_base + (size_t)y0 * row2 + g * 16;
     {
         constexpr int CHUNKS = HEAD_W / 4;
-        for (int c = tid; c < 2 * CHUNKS; c += THREADS) {
+        for (int c = tid; c < 2 * CHUNKS; c += PTH) {
             const float* src = (c >= CHUNKS ? a.wv + (long)m * HEAD_W + 4 * (c - CHUNKS) : a.wk + (long)m * HEAD_W + 4 * c);
             *(float4_t*)(smem + IMG_RAW_AT + c * 16) = *(const float4_t*)src;
         }
     }
     block_barrier();
-    image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), nullptr, m, a.idw, (uint32_t*)smem, tid);
+    // (image_from_raw is written for 512 threads: 256 threads run it twice)
+    for (int t512 = tid; t512 < THREADS; t512 += PTH)
+        image_from_raw<THREADS>((const float*)(smem + IMG_RAW_AT), nullptr, m, a.idw, (uint32_t*)smem, t512);
     if (tid < IMG_DWORDS - IMG_BIAS)
         ((uint32_t*)smem)[IMG_BIAS + tid] = __float_as_uint(shift_of_row(tid) >= 0 ? bias_early * 1.44269504088896341f : -INFINITY);
     block_barrier();
@@ -710,7 +724,7 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     float bias2[3];
     load_operands((const uint32_t*)smem, lane, g, A1, A2, bias2);
     block_barrier();
-    for (int idx = tid; idx < R * 16; idx += THREADS) {                // the padding columns of the ring stay zero
+    for (int idx = tid; idx < R * 16; idx += PTH) {                    // the padding columns of the ring stay zero
         const int unit = idx & 7, side = (idx >> 3) & 1, row = idx >> 4;
         *(uint4_t*)(smem + unit * PS + row * RS + (side ? W + 1 : 0) * 16) = uint4_t{0u, 0u, 0u, 0u};
     }
@@ -723,9 +737,9 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     const unsigned char* q_lds = smem + a.off_q + ((16 * wave + p) * 4 + g) * 16;
     for (int e = 0; e < E2; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
-        const int nb = PX_EPOCH * e + 16 * wave;
+        const int nb = PXE * e + 16 * wave;
         if (p2 & 256u) {
-            const uint4_t qraw = *(const uint4_t*)(q_lds + (e & 1) * (PX_EPOCH * 64));
+            const uint4_t qraw = *(const uint4_t*)(q_lds + (e & 1) * (PXE * 64));
             const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
             const int cx0 = (int)(p2 & 255u) + p;
             const bool next_row = cx0 >= W;
@@ -814,14 +828,17 @@ struct RingPlan {
     bool ok;
 };
 
-static RingPlan plan_ring(const Problem& p)
+// nw: pass waves per block (epochs of 16 nw pixels); per_cu: blocks that share a compute unit;
+// nhwc: the channels-last kernel (LDS: the ring and two q buffers only)
+static RingPlan plan_ring(const Problem& p, int nw = WAVES, int per_cu = 1, bool nhwc = false)
 {
     RingPlan r{};
     r.ok = false;
     const int W = p.W, H = p.H;
+    const int pxe = 16 * nw;
     if (W < MIN_W || W > MAX_W || (W % 8) != 0) return r;
     const long planes = (long)p.B * p.heads;
-    const int n_cu = device_cu_count();
+    const int n_cu = device_cu_count() * per_cu;
     // bands per plane: fewest rounds of blocks over the compute units, each round costing a
     // band's rows plus a start-up share
     double best = 1e300;
@@ -830,7 +847,7 @@ static RingPlan plan_ring(const Problem& p)
         const int rows = (H + nbp - 1) / nbp;
         if ((long)rows * (nbp - 1) >= H) continue;                      // every band has rows
         if (rows < 4 && nbp > 1) break;
-        if (((rows * W + 15) / 16 + WAVES - 1) / WAVES > 64) continue;  // the kernel's schedule table holds 64 epochs
+        if (((rows * W + 15) / 16 + nw - 1) / nw > 64) continue;        // the kernel's schedule table holds 64 epochs
         const long blocks = planes * nbp;
         const long rounds = (blocks + n_cu - 1) / n_cu;
         const double cost = (double)rounds * (rows + 6.0);
@@ -843,18 +860,18 @@ static RingPlan plan_ring(const Problem& p)
     // Ring depth: the rows read during epoch e and the rows written during it (group e + 1)
     // must be distinct ring rows: R >= (last row epoch e + 1 reads) - (first row epoch e reads) + 1.
     const int nr = r.rows_pb;
-    const int E = ((nr * W + 15) / 16 + WAVES - 1) / WAVES;
+    const int E = ((nr * W + 15) / 16 + nw - 1) / nw;
     if (E > 64) return r;
     auto srn = [&](int e) {
         if (e < 0) return -1;
         if (e >= E) return nr + 1;
-        int rb = (PX_EPOCH * e + PX_EPOCH - 1) / W;
+        int rb = (pxe * e + pxe - 1) / W;
         if (rb > nr - 1) rb = nr - 1;
         return rb + 2 < nr + 1 ? rb + 2 : nr + 1;
     };
     int need = 3, rpg = 2;
     for (int e = 0; e < E; ++e) {
-        const int first = (PX_EPOCH * e) / W;
+        const int first = (pxe * e) / W;
         const int cnt = srn(e + 1) - first + 1;
         if (cnt > need) need = cnt;
         if (e >= 1 && srn(e) - srn(e - 1) > rpg) rpg = srn(e) - srn(e - 1);
@@ -875,6 +892,14 @@ static RingPlan plan_ring(const Problem& p)
     r.off_out2 = r.off_out + WAVES * SLOT;
     r.lds_bytes = r.off_out2 + 2 * 32 * (2 * PX_EPOCH + 16);
     if (4 * r.PS > 65535 - 64) return r;                                // V taps are read at an immediate offset
+    if (nhwc) {
+        int bytes = 8 * r.PS;                                           // the ring (at start-up the operand image and the raw kernels) ...
+        if (bytes < IMG_RAW_AT + IMG_RAW_BYTES) bytes = IMG_RAW_AT + IMG_RAW_BYTES;
+        r.off_q = (bytes + 255) & ~255;                                 // ... and two q buffers of one epoch's pixels x 64 bytes
+        r.lds_bytes = r.off_q + 2 * pxe * 64;
+        r.ok = r.lds_bytes * per_cu <= LDS_LIMIT;
+        return r;
+    }
     r.ok = r.lds_bytes <= LDS_LIMIT;
     return r;
 }
@@ -1016,7 +1041,7 @@ bool fwd_ring_nhwc_supported(const Problem& p, bool aligned16)
 {
     if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16ring::D) return false;
     if ((long)p.H * p.W * p.C * 2 >= (1L << 31)) return false;        // 32-bit byte offsets inside a batch item
-    return f16ring::plan_ring(p).ok;
+    return f16ring::plan_ring(p, f16ring::WAVES, 1, true).ok;
 }
 
 hipError_t launch_fwd_ring_nhwc(const Problem& p, const void* q, const void* k, const void* v,
@@ -1024,7 +1049,7 @@ hipError_t launch_fwd_ring_nhwc(const Problem& p, const void* q, const void* k, 
                                 float* lse, hipStream_t st)
 {
     using namespace f16ring;
-    const RingPlan r = plan_ring(p);
+    const RingPlan r = plan_ring(p, WAVES, 1, true);
     if (!r.ok) return hipErrorInvalidValue;
     RingArgs a{};
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
@@ -1032,29 +1057,26 @@ hipError_t launch_fwd_ring_nhwc(const Problem& p, const void* q, const void* k, 
     a.wk = wk; a.wv = wv; a.bias = bias;
     a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads; a.d = D;
     a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
-    a.R = r.R; a.RS = r.RS; a.PS = r.PS;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_q = r.off_q;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    int lds_bytes = 8 * r.PS;                                          // the ring (at start-up the operand image and the raw kernels) ...
-    if (lds_bytes < IMG_RAW_AT + IMG_RAW_BYTES) lds_bytes = IMG_RAW_AT + IMG_RAW_BYTES;
-    a.off_q = (lds_bytes + 255) & ~255;                                // ... and two q buffers of 128 pixels x 64 bytes
-    lds_bytes = a.off_q + 2 * PX_EPOCH * 64;
     static LdsOptIn opt_in;
-    hipError_t e = opt_in.ensure({(const void*)fwd16_ring_nhwc_kernel<2, false>, (const void*)fwd16_ring_nhwc_kernel<2, true>,
-                                  (const void*)fwd16_ring_nhwc_kernel<3, false>, (const void*)fwd16_ring_nhwc_kernel<3, true>,
-                                  (const void*)fwd16_ring_nhwc_kernel<4, false>, (const void*)fwd16_ring_nhwc_kernel<4, true>}, LDS_LIMIT);
+#define SLIDE_NHWC_KERNELS(RPGV)                                                                                     \
+    (const void*)fwd16_ring_nhwc_kernel<RPGV, false, 8, 4>, (const void*)fwd16_ring_nhwc_kernel<RPGV, true, 8, 4>
+    hipError_t e = opt_in.ensure({SLIDE_NHWC_KERNELS(2), SLIDE_NHWC_KERNELS(3), SLIDE_NHWC_KERNELS(4)}, LDS_LIMIT);
+#undef SLIDE_NHWC_KERNELS
     if (e != hipSuccess) return e;
-    const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
-#define SLIDE_NHWC_LAUNCH(RPGV)                                                                                      \
+    const dim3 grid((unsigned)r.n_blocks);
+#define SLIDE_NHWC_LAUNCH(RPGV, NWV, NMV)                                                                            \
     do {                                                                                                             \
-        if (lse) hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, true>), grid, block12, (size_t)lds_bytes, st, a);  \
-        else     hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, false>), grid, block12, (size_t)lds_bytes, st, a); \
+        if (lse) hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, true, NWV, NMV>), grid, dim3((NWV + NMV) * 64), (size_t)r.lds_bytes, st, a);  \
+        else     hipLaunchKernelGGL((fwd16_ring_nhwc_kernel<RPGV, false, NWV, NMV>), grid, dim3((NWV + NMV) * 64), (size_t)r.lds_bytes, st, a); \
     } while (0)
-    if (r.rpg == 2) SLIDE_NHWC_LAUNCH(2);
-    else if (r.rpg == 3) SLIDE_NHWC_LAUNCH(3);
-    else SLIDE_NHWC_LAUNCH(4);
+    if (r.rpg == 2) SLIDE_NHWC_LAUNCH(2, 8, 4);
+    else if (r.rpg == 3) SLIDE_NHWC_LAUNCH(3, 8, 4);
+    else SLIDE_NHWC_LAUNCH(4, 8, 4);
 #undef SLIDE_NHWC_LAUNCH
     return hipGetLastError();
 }
