@@ -77,7 +77,7 @@ struct RingArgs {
 // tap, and every lane holds all nine logits of its pixel.
 constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
 
-template <int RPG, bool LSE, bool PLAIN>
+template <int RPG, bool LSE, bool PLAIN, int DH>
 __global__ void __launch_bounds__(THREADS12)
 fwd16_ring_kernel(const RingArgs a)
 {
@@ -107,8 +107,8 @@ fwd16_ring_kernel(const RingArgs a)
     const int y0 = part * a.rows_pb;
     const int nr = min(a.rows_pb, H - y0);
     const long HW = (long)H * W;
-    const long head_base = ((long)b * a.C + (long)m * a.d) * HW;   // element offset of channel 0 of the head
-    const bool oct_empty = mover && 8 * mv >= a.d;                   // this mover's octet does not exist
+    const long head_base = ((long)b * a.C + (long)m * DH) * HW;   // element offset of channel 0 of the head
+    const bool oct_empty = DH < D && mover && 8 * mv >= DH;         // this mover's octet does not exist
     const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
 
     auto div_w = [&](int x) { return (int)__umulhi((uint32_t)x, a.magic_w); };
@@ -166,7 +166,7 @@ fwd16_ring_kernel(const RingArgs a)
         const bool real = n_first < npix;
         const int nf = real ? n_first : 0;
         const int off = real ? a.off_q + pw * (3 * SLOT) + qo : a.off_dummy;
-        if (nf + 8 * (lane & 1) < npix && (lane >> 1) < a.d) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
+        if (nf + 8 * (lane & 1) < npix && (lane >> 1) < DH) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
     };
 
     // ---- start-up.  The first access to a tensor takes microseconds (cold translation): the
@@ -182,13 +182,13 @@ fwd16_ring_kernel(const RingArgs a)
         // 2 x 32 x 81 floats = 1296 chunks of 16 bytes, K kernels then V kernels; with 24 channels
         // per head the chunks of channels 24 .. 31 are zeros
         constexpr int CHUNKS = HEAD_W / 4;
-        const int head_w = a.d * S * S, chunks_d = head_w / 4;
+        const int head_w = DH * S * S, chunks_d = head_w / 4;
         for (int L = wave; L * 64 < 2 * CHUNKS; L += WAVES) {
             const int c = L * 64 + lane;
             const int cc = c >= CHUNKS ? c - CHUNKS : c;
             const float* src = (c >= CHUNKS ? a.wv : a.wk) + (long)m * head_w + 4 * cc;
             if (c < 2 * CHUNKS) {
-                if (cc < chunks_d) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
+                if (DH == D || cc < chunks_d) load_to_lds_addr(src, lds0 + IMG_RAW_AT + L * 1024);
                 else *(uint4_t*)(smem + IMG_RAW_AT + c * 16) = uint4_t{0u, 0u, 0u, 0u};
             }
         }
@@ -238,14 +238,14 @@ fwd16_ring_kernel(const RingArgs a)
     // q slots: the rows of channels the head does not have stay zero (the first two slots of every
     // pass wave here; the third, which holds start-up rows first, by its mover below)
     auto zero_q_rows = [&](int idx0, int n, int stride, int slot_lo, int slots_per_wave) {
-        const int per_slot = (D - a.d) * 2;                            // 16-byte chunks per slot
+        constexpr int per_slot = DH < D ? (D - DH) * 2 : 1;             // 16-byte chunks per slot
         for (int idx = idx0; idx < n * per_slot; idx += stride) {
             const int sl = idx / per_slot, ch = idx - sl * per_slot;
             const int pw = sl / slots_per_wave, s3 = slot_lo + sl % slots_per_wave;
-            *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + s3 * SLOT + a.d * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
+            *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + s3 * SLOT + DH * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
         }
     };
-    if (a.d < D) zero_q_rows(tid, 2 * WAVES, THREADS12, 0, 2);
+    if (DH < D) zero_q_rows(tid, 2 * WAVES, THREADS12, 0, 2);
     constexpr int NL = 2 * RPG + 2;                                    // loads of a mover per epoch
     if (mover) {
         wait_vmem(n_after_g0);                                         // group 0 has landed
@@ -255,11 +255,11 @@ fwd16_ring_kernel(const RingArgs a)
             for (int j = 0; j < 2; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
-        if (a.d < D) {                                                 // third q slots of pass waves 2 mv, 2 mv + 1
-            const int per_slot = (D - a.d) * 2;
+        if (DH < D) {                                                 // third q slots of pass waves 2 mv, 2 mv + 1
+            constexpr int per_slot = DH < D ? (D - DH) * 2 : 1;
             if (lane < 2 * per_slot) {
                 const int pw = 2 * mv + lane / per_slot, ch = lane % per_slot;
-                *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + 2 * SLOT + a.d * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
+                *(uint4_t*)(smem + a.off_q + pw * (3 * SLOT) + 2 * SLOT + DH * 32 + ch * 16) = uint4_t{0u, 0u, 0u, 0u};
             }
         }
         // group 2 into set 0, as a full round of NL loads
@@ -319,12 +319,12 @@ fwd16_ring_kernel(const RingArgs a)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = 8 * mv + 4 * i + (lane >> 4);
-            if (n0 < npix && c < a.d) val[i] = *(const uint4_t*)(smem + rd + c * OUT_ROW + (lane & 15) * 16);
+            if (n0 < npix && (DH == D || c < DH)) val[i] = *(const uint4_t*)(smem + rd + c * OUT_ROW + (lane & 15) * 16);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = 8 * mv + 4 * i + (lane >> 4);
-            if (n0 < npix && c < a.d) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
+            if (n0 < npix && (DH == D || c < DH)) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
         }
     };
 
@@ -1009,15 +1009,23 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)a.d);
     a.idw = p.two_branch ? 1.0f : 0.0f;
     static LdsOptIn opt_in;
-#define SLIDE_RING_KERNELS(RPGV)                                                                                    \
-    (const void*)fwd16_ring_kernel<RPGV, false, false>, (const void*)fwd16_ring_kernel<RPGV, true, false>,          \
-    (const void*)fwd16_ring_kernel<RPGV, false, true>, (const void*)fwd16_ring_kernel<RPGV, true, true>
+#define SLIDE_RING_KERNELS2(RPGV, DHV)                                                                              \
+    (const void*)fwd16_ring_kernel<RPGV, false, false, DHV>, (const void*)fwd16_ring_kernel<RPGV, true, false, DHV>, \
+    (const void*)fwd16_ring_kernel<RPGV, false, true, DHV>, (const void*)fwd16_ring_kernel<RPGV, true, true, DHV>
+#define SLIDE_RING_KERNELS(RPGV) SLIDE_RING_KERNELS2(RPGV, 32), SLIDE_RING_KERNELS2(RPGV, 24)
     hipError_t e = opt_in.ensure({SLIDE_RING_KERNELS(2), SLIDE_RING_KERNELS(3), SLIDE_RING_KERNELS(4)}, LDS_LIMIT);
 #undef SLIDE_RING_KERNELS
+#undef SLIDE_RING_KERNELS2
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
+    // (the head size is a compile-time constant of the kernel: 32 pays nothing for the empty octet of 24)
+#define SLIDE_RING_LAUNCH4(RPGV, LSEV, PLAINV, DHV)                                                                 \
+    hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, PLAINV, DHV>), grid, block12, (size_t)r.lds_bytes, st, a)
 #define SLIDE_RING_LAUNCH3(RPGV, LSEV, PLAINV)                                                                      \
-    hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, LSEV, PLAINV>), grid, block12, (size_t)r.lds_bytes, st, a)
+    do {                                                                                                            \
+        if (a.d == 24) SLIDE_RING_LAUNCH4(RPGV, LSEV, PLAINV, 24);                                                  \
+        else           SLIDE_RING_LAUNCH4(RPGV, LSEV, PLAINV, 32);                                                  \
+    } while (0)
 #define SLIDE_RING_LAUNCH2(RPGV, LSEV)                                                                              \
     do {                                                                                                            \
         if (plain) SLIDE_RING_LAUNCH3(RPGV, LSEV, true);                                                            \
@@ -1028,11 +1036,13 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
         if (lse) SLIDE_RING_LAUNCH2(RPGV, true);                                                                    \
         else     SLIDE_RING_LAUNCH2(RPGV, false);                                                                   \
     } while (0)
+    if (a.d != 24 && a.d != 32) return hipErrorInvalidValue;
     if (r.rpg == 2) SLIDE_RING_LAUNCH(2);
     else if (r.rpg == 3) SLIDE_RING_LAUNCH(3);
     else SLIDE_RING_LAUNCH(4);
 #undef SLIDE_RING_LAUNCH2
 #undef SLIDE_RING_LAUNCH3
+#undef SLIDE_RING_LAUNCH4
 #undef SLIDE_RING_LAUNCH
     return hipGetLastError();
 }
