@@ -329,6 +329,10 @@ fwd16_ring_kernel(const RingArgs a)
     };
 
     if (mover) {
+        // A mover has few instructions per epoch, each waiting for the one before (LDS read, store,
+        // load, conversion): they go ahead of the two pass waves on its SIMD, or the pass waves
+        // finish their epoch first and then wait for the mover at the barrier.
+        __builtin_amdgcn_s_setprio(3);
         int set_rd = RPG * SLOT;                                       // offset of the set that holds group e + 1
         for (int e = 0; e < E; ++e) {
             const uint32_t cvA = __builtin_amdgcn_readlane(t_cvA, e), cvB = __builtin_amdgcn_readlane(t_cvB, e);
@@ -600,6 +604,7 @@ fwd16_ring_nhwc_kernel(const RingArgs a)
     // The two kinds of waves part here for good (their registers never coexist); both pass the same
     // four start-up barriers and one barrier per epoch.
     if (mover) {
+        __builtin_amdgcn_s_setprio(3);                                 // (as in fwd16_ring_kernel: the movers go first)
         // columns 16 mv .. 16 mv + 15, lane = pixel (lane / 4) x octet (lane % 4)
         // Every load is unconditional (lanes and rows that have nothing to fetch read a valid
         // address and get zeros afterwards): straight-line code, in which the compiler counts the
