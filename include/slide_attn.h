@@ -196,6 +196,18 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
                            int aligned16);
 
 /*
+ * The kernels slide_attn_bwd would run, for tests that must know which code ran: 0 = invalid
+ * arguments, 10 = general kernels (float32 vector arithmetic), 20 = tiled matrix-core kernels
+ * (bf16, d = 32, ksize 3; the kernel-gradient kernel also needs W % 8 == 0, else the general
+ * one takes that part), 21 = the same with the streaming kernel for the key and value
+ * gradients (maps 32..56 columns wide, W % 8 == 0, bands and rings that fit the LDS).
+ * aligned16: whether every activation, gradient and workspace pointer is 16-byte aligned.
+ * Launches nothing; reads the compute-unit count of the current device (256 if there is none).
+ */
+int slide_attn_bwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,
+                           int aligned16);
+
+/*
  * Plain-shift forward: local attention over the ksize x ksize window whose keys and values
  * are the fixed shifts alone (Sec. 4.2: Eq. 9 rewritten as one-hot depthwise kernels in
  * Eq. 10-13; the "without deformed shifting" stage of Fig. 1 and Fig. 5).  Computes what

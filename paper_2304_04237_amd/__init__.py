@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     slide_attn_fwd_shift,
     slide_attn_fwd_traffic_probe,
     slide_attn_fwd_variant,
+    slide_attn_bwd_variant,
     slide_attn_workspace_bytes,
     slide_reparam,
     slide_status_string,

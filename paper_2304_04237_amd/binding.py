@@ -46,6 +46,8 @@ def load_library():
     lib.slide_attn_fwd_path.argtypes = [i] * 7
     lib.slide_attn_fwd_variant.restype = i
     lib.slide_attn_fwd_variant.argtypes = [i] * 8
+    lib.slide_attn_bwd_variant.restype = i
+    lib.slide_attn_bwd_variant.argtypes = [i] * 8
     lib.slide_attn_fwd.restype = i
     lib.slide_attn_fwd.argtypes = [_vp] * 8 + [i] * 7 + [_vp, sz, _vp]
     lib.slide_attn_fwd_noalloc.restype = i
@@ -112,6 +114,11 @@ def slide_attn_fwd_path(B, H, W, C, heads, ksize, dtype):
 def slide_attn_fwd_variant(B, H, W, C, heads, ksize, dtype, aligned16=True):
     code = dtype if isinstance(dtype, int) else (SLIDE_F32 if dtype == torch.float32 else SLIDE_BF16)
     return int(load_library().slide_attn_fwd_variant(B, H, W, C, heads, ksize, code, int(bool(aligned16))))
+
+
+def slide_attn_bwd_variant(B, H, W, C, heads, ksize, dtype, aligned16=True):
+    code = dtype if isinstance(dtype, int) else (SLIDE_F32 if dtype == torch.float32 else SLIDE_BF16)
+    return int(load_library().slide_attn_bwd_variant(B, H, W, C, heads, ksize, code, int(bool(aligned16))))
 
 
 def _check_params(q, wk, wv, bias, heads, ksize):

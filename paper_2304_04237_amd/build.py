@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslide_attn.so")
-SOURCES = ["slide_api.hip", "slide_generic.hip", "slide_fwd16.hip", "slide_fwd16_ring.hip", "slide_bwd_dw.hip", "slide_bwd16.hip", "slide_fwd16_k5.hip"]
+SOURCES = ["slide_api.hip", "slide_generic.hip", "slide_fwd16.hip", "slide_fwd16_ring.hip", "slide_bwd_dw.hip", "slide_bwd16.hip", "slide_bwd16_ring.hip", "slide_fwd16_k5.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

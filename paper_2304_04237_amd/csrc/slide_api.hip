@@ -91,6 +91,14 @@ extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int
     return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
+extern "C" int slide_attn_bwd_variant(int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                      int aligned16)
+{
+    if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    return slide::bwd_variant(p, aligned16 != 0);
+}
+
 // ---- scratch of the entry point that allocates nothing ---------------------------------
 // One array per GPU (every device that loads the library holds its own copy until the process
 // ends).  In host code the array's name is only a handle for hipGetSymbolAddress: kernels and

@@ -30,6 +30,7 @@ constexpr int REC_BYTES = 32;                       // 16 halves per halo pixel 
 // Row i of product (t, j) is channel 8*(i/4) + 4j + (i%4); dword y of lane (i, g) holds the
 // merged weights (one-hot shift included) for the shifts of operand slots 4g+2y and 4g+2y+1.
 constexpr int IMG_DWORDS = 2 * S * 2 * 64 * 2;      // 4608
+static_assert(IMG_DWORDS == BWD_DKDV_IMG_DWORDS, "the streaming dk/dv kernel reads the same image");
 
 // idw = 1: wk, wv are the learned kernels of the two-branch form and the fixed shift path
 // (weight 1 where shift and tap coincide) is added here; 0: merged kernels

@@ -835,9 +835,14 @@ struct RingPlan {
 
 // nw: pass waves per block (epochs of 16 nw pixels); per_cu: blocks that share a compute unit;
 // nhwc: the channels-last kernel (LDS: the ring and two q buffers only)
-static RingPlan plan_ring(const Problem& p, int nw = WAVES, int per_cu = 1, bool nhwc = false)
+}  // namespace f16ring
+
+// Bands of rows per plane, ring depth and rows per group of a streaming kernel with nw pass
+// waves per block (epochs of 16 nw pixels) and per_cu blocks per compute unit.
+RingRows plan_ring_rows(const Problem& p, int nw, int per_cu)
 {
-    RingPlan r{};
+    using namespace f16ring;
+    RingRows r{};
     r.ok = false;
     const int W = p.W, H = p.H;
     const int pxe = 16 * nw;
@@ -884,6 +889,24 @@ static RingPlan plan_ring(const Problem& p, int nw = WAVES, int per_cu = 1, bool
     if (rpg < srn(0) - 1) rpg = srn(0) - 1;                             // group 0 (srn(0) + 1 rows) fits the rpg + 2 start-up slots
     if (rpg > 4) return r;
     if (need < srn(0) + 2) need = srn(0) + 2;
+    r.rpg = rpg;
+    r.R = need;
+    r.ok = true;
+    return r;
+}
+
+namespace f16ring {
+
+static RingPlan plan_ring(const Problem& p, int nw = WAVES, int per_cu = 1, bool nhwc = false)
+{
+    RingPlan r{};
+    r.ok = false;
+    const RingRows rr = plan_ring_rows(p, nw, per_cu);
+    if (!rr.ok) return r;
+    const int W = p.W;
+    const int pxe = 16 * nw;
+    const int rpg = rr.rpg, need = rr.R;
+    r.nbp = rr.nbp; r.rows_pb = rr.rows_pb; r.n_blocks = rr.n_blocks;
     r.rpg = rpg;
     r.R = need;
     r.RS = (W + 2) * 16;

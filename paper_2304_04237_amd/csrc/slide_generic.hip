@@ -571,7 +571,11 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     if (e != hipSuccess) return e;
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p);
-        e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
+        // (the streaming kernel where it runs: maps of 32..56 columns, a and dl as halves)
+        if (half_ws && fwd_ring_enabled() && bwd_dkdv_ring_supported(p, aligned16({dk, dv})))
+            e = launch_bwd_dkdv_ring(p, dout, q, attn_ws, dl_ws, dk, dv, image_ws, st);
+        else
+            e = launch_bwd_dkdv_mfma(p, dout, q, wk, wv, attn_ws, dl_ws, half_ws, dk, dv, image_ws, st);
     } else {
         if (few_pixels(p)) {
             dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
@@ -605,6 +609,14 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
         hipLaunchKernelGGL(bwd_dbias_kernel, dim3((unsigned)(p.heads * S)), dim3(256), 0, st,
                            dl_ws, dbias, p.B, p.plane(), p.heads, S, p.accumulate);
     return hipGetLastError();
+}
+
+int bwd_variant(const Problem& p, bool all_aligned16)
+{
+    const bool fast = bwd_dkdv_mfma_supported(p) && all_aligned16;
+    if (!fast) return 10;
+    const bool half_ws = bwd_dw_mfma_supported(p);
+    return (half_ws && fwd_ring_enabled() && bwd_dkdv_ring_supported(p, all_aligned16)) ? 21 : 20;
 }
 
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,

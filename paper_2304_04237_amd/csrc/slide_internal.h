@@ -57,6 +57,10 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
+// which kernels launch_bwd_generic runs: 10 general, 20 tiled matrix-core kernels, 21 the same
+// with the streaming dk/dv kernel; aligned16: every pointer is 16-byte aligned
+int bwd_variant(const Problem& p, bool aligned16);
+
 // adds n_chunks partial sums per entry in a fixed order; bias_partial [n_chunks][nbias] -> dbias
 // in the same launch (dbias may be null)
 hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, long side, int n_chunks,
@@ -83,6 +87,17 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
                                 const void* attn_ws, const void* dl_ws, bool half_ws,
                                 void* dk, void* dv, void* image_ws, hipStream_t st);
 
+// dwords per head of the dk/dv kernels' operand image (side x tap x channel half x lane x 2)
+constexpr int BWD_DKDV_IMG_DWORDS = 2 * 9 * 2 * 64 * 2;
+
+// the same gradients by the streaming kernel (slide_bwd16_ring.hip): bf16, d == 32, ksize 3,
+// 32 <= W <= 56, W % 8 == 0, every pointer 16-byte aligned, a and dl as halves; reads the operand
+// image that launch_bwd_pixel_mfma prepared
+bool bwd_dkdv_ring_supported(const Problem& p, bool aligned16);
+hipError_t launch_bwd_dkdv_ring(const Problem& p, const void* dout, const void* q,
+                                const void* attn_ws, const void* dl_ws, void* dk, void* dv,
+                                const void* image_ws, hipStream_t st);
+
 // ---- matrix-core forward (slide_fwd16.hip): bf16, d == 32, ksize 3
 bool fwd_mfma_supported(const Problem& p);
 size_t fwd_mfma_workspace_bytes(const Problem& p);     // prepared weight operands, per head
@@ -101,6 +116,12 @@ bool fwd_ring_enabled();                               // false if the environme
 hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const void* v,
                            const float* wk, const float* wv, const float* bias, void* out,
                            float* lse, bool plain, hipStream_t st);
+
+// bands of rows per plane (nbp bands of rows_pb rows, n_blocks blocks in all), ring depth R and
+// most new rows per epoch rpg of a streaming kernel with nw pass waves per block and per_cu
+// blocks per compute unit; !ok: the map is not one a streaming kernel takes
+struct RingRows { int nbp, rows_pb, n_blocks, R, rpg; bool ok; };
+RingRows plan_ring_rows(const Problem& p, int nw, int per_cu);
 
 // the streaming kernel for channels-last activations (Problem::nhwc): bf16, d == 32, ksize 3,
 // 32 <= W <= 64, W % 8 == 0, every pointer 16-byte aligned; needs no workspace
