@@ -323,13 +323,17 @@ struct PixelArgs {
 __device__ __forceinline__ void window_dots(const uint4_t (&yd)[S], const half2_t (&xs)[4],
                                             const half8_t (&A)[S], float4_t& acc)
 {
+    // (two accumulation chains, even and odd taps: a product does not wait for the one before it)
+    float4_t accb = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int t = 0; t < S; ++t) {
         uint4_t bb;
 #pragma unroll
         for (int y = 0; y < 4; ++y) bb[y] = as_dword(xs[y] * as_half2(yd[t][y]));
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
+        if (t & 1) accb = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], __builtin_bit_cast(half8_t, bb), accb, 0, 0, 0);
+        else       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A[t], __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
     }
+    acc += accb;
 }
 // 8 channels as bf16 patterns (one per dword) -> halves divided by 16
 __device__ __forceinline__ void raw_to_halves(const uint32_t (&raw)[8], half2_t (&sc)[4])
@@ -492,34 +496,26 @@ bwd_pixel_kernel16(const PixelArgs a)
         b2[0] = pack_half(dl[0], dl[1]);
         b2[1] = pack_half(dl[2], 0.0f);
         const half4_t B2 = __builtin_bit_cast(half4_t, b2);
+        // the 18 products, each two products ahead of the multiply-adds that use it (product uu < 16:
+        // channel uu % 8 of the lane's octet, taps 4 (uu / 8) .. + 3; 16, 17: tap 8 of channels 0..3, 4..7)
         float o[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float4_t w0 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[e], B2, c0, 0, 0, 0);
-            const float4_t w1 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[8 + e], B2, c1, 0, 0, 0);
-            float s0 = 0.0f;
+        for (int e = 0; e < 8; ++e) o[e] = 0.0f;
+        float4_t w[2 * S];
+        constexpr int AHEAD = 2;
+#pragma unroll
+        for (int uu = 0; uu < AHEAD; ++uu) w[uu] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[uu], B2, c0, 0, 0, 0);
+#pragma unroll
+        for (int uu = 0; uu < 2 * S; ++uu) {
+            if (uu + AHEAD < 2 * S) w[uu + AHEAD] = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[uu + AHEAD], B2, c1, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                s0 = fmaf(w0[r], (float)as_half2(xd[r][e >> 1])[e & 1], s0);
-                s0 = fmaf(w1[r], (float)as_half2(xd[4 + r][e >> 1])[e & 1], s0);
+                const int e = uu < 16 ? (uu & 7) : 4 * (uu - 16) + r;
+                const int tap = uu < 16 ? 4 * (uu >> 3) + r : 8;
+                o[e] = fmaf(w[uu][r], (float)as_half2(xd[tap][e >> 1])[e & 1], o[e]);
             }
-            o[e] = s0;
-            if ((e & 1) == 1) {
-                asm volatile("" : "+v"(o[e - 1]), "+v"(o[e]));         // bound the live MFMA results
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        {
-            const float4_t c8 = c0;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const float4_t w8 = __builtin_amdgcn_mfma_f32_16x16x16f16(A2k[16 + j], B2, c8, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = 4 * j + r;
-                    o[e] = fmaf(w8[r], (float)as_half2(xd[8][e >> 1])[e & 1], o[e]);
-                }
-            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (valid) {
 #pragma unroll
