@@ -199,8 +199,10 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
  * The kernels slide_attn_bwd would run, for tests that must know which code ran: 0 = invalid
  * arguments, 10 = general kernels (float32 vector arithmetic), 20 = tiled matrix-core kernels
  * (bf16, d = 32, ksize 3; the kernel-gradient kernel also needs W % 8 == 0, else the general
- * one takes that part), 21 = the same with the streaming kernel for the key and value
- * gradients (maps 32..56 columns wide, W % 8 == 0, bands and rings that fit the LDS).
+ * one takes that part); 1 is added where the key and value gradients run in the streaming
+ * kernel (maps 32..56 columns wide, W % 8 == 0, bands and rings that fit the LDS), 2 where the
+ * per-pixel part (attention recompute, logit and query gradients) does (maps 32..64 columns
+ * wide): 21, 22, 23.
  * aligned16: whether every activation, gradient and workspace pointer is 16-byte aligned.
  * Launches nothing; reads the compute-unit count of the current device (256 if there is none).
  */

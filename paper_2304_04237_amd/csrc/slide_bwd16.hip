@@ -542,13 +542,18 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p)
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 void* dkdv_image_ws, hipStream_t st)
+                                 void* dkdv_image_ws, bool streaming, hipStream_t st)
 {
     using namespace b16path;
     const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
     uint32_t* image = (uint32_t*)image_ws;
     hipLaunchKernelGGL(prep_bwd_weights_kernel, dim3(S, (unsigned)p.heads, 2), dim3(256), 0, st,
                        wk, wv, bias, image, (uint32_t*)dkdv_image_ws, p.two_branch ? 1.0f : 0.0f);
+    if (streaming) {
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+        return launch_bwd_pixel_ring(p, dout, q, k, v, dq, attn_ws, dl_ws, image, st);
+    }
     PixelArgs a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q;
     a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;

@@ -554,8 +554,10 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
     if (fast) {
         void* image_ws = (char*)partial + bwd_partial_bytes(p) + bwd_dkdv_mfma_image_bytes(p);
         void* dkdv_image_ws = (char*)partial + bwd_partial_bytes(p);
+        // (the streaming kernel where it runs: maps of 32..64 columns, a and dl as halves)
+        const bool streaming = half_ws && fwd_ring_enabled() && bwd_pixel_ring_supported(p, aligned16({dq}));
         e = launch_bwd_pixel_mfma(p, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, half_ws, image_ws,
-                                  dkdv_image_ws, st);
+                                  dkdv_image_ws, streaming, st);
     } else {
         if (few_pixels(p)) {
             dim3 grid8((unsigned)((p.plane() * 8 + 255) / 256), (unsigned)p.heads, (unsigned)p.B);
@@ -616,7 +618,8 @@ int bwd_variant(const Problem& p, bool all_aligned16)
     const bool fast = bwd_dkdv_mfma_supported(p) && all_aligned16;
     if (!fast) return 10;
     const bool half_ws = bwd_dw_mfma_supported(p);
-    return (half_ws && fwd_ring_enabled() && bwd_dkdv_ring_supported(p, all_aligned16)) ? 21 : 20;
+    if (!half_ws || !fwd_ring_enabled()) return 20;
+    return 20 + (bwd_dkdv_ring_supported(p, all_aligned16) ? 1 : 0) + (bwd_pixel_ring_supported(p, all_aligned16) ? 2 : 0);
 }
 
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,

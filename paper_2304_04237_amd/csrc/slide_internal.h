@@ -57,8 +57,9 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
-// which kernels launch_bwd_generic runs: 10 general, 20 tiled matrix-core kernels, 21 the same
-// with the streaming dk/dv kernel; aligned16: every pointer is 16-byte aligned
+// which kernels launch_bwd_generic runs: 10 general, 20 tiled matrix-core kernels, + 1 with the
+// streaming dk/dv kernel, + 2 with the streaming per-pixel kernel; aligned16: every pointer is
+// 16-byte aligned
 int bwd_variant(const Problem& p, bool aligned16);
 
 // adds n_chunks partial sums per entry in a fixed order; bias_partial [n_chunks][nbias] -> dbias
@@ -81,7 +82,7 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p);
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 void* dkdv_image_ws, hipStream_t st);   // also prepares the dk/dv kernel's operand image
+                                 void* dkdv_image_ws, bool streaming, hipStream_t st);   // also prepares the dk/dv kernel's operand image; streaming: launch_bwd_pixel_ring does the rest
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
                                 const void* attn_ws, const void* dl_ws, bool half_ws,
@@ -89,6 +90,19 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
 
 // dwords per head of the dk/dv kernels' operand image (side x tap x channel half x lane x 2)
 constexpr int BWD_DKDV_IMG_DWORDS = 2 * 9 * 2 * 64 * 2;
+
+// dword offsets inside the per-pixel backward kernels' per-head operand image: merged K kernel
+// and merged V kernel as logit-side operands (tap x lane x 4), merged K kernel as value-side
+// operand (product x lane x 2), 16 bias words; dwords per head
+constexpr int BWD_PX_A1K = 0, BWD_PX_A1V = 2304, BWD_PX_A2K = 4608, BWD_PX_BIAS = 6912, BWD_PX_IMG_DWORDS = 6928;
+
+// the per-pixel backward by the streaming kernel (slide_bwd16_ring.hip): bf16, d == 32, ksize 3,
+// 32 <= W <= 64, W % 8 == 0, every pointer 16-byte aligned, a and dl written as halves; reads the
+// operand image that launch_bwd_pixel_mfma prepares
+bool bwd_pixel_ring_supported(const Problem& p, bool aligned16);
+hipError_t launch_bwd_pixel_ring(const Problem& p, const void* dout, const void* q, const void* k,
+                                 const void* v, void* dq, void* attn_ws, void* dl_ws,
+                                 const void* image_ws, hipStream_t st);
 
 // the same gradients by the streaming kernel (slide_bwd16_ring.hip): bf16, d == 32, ksize 3,
 // 32 <= W <= 56, W % 8 == 0, every pointer 16-byte aligned, a and dl as halves; reads the operand
