@@ -1,6 +1,9 @@
-// Streaming matrix-core kernel for the key and value gradients of Slide Attention on gfx950
-// (bf16 activations, head size 32, 3x3 window, maps of 32..56 columns, a multiple of 8, rows
-// and pointers 16-byte aligned).  The paper gives no backward; this is the chain rule through
+// Streaming matrix-core kernels of the backward of Slide Attention on gfx950 (bf16 activations,
+// head size 32, 3x3 window, rows and pointers 16-byte aligned): the key and value gradients
+// (maps of 32..56 columns, a multiple of 8; first part of this file) and the per-pixel part,
+// attention recompute, logit and query gradients (maps of 32..64 columns; second part).
+//
+// Key and value gradients.  The paper gives no backward; this is the chain rule through
 // the operator of Sec. 4.1-4.3, in the gather form of slide_bwd16.hip:
 //     dk[c,y] = scale * sum_u q[c,p']  * sum_s W~k[c,s,t] dl[p',s]
 //     dv[c,y] =         sum_u dO[c,p'] * sum_s W~v[c,s,t]  a[p',s]      p' = y + off(u), t = 8 - u

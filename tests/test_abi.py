@@ -186,6 +186,22 @@ def test_forward_variant_selection(lib):
     assert v(256, 2, 64, 64, 2, 3, 1, 1) == 24                     # two-row planes: streaming kernel
 
 
+def test_backward_variant_selection(lib):
+    """Which kernels serve the backward of a problem (256 compute units assumed when there is
+    no device)."""
+    v = lib.slide_attn_bwd_variant
+    assert v(1, 14, 14, 64, 3, 3, 0, 1) == 0                       # invalid
+    assert v(1, 14, 14, 64, 2, 3, 0, 1) == 10                      # float32: general kernels
+    assert v(64, 28, 28, 128, 4, 5, 1, 1) == 10                    # 5x5
+    assert v(128, 56, 56, 64, 2, 3, 1, 1) == 23                    # stage-1 training: both streaming kernels
+    assert v(128, 56, 56, 64, 2, 3, 1, 0) == 10                    # unaligned pointers: general kernels
+    assert v(2, 33, 32, 64, 2, 3, 1, 1) == 22                      # too narrow for the dk/dv kernel's record rings
+    assert v(3, 40, 64, 32, 1, 3, 1, 1) == 22                      # 64 columns: a dl / a row is more than one load
+    assert v(2, 13, 72, 32, 1, 3, 1, 1) == 20                      # wider than 64: tiled kernels
+    assert v(50, 20, 40, 96, 3, 3, 1, 1) == 20                     # bands of 20 rows of 40 columns need too deep a ring
+    assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0: tiled kernels, general kernel-gradient part
+
+
 def test_binding_rejects_mismatched_parameter_shapes(lib):
     """Shape mistakes are reported by the binding; they must not reach a kernel."""
     import torch

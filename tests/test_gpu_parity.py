@@ -216,6 +216,29 @@ def test_backward_matches_oracle(shape):
         assert torch.equal(a, b)
 
 
+def test_backward_unaligned_gradient_buffers_take_the_tiled_kernels():
+    """dq, dk, dv that start 2 bytes into an allocation: the streaming kernels, which store 16
+    bytes per lane, are not used; the results are those of the aligned call."""
+    B, H, W, C, heads, ksize = 3, 12, 56, 64, 2, 3
+    d, g, n = gpu_problem(B, H, W, C, heads, ksize, "bf16", seed=77)
+    assert sa.slide_attn_bwd_variant(B, H, W, C, heads, ksize, torch.bfloat16, True) == 23
+    ref = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize)
+    numel = B * C * H * W
+    views = []
+    for _ in range(3):
+        buf = torch.zeros(numel + 8, dtype=torch.bfloat16, device="cuda:0")
+        view = buf[1:1 + numel].view(B, C, H, W)
+        assert view.data_ptr() % 16 != 0
+        views.append(view)
+    outs = (views[0], views[1], views[2], torch.empty_like(g["wk"]), torch.empty_like(g["wv"]), torch.empty_like(g["bias"]))
+    got = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, ksize, outputs=outs)
+    torch.cuda.synchronize()
+    want = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, ksize)
+    for name, a, b, w in zip(GRAD_NAMES, got, ref, want):
+        check(name, "bf16", a, w)
+        check(name, "bf16", b, w)
+
+
 TWO_BRANCH_SHAPES = [
     # B, H, W, C, heads, ksize, dtype
     (1, 14, 14, 64, 2, 3, "f32"),        # general kernels
@@ -223,6 +246,7 @@ TWO_BRANCH_SHAPES = [
     (2, 9, 21, 64, 2, 3, "bf16"),        # matrix-core forward, one tile per block; float32 workspace
     (2, 31, 24, 64, 2, 3, "bf16"),       # all backward kernels on the matrix cores
     (2, 17, 13, 128, 4, 5, "bf16"),      # 5x5 matrix-core forward, general backward
+    (3, 21, 48, 64, 2, 3, "bf16"),       # streaming forward and streaming backward kernels
 ]
 
 
