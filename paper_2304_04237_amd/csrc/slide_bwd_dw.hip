@@ -68,6 +68,7 @@ struct Args {
     float* dbias_partial;                     // [NB][heads][9]
     int B, H, W, C, heads;
     int n_strips, n_ct, NB;
+    int nbp, rows_pb;                         // streaming kernel: bands of rows per plane, rows per band
     float scale;
 };
 
@@ -387,6 +388,305 @@ bwd_dw_kernel(const Args a)
     }
 }
 
+// ------------------------------------------------------------------ streaming form
+// The same products for maps of 32..56 columns (one column tile), with the data movement of the
+// streaming forward: a block of 8 product waves (four channels each, as above) and 4 mover
+// waves walks down bands of rows of (batch, head) planes, one row per epoch.  The movers stage
+// every row once: 16-byte loads into registers two epochs ahead (mover j: channels 8j..8j+7 of
+// k, v, q, dO; a lane owns one 8-pixel piece of one channel's row), conversion to halves, and
+// the rows go into rings in LDS in the layout of the kernel above (k and v: four row slots per
+// channel, plain and moved by one pixel; q and dO: two row slots).  The product waves read
+// the three window rows of a step through one address per row (ring slots wrap).  One block
+// barrier per row.  Accumulators live across all bands a block visits; partial sums as above.
+namespace ring {
+constexpr int RK = 4, RQ = 2;                 // ring slots per channel: k, v / q, dO
+constexpr int MOVERS = 4, THREADS_R = (WAVES + MOVERS) * 64;
+// halves per channel in a ring: its row slots plus 32, so that the channel stride is 16 dwords
+// past a multiple of the 64 banks and the four channels of a product wave (and the eight of a
+// mover) use different quarters of the banks
+constexpr int KCH = RK * KP + 32, QCH = RQ * QP + 32;
+constexpr int K_BYTES = D * KCH * 2;          // 26624
+constexpr int Q_BYTES = D * QCH * 2;          // 10240
+constexpr int OFF_K = 0, OFF_V = OFF_K + K_BYTES, OFF_K1 = OFF_V + K_BYTES + 8, OFF_V1 = OFF_K1 + K_BYTES,
+              OFF_Q = OFF_V1 + K_BYTES + 8, OFF_DO = OFF_Q + Q_BYTES, OFF_ZERO = OFF_DO + Q_BYTES,
+              LDS_BYTES = OFF_ZERO + 256;
+static_assert(OFF_K % 16 == 0 && OFF_V % 16 == 0 && OFF_K1 % 16 == 8 && OFF_V1 % 16 == 8 && OFF_Q % 16 == 0, "bank phase of the copies");
+static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+
+// the tap windows of the three window rows of a step: four consecutive dwords from each of
+// three dword-aligned LDS addresses per tensor, as 8-byte two-dword reads (see lds_read_windows)
+__device__ __forceinline__ void lds_read_windows3(const uint32_t (&ak)[3], const uint32_t (&av)[3],
+                                                  uint32_t (&k)[3][4], uint32_t (&v)[3][4])
+{
+    uint2_t k0a, k0b, k1a, k1b, k2a, k2b, v0a, v0b, v1a, v1b, v2a, v2b;
+    asm volatile("ds_read2_b32 %0, %12 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %1, %12 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %6, %15 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %7, %15 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %2, %13 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %3, %13 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %8, %16 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %9, %16 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %4, %14 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %5, %14 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %10, %17 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %11, %17 offset0:2 offset1:3\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(k0a), "=&v"(k0b), "=&v"(k1a), "=&v"(k1b), "=&v"(k2a), "=&v"(k2b),
+                   "=&v"(v0a), "=&v"(v0b), "=&v"(v1a), "=&v"(v1b), "=&v"(v2a), "=&v"(v2b)
+                 : "v"(ak[0]), "v"(ak[1]), "v"(ak[2]), "v"(av[0]), "v"(av[1]), "v"(av[2])
+                 : "memory");
+    k[0][0] = k0a[0]; k[0][1] = k0a[1]; k[0][2] = k0b[0]; k[0][3] = k0b[1];
+    k[1][0] = k1a[0]; k[1][1] = k1a[1]; k[1][2] = k1b[0]; k[1][3] = k1b[1];
+    k[2][0] = k2a[0]; k[2][1] = k2a[1]; k[2][2] = k2b[0]; k[2][3] = k2b[1];
+    v[0][0] = v0a[0]; v[0][1] = v0a[1]; v[0][2] = v0b[0]; v[0][3] = v0b[1];
+    v[1][0] = v1a[0]; v[1][1] = v1a[1]; v[1][2] = v1b[0]; v[1][3] = v1b[1];
+    v[2][0] = v2a[0]; v[2][1] = v2a[1]; v[2][2] = v2b[0]; v[2][3] = v2b[1];
+}
+
+// all LDS operations of this wave are done, then the block barrier; loads from global memory
+// stay in flight across it (__syncthreads would wait for them: the rows fetched two epochs ahead)
+__device__ __forceinline__ void row_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ void __launch_bounds__(THREADS_R)
+bwd_dw_ring_kernel(const Args a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool mover = wave >= WAVES;
+    const int i = lane & 15, g = lane >> 4;
+    const int m = blockIdx.x / a.NB, j = blockIdx.x - m * a.NB;
+    const int H = a.H, W = a.W;
+    const long HW = (long)H * W;
+    const int NXC = W >> 3;
+
+    // zero all of LDS once: margins and the zero block stay zero for the whole kernel
+    for (int o = tid * 16; o < LDS_BYTES; o += THREADS_R * 16) *(uint4_t*)(smem + o) = uint4_t{0u, 0u, 0u, 0u};
+    __syncthreads();
+
+    const int n_items = a.B * a.nbp;                               // bands of this head over the batch
+    const half2_t one2 = {(_Float16)1.0f, (_Float16)1.0f};
+    const half2_t in2 = {(_Float16)IN_SCALE, (_Float16)IN_SCALE};
+
+    if (mover) {
+        // ---- movers: lane = (channel mv * 8 + lane / 8, piece lane % 8) of a row of k, v, q, dO
+        const int mv = wave - WAVES;
+        const int ch = mv * 8 + (lane >> 3), x = lane & 7;
+        const bool has = x < NXC;
+        const int xs = has ? x : 0;                                // (idle lanes load piece 0 and store nothing)
+        struct Stage { uint4_t k, v, q, d; uint32_t kl, vl; };
+        __builtin_amdgcn_s_setprio(3);                             // the movers go ahead of the product waves of their SIMD
+        for (int item = j; item < n_items; item += a.NB) {
+            const int b = item / a.nbp, part = item - b * a.nbp;
+            const int y0 = part * a.rows_pb, nr = min(a.rows_pb, H - y0);
+            const long ch_base = ((long)b * a.C + m * D + ch) * HW + 8 * xs;
+            // stage s: row y0 + s + 2 of k and v into slot (s + 2) % 4, row y0 + s + 1 of q and dO
+            // into slot (s + 1) % 2.  Every load is unconditional (rows outside the map are
+            // clamped and written as zeros): straight-line code, in which the compiler counts
+            // the loads in flight.
+            auto load_stage = [&](int s, Stage& r) {
+                const int ykv = min(max(y0 + s + 2, 0), H - 1), yq = min(max(y0 + s + 1, 0), H - 1);
+                const bf16_bits* pk = a.k + ch_base + (long)ykv * W;
+                const bf16_bits* pv = a.v + ch_base + (long)ykv * W;
+                r.k = *(const uint4_t*)pk; r.v = *(const uint4_t*)pv;
+                r.kl = pk[xs > 0 ? -1 : 0]; r.vl = pv[xs > 0 ? -1 : 0];
+                r.q = *(const uint4_t*)(a.q + ch_base + (long)yq * W);
+                r.d = *(const uint4_t*)(a.dout + ch_base + (long)yq * W);
+            };
+            auto write_kv = [&](int off_plain, int off_moved, int slot, bool in_map, uint4_t raw, uint32_t left_raw) {
+                uint4_t val = bf16x8_to_half(raw, one2);
+                uint32_t left = (x > 0) ? bf16_to_half_bits(left_raw) : 0u;
+                if (!in_map) { val = uint4_t{0u, 0u, 0u, 0u}; left = 0u; }
+                const int at = (ch * KCH + slot * KP + 8 + 8 * x) * 2;
+                *(uint4_t*)(smem + off_plain + at) = val;
+                // the copy moved right by one pixel: (left neighbour, pixels 0..6) here, pixel 7
+                // opens the next piece (written by that piece's lane, or below at the row's end)
+                uint4_t mvd;
+                mvd[0] = (val[0] << 16) | left;
+#pragma unroll
+                for (int y = 1; y < 4; ++y) mvd[y] = __builtin_amdgcn_alignbit(val[y], val[y - 1], 16);
+                *(uint2_t*)(smem + off_moved + at) = uint2_t{mvd[0], mvd[1]};
+                *(uint2_t*)(smem + off_moved + at + 8) = uint2_t{mvd[2], mvd[3]};
+                if (x == NXC - 1) *(uint16_t*)(smem + off_moved + at + 16) = (uint16_t)(val[3] >> 16);
+            };
+            auto write_stage = [&](int s, const Stage& r) {
+                if (!has) return;
+                const int ykv = y0 + s + 2, yq = y0 + s + 1;
+                const bool kv_in = ykv >= 0 && ykv < H;
+                const int slot = (s + 2) & 3;
+                write_kv(OFF_K, OFF_K1, slot, kv_in, r.k, r.kl);
+                write_kv(OFF_V, OFF_V1, slot, kv_in, r.v, r.vl);
+                if (s + 1 >= 0 && s + 1 < nr) {                       // (rows of the band only)
+                    const int at = (ch * QCH + ((s + 1) & 1) * QP + 8 * x) * 2;
+                    *(uint4_t*)(smem + OFF_Q + at) = bf16x8_to_half(r.q, in2);
+                    *(uint4_t*)(smem + OFF_DO + at) = bf16x8_to_half(r.d, in2);
+                }
+            };
+            // Four register sets (stage s in set s % 4): a row is fetched four epochs before it is
+            // written.  The epoch loop is unrolled by four and runs a multiple of four epochs (the
+            // product waves pass the same barriers; a stage past the band writes a slot nobody reads).
+            Stage s0_, s1_, s2_, s3_;
+            load_stage(-3, s1_); load_stage(-2, s2_); load_stage(-1, s3_); load_stage(0, s0_);
+            write_stage(-3, s1_); load_stage(1, s1_);
+            write_stage(-2, s2_); load_stage(2, s2_);
+            write_stage(-1, s3_); load_stage(3, s3_);
+            row_barrier();                                         // rows -1, 0, 1 of k and v, row 0 of q and dO are in place
+            const int nr4 = (nr + 3) & ~3;
+            for (int r = 0; r < nr4; r += 4) {
+                write_stage(r, s0_); load_stage(r + 4, s0_);
+                row_barrier();
+                write_stage(r + 1, s1_); load_stage(r + 5, s1_);
+                row_barrier();
+                write_stage(r + 2, s2_); load_stage(r + 6, s2_);
+                row_barrier();
+                write_stage(r + 3, s3_); load_stage(r + 7, s3_);
+                row_barrier();
+            }
+        }
+        return;
+    }
+
+    // ---- product waves
+    const int c0 = m * D + wave * CPW;
+    constexpr int ROWS = 3 * CPW;
+    const int lcc = (i < ROWS) ? i / 3 : 0, tx = (i < ROWS) ? i - 3 * (i / 3) : 0;
+    const int chl = wave * CPW + lcc;                              // channel of the head that row i belongs to
+    // byte offset of the lane's tap window inside ring slot 0 of its channel: + slot * KP * 2 + 64 * h
+    const uint32_t kwin = (uint32_t)(uintptr_t)smem +
+                          (uint32_t)((chl * KCH + 8 + 8 * g) * 2 + (tx == 2 ? 4 : 0) + (tx == 1 ? OFF_K : OFF_K1));
+    const int q_off = (i < ROWS) ? (chl * QCH + 8 * g) * 2 : -1;   // + slot * QP * 2 + 64 * h; -1: masked row, read zeros
+    float4_t acc_k[3], acc_v[3];
+#pragma unroll
+    for (int ty = 0; ty < 3; ++ty) { acc_k[ty] = float4_t{0, 0, 0, 0}; acc_v[ty] = float4_t{0, 0, 0, 0}; }
+    const bool bias_lane = (wave == 0) && (i == ROWS);            // row 12 of the first product sums dl
+    const uint32_t b_lane = (uint32_t)(((long)(i < S ? i : 0) * HW + 8 * g) * 2);
+    const bool second_half = W > 32;
+
+    for (int item = j; item < n_items; item += a.NB) {
+        const int b = item / a.nbp, part = item - b * a.nbp;
+        const int y0 = part * a.rows_pb, nr = min(a.rows_pb, H - y0);
+        // dl and a of a row as the B operands, straight from global memory one row ahead: lane
+        // (n, g) holds the 8 pixels 32 h + 8 g .. of shift n
+        uint4_t Bop[2][2];
+        // (unconditional loads, so that the compiler counts them exactly and waits where they are
+        // used: lanes and pieces without data read a valid address and are zeroed at use)
+        auto load_B = [&](int r, uint4_t (&dst)[2][2]) {
+            const int yr = min(y0 + r, H - 1);
+            const long at = ((long)b * a.heads + m) * S * HW + (long)yr * W;   // uniform
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int px = (32 * h + 8 * g < W) ? 32 * h : 0;
+                dst[h][0] = *(const uint4_t*)((const char*)(a.dl + at + px) + b_lane);
+                dst[h][1] = *(const uint4_t*)((const char*)(a.attn + at + px) + b_lane);
+            }
+        };
+        // one row: the three window rows of every step against the row's dl / a operands
+        auto row_products = [&](int r, const uint4_t (&Bq)[2][2]) {
+            uint32_t ak[3], av[3];
+#pragma unroll
+            for (int ty = 0; ty < 3; ++ty) {
+                ak[ty] = kwin + (uint32_t)(((r + ty + 3) & 3) * (KP * 2));   // row r - 1 + ty sits in slot (r - 1 + ty) % 4
+                av[ty] = ak[ty] + (OFF_V - OFF_K);
+            }
+            const int qs = q_off >= 0 ? q_off + (r & 1) * (QP * 2) : -1;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (h == 0 || second_half) {
+                    const bool b_ok = i < S && 32 * h + 8 * g < W;
+                    const uint4_t z4 = {0u, 0u, 0u, 0u};
+                    const half8_t Bdl = __builtin_bit_cast(half8_t, b_ok ? Bq[h][0] : z4);
+                    const half8_t Ba = __builtin_bit_cast(half8_t, b_ok ? Bq[h][1] : z4);
+                    const uint4_t qv = *(const uint4_t*)(smem + (qs >= 0 ? OFF_Q + qs + 64 * h : OFF_ZERO));
+                    const uint4_t dv = *(const uint4_t*)(smem + (qs >= 0 ? OFF_DO + qs + 64 * h : OFF_ZERO));
+                    uint32_t kw[3][4], vw[3][4];
+                    {
+                        const uint32_t akh[3] = {ak[0] + 64u * h, ak[1] + 64u * h, ak[2] + 64u * h};
+                        const uint32_t avh[3] = {av[0] + 64u * h, av[1] + 64u * h, av[2] + 64u * h};
+                        lds_read_windows3(akh, avh, kw, vw);
+                    }
+#pragma unroll
+                    for (int ty = 0; ty < 3; ++ty) {
+                        uint4_t pk, pv;
+#pragma unroll
+                        for (int y = 0; y < 4; ++y) {
+                            pk[y] = as_dword(as_half2(qv[y]) * as_half2(kw[ty][y]));
+                            pv[y] = as_dword(as_half2(dv[y]) * as_half2(vw[ty][y]));
+                        }
+                        if (ty == 0 && wave == 0) {
+#pragma unroll
+                            for (int y = 0; y < 4; ++y) pk[y] = bias_lane ? as_dword(one2) : pk[y];
+                        }
+                        acc_k[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, pk), Bdl, acc_k[ty], 0, 0, 0);
+                        acc_v[ty] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, pv), Ba, acc_v[ty], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        // four operand sets (row r in set r % 4), fetched three rows ahead; the loop is unrolled by
+        // four and runs a multiple of four epochs, like the movers'
+        uint4_t B1[2][2], B2[2][2], B3[2][2];
+        load_B(0, Bop); load_B(1, B1); load_B(2, B2);
+        row_barrier();                                             // (the movers' first rows)
+        const int nr4 = (nr + 3) & ~3;
+        for (int r = 0; r < nr4; r += 4) {
+            load_B(r + 3, B3);
+            if (r < nr) row_products(r, Bop);
+            row_barrier();
+            load_B(r + 4, Bop);
+            if (r + 1 < nr) row_products(r + 1, B1);
+            row_barrier();
+            load_B(r + 5, B1);
+            if (r + 2 < nr) row_products(r + 2, B2);
+            row_barrier();
+            load_B(r + 6, B2);
+            if (r + 3 < nr) row_products(r + 3, B3);
+            row_barrier();
+        }
+    }
+
+    // ---- partial sums of this block (as in bwd_dw_kernel)
+    const int n = i;
+    const float out_scale = 1.0f / IN_SCALE;
+    if (n < S) {
+        const long side = (long)a.C * S * S;
+        float* base = a.partial + (long)j * 2 * side;
+#pragma unroll
+        for (int ty = 0; ty < 3; ++ty) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 4 * g + r;
+                if (row < ROWS) {
+                    const int cc = row / 3, t = 3 * ty + row - 3 * cc;
+                    base[((long)(c0 + cc) * S + n) * S + t] = acc_k[ty][r] * (a.scale * out_scale);
+                    base[side + ((long)(c0 + cc) * S + n) * S + t] = acc_v[ty][r] * out_scale;
+                }
+            }
+        }
+        if (wave == 0 && g == 3)                                   // row 12 = 4*3 + 0
+            a.dbias_partial[((long)j * a.heads + m) * S + n] = acc_k[0][0];
+    }
+}
+
+// bands per plane: enough work items for the blocks of a head, bands of at least 4 rows
+static int bands_per_plane(const Problem& p, int n_cu)
+{
+    long want = n_cu / p.heads;
+    if (want < 1) want = 1;
+    long nbp = (want + p.B - 1) / p.B;
+    const long most = p.H >= 8 ? p.H / 4 : 1;
+    if (nbp > most) nbp = most;
+    if (nbp < 1) nbp = 1;
+    // every band has rows
+    while (nbp > 1 && ((p.H + nbp - 1) / nbp) * (nbp - 1) >= p.H) --nbp;
+    return (int)nbp;
+}
+}  // namespace ring
+
 // n_cu: compute units to fill (the workspace query passes the upper bound MAX_CU_PLANNED)
 static int blocks_per_head(const Problem& p, int n_cu)
 {
@@ -402,6 +702,12 @@ static int blocks_per_head(const Problem& p, int n_cu)
 bool bwd_dw_mfma_supported(const Problem& p)
 {
     return p.dtype == 1 && p.ksize == 3 && p.C == p.heads * dwpath::D && (p.W % 8) == 0;
+}
+
+// the streaming form of the kernel: one column tile, rows of at least four 8-pixel pieces
+bool bwd_dw_ring_supported(const Problem& p)
+{
+    return bwd_dw_mfma_supported(p) && p.W >= 32 && p.W <= dwpath::TW;
 }
 
 // floats: per-block kernel-gradient partials, then per-block bias partials
@@ -425,10 +731,28 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
     a.n_strips = (p.H + R - 1) / R; a.n_ct = (p.W + TW - 1) / TW;
     a.scale = 1.0f / sqrtf((float)D);
-    static LdsOptIn opt_in;
-    hipError_t e = opt_in.ensure({(const void*)bwd_dw_kernel}, LDS_BYTES);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
+    if (bwd_dw_ring_supported(p) && fwd_ring_enabled()) {
+        // the streaming form: work items are bands of rows of one batch item's head plane
+        const int n_cu = device_cu_count();
+        a.nbp = ring::bands_per_plane(p, n_cu);
+        a.rows_pb = (p.H + a.nbp - 1) / a.nbp;
+        long nb = n_cu / p.heads;
+        if (nb < 1) nb = 1;
+        if (nb > (long)p.B * a.nbp) nb = (long)p.B * a.nbp;
+        if (nb > a.NB) nb = a.NB;                               // (never more partials than the workspace was sized for)
+        a.NB = (int)nb;
+        a.dbias_partial = partial + (size_t)a.NB * 2 * p.C * 81;
+        static LdsOptIn opt_in_ring;
+        hipError_t er = opt_in_ring.ensure({(const void*)ring::bwd_dw_ring_kernel}, ring::LDS_BYTES);
+        if (er != hipSuccess) return er;
+        hipLaunchKernelGGL(ring::bwd_dw_ring_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(ring::THREADS_R),
+                           (size_t)ring::LDS_BYTES, st, a);
+    } else {
+        static LdsOptIn opt_in;
+        hipError_t e = opt_in.ensure({(const void*)bwd_dw_kernel}, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(bwd_dw_kernel, dim3((unsigned)(a.NB * p.heads)), dim3(THREADS), (size_t)LDS_BYTES, st, a);
+    }
     const long side = (long)p.C * 81;
     return launch_bwd_dw_reduce(partial, dwk, dwv, side, a.NB, a.dbias_partial, dbias, p.heads * 9,
                                 p.accumulate, st);

@@ -71,6 +71,7 @@ hipError_t launch_bwd_dw_reduce(const float* partial, float* dwk, float* dwv, lo
 // ---- matrix-core kernel/bias gradients (slide_bwd_dw.hip): bf16, d == 32, ksize 3, W % 8 == 0
 bool bwd_dw_mfma_supported(const Problem& p);
 size_t bwd_dw_mfma_partial_floats(const Problem& p);
+bool bwd_dw_ring_supported(const Problem& p);         // launch_bwd_dw_mfma runs its streaming form (maps 32..56 columns wide)
 hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                               const void* v, const void* attn_ws, const void* dl_ws,   // halves
                               float* partial, float* dwk, float* dwv, float* dbias, hipStream_t st);
