@@ -202,7 +202,7 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
  * one takes that part); 1 is added where the key and value gradients run in the streaming
  * kernel (maps 32..56 columns wide, W % 8 == 0, bands and rings that fit the LDS), 2 where the
  * per-pixel part (attention recompute, logit and query gradients) does (maps 32..64 columns
- * wide): 21, 22, 23.
+ * wide), 4 where the kernel and bias gradients do (maps 32..56 columns wide): 21 .. 27.
  * aligned16: whether every activation, gradient and workspace pointer is 16-byte aligned.
  * Launches nothing; reads the compute-unit count of the current device (256 if there is none).
  */

@@ -619,7 +619,8 @@ int bwd_variant(const Problem& p, bool all_aligned16)
     if (!fast) return 10;
     const bool half_ws = bwd_dw_mfma_supported(p);
     if (!half_ws || !fwd_ring_enabled()) return 20;
-    return 20 + (bwd_dkdv_ring_supported(p, all_aligned16) ? 1 : 0) + (bwd_pixel_ring_supported(p, all_aligned16) ? 2 : 0);
+    return 20 + (bwd_dkdv_ring_supported(p, all_aligned16) ? 1 : 0) + (bwd_pixel_ring_supported(p, all_aligned16) ? 2 : 0) +
+           (bwd_dw_ring_supported(p) ? 4 : 0);
 }
 
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,

@@ -58,8 +58,8 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* workspace, hipStream_t st);
 
 // which kernels launch_bwd_generic runs: 10 general, 20 tiled matrix-core kernels, + 1 with the
-// streaming dk/dv kernel, + 2 with the streaming per-pixel kernel; aligned16: every pointer is
-// 16-byte aligned
+// streaming dk/dv kernel, + 2 with the streaming per-pixel kernel, + 4 with the streaming form
+// of the kernel-gradient kernel; aligned16: every pointer is 16-byte aligned
 int bwd_variant(const Problem& p, bool aligned16);
 
 // adds n_chunks partial sums per entry in a fixed order; bias_partial [n_chunks][nbias] -> dbias
