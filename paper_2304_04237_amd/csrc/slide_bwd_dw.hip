@@ -407,10 +407,12 @@ constexpr int MOVERS = 4, THREADS_R = (WAVES + MOVERS) * 64;
 constexpr int KCH = RK * KP + 32, QCH = RQ * QP + 32;
 constexpr int K_BYTES = D * KCH * 2;          // 26624
 constexpr int Q_BYTES = D * QCH * 2;          // 10240
-constexpr int OFF_K = 0, OFF_V = OFF_K + K_BYTES, OFF_K1 = OFF_V + K_BYTES + 8, OFF_V1 = OFF_K1 + K_BYTES,
-              OFF_Q = OFF_V1 + K_BYTES + 8, OFF_DO = OFF_Q + Q_BYTES, OFF_ZERO = OFF_DO + Q_BYTES,
+// (the moved copies start 8 banks after a multiple of 64: within the 16 banks of a channel the
+// plain windows of two lane groups use the first eight, the moved windows the rest)
+constexpr int OFF_K = 0, OFF_V = OFF_K + K_BYTES, OFF_K1 = OFF_V + K_BYTES + 32, OFF_V1 = OFF_K1 + K_BYTES,
+              OFF_Q = OFF_V1 + K_BYTES + 32, OFF_DO = OFF_Q + Q_BYTES, OFF_ZERO = OFF_DO + Q_BYTES,
               LDS_BYTES = OFF_ZERO + 256;
-static_assert(OFF_K % 16 == 0 && OFF_V % 16 == 0 && OFF_K1 % 16 == 8 && OFF_V1 % 16 == 8 && OFF_Q % 16 == 0, "bank phase of the copies");
+static_assert(K_BYTES % 256 == 0 && OFF_K % 256 == 0 && OFF_K1 % 256 == 32 && OFF_V1 % 256 == 32 && OFF_Q % 16 == 0, "bank phase of the copies");
 static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 
 // the tap windows of the three window rows of a step: four consecutive dwords from each of
