@@ -453,6 +453,31 @@ __device__ __forceinline__ void row_barrier()
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// The tap windows of ONE row for both steps (pixels 0..31 and 32..63) and both tensors: a row's
+// windows are read once and serve as the bottom, middle and top window row of three successive
+// rows of products.
+struct RowWindows { uint32_t k[2][4], v[2][4]; };
+__device__ __forceinline__ void lds_read_row_windows(uint32_t ak, uint32_t av, RowWindows& w)
+{
+    uint2_t k0a, k0b, k1a, k1b, v0a, v0b, v1a, v1b;
+    asm volatile("ds_read2_b32 %0, %8 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %1, %8 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %4, %9 offset0:0 offset1:1\n\t"
+                 "ds_read2_b32 %5, %9 offset0:2 offset1:3\n\t"
+                 "ds_read2_b32 %2, %8 offset0:16 offset1:17\n\t"
+                 "ds_read2_b32 %3, %8 offset0:18 offset1:19\n\t"
+                 "ds_read2_b32 %6, %9 offset0:16 offset1:17\n\t"
+                 "ds_read2_b32 %7, %9 offset0:18 offset1:19\n\t"
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(k0a), "=&v"(k0b), "=&v"(k1a), "=&v"(k1b), "=&v"(v0a), "=&v"(v0b), "=&v"(v1a), "=&v"(v1b)
+                 : "v"(ak), "v"(av)
+                 : "memory");
+    w.k[0][0] = k0a[0]; w.k[0][1] = k0a[1]; w.k[0][2] = k0b[0]; w.k[0][3] = k0b[1];
+    w.k[1][0] = k1a[0]; w.k[1][1] = k1a[1]; w.k[1][2] = k1b[0]; w.k[1][3] = k1b[1];
+    w.v[0][0] = v0a[0]; w.v[0][1] = v0a[1]; w.v[0][2] = v0b[0]; w.v[0][3] = v0b[1];
+    w.v[1][0] = v1a[0]; w.v[1][1] = v1a[1]; w.v[1][2] = v1b[0]; w.v[1][3] = v1b[1];
+}
+
 __global__ void __launch_bounds__(THREADS_R)
 bwd_dw_ring_kernel(const Args a)
 {
@@ -530,7 +555,7 @@ bwd_dw_ring_kernel(const Args a)
                 }
             };
             // Four register sets (stage s in set s % 4): a row is fetched four epochs before it is
-            // written.  The epoch loop is unrolled by four and runs a multiple of four epochs (the
+            // written.  The epoch loop is unrolled by four and runs a multiple of twelve epochs (the
             // product waves pass the same barriers; a stage past the band writes a slot nobody reads).
             Stage s0_, s1_, s2_, s3_;
             load_stage(-3, s1_); load_stage(-2, s2_); load_stage(-1, s3_); load_stage(0, s0_);
@@ -538,8 +563,8 @@ bwd_dw_ring_kernel(const Args a)
             write_stage(-2, s2_); load_stage(2, s2_);
             write_stage(-1, s3_); load_stage(3, s3_);
             row_barrier();                                         // rows -1, 0, 1 of k and v, row 0 of q and dO are in place
-            const int nr4 = (nr + 3) & ~3;
-            for (int r = 0; r < nr4; r += 4) {
+            const int nr12 = ((nr + 11) / 12) * 12;                  // (a multiple of four and of the product waves' six)
+            for (int r = 0; r < nr12; r += 4) {
                 write_stage(r, s0_); load_stage(r + 4, s0_);
                 row_barrier();
                 write_stage(r + 1, s1_); load_stage(r + 5, s1_);
@@ -587,14 +612,14 @@ bwd_dw_ring_kernel(const Args a)
                 dst[h][1] = *(const uint4_t*)((const char*)(a.attn + at + px) + b_lane);
             }
         };
-        // one row: the three window rows of every step against the row's dl / a operands
-        auto row_products = [&](int r, const uint4_t (&Bq)[2][2]) {
-            uint32_t ak[3], av[3];
-#pragma unroll
-            for (int ty = 0; ty < 3; ++ty) {
-                ak[ty] = kwin + (uint32_t)(((r + ty + 3) & 3) * (KP * 2));   // row r - 1 + ty sits in slot (r - 1 + ty) % 4
-                av[ty] = ak[ty] + (OFF_V - OFF_K);
-            }
+        // one row of products: window rows r - 1 (lo) and r (mid) are held from the two rows before,
+        // row r + 1 (hi) is read here; against the row's dl / a operands
+        auto read_row = [&](int rho, RowWindows& w) {
+            const uint32_t ak = kwin + (uint32_t)((rho & 3) * (KP * 2));      // row rho sits in slot rho % 4
+            lds_read_row_windows(ak, ak + (OFF_V - OFF_K), w);
+        };
+        auto row_products = [&](int r, const RowWindows& lo, const RowWindows& mid, RowWindows& hi, const uint4_t (&Bq)[2][2]) {
+            read_row(r + 1, hi);
             const int qs = q_off >= 0 ? q_off + (r & 1) * (QP * 2) : -1;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -605,19 +630,14 @@ bwd_dw_ring_kernel(const Args a)
                     const half8_t Ba = __builtin_bit_cast(half8_t, b_ok ? Bq[h][1] : z4);
                     const uint4_t qv = *(const uint4_t*)(smem + (qs >= 0 ? OFF_Q + qs + 64 * h : OFF_ZERO));
                     const uint4_t dv = *(const uint4_t*)(smem + (qs >= 0 ? OFF_DO + qs + 64 * h : OFF_ZERO));
-                    uint32_t kw[3][4], vw[3][4];
-                    {
-                        const uint32_t akh[3] = {ak[0] + 64u * h, ak[1] + 64u * h, ak[2] + 64u * h};
-                        const uint32_t avh[3] = {av[0] + 64u * h, av[1] + 64u * h, av[2] + 64u * h};
-                        lds_read_windows3(akh, avh, kw, vw);
-                    }
 #pragma unroll
                     for (int ty = 0; ty < 3; ++ty) {
+                        const RowWindows& w = ty == 0 ? lo : (ty == 1 ? mid : hi);
                         uint4_t pk, pv;
 #pragma unroll
                         for (int y = 0; y < 4; ++y) {
-                            pk[y] = as_dword(as_half2(qv[y]) * as_half2(kw[ty][y]));
-                            pv[y] = as_dword(as_half2(dv[y]) * as_half2(vw[ty][y]));
+                            pk[y] = as_dword(as_half2(qv[y]) * as_half2(w.k[h][y]));
+                            pv[y] = as_dword(as_half2(dv[y]) * as_half2(w.v[h][y]));
                         }
                         if (ty == 0 && wave == 0) {
 #pragma unroll
@@ -629,24 +649,33 @@ bwd_dw_ring_kernel(const Args a)
                 }
             }
         };
-        // four operand sets (row r in set r % 4), fetched three rows ahead; the loop is unrolled by
-        // four and runs a multiple of four epochs, like the movers'
-        uint4_t B1[2][2], B2[2][2], B3[2][2];
-        load_B(0, Bop); load_B(1, B1); load_B(2, B2);
+        // Two operand sets (even rows in Bop, odd rows in B1, fetched one row ahead) and three sets
+        // of window rows that rotate: the loop is unrolled by six and runs a multiple of twelve
+        // epochs (the movers' loop is unrolled by four; both pass the same barriers).
+        uint4_t B1[2][2];
+        RowWindows wa, wb, wc;
+        load_B(0, Bop);
         row_barrier();                                             // (the movers' first rows)
-        const int nr4 = (nr + 3) & ~3;
-        for (int r = 0; r < nr4; r += 4) {
-            load_B(r + 3, B3);
-            if (r < nr) row_products(r, Bop);
+        read_row(-1, wa); read_row(0, wb);
+        const int nr12 = ((nr + 11) / 12) * 12;
+        for (int r = 0; r < nr12; r += 6) {
+            load_B(r + 1, B1);
+            if (r < nr) row_products(r, wa, wb, wc, Bop);
+            row_barrier();
+            load_B(r + 2, Bop);
+            if (r + 1 < nr) row_products(r + 1, wb, wc, wa, B1);
+            row_barrier();
+            load_B(r + 3, B1);
+            if (r + 2 < nr) row_products(r + 2, wc, wa, wb, Bop);
             row_barrier();
             load_B(r + 4, Bop);
-            if (r + 1 < nr) row_products(r + 1, B1);
+            if (r + 3 < nr) row_products(r + 3, wa, wb, wc, B1);
             row_barrier();
             load_B(r + 5, B1);
-            if (r + 2 < nr) row_products(r + 2, B2);
+            if (r + 4 < nr) row_products(r + 4, wb, wc, wa, Bop);
             row_barrier();
-            load_B(r + 6, B2);
-            if (r + 3 < nr) row_products(r + 3, B3);
+            load_B(r + 6, Bop);
+            if (r + 5 < nr) row_products(r + 5, wc, wa, wb, B1);
             row_barrier();
         }
     }
