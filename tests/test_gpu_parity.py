@@ -180,12 +180,15 @@ BWD_SHAPES = [
     (3, 29, 48, 64, 2, 3, "bf16"),
     (70, 12, 56, 64, 2, 3, "bf16"),      # more planes than half the compute units: one band per plane
     (66, 25, 48, 64, 2, 3, "bf16"),      # one band of 25 rows per plane: ten epochs
+    (150, 9, 48, 64, 2, 3, "bf16"),      # 300 planes: more blocks than compute units
+    (1, 150, 40, 32, 1, 3, "bf16"),      # a tall map cut into many bands
     (2, 33, 32, 64, 2, 3, "bf16"),       # too narrow for the streaming dk/dv kernel's rings: tiled kernel for that part
     (3, 40, 64, 32, 1, 3, "bf16"),       # the widest map of the streaming per-pixel kernel; tiled dk/dv kernel
 ]
 # shapes of the list whose three parts all run in the streaming kernels (slide_attn_bwd_variant
 # 27), and those where dk/dv do not (26; 22 where the kernel gradients do not either)
-BWD_STREAMING = {(3, 8, 56), (1, 20, 40), (40, 10, 56), (24, 17, 48), (2, 33, 40), (1, 57, 56), (3, 29, 48), (70, 12, 56), (66, 25, 48)}
+BWD_STREAMING = {(3, 8, 56), (1, 20, 40), (40, 10, 56), (24, 17, 48), (2, 33, 40), (1, 57, 56), (3, 29, 48), (70, 12, 56), (66, 25, 48),
+                 (150, 9, 48), (1, 150, 40)}
 BWD_STREAMING_PIXEL_ONLY = {(2, 33, 32), (3, 40, 64)}
 
 
