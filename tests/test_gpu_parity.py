@@ -184,12 +184,20 @@ BWD_SHAPES = [
     (1, 150, 40, 32, 1, 3, "bf16"),      # a tall map cut into many bands
     (2, 33, 32, 64, 2, 3, "bf16"),       # too narrow for the streaming dk/dv kernel's rings: tiled kernel for that part
     (3, 40, 64, 32, 1, 3, "bf16"),       # the widest map of the streaming per-pixel kernel; tiled dk/dv kernel
+    # maps lower than the window's reach or than one epoch in the streaming kernels: a band ends
+    # inside the first groups of rows
+    (2, 3, 56, 64, 2, 3, "bf16"),
+    (3, 5, 48, 32, 1, 3, "bf16"),
+    (5, 4, 40, 64, 2, 3, "bf16"),
+    (2, 6, 32, 64, 2, 3, "bf16"),
+    (1, 1, 56, 32, 1, 3, "bf16"),        # a single row: rings too short for the streaming dk/dv kernel
+    (6, 2, 48, 64, 2, 3, "bf16"),
 ]
 # shapes of the list whose three parts all run in the streaming kernels (slide_attn_bwd_variant
 # 27), and those where dk/dv do not (26; 22 where the kernel gradients do not either)
 BWD_STREAMING = {(3, 8, 56), (1, 20, 40), (40, 10, 56), (24, 17, 48), (2, 33, 40), (1, 57, 56), (3, 29, 48), (70, 12, 56), (66, 25, 48),
-                 (150, 9, 48), (1, 150, 40)}
-BWD_STREAMING_PIXEL_ONLY = {(2, 33, 32), (3, 40, 64)}
+                 (150, 9, 48), (1, 150, 40), (2, 3, 56), (3, 5, 48), (5, 4, 40), (2, 6, 32)}
+BWD_STREAMING_PIXEL_ONLY = {(2, 33, 32), (3, 40, 64), (1, 1, 56), (6, 2, 48)}
 
 
 @pytest.mark.parametrize("shape", BWD_SHAPES)
