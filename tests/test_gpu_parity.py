@@ -227,6 +227,43 @@ def test_backward_matches_oracle(shape):
         assert torch.equal(a, b)
 
 
+def _random_streaming_shapes(seed, count):
+    """Seeded shapes in the range of the streaming kernels (widths 32..64, heights from one row
+    to more than one band, one to three heads, up to a few hundred planes)."""
+    import random
+    rng = random.Random(seed)
+    shapes = []
+    for _ in range(count):
+        W = rng.choice([32, 40, 48, 56, 64])
+        H = rng.choice([1, 2, 3, 4, 5, 7, 9, 11, 13, 16, 19, 23, 27, 31, 37, 45, 61])
+        heads = rng.choice([1, 2, 3])
+        B = rng.choice([1, 2, 3, 5, 8, 13, 21, 40, 70, 130, 260])
+        while B * H * W * heads > 250000:
+            B = max(1, B // 2)
+        shapes.append((B, H, W, 32 * heads, heads))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_streaming_shapes(3, 16))
+def test_forward_and_backward_random_streaming_shapes(shape):
+    """Forward (with the log of the softmax denominator) and all six gradients against the
+    oracle on seeded random shapes, whichever kernels the dispatch picks for them."""
+    B, H, W, C, heads = shape
+    print("random streaming case", shape, "forward path", sa.slide_attn_fwd_path(B, H, W, C, heads, 3, torch.bfloat16),
+          "backward variant", sa.slide_attn_bwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True), flush=True)
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=7000 + B + 3 * H + 5 * W)
+    lse = torch.empty((B, heads, H, W), dtype=torch.float32, device="cuda:0")
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, lse=lse)
+    grads = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3, return_lse=True)
+    check("out", "bf16", out, ref)
+    check("lse", "bf16", lse, ref_lse)
+    refg = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3)
+    for name, got, want in zip(GRAD_NAMES, grads, refg):
+        check(name, "bf16", got, want)
+
+
 def test_backward_unaligned_gradient_buffers_take_the_tiled_kernels():
     """dq, dk, dv that start 2 bytes into an allocation: the streaming kernels, which store 16
     bytes per lane, are not used; the results are those of the aligned call."""
