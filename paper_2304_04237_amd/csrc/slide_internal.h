@@ -29,20 +29,28 @@ struct Problem {
 constexpr int MAX_CU_PLANNED = 256;
 int device_cu_count();
 
-// Opt-in of a set of kernels to `bytes` of dynamic LDS: done once per process, safe when
-// several host threads call into the library at the same time; the first error sticks.
+// Opt-in of a set of kernels to `bytes` of dynamic LDS: the attribute belongs to the device that
+// is current, so it is set once per device (safe when several host threads call into the
+// library at the same time; the first error on a device sticks for that device).
 struct LdsOptIn {
-    std::once_flag once;
-    hipError_t err = hipSuccess;
+    static constexpr int MAX_DEV = 64;
+    std::once_flag once[MAX_DEV];
+    hipError_t err[MAX_DEV] = {};
     hipError_t ensure(std::initializer_list<const void*> kernels, int bytes)
     {
-        std::call_once(once, [&] {
+        auto set_all = [&]() {
             for (const void* f : kernels) {
-                err = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-                if (err != hipSuccess) return;
+                const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+                if (e != hipSuccess) return e;
             }
-        });
-        return err;
+            return hipSuccess;
+        };
+        int dev = 0;
+        const hipError_t eg = hipGetDevice(&dev);
+        if (eg != hipSuccess) return eg;
+        if (dev < 0 || dev >= MAX_DEV) return set_all();            // (beyond the table: every call)
+        std::call_once(once[dev], [&] { err[dev] = set_all(); });
+        return err[dev];
     }
 };
 
