@@ -203,6 +203,10 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
  * kernel (maps 32..56 columns wide, W % 8 == 0, bands and rings that fit the LDS), 2 where the
  * per-pixel part (attention recompute, logit and query gradients) does (maps 32..64 columns
  * wide), 4 where the kernel and bias gradients do (maps 32..56 columns wide): 21 .. 27.
+ * 100 + v: heads narrower than 32 channels (bf16, ksize 3, W % 8 == 0, 16-byte aligned pointers;
+ * e.g. 24 channels per head): the kernels of variant v run on copies of q, k, v, dO and the
+ * kernels padded with zero channels to 32 per head, made in the workspace (which is that much
+ * larger for these shapes), with the logit scale of the true head size.
  * aligned16: whether every activation, gradient and workspace pointer is 16-byte aligned.
  * Launches nothing; reads the compute-unit count of the current device (256 if there is none).
  */

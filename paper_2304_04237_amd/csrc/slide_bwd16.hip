@@ -559,8 +559,8 @@ hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void*
     a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.dq = (bf16_bits*)dq; a.attn = attn_ws; a.dl = dl_ws; a.image = image;
     fill_grid(a.g, p, t, k, v);
-    a.scale = 1.0f / sqrtf((float)D);
-    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.scale = p.logit_scale();
+    a.scale_log2e = 1.44269504088896341f * p.logit_scale();
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)bwd_pixel_kernel16<false>, (const void*)bwd_pixel_kernel16<true>}, LDS_LIMIT);
     if (e != hipSuccess) return e;
@@ -599,7 +599,7 @@ hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* 
     fill_grid(a.g, p, t, q, dout);
     a.rec_dl = t.buf_bytes;
     a.rec_a = t.buf_bytes + t.halo_px * REC_BYTES;
-    a.scale = 1.0f / sqrtf((float)D);
+    a.scale = p.logit_scale();
     const int lds_bytes = t.buf_bytes + 2 * t.halo_px * REC_BYTES;
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)bwd_dkdv_kernel16<false>, (const void*)bwd_dkdv_kernel16<true>}, LDS_LIMIT);

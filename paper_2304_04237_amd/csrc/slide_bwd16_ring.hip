@@ -904,7 +904,7 @@ hipError_t launch_bwd_dkdv_ring(const Problem& p, const void* dout, const void* 
     a.off_out = r.off_out;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.rr.R - 1) / r.rr.R);
-    a.scale = 1.0f / sqrtf((float)t16::D);
+    a.scale = p.logit_scale();
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)bwd16_ring_dkdv_kernel<2>, (const void*)bwd16_ring_dkdv_kernel<3>,
                                   (const void*)bwd16_ring_dkdv_kernel<4>}, t16::LDS_LIMIT);
@@ -942,8 +942,8 @@ hipError_t launch_bwd_pixel_ring(const Problem& p, const void* dout, const void*
     a.off_out = r.off_out; a.off_a1v = r.off_a1v;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.rr.R - 1) / r.rr.R);
-    a.scale = 1.0f / sqrtf((float)t16::D);
-    a.scale_log2e = 1.44269504088896341f / sqrtf((float)t16::D);
+    a.scale = p.logit_scale();
+    a.scale_log2e = 1.44269504088896341f * p.logit_scale();
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)bwd16_ring_pixel_kernel<2>, (const void*)bwd16_ring_pixel_kernel<3>,
                                   (const void*)bwd16_ring_pixel_kernel<4>}, t16::LDS_LIMIT);

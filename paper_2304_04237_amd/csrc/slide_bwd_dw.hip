@@ -761,7 +761,7 @@ hipError_t launch_bwd_dw_mfma(const Problem& p, const void* dout, const void* q,
     a.dbias_partial = partial + (size_t)a.NB * 2 * p.C * 81;
     a.B = p.B; a.H = p.H; a.W = p.W; a.C = p.C; a.heads = p.heads;
     a.n_strips = (p.H + R - 1) / R; a.n_ct = (p.W + TW - 1) / TW;
-    a.scale = 1.0f / sqrtf((float)D);
+    a.scale = p.logit_scale();
     if (bwd_dw_ring_supported(p) && fwd_ring_enabled()) {
         // the streaming form: work items are bands of rows of one batch item's head plane
         const int n_cu = device_cu_count();

@@ -520,10 +520,93 @@ static size_t bwd_partial_bytes(const Problem& p)
     return (part + 15) & ~(size_t)15;
 }
 
-size_t bwd_generic_workspace_bytes(const Problem& p)
+static size_t bwd_workspace_bytes_as_given(const Problem& p)
 {
     size_t per = (size_t)p.B * p.heads * p.S() * (size_t)p.plane() * sizeof(float);
     return 2 * per + bwd_partial_bytes(p) + (bwd_dkdv_mfma_supported(p) ? bwd_dkdv_mfma_image_bytes(p) + bwd_pixel_mfma_image_bytes(p) : 0);
+}
+
+// ---- heads narrower than 32 channels (bf16, 3x3 window; e.g. 24 channels per head, App. A)
+// The matrix-core backward kernels work on heads of 32 channels.  A narrower head is run
+// through them on copies padded with zero channels: q, k, v, dO and the kernels are copied into
+// the workspace with every head widened to 32 channels, the kernels run on the padded problem
+// with the logit scale of the true head size, and dq, dk, dv, dwk, dwv are copied back without
+// the padding (zero channels add nothing to logits, outputs or the other channels' gradients;
+// dbias needs no copy).  Costs two more passes over the activations, far less than the
+// general fp32 kernels these shapes ran on.
+constexpr int PAD_D = 32;
+static size_t pad_act_bytes(const Problem& p32)
+{
+    return (((size_t)p32.B * p32.C * (size_t)p32.plane() * 2) + 255) & ~(size_t)255;
+}
+static size_t pad_w_bytes(const Problem& p32)
+{
+    return (((size_t)p32.C * p32.S() * p32.S() * sizeof(float)) + 255) & ~(size_t)255;
+}
+// the padded problem, if this problem takes that path (decided from the shape alone)
+static bool bwd_padded_problem(const Problem& p, Problem& p32)
+{
+    if (p.dtype != 1 || p.ksize != 3 || p.heads < 1 || p.C % p.heads != 0) return false;
+    const int d = p.d();
+    if (d < 1 || d >= PAD_D) return false;
+    p32 = p;
+    p32.C = p.heads * PAD_D;
+    p32.scale_dim = d;
+    if ((long)p.B * p32.C >= (1L << 31) || (p.plane() * 2 + 4095) / 4096 > 65535) return false;   // grid of the copy kernels
+    return bwd_dkdv_mfma_supported(p32) && bwd_dw_mfma_supported(p32);
+}
+static size_t bwd_padded_workspace_bytes(const Problem& p32)
+{
+    const size_t inner = (bwd_workspace_bytes_as_given(p32) + 255) & ~(size_t)255;
+    return inner + 7 * pad_act_bytes(p32) + 4 * pad_w_bytes(p32);
+}
+
+size_t bwd_generic_workspace_bytes(const Problem& p)
+{
+    size_t need = bwd_workspace_bytes_as_given(p);
+    Problem p32;
+    if (bwd_padded_problem(p, p32)) {
+        const size_t padded = bwd_padded_workspace_bytes(p32);
+        if (padded > need) need = padded;       // (pointers that are not 16-byte aligned still take the general kernels)
+    }
+    return need;
+}
+
+struct PadArgs {
+    const uint4* src[4]; uint4* dst[4];         // tensors handled by one launch (blockIdx.z)
+    int heads, d_src, d_dst;                    // channels per head in src and dst
+    long chunks;                                // 16-byte chunks per channel plane
+};
+// dst[b][m * d_dst + j] = src[b][m * d_src + j] for j < min(d_src, d_dst); channels of dst past
+// d_src are zero.  One thread per 16-byte chunk of a dst channel plane.
+__global__ void __launch_bounds__(256)
+repack_heads_kernel(const PadArgs a)
+{
+    const long x = (long)blockIdx.y * 256 + threadIdx.x;
+    if (x >= a.chunks) return;
+    const int cd = blockIdx.x;                  // channel of dst, over B * heads * d_dst
+    const int per_item = a.heads * a.d_dst;
+    const int b = cd / per_item, r = cd - b * per_item;
+    const int m = r / a.d_dst, j = r - m * a.d_dst;
+    const int t = blockIdx.z;
+    uint4 val = make_uint4(0u, 0u, 0u, 0u);
+    if (j < a.d_src) val = a.src[t][((long)(b * a.heads + m) * a.d_src + j) * a.chunks + x];
+    a.dst[t][(long)cd * a.chunks + x] = val;
+}
+// the same for kernel tensors [C, S, S] float32 (n = S * S entries per channel), two tensors
+__global__ void __launch_bounds__(256)
+repack_kernels_kernel(const float* __restrict__ src0, const float* __restrict__ src1,
+                      float* __restrict__ dst0, float* __restrict__ dst1,
+                      int heads, int d_src, int d_dst, int n)
+{
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    const long total = (long)heads * d_dst * n;
+    if (e >= total) return;
+    const int c = (int)(e / n), i = (int)(e - (long)c * n);
+    const int m = c / d_dst, j = c - m * d_dst;
+    const float* src = blockIdx.y ? src1 : src0;
+    float* dst = blockIdx.y ? dst1 : dst0;
+    dst[e] = j < d_src ? src[((long)(m * d_src + j)) * n + i] : 0.0f;
 }
 
 // every activation pointer and the workspace are 16-byte aligned (vector loads)
@@ -615,6 +698,8 @@ static hipError_t launch_bwd_t(const Problem& p, const void* dout, const void* q
 
 int bwd_variant(const Problem& p, bool all_aligned16)
 {
+    Problem p32;
+    if (all_aligned16 && bwd_padded_problem(p, p32)) return 100 + bwd_variant(p32, true);
     const bool fast = bwd_dkdv_mfma_supported(p) && all_aligned16;
     if (!fast) return 10;
     const bool half_ws = bwd_dw_mfma_supported(p);
@@ -623,11 +708,64 @@ int bwd_variant(const Problem& p, bool all_aligned16)
            (bwd_dw_ring_supported(p) ? 4 : 0);
 }
 
+// the backward of heads narrower than 32 channels through the matrix-core kernels (see above)
+static hipError_t launch_bwd_padded(const Problem& p, const Problem& p32, const void* dout, const void* q,
+                                    const void* k, const void* v, const float* wk, const float* wv,
+                                    const float* bias, void* dq, void* dk, void* dv, float* dwk,
+                                    float* dwv, float* dbias, void* workspace, hipStream_t st)
+{
+    const size_t inner = (bwd_workspace_bytes_as_given(p32) + 255) & ~(size_t)255;
+    const size_t act = pad_act_bytes(p32), wb = pad_w_bytes(p32);
+    char* base = (char*)workspace + inner;
+    void* pin[4];                               // dO, q, k, v padded
+    void* pout[3];                              // dq, dk, dv padded
+    for (int i = 0; i < 4; ++i) pin[i] = base + (size_t)i * act;
+    for (int i = 0; i < 3; ++i) pout[i] = base + (size_t)(4 + i) * act;
+    float* wk32 = (float*)(base + 7 * act);
+    float* wv32 = (float*)(base + 7 * act + wb);
+    float* dwk32 = (float*)(base + 7 * act + 2 * wb);
+    float* dwv32 = (float*)(base + 7 * act + 3 * wb);
+    const int d = p.d(), n = p.S() * p.S();
+    const long chunks = p.plane() * 2 / 16;     // (W % 8 == 0: a channel plane is whole 16-byte chunks)
+    const unsigned gx = (unsigned)((chunks + 255) / 256);
+    {
+        PadArgs a{};
+        const void* src[4] = {dout, q, k, v};
+        for (int i = 0; i < 4; ++i) { a.src[i] = (const uint4*)src[i]; a.dst[i] = (uint4*)pin[i]; }
+        a.heads = p.heads; a.d_src = d; a.d_dst = PAD_D; a.chunks = chunks;
+        hipLaunchKernelGGL(repack_heads_kernel, dim3((unsigned)(p.B * p.heads * PAD_D), gx, 4), dim3(256), 0, st, a);
+    }
+    const unsigned gw = (unsigned)(((long)p.heads * PAD_D * n + 255) / 256);
+    hipLaunchKernelGGL(repack_kernels_kernel, dim3(gw, 2), dim3(256), 0, st, wk, wv, wk32, wv32, p.heads, d, PAD_D, n);
+    if (p.accumulate)                           // the sums continue from what dwk, dwv hold
+        hipLaunchKernelGGL(repack_kernels_kernel, dim3(gw, 2), dim3(256), 0, st, (const float*)dwk, (const float*)dwv,
+                           dwk32, dwv32, p.heads, d, PAD_D, n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_bwd_t<bf16_bits, 3>(p32, pin[0], pin[1], pin[2], pin[3], wk32, wv32, bias, pout[0], pout[1], pout[2],
+                                dwk32, dwv32, dbias, workspace, st);
+    if (e != hipSuccess) return e;
+    {
+        PadArgs a{};
+        void* dst[3] = {dq, dk, dv};
+        for (int i = 0; i < 3; ++i) { a.src[i] = (const uint4*)pout[i]; a.dst[i] = (uint4*)dst[i]; }
+        a.heads = p.heads; a.d_src = PAD_D; a.d_dst = d; a.chunks = chunks;
+        hipLaunchKernelGGL(repack_heads_kernel, dim3((unsigned)(p.B * p.heads * d), gx, 3), dim3(256), 0, st, a);
+    }
+    const unsigned gu = (unsigned)(((long)p.heads * d * n + 255) / 256);
+    hipLaunchKernelGGL(repack_kernels_kernel, dim3(gu, 2), dim3(256), 0, st, (const float*)dwk32, (const float*)dwv32,
+                       dwk, dwv, p.heads, PAD_D, d, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,
                               const void* v, const float* wk, const float* wv, const float* bias,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st)
 {
+    Problem p32;
+    if (bwd_padded_problem(p, p32) && aligned16({dout, q, k, v, dq, dk, dv, workspace}))
+        return launch_bwd_padded(p, p32, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias, workspace, st);
     SLIDE_DISPATCH(launch_bwd_t, p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias,
                    workspace, st);
 }

@@ -5,6 +5,7 @@
 #include <stddef.h>
 #include <stdint.h>
 #include <initializer_list>
+#include <cmath>
 #include <mutex>
 
 namespace slide {
@@ -18,7 +19,11 @@ struct Problem {
     int accumulate = 0;
     // activations are stored [B, H, W, C] (channels last) instead of [B, C, H, W]; forward only
     int nhwc = 0;
+    // channels per head that the logit scale 1/sqrt(d) is taken from when the tensors handed to
+    // the kernels carry heads padded to more channels (backward of heads narrower than 32); 0: d()
+    int scale_dim = 0;
     int d() const { return C / heads; }
+    float logit_scale() const { return 1.0f / sqrtf((float)(scale_dim ? scale_dim : d())); }
     int S() const { return ksize * ksize; }
     long plane() const { return (long)H * W; }
 };

@@ -200,6 +200,10 @@ def test_backward_variant_selection(lib):
     assert v(2, 13, 72, 32, 1, 3, 1, 1) == 20                      # wider than 64: tiled kernels
     assert v(50, 20, 40, 96, 3, 3, 1, 1) == 24                     # bands of 20 rows of 40 columns need too deep a ring: only the kernel gradients stream
     assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0: tiled kernels, general kernel-gradient part
+    assert v(128, 56, 56, 48, 2, 3, 1, 1) == 127                   # 24 channels per head: the streaming kernels on padded copies
+    assert v(128, 56, 56, 48, 2, 3, 1, 0) == 10                    # ... not from unaligned pointers
+    assert v(4, 13, 72, 16, 2, 3, 1, 1) == 120                     # 8 channels per head, wide map: the tiled kernels on padded copies
+    assert v(4, 13, 72, 128, 2, 3, 1, 1) == 10                     # 64 channels per head: general kernels
 
 
 def test_binding_rejects_mismatched_parameter_shapes(lib):

@@ -264,6 +264,54 @@ def test_forward_and_backward_random_streaming_shapes(shape):
         check(name, "bf16", got, want)
 
 
+# heads narrower than 32 channels (bf16, 3x3): the backward runs the matrix-core kernels on
+# copies padded to 32 channels per head (slide_attn_bwd_variant 100 + the variant of the padded problem)
+NARROW_HEAD_SHAPES = [
+    (2, 9, 40, 48, 2, 127),              # 24 channels per head (the head size of App. A's CSwin-like stages)
+    (3, 20, 56, 72, 3, 127),
+    (2, 14, 48, 16, 1, 127),             # 16
+    (1, 7, 32, 24, 3, 126),              # 8 (too narrow a map for the streaming dk/dv kernel)
+    (2, 13, 72, 48, 2, 120),             # wider than the streaming kernels take: tiled kernels
+    (5, 3, 56, 24, 1, 127),
+    (130, 5, 40, 48, 2, 127),            # 260 planes
+    (2, 9, 21, 48, 2, 120),              # W % 8 != 0: not this path's kernel-gradient kernel ... general kernels
+]
+
+
+@pytest.mark.parametrize("shape", NARROW_HEAD_SHAPES)
+def test_backward_narrow_heads(shape):
+    B, H, W, C, heads, variant = shape
+    print("narrow-head backward case", shape, flush=True)
+    got_variant = sa.slide_attn_bwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True)
+    if W % 8 != 0:
+        assert got_variant == 10
+    else:
+        assert got_variant == variant, got_variant
+    assert sa.slide_attn_bwd_variant(B, H, W, C, heads, 3, torch.bfloat16, False) == 10
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=1200 + H + W + C)
+    dev = g["q"].device
+    grads = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    torch.cuda.synchronize()
+    ref = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3)
+    for name, got, want in zip(GRAD_NAMES, grads, ref):
+        check(name, "bf16", got, want)
+    again = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    for a, b in zip(grads, again):
+        assert torch.equal(a, b)
+    # training form with accumulation: learned kernels in, a second call doubles the parameter gradients
+    wk_l, wv_l = d["wk_learned"].to(dev), d["wv_learned"].to(dev)
+    tb = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, 3)
+    for name, got, want in zip(GRAD_NAMES, tb, ref):
+        check(name, "bf16", got, want)                 # (learned kernels in: the gradients are those of the merged form)
+    first = [t.clone() for t in tb]
+    acc = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, 3,
+                                       outputs=tb, accumulate=True)
+    for idx in range(3):
+        assert torch.equal(acc[idx], first[idx])
+    for idx in range(3, 6):
+        assert torch.equal(acc[idx], 2 * first[idx])
+
+
 def test_backward_unaligned_gradient_buffers_take_the_tiled_kernels():
     """dq, dk, dv that start 2 bytes into an allocation: the streaming kernels, which store 16
     bytes per lane, are not used; the results are those of the aligned call."""
