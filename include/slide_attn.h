@@ -169,6 +169,25 @@ int slide_attn_bwd_two_branch(const void* dout, const void* q, const void* k, co
                               int B, int H, int W, int C, int heads, int ksize, int dtype,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Backward for channels-last activations (the layout of slide_attn_fwd_nhwc; the [B, HW, C]
+ * token tensors of window-attention blocks, App. A): dout, q, k, v and dq, dk, dv are
+ * [B,H,W,C] of `dtype`; kernels, bias and their gradients as in slide_attn_bwd.  The
+ * activations are turned into [B,C,H,W] copies in the workspace, the backward kernels of
+ * slide_attn_bwd run on those (same kernels, same results), and the three activation
+ * gradients are turned back.  two_branch != 0: wk, wv are the learned kernels (as in
+ * slide_attn_bwd_two_branch); accumulate as there.
+ * workspace: at least slide_attn_bwd_nhwc_workspace_bytes(...) bytes (0 for invalid
+ * arguments; host-only, no HIP call), 16-byte aligned.  Errors as slide_attn_bwd.
+ */
+size_t slide_attn_bwd_nhwc_workspace_bytes(int B, int H, int W, int C, int heads, int ksize, int dtype);
+int slide_attn_bwd_nhwc(const void* dout, const void* q, const void* k, const void* v,
+                        const float* wk, const float* wv, const float* bias,
+                        void* dq, void* dk, void* dv,
+                        float* dwk, float* dwv, float* dbias, int two_branch, int accumulate,
+                        int B, int H, int W, int C, int heads, int ksize, int dtype,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* slide_status_string(int status);
 

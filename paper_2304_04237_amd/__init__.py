@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     slide_attn_bwd,
+    slide_attn_bwd_nhwc,
     slide_attn_bwd_two_branch,
     slide_attn_fwd,
     slide_attn_fwd_nhwc,

@@ -56,6 +56,10 @@ def load_library():
     lib.slide_attn_fwd_shift.argtypes = [_vp] * 6 + [i] * 7 + [_vp]
     lib.slide_attn_fwd_nhwc.restype = i
     lib.slide_attn_fwd_nhwc.argtypes = [_vp] * 8 + [i] * 7 + [_vp]
+    lib.slide_attn_bwd_nhwc_workspace_bytes.restype = sz
+    lib.slide_attn_bwd_nhwc_workspace_bytes.argtypes = [i] * 7
+    lib.slide_attn_bwd_nhwc.restype = i
+    lib.slide_attn_bwd_nhwc.argtypes = [_vp] * 13 + [i] * 9 + [_vp, sz, _vp]
     lib.slide_attn_fwd_traffic_probe.restype = i
     lib.slide_attn_fwd_traffic_probe.argtypes = [_vp] * 4 + [i] * 6 + [_vp]
     lib.slide_attn_bwd.restype = i
@@ -229,6 +233,54 @@ def slide_attn_fwd_nhwc(q, k, v, wk, wv, bias, heads, ksize, out=None, lse=None)
                                               _dev(lse, "lse", torch.float32),
                                               B, H, W, C, heads, ksize, code, _stream()))
     return out
+
+
+def slide_attn_bwd_nhwc(dout, q, k, v, wk, wv, bias, heads, ksize, workspace=None, outputs=None,
+                        two_branch=False, accumulate=False):
+    """Backward for channels-last activations [B, H, W, C]: returns (dq, dk, dv, dwk, dwv, dbias),
+    the first three [B, H, W, C].  two_branch: wk, wv are the learned kernels; accumulate: the
+    parameter gradients are added to what `outputs` holds."""
+    lib = load_library()
+    if q.dim() != 4:
+        raise SlideAttnError("activations must be [B, H, W, C]")
+    B, H, W, C = q.shape
+    S = ksize * ksize
+    for t, n in ((wk, "wk"), (wv, "wv")):
+        if tuple(t.shape) != (C, S, ksize, ksize):
+            raise SlideAttnError("%s must be [C, k*k, k, k] = %s, got %s" % (n, (C, S, ksize, ksize), tuple(t.shape)))
+    if bias is not None and tuple(bias.shape) != (heads, S):
+        raise SlideAttnError("bias must be [heads, k*k] = %s, got %s" % ((heads, S), tuple(bias.shape)))
+    code = _dtype_code(q)
+    for t, n in ((k, "k"), (v, "v"), (dout, "dout")):
+        if t.shape != q.shape or t.dtype != q.dtype:
+            raise SlideAttnError("%s must match q in shape and dtype" % n)
+    if outputs is None:
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        dwk, dwv = torch.empty_like(wk), torch.empty_like(wv)
+        dbias = torch.empty_like(bias) if bias is not None else None
+    else:
+        dq, dk, dv, dwk, dwv, dbias = outputs
+        for t, n in ((dq, "dq"), (dk, "dk"), (dv, "dv")):
+            if t.shape != q.shape or t.dtype != q.dtype:
+                raise SlideAttnError("%s must match q in shape and dtype" % n)
+        for t, n, like in ((dwk, "dwk", wk), (dwv, "dwv", wv), (dbias, "dbias", bias)):
+            if (t is None) != (like is None) or (t is not None and t.shape != like.shape):
+                raise SlideAttnError("%s must have the shape of the parameter it is the gradient of" % n)
+    need = lib.slide_attn_bwd_nhwc_workspace_bytes(B, H, W, C, heads, ksize, code)
+    if workspace is None:
+        workspace = torch.empty(max(need, 1), dtype=torch.uint8, device=q.device)
+    elif not workspace.is_cuda:
+        raise SlideAttnError("workspace must live on the GPU")
+    _check(lib.slide_attn_bwd_nhwc(_dev(dout, "dout"), _dev(q, "q"), _dev(k, "k"), _dev(v, "v"),
+                                   _dev(wk, "wk", torch.float32), _dev(wv, "wv", torch.float32),
+                                   _dev(bias, "bias", torch.float32),
+                                   _dev(dq, "dq", q.dtype), _dev(dk, "dk", q.dtype), _dev(dv, "dv", q.dtype),
+                                   _dev(dwk, "dwk", torch.float32), _dev(dwv, "dwv", torch.float32),
+                                   _dev(dbias, "dbias", torch.float32),
+                                   int(bool(two_branch)), int(bool(accumulate)),
+                                   B, H, W, C, heads, ksize, code,
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()))
+    return dq, dk, dv, dwk, dwv, dbias
 
 
 def slide_attn_fwd_traffic_probe(q, k, v, out, heads, mode):

@@ -268,7 +268,7 @@ static int backward(const void* dout, const void* q, const void* k, const void* 
                     void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                     int B, int H, int W, int C, int heads, int ksize, int dtype,
                     int two_branch, int accumulate,
-                    void* workspace, size_t workspace_bytes, void* stream)
+                    void* workspace, size_t workspace_bytes, void* stream, bool nhwc = false)
 {
     int st = check_problem(B, H, W, C, heads, ksize, dtype);
     if (st != SLIDE_OK) return st;
@@ -285,10 +285,35 @@ static int backward(const void* dout, const void* q, const void* k, const void* 
     Problem p{B, H, W, C, heads, ksize, dtype};
     p.two_branch = two_branch;
     p.accumulate = accumulate != 0;
+    if (nhwc) {
+        if (!workspace || workspace_bytes < slide::bwd_nhwc_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
+        hipError_t en = slide::launch_bwd_nhwc(p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv,
+                                               dbias, workspace, (hipStream_t)stream);
+        return en == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+    }
     if (!workspace || workspace_bytes < slide::bwd_generic_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
     hipError_t e = slide::launch_bwd_generic(p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv,
                                              dbias, workspace, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
+}
+
+extern "C" size_t slide_attn_bwd_nhwc_workspace_bytes(int B, int H, int W, int C, int heads, int ksize, int dtype)
+{
+    if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
+    Problem p{B, H, W, C, heads, ksize, dtype};
+    return slide::bwd_nhwc_workspace_bytes(p);
+}
+
+extern "C" int slide_attn_bwd_nhwc(const void* dout, const void* q, const void* k, const void* v,
+                                   const float* wk, const float* wv, const float* bias,
+                                   void* dq, void* dk, void* dv,
+                                   float* dwk, float* dwv, float* dbias, int two_branch, int accumulate,
+                                   int B, int H, int W, int C, int heads, int ksize, int dtype,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return backward(dout, q, k, v, wk, wv, bias, nullptr, nullptr, dq, dk, dv, dwk, dwv, dbias,
+                    B, H, W, C, heads, ksize, dtype, two_branch != 0, accumulate, workspace, workspace_bytes,
+                    stream, true);
 }
 
 extern "C" int slide_attn_bwd(const void* dout, const void* q, const void* k, const void* v,

@@ -758,6 +758,147 @@ static hipError_t launch_bwd_padded(const Problem& p, const Problem& p32, const 
     return hipGetLastError();
 }
 
+// ---- channels-last backward.  The backward kernels work on [B, C, H, W]; activations stored
+// [B, H, W, C] (the [B, HW, C] token tensors of window-attention blocks, App. A) are turned into
+// that layout in the workspace, the backward runs on the copies, and dq, dk, dv are turned back.
+// Two more passes over the activations, as for the narrow heads above.
+struct RelayoutArgs {
+    const void* src[4]; void* dst[4];           // tensors of one launch (blockIdx.y)
+    int B, C;
+    long P;                                     // pixels per batch item
+    int c_tiles; long p_tiles;                  // tiles of 64 channels / 64 pixels
+};
+constexpr int RL_TILE = 64, RL_ROW = RL_TILE + 8;   // (rows of the LDS tile stay 16-byte aligned)
+// 2-byte elements, C % 8 == 0, P % 8 == 0, 16-byte aligned pointers: 16 bytes per thread on
+// both sides, a 64 x 64 tile transposed through LDS.  TO_PLANAR: [B, P, C] -> [B, C, P].
+template <bool TO_PLANAR>
+__global__ void __launch_bounds__(256)
+relayout16_kernel(const RelayoutArgs a)
+{
+    __shared__ __align__(16) uint16_t tile[RL_TILE * RL_ROW];
+    long tid_tile = blockIdx.x;
+    const long pt = tid_tile % a.p_tiles; tid_tile /= a.p_tiles;
+    const int ct = (int)(tid_tile % a.c_tiles);
+    const int b = (int)(tid_tile / a.c_tiles);
+    const long p0 = pt * RL_TILE;
+    const int c0 = ct * RL_TILE;
+    const uint16_t* src = (const uint16_t*)a.src[blockIdx.y];
+    uint16_t* dst = (uint16_t*)a.dst[blockIdx.y];
+    const long item = (long)b * a.C * a.P;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        // loads run along the contiguous axis of src: channels (TO_PLANAR) or pixels
+        const int outer = idx >> 3, chunk = idx & 7;
+        const long px = TO_PLANAR ? p0 + outer : p0 + 8 * chunk;
+        const int ch = TO_PLANAR ? c0 + 8 * chunk : c0 + outer;
+        if (px < a.P && ch < a.C) {
+            const uint16_t* at = TO_PLANAR ? src + item + px * a.C + ch : src + item + (long)ch * a.P + px;
+            const uint4 v = *(const uint4*)at;
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e)           // tile[contiguous index of dst's rows ...][...]: row = the axis dst keeps outermost
+                tile[(8 * chunk + e) * RL_ROW + outer] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int row = idx >> 3, chunk = idx & 7;     // row: channel (TO_PLANAR) or pixel of the tile
+        const long px = TO_PLANAR ? p0 + 8 * chunk : p0 + row;
+        const int ch = TO_PLANAR ? c0 + row : c0 + 8 * chunk;
+        if (px < a.P && ch < a.C) {
+            const uint4 v = *(const uint4*)(tile + row * RL_ROW + 8 * chunk);
+            uint16_t* at = TO_PLANAR ? dst + item + (long)ch * a.P + px : dst + item + px * a.C + ch;
+            *(uint4*)at = v;
+        }
+    }
+}
+// any element size and shape: one thread per element of dst
+template <typename E, bool TO_PLANAR>
+__global__ void __launch_bounds__(256)
+relayout_elem_kernel(const RelayoutArgs a)
+{
+    const long n = (long)a.B * a.C * a.P;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const E* src = (const E*)a.src[blockIdx.y];
+    E* dst = (E*)a.dst[blockIdx.y];
+    if (TO_PLANAR) {                                     // dst [B, C, P]
+        const long px = i % a.P; const long r = i / a.P;
+        const int c = (int)(r % a.C); const long b = r / a.C;
+        dst[i] = src[(b * a.P + px) * a.C + c];
+    } else {                                             // dst [B, P, C]
+        const int c = (int)(i % a.C); const long r = i / a.C;
+        const long px = r % a.P; const long b = r / a.P;
+        dst[i] = src[(b * a.C + c) * a.P + px];
+    }
+}
+
+static hipError_t launch_relayout(const Problem& p, const void* const* src, void* const* dst, int count,
+                                  bool to_planar, hipStream_t st)
+{
+    RelayoutArgs a{};
+    bool fast = p.dtype == 1 && p.C % 8 == 0 && p.plane() % 8 == 0;
+    for (int i = 0; i < count; ++i) {
+        a.src[i] = src[i]; a.dst[i] = dst[i];
+        fast = fast && (uintptr_t)src[i] % 16 == 0 && (uintptr_t)dst[i] % 16 == 0;
+    }
+    a.B = p.B; a.C = p.C; a.P = p.plane();
+    a.c_tiles = (p.C + RL_TILE - 1) / RL_TILE;
+    a.p_tiles = (a.P + RL_TILE - 1) / RL_TILE;
+    const long tiles = (long)p.B * a.c_tiles * a.p_tiles;
+    const long n = (long)p.B * p.C * a.P;
+    if (fast && tiles < (1L << 31)) {
+        if (to_planar) hipLaunchKernelGGL(relayout16_kernel<true>, dim3((unsigned)tiles, (unsigned)count), dim3(256), 0, st, a);
+        else           hipLaunchKernelGGL(relayout16_kernel<false>, dim3((unsigned)tiles, (unsigned)count), dim3(256), 0, st, a);
+    } else {
+        const long blocks = (n + 255) / 256;
+        if (blocks >= (1L << 31)) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)blocks, (unsigned)count);
+        if (p.dtype == 1) {
+            if (to_planar) hipLaunchKernelGGL((relayout_elem_kernel<uint16_t, true>), grid, dim3(256), 0, st, a);
+            else           hipLaunchKernelGGL((relayout_elem_kernel<uint16_t, false>), grid, dim3(256), 0, st, a);
+        } else {
+            if (to_planar) hipLaunchKernelGGL((relayout_elem_kernel<uint32_t, true>), grid, dim3(256), 0, st, a);
+            else           hipLaunchKernelGGL((relayout_elem_kernel<uint32_t, false>), grid, dim3(256), 0, st, a);
+        }
+    }
+    return hipGetLastError();
+}
+
+static size_t nhwc_act_bytes(const Problem& p)
+{
+    return (((size_t)p.B * p.C * (size_t)p.plane() * (p.dtype == 0 ? 4 : 2)) + 255) & ~(size_t)255;
+}
+
+size_t bwd_nhwc_workspace_bytes(const Problem& p)
+{
+    return ((bwd_generic_workspace_bytes(p) + 255) & ~(size_t)255) + 7 * nhwc_act_bytes(p);
+}
+
+hipError_t launch_bwd_nhwc(const Problem& p, const void* dout, const void* q, const void* k,
+                           const void* v, const float* wk, const float* wv, const float* bias,
+                           void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                           void* workspace, hipStream_t st)
+{
+    const size_t inner = (bwd_generic_workspace_bytes(p) + 255) & ~(size_t)255;
+    const size_t act = nhwc_act_bytes(p);
+    char* base = (char*)workspace + inner;
+    void* planar[7];                            // dO, q, k, v, dq, dk, dv as [B, C, H, W]
+    for (int i = 0; i < 7; ++i) planar[i] = base + (size_t)i * act;
+    const void* src[4] = {dout, q, k, v};
+    hipError_t e = launch_relayout(p, src, planar, 4, true, st);
+    if (e != hipSuccess) return e;
+    e = launch_bwd_generic(p, planar[0], planar[1], planar[2], planar[3], wk, wv, bias, planar[4], planar[5],
+                           planar[6], dwk, dwv, dbias, workspace, st);
+    if (e != hipSuccess) return e;
+    void* dst[3] = {dq, dk, dv};
+    const void* back[3] = {planar[4], planar[5], planar[6]};
+    return launch_relayout(p, back, dst, 3, false, st);
+}
+
 hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q, const void* k,
                               const void* v, const float* wk, const float* wv, const float* bias,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,

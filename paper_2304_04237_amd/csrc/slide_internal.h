@@ -70,6 +70,14 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
+// channels-last activations [B, H, W, C]: the backward on copies turned into [B, C, H, W] in the
+// workspace (p describes the problem without the layout flag)
+size_t bwd_nhwc_workspace_bytes(const Problem& p);
+hipError_t launch_bwd_nhwc(const Problem& p, const void* dout, const void* q, const void* k,
+                           const void* v, const float* wk, const float* wv, const float* bias,
+                           void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
+                           void* workspace, hipStream_t st);
+
 // which kernels launch_bwd_generic runs: 10 general, 20 tiled matrix-core kernels, + 1 with the
 // streaming dk/dv kernel, + 2 with the streaming per-pixel kernel, + 4 with the streaming form
 // of the kernel-gradient kernel; aligned16: every pointer is 16-byte aligned

@@ -86,3 +86,55 @@ def test_nhwc_forward_stage1_full_size():
         sl = slice(b, b + 1)
         refp = oracle.fwd(n["q"][sl], n["k"][sl], n["v"][sl], wkn, wvn, n["bias"], wl.heads, wl.ksize)
         assert np.abs(out[sl] - refp).max() <= 2e-2
+
+
+NHWC_BWD_SHAPES = [
+    (2, 9, 40, 64, 2, 3, "bf16"),        # streaming kernels behind the layout change
+    (3, 20, 56, 96, 3, 3, "bf16"),
+    (1, 13, 72, 32, 1, 3, "bf16"),       # tiled kernels
+    (2, 9, 40, 48, 2, 3, "bf16"),        # 24 channels per head: layout change, then the padded copies
+    (2, 7, 9, 20, 2, 3, "bf16"),         # C % 8 != 0, H*W % 8 != 0: element-wise layout change, general kernels
+    (1, 6, 7, 24, 3, 5, "f32"),
+    (2, 5, 8, 16, 2, 1, "f32"),
+    (40, 12, 56, 64, 2, 3, "bf16"),      # 430 tiles of the layout change
+]
+
+
+@pytest.mark.parametrize("shape", NHWC_BWD_SHAPES)
+def test_nhwc_backward_matches_oracle(shape):
+    """Channels-last backward against the oracle (which works on [B,C,H,W]: the test permutes),
+    bit-identical to the planar entry point on permuted tensors, two-branch form with accumulation."""
+    B, H, W, C, heads, ksize, dtype = shape
+    print("channels-last backward case", shape, flush=True)
+    d = synth.make_inputs(B, H, W, C, heads, ksize, dtype, seed=1300 + H + W + C, with_dout=True)
+    dev = torch.device("cuda:0")
+    planar = {n: d[n].to(dev).to(tdtype(dtype)) for n in ("q", "k", "v", "dout")}
+    g = {n: to_nhwc(planar[n]) for n in planar}
+    wk_l, wv_l = d["wk_learned"].to(dev), d["wv_learned"].to(dev)
+    wk, wv = sa.slide_reparam(wk_l), sa.slide_reparam(wv_l)
+    bias = d["bias"].to(dev)
+    grads = sa.slide_attn_bwd_nhwc(g["dout"], g["q"], g["k"], g["v"], wk, wv, bias, heads, ksize)
+    torch.cuda.synchronize()
+    n = {x: d[x].double().numpy() for x in ("q", "k", "v", "dout", "bias")}
+    ref = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], wk.double().cpu().numpy(), wv.double().cpu().numpy(),
+                     n["bias"], heads, ksize)
+    names = "dq dk dv dwk dwv dbias".split()
+    for i, name in enumerate(names):
+        got = grads[i].permute(0, 3, 1, 2) if i < 3 else grads[i]
+        assert i >= 3 or tuple(grads[i].shape) == (B, H, W, C)
+        check(name, dtype, got, ref[i])
+    # the planar entry point on the permuted tensors: same kernels, same bits
+    gp = sa.slide_attn_bwd(planar["dout"], planar["q"], planar["k"], planar["v"], wk, wv, bias, heads, ksize)
+    for i in range(6):
+        assert torch.equal(grads[i].permute(0, 3, 1, 2) if i < 3 else grads[i], gp[i]), names[i]
+    # learned kernels in, accumulation over two calls
+    tb = sa.slide_attn_bwd_nhwc(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, bias, heads, ksize, two_branch=True)
+    first = [t.clone() for t in tb]
+    for i, name in enumerate(names):
+        check(name, dtype, first[i].permute(0, 3, 1, 2) if i < 3 else first[i], ref[i])
+    acc = sa.slide_attn_bwd_nhwc(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, bias, heads, ksize, outputs=tb,
+                                 two_branch=True, accumulate=True)
+    for i in range(3):
+        assert torch.equal(acc[i], first[i])
+    for i in range(3, 6):
+        assert torch.equal(acc[i], 2 * first[i])
