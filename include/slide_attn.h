@@ -194,9 +194,9 @@ const char* slide_status_string(int status);
 /*
  * Which forward implementation slide_attn_fwd would run for this problem:
  * 0 = invalid arguments, 1 = general kernel (any supported ksize / head size /
- * dtype, float32 vector arithmetic), 2 = matrix-core kernel (bf16, d = 32,
- * ksize 3), 3 = matrix-core kernel for ksize 5 (bf16, d = 32).  Host-only; for
- * tests and benchmarks.
+ * dtype, float32 vector arithmetic), 2 = matrix-core kernel (bf16, ksize 3, d = 32, or
+ * d = 64 on maps the streaming kernel takes), 3 = matrix-core kernel for ksize 5 (bf16,
+ * d = 32).  For tests and benchmarks.
  */
 int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dtype);
 
@@ -207,7 +207,10 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
  * during the passes of the current one) with the tile width taken from its arguments / fixed
  * at 64, 24 = streaming ksize-3 kernel (a block walks down a band of rows, K/V rows in an LDS
  * ring; maps 32..64 columns wide; head size 32, or 24 with the fourth channel octet of every
- * head left empty), 30 = ksize-5 matrix-core kernel.  aligned16: whether
+ * head left empty), 25 = two launches of the streaming kernel for heads of 64 channels (each
+ * head as two halves of 32 whose shares of the logits cross the workspace; a call that brings
+ * less workspace than slide_attn_workspace_bytes says runs on the general kernel), 30 = ksize-5
+ * matrix-core kernel.  aligned16: whether
  * q, k, v, out, wk, wv are all 16-byte aligned (kernels 21, 23, 24 need that).  Launches
  * nothing; reads the compute-unit count of the current device (256 if there is none).
  */

@@ -71,6 +71,9 @@ extern "C" size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int hea
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
     if (backward) return slide::bwd_generic_workspace_bytes(p);
+    // heads of 64 channels: what the two-launch streaming forward exchanges (a caller that brings
+    // less gets the general kernel, which needs none)
+    if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, true)) return slide::fwd_ring_wide_workspace_bytes(p);
     return slide::fwd_mfma_supported(p) ? slide::fwd_mfma_workspace_bytes(p) : slide::fwd_mfma5_workspace_bytes(p);
 }
 
@@ -78,6 +81,7 @@ extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ks
 {
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
+    if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, true)) return 2;
     return slide::fwd_mfma_supported(p) ? 2 : (slide::fwd_mfma5_supported(p) ? 3 : 1);
 }
 
@@ -88,6 +92,7 @@ extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int
     Problem p{B, H, W, C, heads, ksize, dtype};
     if (slide::fwd_mfma_supported(p)) return slide::fwd_mfma_variant(p, aligned16 != 0);
     if (C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16 != 0)) return 24;
+    if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, aligned16 != 0)) return 25;
     return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
@@ -149,6 +154,11 @@ static int forward(const void* q, const void* k, const void* v,
         // head size 24 on the streaming matrix-core kernel (no workspace); every other problem of
         // that head size runs on the general kernel below
         e = slide::launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, false, (hipStream_t)stream);
+    } else if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, aligned16) && workspace &&
+               workspace_bytes >= slide::fwd_ring_wide_workspace_bytes(p) && aligned_to(workspace, 16)) {
+        // heads of 64 channels: two launches of the streaming kernel (without that much workspace:
+        // the general kernel below)
+        e = slide::launch_fwd_ring_wide(p, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
     } else if (slide::fwd_mfma_supported(p)) {
         if (!workspace || workspace_bytes < slide::fwd_mfma_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
@@ -182,7 +192,11 @@ extern "C" int slide_attn_fwd_noalloc(const void* q, const void* k, const void* 
     int st = check_problem(B, H, W, C, heads, ksize, dtype);
     if (st != SLIDE_OK) return st;
     if (!q || !k || !v || !wk || !wv || !out) return SLIDE_ERR_NULL;
-    const size_t need = slide_attn_workspace_bytes(B, H, W, C, heads, ksize, dtype, 0);
+    size_t need = slide_attn_workspace_bytes(B, H, W, C, heads, ksize, dtype, 0);
+    {   // (heads of 64 channels whose partial logits do not fit the scratch run on the general kernel, which needs none)
+        Problem pw{B, H, W, C, heads, ksize, dtype};
+        if (need > NOALLOC_SCRATCH_BYTES && slide::fwd_ring_wide_supported(pw, true)) need = 0;
+    }
     if (need > NOALLOC_SCRATCH_BYTES) return SLIDE_ERR_WORKSPACE;
     void* ws = nullptr;
     if (noalloc_scratch(&ws) != hipSuccess) {

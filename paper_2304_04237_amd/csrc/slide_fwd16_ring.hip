@@ -56,6 +56,7 @@ struct RingArgs {
     int off_raw, off_dummy, off_q, off_out, off_out2;   // LDS byte offsets: K/V landing slots, dump slot, q slots, per-wave result slots, the block's two result buffers
     uint32_t magic_w, magic_r;                 // ceil(2^32 / W), ceil(2^32 / R): x / W == umulhi(x, magic_w) for x < 2^26
     float scale_log2e, idw;
+    float* part;                               // heads of 64 channels (MODE 1, 2): partial logits of every half head, [B, 2 heads, 9, H, W], times scale_log2e
 };
 
 // RPG: most rows a group of new K/V rows can have (rows that one epoch is the first to read).
@@ -75,9 +76,17 @@ struct RingArgs {
 // depthwise kernel, so the shifted keys and values are the taps themselves).  No kernels are
 // read and no operand image is built; the matrix core only adds the 32 channel products of a
 // tap, and every lane holds all nine logits of its pixel.
+//
+// MODE: heads of 64 channels run as two half heads of 32 (the arguments then describe twice as
+// many heads; bias and lse are indexed by the pair) in two launches.  The logit of Eq. 2 is a
+// sum over the channels of the head, so MODE 1 only forms each half head's share of the nine
+// logits (key side; nothing else is computed or stored) and writes it to `part`; MODE 2 is the
+// whole kernel, which adds the other half's share to its own before the softmax: both halves
+// get the same attention weights, each applies them to its own 32 value channels.  MODE 0:
+// heads of DH channels, one launch.
 constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
 
-template <int RPG, bool LSE, bool PLAIN, int DH>
+template <int RPG, bool LSE, bool PLAIN, int DH, int MODE = 0>
 __global__ void __launch_bounds__(THREADS12)
 fwd16_ring_kernel(const RingArgs a)
 {
@@ -172,9 +181,10 @@ fwd16_ring_kernel(const RingArgs a)
     // ---- start-up.  The first access to a tensor takes microseconds (cold translation): the
     // bias is fetched first thing, next to the kernels, not where it is used.
     float bias_early = 0.0f;                                           // PLAIN: bias of shift `lane`; else the image's bias word of logit row `tid`
-    if (a.bias && !mover) {
-        if (PLAIN) { if (lane < S) bias_early = a.bias[m * S + lane]; }
-        else if (tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[m * S + shift_of_row(tid)];
+    const int mb = MODE ? m >> 1 : m;                                  // head that the bias and lse belong to
+    if (a.bias && !mover && MODE != 1) {
+        if (PLAIN) { if (lane < S) bias_early = a.bias[mb * S + lane]; }
+        else if (tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[mb * S + shift_of_row(tid)];
     }
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;                                                // mover: loads issued after group 0
@@ -343,7 +353,7 @@ fwd16_ring_kernel(const RingArgs a)
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int k = 0; k < RPG; ++k) raw[j][k] = read_row(slot_off(j, 0) + set_rd + k * SLOT);
-            if (e > 0) store_results(PX_EPOCH * (e - 1), out2_rd);       // (contains the wait for its LDS reads)
+            if (MODE != 1 && e > 0) store_results(PX_EPOCH * (e - 1), out2_rd);   // (contains the wait for its LDS reads)
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             // the epoch's round of loads: group e + 3 into the slots just read, q(e + 2) of two pass waves
 #pragma unroll
@@ -384,7 +394,7 @@ fwd16_ring_kernel(const RingArgs a)
             else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
             block_barrier();
         }
-        store_results(PX_EPOCH * (E - 1), out2_rd);
+        if (MODE != 1) store_results(PX_EPOCH * (E - 1), out2_rd);
         wait_vmem(0);                                                  // no load into this block's LDS outlives it
         return;
     }
@@ -396,7 +406,18 @@ fwd16_ring_kernel(const RingArgs a)
     const unsigned char* tap_base = smem + g * PS;
     const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
     int nb = 16 * wave;
-    float* lse_ptr = LSE ? a.lse + ((long)plane * H + y0) * W : nullptr;
+    float* lse_ptr = LSE ? a.lse + ((long)(MODE ? plane >> 1 : plane) * H + y0) * W : nullptr;
+    // MODE 1: this half head's share of the logits goes out; MODE 2: the other half's comes in,
+    // fetched one epoch ahead (lane (p, g) holds the shifts g, 4 + g, 8 + g of pixel p)
+    float* part_out = MODE == 1 ? a.part + (long)plane * S * HW + (long)y0 * W : nullptr;
+    const float* part_in = MODE == 2 ? a.part + (long)(plane ^ 1) * S * HW + (long)y0 * W : nullptr;
+    float oth[3] = {0.0f, 0.0f, 0.0f};
+    auto fetch_other = [&](int n_first) {
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            oth[r] = (n_first + p < npix && (r < 2 || g == 0)) ? part_in[(long)(4 * r + g) * HW + n_first + p] : 0.0f;
+    };
+    if (MODE == 2) fetch_other(nb);
     for (int e = 0; e < E; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
         if (p2 & 256u) {
@@ -464,19 +485,31 @@ fwd16_ring_kernel(const RingArgs a)
                     else       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
                 }
                 acc1 += acc1b;
+                if (MODE == 1) {
+                    if (nb + p < npix) {
+#pragma unroll
+                        for (int r = 0; r < 3; ++r)
+                            if (r < 2 || g == 0) part_out[(long)(4 * r + g) * HW + nb + p] = acc1[r] * a.scale_log2e;
+                    }
+                } else {
                 uint4_t vd[S];
 #pragma unroll
                 for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
                 float l[3];
 #pragma unroll
                 for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
+                if (MODE == 2) {
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) l[r] += oth[r];
+                    fetch_other(nb + PX_EPOCH);
+                }
                 const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
                 float pr[3];
 #pragma unroll
                 for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
                 const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
                 const float inv = __builtin_amdgcn_rcpf(den);
-                if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+                if (LSE) { if (g == 0 && nb + p < npix && (MODE != 2 || (m & 1) == 0)) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
                 uint2_t b2;
                 b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
                 b2[1] = pack_half(pr[2] * inv, 0.0f);
@@ -499,7 +532,9 @@ fwd16_ring_kernel(const RingArgs a)
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                }
             }
+            if (MODE != 1) {
             uint4_t ov;
 #pragma unroll
             for (int y = 0; y < 4; ++y) {
@@ -516,6 +551,7 @@ fwd16_ring_kernel(const RingArgs a)
             const uint2_t ra2 = lds_read_tr(o_slot + P0 * 64 + ((oct_s ^ ((P0 >> 2) & 3)) << 4) + (sa & 1) * 8);
             const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
             *(uint4_t*)(smem + out2_wr + st_c * OUT_ROW + (16 * wave + 8 * st_hh) * 2) = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
+            }
         }
         { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
         { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
@@ -1036,6 +1072,7 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf((float)a.d);
     a.idw = p.two_branch ? 1.0f : 0.0f;
+    a.part = nullptr;
     static LdsOptIn opt_in;
 #define SLIDE_RING_KERNELS2(RPGV, DHV)                                                                              \
     (const void*)fwd16_ring_kernel<RPGV, false, false, DHV>, (const void*)fwd16_ring_kernel<RPGV, true, false, DHV>, \
@@ -1072,6 +1109,68 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
 #undef SLIDE_RING_LAUNCH3
 #undef SLIDE_RING_LAUNCH4
 #undef SLIDE_RING_LAUNCH
+    return hipGetLastError();
+}
+
+// ---- heads of 64 channels (bf16, 3x3): two launches of the streaming kernel over half heads
+static Problem half_head_problem(const Problem& p)
+{
+    Problem h = p;
+    h.heads = 2 * p.heads;                      // same C: 32 channels per (half) head
+    return h;
+}
+
+bool fwd_ring_wide_supported(const Problem& p, bool aligned16)
+{
+    if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * 64) return false;
+    if ((long)p.H * p.W * 2 * f16ring::D >= (1L << 31)) return false;
+    if ((long)p.B * p.heads * 2 * 9 * p.H * p.W >= (1L << 31)) return false;   // index arithmetic of the partial logits
+    return f16ring::plan_ring(half_head_problem(p)).ok;
+}
+
+size_t fwd_ring_wide_workspace_bytes(const Problem& p)
+{
+    return (size_t)p.B * p.heads * 2 * 9 * (size_t)p.plane() * sizeof(float);
+}
+
+hipError_t launch_fwd_ring_wide(const Problem& p, const void* q, const void* k, const void* v,
+                                const float* wk, const float* wv, const float* bias, void* out,
+                                float* lse, void* workspace, hipStream_t st)
+{
+    using namespace f16ring;
+    const Problem h = half_head_problem(p);
+    const RingPlan r = plan_ring(h);
+    if (!r.ok) return hipErrorInvalidValue;
+    RingArgs a;
+    a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.out = (bf16_bits*)out; a.lse = lse;
+    a.wk = wk; a.wv = wv; a.bias = bias;
+    a.B = h.B; a.H = h.H; a.W = h.W; a.C = h.C; a.heads = h.heads; a.d = D;
+    a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out; a.off_out2 = r.off_out2;
+    a.magic_w = (uint32_t)(((1ULL << 32) + h.W - 1) / h.W);
+    a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
+    a.scale_log2e = 1.44269504088896341f / sqrtf(64.0f);               // (the head has 64 channels)
+    a.idw = p.two_branch ? 1.0f : 0.0f;
+    a.part = (float*)workspace;
+    static LdsOptIn opt_in;
+#define SLIDE_WIDE_KERNELS(RPGV)                                                                                    \
+    (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 1>, (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 2>, \
+    (const void*)fwd16_ring_kernel<RPGV, true, false, 32, 2>
+    hipError_t e = opt_in.ensure({SLIDE_WIDE_KERNELS(2), SLIDE_WIDE_KERNELS(3), SLIDE_WIDE_KERNELS(4)}, LDS_LIMIT);
+#undef SLIDE_WIDE_KERNELS
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
+#define SLIDE_WIDE_LAUNCH(RPGV)                                                                                     \
+    do {                                                                                                            \
+        hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false, false, 32, 1>), grid, block12, (size_t)r.lds_bytes, st, a); \
+        if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true, false, 32, 2>), grid, block12, (size_t)r.lds_bytes, st, a);  \
+        else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false, false, 32, 2>), grid, block12, (size_t)r.lds_bytes, st, a); \
+    } while (0)
+    if (r.rpg == 2) SLIDE_WIDE_LAUNCH(2);
+    else if (r.rpg == 3) SLIDE_WIDE_LAUNCH(3);
+    else SLIDE_WIDE_LAUNCH(4);
+#undef SLIDE_WIDE_LAUNCH
     return hipGetLastError();
 }
 

@@ -159,6 +159,15 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
 struct RingRows { int nbp, rows_pb, n_blocks, R, rpg; bool ok; };
 RingRows plan_ring_rows(const Problem& p, int nw, int per_cu);
 
+// heads of 64 channels on the streaming forward (bf16, ksize 3, maps the streaming kernel
+// takes): two launches over half heads, the halves' shares of the logits exchanged through the
+// workspace (fwd_ring_wide_workspace_bytes, 16-byte aligned)
+bool fwd_ring_wide_supported(const Problem& p, bool aligned16);
+size_t fwd_ring_wide_workspace_bytes(const Problem& p);
+hipError_t launch_fwd_ring_wide(const Problem& p, const void* q, const void* k, const void* v,
+                                const float* wk, const float* wv, const float* bias, void* out,
+                                float* lse, void* workspace, hipStream_t st);
+
 // the streaming kernel for channels-last activations (Problem::nhwc): bf16, d == 32, ksize 3,
 // 32 <= W <= 64, W % 8 == 0, every pointer 16-byte aligned; needs no workspace
 bool fwd_ring_nhwc_supported(const Problem& p, bool aligned16);

@@ -462,6 +462,47 @@ def test_forward_kernel_variants_match_oracle(shape):
     check("lse", "bf16", lse, ref_lse)
 
 
+# heads of 64 channels (the head size of the PVT-style stages of App. A): two launches of the
+# streaming forward over half heads (slide_attn_fwd_variant 25)
+WIDE_HEAD_SHAPES = [
+    (2, 9, 40, 64, 1, 25),
+    (3, 20, 56, 128, 2, 25),
+    (4, 56, 56, 64, 1, 25),              # the stage-1 map
+    (1, 1, 56, 64, 1, 25),
+    (5, 33, 32, 128, 2, 25),
+    (130, 5, 48, 64, 1, 25),
+    (2, 13, 72, 64, 1, 10),              # wider than the streaming kernel takes: general kernel
+    (2, 9, 21, 64, 1, 10),
+]
+
+
+@pytest.mark.parametrize("shape", WIDE_HEAD_SHAPES)
+def test_forward_heads_of_64_channels(shape):
+    B, H, W, C, heads, variant = shape
+    print("wide-head forward case", shape, flush=True)
+    assert sa.slide_attn_fwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True) == variant
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=1400 + H + W + C)
+    dev = g["q"].device
+    lse = torch.full((B, heads, H, W), float("nan"), dtype=torch.float32, device=dev)
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, lse=lse)
+    out_nl = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out_nl)
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3, return_lse=True)
+    check("out", "bf16", out, ref)
+    check("lse", "bf16", lse, ref_lse)
+    # no bias; learned kernels in (training form)
+    out0 = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], None, heads, 3)
+    check("out(no bias)", "bf16", out0, oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], None, heads, 3))
+    out2 = sa.slide_attn_fwd_two_branch(g["q"], g["k"], g["v"], d["wk_learned"].to(dev), d["wv_learned"].to(dev),
+                                        g["bias"], heads, 3)
+    check("out(two-branch)", "bf16", out2, ref)
+    # a caller without workspace for the partial logits gets the general kernel: same result within the tolerance
+    small = torch.empty(16, dtype=torch.uint8, device=dev)
+    out_g = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, workspace=small)
+    check("out(general kernel)", "bf16", out_g, ref)
+
+
 def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
     assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 24
