@@ -184,6 +184,11 @@ def test_forward_variant_selection(lib):
     # many small planes: enough tiles, but a tile buffer too small to build the operand image in
     assert v(128, 8, 8, 128, 4, 3, 1, 1) == 20
     assert v(256, 2, 64, 64, 2, 3, 1, 1) == 24                     # two-row planes: streaming kernel
+    assert v(64, 56, 56, 64, 1, 3, 1, 1) == 25                     # one head of 64 channels: two launches over half heads
+    assert v(64, 56, 56, 64, 1, 3, 1, 0) == 10                     # ... not from unaligned pointers
+    assert v(8, 100, 128, 64, 1, 3, 1, 1) == 10                    # ... nor on a map the streaming kernel does not take
+    assert lib.slide_attn_workspace_bytes(64, 56, 56, 64, 1, 3, 1, 0) == 64 * 2 * 9 * 56 * 56 * 4   # the halves' partial logits
+    assert lib.slide_attn_fwd_path(64, 56, 56, 64, 1, 3, 1) == 2
 
 
 def test_backward_variant_selection(lib):
