@@ -186,6 +186,7 @@ fwd16_ring_kernel(const RingArgs a)
         if (PLAIN) { if (lane < S) bias_early = a.bias[mb * S + lane]; }
         else if (tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[mb * S + shift_of_row(tid)];
     }
+    constexpr int NJ = MODE == 1 ? 1 : 2;                               // tensors a mover stages: K, and V unless only logits are formed
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;                                                // mover: loads issued after group 0
     if (!PLAIN && !mover) {
@@ -207,7 +208,7 @@ fwd16_ring_kernel(const RingArgs a)
         for (int k = 0; k <= v0; ++k) {                                // group 0 (at most RPG + 2 rows)
             const int gy = y0 - 1 + k;
             if (gy >= 0 && gy < H)
-                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+                for (int j = 0; j < NJ; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
         }
         for (int i = 0; i < 2; ++i) {
             load_q(2 * mv + i, 16 * (2 * mv + i), 0);
@@ -217,8 +218,8 @@ fwd16_ring_kernel(const RingArgs a)
         for (int k = 0; k < v1 - v0; ++k) {                            // group 1 into set 1
             const int gy = y0 + v0 + k;
             if (gy >= 0 && gy < H) {
-                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
-                n_after_g0 += 2;
+                for (int j = 0; j < NJ; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
+                n_after_g0 += NJ;
             }
         }
     }
@@ -256,13 +257,13 @@ fwd16_ring_kernel(const RingArgs a)
         }
     };
     if (DH < D) zero_q_rows(tid, 2 * WAVES, THREADS12, 0, 2);
-    constexpr int NL = 2 * RPG + 2;                                    // loads of a mover per epoch
+    constexpr int NL = NJ * RPG + 2;                                   // loads of a mover per epoch
     if (mover) {
         wait_vmem(n_after_g0);                                         // group 0 has landed
         for (int k = 0; k <= v0; ++k) {                                // group 0 -> ring rows 0 .. v0
             RawRow r0[2];
-            for (int j = 0; j < 2; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
-            for (int j = 0; j < 2; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
+            for (int j = 0; j < NJ; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+            for (int j = 0; j < NJ; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
         if (DH < D) {                                                 // third q slots of pass waves 2 mv, 2 mv + 1
@@ -277,7 +278,7 @@ fwd16_ring_kernel(const RingArgs a)
         for (int k = 0; k < RPG; ++k) {
             const int gy = y0 + v1 + k;
             const bool real = k < v2 - v1 && gy >= 0 && gy < H;
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
                 load_row(j, (uint32_t)min(max(gy, 0), H - 1) * w2, real ? slot_off(j, k) : a.off_dummy);
         }
         load_q(0, npix, 0);
@@ -350,7 +351,7 @@ fwd16_ring_kernel(const RingArgs a)
             // group e + 1 has landed (waited for at the end of the previous epoch): fetch it
             RawRow raw[2][RPG];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int k = 0; k < RPG; ++k) raw[j][k] = read_row(slot_off(j, 0) + set_rd + k * SLOT);
             if (MODE != 1 && e > 0) store_results(PX_EPOCH * (e - 1), out2_rd);   // (contains the wait for its LDS reads)
@@ -360,7 +361,7 @@ fwd16_ring_kernel(const RingArgs a)
             for (int k = 0; k < RPG; ++k) {
                 const bool real = (cvB >> (17 + k)) & 1u;
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NJ; ++j)
                     load_row(j, real ? ldo + (uint32_t)k * w2 : ldo, real ? slot_off(j, 0) + set_rd + k * SLOT : a.off_dummy);
             }
 #pragma unroll
@@ -373,7 +374,7 @@ fwd16_ring_kernel(const RingArgs a)
                     const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
                     if (k < cnt) {
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) write_row_in_map(j, pos, raw[j][k]);
+                        for (int j = 0; j < NJ; ++j) write_row_in_map(j, pos, raw[j][k]);
                     }
                 }
             } else {
@@ -382,14 +383,16 @@ fwd16_ring_kernel(const RingArgs a)
                     const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
                     if (k < cnt) {
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) write_row(j, pos, !((cvB >> (13 + k)) & 1u), raw[j][k]);
+                        for (int j = 0; j < NJ; ++j) write_row(j, pos, !((cvB >> (13 + k)) & 1u), raw[j][k]);
                     }
                 }
             }
             set_rd = RPG * SLOT - set_rd;
             { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
             { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
-            if (NL == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            if (NL == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else if (NL == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+            else if (NL == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             else if (NL == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(10)" ::: "memory");
             block_barrier();
