@@ -229,6 +229,10 @@ int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int ksize, int
  * e.g. 24 channels per head): the kernels of variant v run on copies of q, k, v, dO and the
  * kernels padded with zero channels to 32 per head, made in the workspace (which is that much
  * larger for these shapes), with the logit scale of the true head size.
+ * 200 + v: heads of 64 channels (bf16, ksize 3, maps the streaming per-pixel kernel takes, 16-byte
+ * aligned pointers): every head runs as two half heads of 32 through the kernels of variant v;
+ * the per-pixel part takes two launches, which exchange the halves' shares of the logits and of
+ * the attention gradient through the workspace.
  * aligned16: whether every activation, gradient and workspace pointer is 16-byte aligned.
  * Launches nothing; reads the compute-unit count of the current device (256 if there is none).
  */

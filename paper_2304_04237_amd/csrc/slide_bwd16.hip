@@ -253,7 +253,7 @@ constexpr float G_SCALE = 0.0625f, W_SCALE = 16.0f;
 
 __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk, const float* __restrict__ wv,
                                                    const float* __restrict__ bias, uint32_t* __restrict__ image,
-                                                   int t, int m, float idw)
+                                                   int t, int m, float idw, int bias_shift)
 {
     uint32_t* img = image + (long)m * PX_IMG_DWORDS;
     const int tid = threadIdx.x;
@@ -293,7 +293,7 @@ __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk,
     if (t == 0 && tid < 16) {
         const int s = shift_of_row(tid);
         float b = -INFINITY;
-        if (s >= 0) b = bias ? bias[m * S + s] * 1.44269504088896341f : 0.0f;
+        if (s >= 0) b = bias ? bias[(m >> bias_shift) * S + s] * 1.44269504088896341f : 0.0f;
         img[PX_BIAS + tid] = __float_as_uint(b);
     }
 }
@@ -303,9 +303,10 @@ __device__ __forceinline__ void prep_pixel_weights(const float* __restrict__ wk,
 __global__ void __launch_bounds__(256)
 prep_bwd_weights_kernel(const float* __restrict__ wk, const float* __restrict__ wv,
                         const float* __restrict__ bias, uint32_t* __restrict__ pixel_image,
-                        uint32_t* __restrict__ dkdv_image, float idw)
+                        uint32_t* __restrict__ dkdv_image, float idw, int bias_shift)
 {
-    if (blockIdx.z == 0) prep_pixel_weights(wk, wv, bias, pixel_image, blockIdx.x, blockIdx.y, idw);
+    // (bias_shift 1: the heads are half heads of 64-channel heads, a pair shares a bias row)
+    if (blockIdx.z == 0) prep_pixel_weights(wk, wv, bias, pixel_image, blockIdx.x, blockIdx.y, idw, bias_shift);
     else                 prep_dkdv_weights(wk, wv, dkdv_image, blockIdx.x, blockIdx.y, idw);
 }
 
@@ -542,17 +543,25 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p)
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 void* dkdv_image_ws, bool streaming, hipStream_t st)
+                                 void* dkdv_image_ws, bool streaming, hipStream_t st, float* part)
 {
     using namespace b16path;
     const TilePlan t = plan_tiles(p, LDS_LIMIT / 2, 64, 64);
     uint32_t* image = (uint32_t*)image_ws;
     hipLaunchKernelGGL(prep_bwd_weights_kernel, dim3(S, (unsigned)p.heads, 2), dim3(256), 0, st,
-                       wk, wv, bias, image, (uint32_t*)dkdv_image_ws, p.two_branch ? 1.0f : 0.0f);
+                       wk, wv, bias, image, (uint32_t*)dkdv_image_ws, p.two_branch ? 1.0f : 0.0f, part ? 1 : 0);
+    if (part) {
+        // half heads of 64-channel heads: the shares of logits and da first, then the whole kernel
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess || !streaming) return e0 != hipSuccess ? e0 : hipErrorInvalidValue;
+        e0 = launch_bwd_pixel_ring(p, dout, q, k, v, dq, attn_ws, dl_ws, image, st, 1, part);
+        if (e0 != hipSuccess) return e0;
+        return launch_bwd_pixel_ring(p, dout, q, k, v, dq, attn_ws, dl_ws, image, st, 2, part);
+    }
     if (streaming) {
         hipError_t e0 = hipGetLastError();
         if (e0 != hipSuccess) return e0;
-        return launch_bwd_pixel_ring(p, dout, q, k, v, dq, attn_ws, dl_ws, image, st);
+        return launch_bwd_pixel_ring(p, dout, q, k, v, dq, attn_ws, dl_ws, image, st, 0, nullptr);
     }
     PixelArgs a;
     a.dout = (const bf16_bits*)dout; a.q = (const bf16_bits*)q;

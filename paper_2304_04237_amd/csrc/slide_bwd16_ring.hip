@@ -501,9 +501,16 @@ struct PixelArgs {
     int off_raw, off_dummy, off_q, off_do, off_out, off_a1v;   // LDS byte offsets: K/V landing slots, dump slot, q slots and dO slots (2 KB per pass wave each), result slots, V-kernel operands
     uint32_t magic_w, magic_r;
     float scale, scale_log2e;
+    float* part;                               // heads of 64 channels (MODE 1, 2): every half head's share of the logits (times scale_log2e) and of da, [B, 2 heads, 2, 9, H, W]
 };
 
-template <int RPG>
+// MODE: heads of 64 channels run as two half heads of 32 (the arguments describe twice as many
+// heads).  Logits and da are sums over the channels of the whole head: MODE 1 forms each half's
+// share of both and writes them to `part`, nothing else; MODE 2 is the whole kernel with the
+// other half's shares added in, so both halves arrive at the same a and dl (each writes its
+// copy, which the other two backward kernels read per half head) and each forms dq of its own
+// 32 channels.  MODE 0: heads of 32 channels, one launch.
+template <int RPG, int MODE = 0>
 __global__ void __launch_bounds__(THREADS)
 bwd16_ring_pixel_kernel(const PixelArgs a)
 {
@@ -722,10 +729,19 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
     _Float16* dl_base = a.dl + (long)plane * S * HW + (long)y0 * W;
     const int q_rd = (8 * g + (p >> 2)) * 32 + (p & 3) * 8;            // the lane's piece of a [32 channels][16 pixels] slot
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    // lane (p, g) holds the shifts g, 4 + g, 8 + g of pixel p
+    float* part_out = MODE == 1 ? a.part + (long)plane * 2 * S * HW + (long)y0 * W : nullptr;
+    const float* part_in = MODE == 2 ? a.part + (long)(plane ^ 1) * 2 * S * HW + (long)y0 * W : nullptr;
     int nb = 16 * wave;
     for (int e = 0; e < E; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
         if (p2 & 256u) {
+            float oth_l[3] = {0.0f, 0.0f, 0.0f}, oth_da[3] = {0.0f, 0.0f, 0.0f};
+            if (MODE == 2) {                                            // (used after the first chain of products)
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+                    oth_l[r] = (nb + p < npix && (r < 2 || g == 0)) ? part_in[(long)(4 * r + g) * HW + nb + p] : 0.0f;
+            }
             const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
             const int cx0 = (int)(p2 & 255u) + p;
             const bool next_row = cx0 >= W;
@@ -763,12 +779,22 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             float l[3], pr[3];
 #pragma unroll
             for (int r = 0; r < 3; ++r) l[r] = fmaf(acc[r], a.scale_log2e, bias2[r]);
+            if (MODE == 2) {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) l[r] += oth_l[r];
+            }
+            const float lg_own[3] = {acc[0] * a.scale_log2e, acc[1] * a.scale_log2e, acc[2] * a.scale_log2e};
             const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
 #pragma unroll
             for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
             const float inv = __builtin_amdgcn_rcpf(allsum_groups(pr[0] + pr[1] + pr[2]));
 #pragma unroll
             for (int r = 0; r < 3; ++r) pr[r] *= inv;
+            if (MODE == 2) {                                            // (used after the second chain; fetched here: no registers to hold it earlier)
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+                    oth_da[r] = (nb + p < npix && (r < 2 || g == 0)) ? part_in[(long)(S + 4 * r + g) * HW + nb + p] : 0.0f;
+            }
             // ---- da[s] = dO . Vs[s], then dl
             xs[0] = as_half2(bf16x2_to_half2(d0[0])) * sc; xs[1] = as_half2(bf16x2_to_half2(d0[1])) * sc;
             xs[2] = as_half2(bf16x2_to_half2(d1[0])) * sc; xs[3] = as_half2(bf16x2_to_half2(d1[1])) * sc;
@@ -783,6 +809,21 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
                 else       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1v, __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
             }
             acc += accb;
+            if (MODE == 1) {
+                if (nb + p < npix) {
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        if (r < 2 || g == 0) {
+                            part_out[(long)(4 * r + g) * HW + nb + p] = lg_own[r];
+                            part_out[(long)(S + 4 * r + g) * HW + nb + p] = acc[r];
+                        }
+                    }
+                }
+            } else {
+            if (MODE == 2) {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) acc[r] += oth_da[r];
+            }
             // k taps again for the dq step
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -843,6 +884,7 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             const uint2_t rb2 = lds_read_tr(o_slot + P1 * 64 + ((oct_s ^ ((P1 >> 2) & 3)) << 4) + (sa & 1) * 8);
             const int n0 = nb + 8 * st_hh;
             if (n0 < npix) *(uint4_t*)(dq_base + (uint32_t)n0 * 2u) = uint4_t{ra2[0], ra2[1], rb2[0], rb2[1]};
+            }
         }
         nb += PX_EPOCH;
         block_barrier();
@@ -926,7 +968,7 @@ bool bwd_pixel_ring_supported(const Problem& p, bool aligned16)
 
 hipError_t launch_bwd_pixel_ring(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, void* dq, void* attn_ws, void* dl_ws,
-                                 const void* image_ws, hipStream_t st)
+                                 const void* image_ws, hipStream_t st, int mode, float* part)
 {
     using namespace b16ring;
     const PixelPlan r = plan_pixel(p);
@@ -944,14 +986,25 @@ hipError_t launch_bwd_pixel_ring(const Problem& p, const void* dout, const void*
     a.magic_r = (uint32_t)(((1ULL << 32) + r.rr.R - 1) / r.rr.R);
     a.scale = p.logit_scale();
     a.scale_log2e = 1.44269504088896341f * p.logit_scale();
+    a.part = part;
+    if (mode < 0 || mode > 2 || (mode != 0 && !part)) return hipErrorInvalidValue;
     static LdsOptIn opt_in;
-    hipError_t e = opt_in.ensure({(const void*)bwd16_ring_pixel_kernel<2>, (const void*)bwd16_ring_pixel_kernel<3>,
-                                  (const void*)bwd16_ring_pixel_kernel<4>}, t16::LDS_LIMIT);
+#define SLIDE_PX_KERNELS(RPGV) (const void*)bwd16_ring_pixel_kernel<RPGV, 0>, (const void*)bwd16_ring_pixel_kernel<RPGV, 1>, \
+                               (const void*)bwd16_ring_pixel_kernel<RPGV, 2>
+    hipError_t e = opt_in.ensure({SLIDE_PX_KERNELS(2), SLIDE_PX_KERNELS(3), SLIDE_PX_KERNELS(4)}, t16::LDS_LIMIT);
+#undef SLIDE_PX_KERNELS
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)r.rr.n_blocks), block(THREADS);
-    if (r.rr.rpg == 2) hipLaunchKernelGGL(bwd16_ring_pixel_kernel<2>, grid, block, (size_t)r.lds_bytes, st, a);
-    else if (r.rr.rpg == 3) hipLaunchKernelGGL(bwd16_ring_pixel_kernel<3>, grid, block, (size_t)r.lds_bytes, st, a);
-    else hipLaunchKernelGGL(bwd16_ring_pixel_kernel<4>, grid, block, (size_t)r.lds_bytes, st, a);
+#define SLIDE_PX_LAUNCH(RPGV)                                                                                      \
+    do {                                                                                                           \
+        if (mode == 0)      hipLaunchKernelGGL((bwd16_ring_pixel_kernel<RPGV, 0>), grid, block, (size_t)r.lds_bytes, st, a); \
+        else if (mode == 1) hipLaunchKernelGGL((bwd16_ring_pixel_kernel<RPGV, 1>), grid, block, (size_t)r.lds_bytes, st, a); \
+        else                hipLaunchKernelGGL((bwd16_ring_pixel_kernel<RPGV, 2>), grid, block, (size_t)r.lds_bytes, st, a); \
+    } while (0)
+    if (r.rr.rpg == 2) SLIDE_PX_LAUNCH(2);
+    else if (r.rr.rpg == 3) SLIDE_PX_LAUNCH(3);
+    else SLIDE_PX_LAUNCH(4);
+#undef SLIDE_PX_LAUNCH
     return hipGetLastError();
 }
 

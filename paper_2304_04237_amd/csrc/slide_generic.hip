@@ -561,6 +561,9 @@ static size_t bwd_padded_workspace_bytes(const Problem& p32)
     return inner + 7 * pad_act_bytes(p32) + 4 * pad_w_bytes(p32);
 }
 
+static bool bwd_wide_problem(const Problem& p, Problem& h);      // heads of 64 channels, below
+static size_t bwd_wide_workspace_bytes(const Problem& h);
+
 size_t bwd_generic_workspace_bytes(const Problem& p)
 {
     size_t need = bwd_workspace_bytes_as_given(p);
@@ -568,6 +571,11 @@ size_t bwd_generic_workspace_bytes(const Problem& p)
     if (bwd_padded_problem(p, p32)) {
         const size_t padded = bwd_padded_workspace_bytes(p32);
         if (padded > need) need = padded;       // (pointers that are not 16-byte aligned still take the general kernels)
+    }
+    Problem h;
+    if (bwd_wide_problem(p, h)) {
+        const size_t wide = bwd_wide_workspace_bytes(h);
+        if (wide > need) need = wide;
     }
     return need;
 }
@@ -700,6 +708,7 @@ int bwd_variant(const Problem& p, bool all_aligned16)
 {
     Problem p32;
     if (all_aligned16 && bwd_padded_problem(p, p32)) return 100 + bwd_variant(p32, true);
+    if (all_aligned16 && bwd_wide_problem(p, p32)) return 200 + bwd_variant(p32, true);
     const bool fast = bwd_dkdv_mfma_supported(p) && all_aligned16;
     if (!fast) return 10;
     const bool half_ws = bwd_dw_mfma_supported(p);
@@ -755,6 +764,74 @@ static hipError_t launch_bwd_padded(const Problem& p, const Problem& p32, const 
     const unsigned gu = (unsigned)(((long)p.heads * d * n + 255) / 256);
     hipLaunchKernelGGL(repack_kernels_kernel, dim3(gu, 2), dim3(256), 0, st, (const float*)dwk32, (const float*)dwv32,
                        dwk, dwv, p.heads, PAD_D, d, n);
+    return hipGetLastError();
+}
+
+// ---- heads of 64 channels (bf16, 3x3 window, maps the streaming per-pixel kernel takes)
+// The matrix-core kernels work on heads of 32 channels.  Given the attention weights a and the
+// logit gradients dl, the key, value and kernel gradients are separate per channel, so a head of
+// 64 runs through them as two half heads; only the per-pixel part sums over the whole head
+// (logits and da), which its streaming kernel does in two launches that exchange the halves'
+// shares (launch_bwd_pixel_ring, modes 1 and 2).  Both halves write their own copy of a and dl;
+// the bias gradient comes out once per half head and the first of each pair is kept.
+static bool bwd_wide_problem(const Problem& p, Problem& h)
+{
+    if (p.dtype != 1 || p.ksize != 3 || p.C != p.heads * 64 || !fwd_ring_enabled()) return false;
+    h = p;
+    h.heads = 2 * p.heads;
+    h.scale_dim = 64;
+    if ((long)p.B * h.heads * 2 * p.S() * p.plane() >= (1L << 31)) return false;
+    return bwd_dkdv_mfma_supported(h) && bwd_dw_mfma_supported(h) && bwd_pixel_ring_supported(h, true);
+}
+static size_t wide_part_bytes(const Problem& h)
+{
+    return (((size_t)h.B * h.heads * 2 * h.S() * (size_t)h.plane() * sizeof(float)) + 255) & ~(size_t)255;
+}
+static size_t bwd_wide_workspace_bytes(const Problem& h)
+{
+    const size_t dbias_tmp = (((size_t)h.heads * h.S() * sizeof(float)) + 255) & ~(size_t)255;
+    return ((bwd_workspace_bytes_as_given(h) + 255) & ~(size_t)255) + wide_part_bytes(h) + dbias_tmp;
+}
+// tmp [2 heads][S] <-> dbias [heads][S]: row 2m of tmp is head m
+__global__ void wide_dbias_kernel(float* __restrict__ tmp, float* __restrict__ dbias, int n, int S, int to_tmp)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int m = i / S, s = i - m * S;
+    if (to_tmp) { tmp[(2 * m) * S + s] = dbias[i]; tmp[(2 * m + 1) * S + s] = 0.0f; }
+    else dbias[i] = tmp[(2 * m) * S + s];
+}
+
+static hipError_t launch_bwd_wide(const Problem& p, const Problem& h, const void* dout, const void* q,
+                                  const void* k, const void* v, const float* wk, const float* wv,
+                                  const float* bias, void* dq, void* dk, void* dv, float* dwk,
+                                  float* dwv, float* dbias, void* workspace, hipStream_t st)
+{
+    const int S = h.S();
+    const size_t per = (size_t)h.B * h.heads * S * (size_t)h.plane();
+    float* attn_ws = (float*)workspace;
+    float* dl_ws = attn_ws + per;
+    float* partial = dl_ws + per;
+    void* dkdv_image_ws = (char*)partial + bwd_partial_bytes(h);
+    void* image_ws = (char*)dkdv_image_ws + bwd_dkdv_mfma_image_bytes(h);
+    char* extra = (char*)workspace + ((bwd_workspace_bytes_as_given(h) + 255) & ~(size_t)255);
+    float* part = (float*)extra;
+    float* dbias_tmp = (float*)(extra + wide_part_bytes(h));
+    hipError_t e = launch_bwd_pixel_mfma(h, dout, q, k, v, wk, wv, bias, dq, attn_ws, dl_ws, true, image_ws,
+                                         dkdv_image_ws, true, st, part);
+    if (e != hipSuccess) return e;
+    if (bwd_dkdv_ring_supported(h, true))
+        e = launch_bwd_dkdv_ring(h, dout, q, attn_ws, dl_ws, dk, dv, dkdv_image_ws, st);
+    else
+        e = launch_bwd_dkdv_mfma(h, dout, q, wk, wv, attn_ws, dl_ws, true, dk, dv, dkdv_image_ws, st);
+    if (e != hipSuccess) return e;
+    const int nb = p.heads * S;
+    if (dbias && p.accumulate)
+        hipLaunchKernelGGL(wide_dbias_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, dbias_tmp, dbias, nb, S, 1);
+    e = launch_bwd_dw_mfma(h, dout, q, k, v, attn_ws, dl_ws, partial, dwk, dwv, dbias ? dbias_tmp : nullptr, st);
+    if (e != hipSuccess) return e;
+    if (dbias)
+        hipLaunchKernelGGL(wide_dbias_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, dbias_tmp, dbias, nb, S, 0);
     return hipGetLastError();
 }
 
@@ -907,6 +984,8 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
     Problem p32;
     if (bwd_padded_problem(p, p32) && aligned16({dout, q, k, v, dq, dk, dv, workspace}))
         return launch_bwd_padded(p, p32, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias, workspace, st);
+    if (bwd_wide_problem(p, p32) && aligned16({dout, q, k, v, dq, dk, dv, workspace}))
+        return launch_bwd_wide(p, p32, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias, workspace, st);
     SLIDE_DISPATCH(launch_bwd_t, p, dout, q, k, v, wk, wv, bias, dq, dk, dv, dwk, dwv, dbias,
                    workspace, st);
 }

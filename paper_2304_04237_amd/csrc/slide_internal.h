@@ -104,7 +104,7 @@ size_t bwd_pixel_mfma_image_bytes(const Problem& p);
 hipError_t launch_bwd_pixel_mfma(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, const float* wk, const float* wv, const float* bias,
                                  void* dq, void* attn_ws, void* dl_ws, bool half_ws, void* image_ws,
-                                 void* dkdv_image_ws, bool streaming, hipStream_t st);   // also prepares the dk/dv kernel's operand image; streaming: launch_bwd_pixel_ring does the rest
+                                 void* dkdv_image_ws, bool streaming, hipStream_t st, float* part = nullptr);   // also prepares the dk/dv kernel's operand image; streaming: launch_bwd_pixel_ring does the rest; part: the heads are half heads of 64-channel heads (streaming only), see launch_bwd_pixel_ring
 hipError_t launch_bwd_dkdv_mfma(const Problem& p, const void* dout, const void* q,
                                 const float* wk, const float* wv,
                                 const void* attn_ws, const void* dl_ws, bool half_ws,
@@ -124,7 +124,10 @@ constexpr int BWD_PX_A1K = 0, BWD_PX_A1V = 2304, BWD_PX_A2K = 4608, BWD_PX_BIAS 
 bool bwd_pixel_ring_supported(const Problem& p, bool aligned16);
 hipError_t launch_bwd_pixel_ring(const Problem& p, const void* dout, const void* q, const void* k,
                                  const void* v, void* dq, void* attn_ws, void* dl_ws,
-                                 const void* image_ws, hipStream_t st);
+                                 const void* image_ws, hipStream_t st, int mode = 0, float* part = nullptr);
+// (mode 1 / 2 with part [B, heads, 2, 9, H, W] float32: the heads are the half heads of heads of
+// 64 channels; launch 1 writes every half's share of the logits and of da to part, launch 2 adds
+// the other half's shares in and does the rest)
 
 // the same gradients by the streaming kernel (slide_bwd16_ring.hip): bf16, d == 32, ksize 3,
 // 32 <= W <= 56, W % 8 == 0, every pointer 16-byte aligned, a and dl as halves; reads the operand

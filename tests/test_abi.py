@@ -208,7 +208,9 @@ def test_backward_variant_selection(lib):
     assert v(128, 56, 56, 48, 2, 3, 1, 1) == 127                   # 24 channels per head: the streaming kernels on padded copies
     assert v(128, 56, 56, 48, 2, 3, 1, 0) == 10                    # ... not from unaligned pointers
     assert v(4, 13, 72, 16, 2, 3, 1, 1) == 120                     # 8 channels per head, wide map: the tiled kernels on padded copies
-    assert v(4, 13, 72, 128, 2, 3, 1, 1) == 10                     # 64 channels per head: general kernels
+    assert v(4, 13, 72, 128, 2, 3, 1, 1) == 10                     # 64 channels per head on a wide map: general kernels
+    assert v(128, 56, 56, 64, 1, 3, 1, 1) == 227                   # 64 channels per head: half heads through the streaming kernels
+    assert v(128, 56, 56, 64, 1, 3, 1, 0) == 10
 
 
 def test_binding_rejects_mismatched_parameter_shapes(lib):

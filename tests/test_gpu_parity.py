@@ -503,6 +503,48 @@ def test_forward_heads_of_64_channels(shape):
     check("out(general kernel)", "bf16", out_g, ref)
 
 
+# backward of heads of 64 channels: half heads through the matrix-core kernels, the per-pixel part in
+# two launches that exchange the halves' shares of logits and da (slide_attn_bwd_variant 200 + ...)
+WIDE_HEAD_BWD_SHAPES = [
+    (2, 9, 40, 64, 1, 227),
+    (3, 20, 56, 128, 2, 227),
+    (2, 33, 32, 64, 1, 226),             # tiled dk/dv kernel
+    (1, 5, 64, 64, 1, 222),              # 64 columns: only the per-pixel part streams
+    (130, 5, 48, 64, 1, 227),
+    (4, 56, 56, 64, 1, 227),             # the stage-1 map
+    (2, 13, 72, 64, 1, 10),              # wider than the streaming per-pixel kernel takes: general kernels
+]
+
+
+@pytest.mark.parametrize("shape", WIDE_HEAD_BWD_SHAPES)
+def test_backward_heads_of_64_channels(shape):
+    B, H, W, C, heads, variant = shape
+    print("wide-head backward case", shape, flush=True)
+    assert sa.slide_attn_bwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True) == variant
+    assert sa.slide_attn_bwd_variant(B, H, W, C, heads, 3, torch.bfloat16, False) == 10
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=1500 + H + W + C)
+    dev = g["q"].device
+    grads = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    torch.cuda.synchronize()
+    ref = oracle.bwd(n["dout"], n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3)
+    for name, got, want in zip(GRAD_NAMES, grads, ref):
+        check(name, "bf16", got, want)
+    again = sa.slide_attn_bwd(g["dout"], g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3)
+    for a, b in zip(grads, again):
+        assert torch.equal(a, b)
+    wk_l, wv_l = d["wk_learned"].to(dev), d["wv_learned"].to(dev)
+    tb = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, 3)
+    for name, got, want in zip(GRAD_NAMES, tb, ref):
+        check(name, "bf16", got, want)
+    first = [t.clone() for t in tb]
+    acc = sa.slide_attn_bwd_two_branch(g["dout"], g["q"], g["k"], g["v"], wk_l, wv_l, g["bias"], heads, 3,
+                                       outputs=tb, accumulate=True)
+    for idx in range(3):
+        assert torch.equal(acc[idx], first[idx])
+    for idx in range(3, 6):
+        assert torch.equal(acc[idx], 2 * first[idx])
+
+
 def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
     assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 24
