@@ -210,7 +210,9 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
  * head left empty), 25 = two launches of the streaming kernel for heads of 64 channels (each
  * head as two halves of 32 whose shares of the logits cross the workspace; a call that brings
  * less workspace than slide_attn_workspace_bytes says runs on the general kernel), 30 = ksize-5
- * matrix-core kernel.  aligned16: whether
+ * matrix-core kernel, 100 + v = heads narrower than 32 channels (bf16, ksize 3, H * W % 8 == 0)
+ * through kernel v on copies of q, k, v and the kernels padded to 32 channels per head in the
+ * workspace (again the general kernel for a call with less workspace).  aligned16: whether
  * q, k, v, out, wk, wv are all 16-byte aligned (kernels 21, 23, 24 need that).  Launches
  * nothing; reads the compute-unit count of the current device (256 if there is none).
  */

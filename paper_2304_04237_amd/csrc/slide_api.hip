@@ -74,6 +74,10 @@ extern "C" size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int hea
     // heads of 64 channels: what the two-launch streaming forward exchanges (a caller that brings
     // less gets the general kernel, which needs none)
     if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, true)) return slide::fwd_ring_wide_workspace_bytes(p);
+    // heads narrower than 32 channels: the padded copies (head size 24 on the streaming kernel's maps needs none)
+    Problem p32;
+    if (!(C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, true)) && slide::fwd_padded_problem(p, p32))
+        return slide::fwd_padded_workspace_bytes(p32);
     return slide::fwd_mfma_supported(p) ? slide::fwd_mfma_workspace_bytes(p) : slide::fwd_mfma5_workspace_bytes(p);
 }
 
@@ -82,6 +86,8 @@ extern "C" int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ks
     if (check_problem(B, H, W, C, heads, ksize, dtype) != SLIDE_OK) return 0;
     Problem p{B, H, W, C, heads, ksize, dtype};
     if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, true)) return 2;
+    Problem p32;
+    if (slide::fwd_padded_problem(p, p32) || (C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, true))) return 2;
     return slide::fwd_mfma_supported(p) ? 2 : (slide::fwd_mfma5_supported(p) ? 3 : 1);
 }
 
@@ -93,6 +99,8 @@ extern "C" int slide_attn_fwd_variant(int B, int H, int W, int C, int heads, int
     if (slide::fwd_mfma_supported(p)) return slide::fwd_mfma_variant(p, aligned16 != 0);
     if (C == heads * 24 && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16 != 0)) return 24;
     if (slide::fwd_ring_enabled() && slide::fwd_ring_wide_supported(p, aligned16 != 0)) return 25;
+    Problem p32;
+    if (aligned16 && slide::fwd_padded_problem(p, p32)) return 100 + slide::fwd_mfma_variant(p32, true);
     return slide::fwd_mfma5_supported(p) ? 30 : 10;
 }
 
@@ -167,8 +175,16 @@ static int forward(const void* q, const void* k, const void* v,
         if (!workspace || workspace_bytes < slide::fwd_mfma5_workspace_bytes(p)) return SLIDE_ERR_WORKSPACE;
         if (!aligned_to(workspace, 16)) return SLIDE_ERR_ALIGN;
         e = slide::launch_fwd_mfma5(p, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
-    } else
-        e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, lse, (hipStream_t)stream);
+    } else {
+        // heads narrower than 32 channels through the matrix-core kernels on padded copies, when
+        // the caller brought the workspace for them; the general kernel otherwise
+        Problem p32;
+        if (aligned16 && slide::fwd_padded_problem(p, p32) && workspace && aligned_to(workspace, 16) &&
+            workspace_bytes >= slide::fwd_padded_workspace_bytes(p32))
+            e = slide::launch_fwd_padded(p, p32, q, k, v, wk, wv, bias, out, lse, workspace, (hipStream_t)stream);
+        else
+            e = slide::launch_fwd_generic(p, q, k, v, wk, wv, bias, out, lse, (hipStream_t)stream);
+    }
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;
 }
 
@@ -195,7 +211,8 @@ extern "C" int slide_attn_fwd_noalloc(const void* q, const void* k, const void* 
     size_t need = slide_attn_workspace_bytes(B, H, W, C, heads, ksize, dtype, 0);
     {   // (heads of 64 channels whose partial logits do not fit the scratch run on the general kernel, which needs none)
         Problem pw{B, H, W, C, heads, ksize, dtype};
-        if (need > NOALLOC_SCRATCH_BYTES && slide::fwd_ring_wide_supported(pw, true)) need = 0;
+        Problem p32;
+        if (need > NOALLOC_SCRATCH_BYTES && (slide::fwd_ring_wide_supported(pw, true) || slide::fwd_padded_problem(pw, p32))) need = 0;
     }
     if (need > NOALLOC_SCRATCH_BYTES) return SLIDE_ERR_WORKSPACE;
     void* ws = nullptr;

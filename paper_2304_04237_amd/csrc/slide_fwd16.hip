@@ -587,7 +587,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     a.g.small_first = pipelined;
     a.buf_stride = t.buf_bytes;
     a.a_base = (pipelined ? 2 : 1) * t.buf_bytes;
-    a.scale_log2e = 1.44269504088896341f / sqrtf((float)D);
+    a.scale_log2e = 1.44269504088896341f * p.logit_scale();
     a.idw = p.two_branch ? 1.0f : 0.0f;
     static LdsOptIn opt_in;
     hipError_t e = opt_in.ensure({(const void*)fwd16_kernel<FWD_WAVES>,

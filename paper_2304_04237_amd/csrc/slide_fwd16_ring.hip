@@ -1073,7 +1073,7 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out; a.off_out2 = r.off_out2;
     a.magic_w = (uint32_t)(((1ULL << 32) + p.W - 1) / p.W);
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
-    a.scale_log2e = 1.44269504088896341f / sqrtf((float)a.d);
+    a.scale_log2e = 1.44269504088896341f * p.logit_scale();
     a.idw = p.two_branch ? 1.0f : 0.0f;
     a.part = nullptr;
     static LdsOptIn opt_in;

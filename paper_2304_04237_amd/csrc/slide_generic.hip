@@ -767,6 +767,58 @@ static hipError_t launch_bwd_padded(const Problem& p, const Problem& p32, const 
     return hipGetLastError();
 }
 
+// ---- forward of heads narrower than 32 channels, the same way (head size 24 on maps of the
+// streaming kernel runs there directly and never comes here)
+bool fwd_padded_problem(const Problem& p, Problem& p32)
+{
+    if (p.dtype != 1 || p.ksize != 3 || p.heads < 1 || p.C % p.heads != 0) return false;
+    const int d = p.d();
+    if (d < 1 || d >= PAD_D || p.plane() % 8 != 0) return false;     // (a channel plane is whole 16-byte chunks)
+    p32 = p;
+    p32.C = p.heads * PAD_D;
+    p32.scale_dim = d;
+    if ((long)p.B * p32.C >= (1L << 31) || (p.plane() * 2 + 4095) / 4096 > 65535) return false;
+    return fwd_mfma_supported(p32);
+}
+size_t fwd_padded_workspace_bytes(const Problem& p32)
+{
+    const size_t inner = (fwd_mfma_workspace_bytes(p32) + 255) & ~(size_t)255;
+    return inner + 4 * pad_act_bytes(p32) + 2 * pad_w_bytes(p32);
+}
+hipError_t launch_fwd_padded(const Problem& p, const Problem& p32, const void* q, const void* k, const void* v,
+                             const float* wk, const float* wv, const float* bias, void* out, float* lse,
+                             void* workspace, hipStream_t st)
+{
+    const size_t inner = (fwd_mfma_workspace_bytes(p32) + 255) & ~(size_t)255;
+    const size_t act = pad_act_bytes(p32), wb = pad_w_bytes(p32);
+    char* base = (char*)workspace + inner;
+    void* pin[3] = {base, base + act, base + 2 * act};
+    void* pout = base + 3 * act;
+    float* wk32 = (float*)(base + 4 * act);
+    float* wv32 = (float*)(base + 4 * act + wb);
+    const int d = p.d(), n = p.S() * p.S();
+    const long chunks = p.plane() * 2 / 16;
+    const unsigned gx = (unsigned)((chunks + 255) / 256);
+    {
+        PadArgs a{};
+        const void* src[3] = {q, k, v};
+        for (int i = 0; i < 3; ++i) { a.src[i] = (const uint4*)src[i]; a.dst[i] = (uint4*)pin[i]; }
+        a.heads = p.heads; a.d_src = d; a.d_dst = PAD_D; a.chunks = chunks;
+        hipLaunchKernelGGL(repack_heads_kernel, dim3((unsigned)(p.B * p.heads * PAD_D), gx, 3), dim3(256), 0, st, a);
+    }
+    const unsigned gw = (unsigned)(((long)p.heads * PAD_D * n + 255) / 256);
+    hipLaunchKernelGGL(repack_kernels_kernel, dim3(gw, 2), dim3(256), 0, st, wk, wv, wk32, wv32, p.heads, d, PAD_D, n);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = launch_fwd_mfma(p32, pin[0], pin[1], pin[2], wk32, wv32, bias, pout, lse, workspace, st);
+    if (e != hipSuccess) return e;
+    PadArgs a{};
+    a.src[0] = (const uint4*)pout; a.dst[0] = (uint4*)out;
+    a.heads = p.heads; a.d_src = PAD_D; a.d_dst = d; a.chunks = chunks;
+    hipLaunchKernelGGL(repack_heads_kernel, dim3((unsigned)(p.B * p.heads * d), gx, 1), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
 // ---- heads of 64 channels (bf16, 3x3 window, maps the streaming per-pixel kernel takes)
 // The matrix-core kernels work on heads of 32 channels.  Given the attention weights a and the
 // logit gradients dl, the key, value and kernel gradients are separate per channel, so a head of

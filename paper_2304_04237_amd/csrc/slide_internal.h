@@ -70,6 +70,14 @@ hipError_t launch_bwd_generic(const Problem& p, const void* dout, const void* q,
                               void* dq, void* dk, void* dv, float* dwk, float* dwv, float* dbias,
                               void* workspace, hipStream_t st);
 
+// forward of heads narrower than 32 channels (bf16, ksize 3, H * W % 8 == 0) through the
+// matrix-core kernels on copies padded to 32 channels per head (p32: the padded problem)
+bool fwd_padded_problem(const Problem& p, Problem& p32);
+size_t fwd_padded_workspace_bytes(const Problem& p32);
+hipError_t launch_fwd_padded(const Problem& p, const Problem& p32, const void* q, const void* k, const void* v,
+                             const float* wk, const float* wv, const float* bias, void* out, float* lse,
+                             void* workspace, hipStream_t st);
+
 // channels-last activations [B, H, W, C]: the backward on copies turned into [B, C, H, W] in the
 // workspace (p describes the problem without the layout flag)
 size_t bwd_nhwc_workspace_bytes(const Problem& p);

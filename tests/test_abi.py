@@ -73,10 +73,12 @@ def test_forward_rejects_bad_arguments_on_the_host(lib):
 
 
 def test_variant_query_knows_head_size_24():
-    # head size 24 runs on the streaming kernel where the map fits it, else on the general kernel
+    # head size 24 runs on the streaming kernel where the map fits it, else on padded copies
+    # through the other matrix-core kernels, else on the general kernel
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, True) == 24
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, False) == 10
-    assert sa.slide_attn_fwd_variant(2, 56, 72, 48, 2, 3, 1, True) == 10      # wider than the ring takes
+    assert sa.slide_attn_fwd_variant(2, 56, 72, 48, 2, 3, 1, True) == 120     # wider than the ring takes: padded to 32 channels per head, tile kernel
+    assert sa.slide_attn_fwd_variant(2, 9, 21, 48, 2, 3, 1, True) == 10       # H * W % 8 != 0: general kernel
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 5, 1, True) == 10      # 5x5 window
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 0, True) == 10      # float32
 

@@ -503,6 +503,40 @@ def test_forward_heads_of_64_channels(shape):
     check("out(general kernel)", "bf16", out_g, ref)
 
 
+# forward of heads narrower than 32 channels on padded copies (slide_attn_fwd_variant 100 + the
+# variant of the padded problem); head size 24 on the streaming kernel's maps runs there directly
+NARROW_HEAD_FWD_SHAPES = [
+    (2, 8, 40, 32, 2, 124),              # 16 channels per head
+    (3, 20, 56, 24, 3, 124),             # 8
+    (2, 12, 72, 48, 2, 120),             # 24 on a map wider than the streaming kernel takes
+    (2, 56, 56, 48, 2, 24),              # 24 on the streaming kernel itself
+    (2, 9, 21, 48, 2, 10),               # H * W % 8 != 0: general kernel
+]
+
+
+@pytest.mark.parametrize("shape", NARROW_HEAD_FWD_SHAPES)
+def test_forward_narrow_heads(shape):
+    B, H, W, C, heads, variant = shape
+    print("narrow-head forward case", shape, flush=True)
+    assert sa.slide_attn_fwd_variant(B, H, W, C, heads, 3, torch.bfloat16, True) == variant
+    d, g, n = gpu_problem(B, H, W, C, heads, 3, "bf16", seed=1600 + H + W + C)
+    dev = g["q"].device
+    lse = torch.full((B, heads, H, W), float("nan"), dtype=torch.float32, device=dev)
+    out = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, lse=lse)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.fwd(n["q"], n["k"], n["v"], n["wk"], n["wv"], n["bias"], heads, 3, return_lse=True)
+    check("out", "bf16", out, ref)
+    check("lse", "bf16", lse, ref_lse)
+    out2 = sa.slide_attn_fwd_two_branch(g["q"], g["k"], g["v"], d["wk_learned"].to(dev), d["wv_learned"].to(dev),
+                                        g["bias"], heads, 3)
+    check("out(two-branch)", "bf16", out2, ref)
+    # without the workspace for the padded copies: the general kernel
+    small = torch.empty(16, dtype=torch.uint8, device=dev)
+    if variant >= 100:
+        out_g = sa.slide_attn_fwd(g["q"], g["k"], g["v"], g["wk"], g["wv"], g["bias"], heads, 3, workspace=small)
+        check("out(general kernel)", "bf16", out_g, ref)
+
+
 # backward of heads of 64 channels: half heads through the matrix-core kernels, the per-pixel part in
 # two launches that exchange the halves' shares of logits and da (slide_attn_bwd_variant 200 + ...)
 WIDE_HEAD_BWD_SHAPES = [
