@@ -93,6 +93,7 @@ NHWC_BWD_SHAPES = [
     (3, 20, 56, 96, 3, 3, "bf16"),
     (1, 13, 72, 32, 1, 3, "bf16"),       # tiled kernels
     (2, 9, 40, 48, 2, 3, "bf16"),        # 24 channels per head: layout change, then the padded copies
+    (2, 9, 40, 64, 1, 3, "bf16"),        # 64 channels per head: layout change, then the half heads
     (2, 7, 9, 20, 2, 3, "bf16"),         # C % 8 != 0, H*W % 8 != 0: element-wise layout change, general kernels
     (1, 6, 7, 24, 3, 5, "f32"),
     (2, 5, 8, 16, 2, 1, "f32"),
