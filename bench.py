@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, choices=[2, 3, 4, 5],
                     help="which bf16 benchmark configuration's forward to time (default 2 = stage 1, "
                          "the configuration the metric is quoted on; the others are for profiling)")
+    ap.add_argument("--heads", type=int, default=0,
+                    help="profiling: run the configuration (and the training workload) with this many heads "
+                         "over the same channels, e.g. 1 at stage 1 = one head of 64 channels")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (batch items, heads and tiles are "
@@ -58,6 +61,13 @@ def main():
     torch.cuda.set_device(dev)
 
     wl, data = synth.make_config_inputs(args.config - 1)
+    if args.heads:                              # same tensors' shapes, other head size
+        if wl.C % args.heads != 0:
+            print("bench.py: --heads must divide the %d channels" % wl.C, file=sys.stderr)
+            sys.exit(2)
+        wl = wl._replace(heads=args.heads, name="%s_heads%d" % (wl.name, args.heads))
+        data = synth.make_inputs(wl.B, wl.H, wl.W, wl.C, wl.heads, wl.ksize, wl.dtype, seed=1000 + args.config - 1,
+                                 with_dout=True)
     B, H, W, C, heads, ksize = wl.B, wl.H, wl.W, wl.C, wl.heads, wl.ksize
     px_heads = B * H * W * heads
     esz = 2
@@ -235,7 +245,7 @@ def main():
     ms_per_step = total_ms / args.steps
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json" if args.config == 2 else "none")
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_stage1_fwd.json" if args.config == 2 and not args.heads else "none")
     if os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("bytes_per_launch")
@@ -245,8 +255,9 @@ def main():
     achieved = alg_bytes / (launch_ms * 1e-3) / 1e9
     result = {
         "metric": ("slide-attn fwd Gpixel*head/s at 56x56 stage-1 (reparam + forward per step)"
-                   if args.config == 2 else
-                   "slide-attn fwd Gpixel*head/s, configuration %d (reparam + forward per step)" % args.config),
+                   if args.config == 2 and not args.heads else
+                   "slide-attn fwd Gpixel*head/s, configuration %d%s (reparam + forward per step)"
+                   % (args.config, ", %d heads" % heads if args.heads else "")),
         "value": px_heads / (ms_per_step * 1e-3) / 1e9,
         "unit": "Gpixel*head/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -275,6 +286,9 @@ def main():
         del pool
         torch.cuda.empty_cache()
         wl5, d5 = synth.make_config_inputs(4)
+        if args.heads and wl5.C % args.heads == 0:
+            wl5 = wl5._replace(heads=args.heads, name="%s_heads%d" % (wl5.name, args.heads))
+            d5 = synth.make_inputs(wl5.B, wl5.H, wl5.W, wl5.C, wl5.heads, wl5.ksize, wl5.dtype, seed=1004, with_dout=True)
         sets = []
         for s in range(2):
             d = d5 if s == 0 else synth.make_inputs(wl5.B, wl5.H, wl5.W, wl5.C, wl5.heads, wl5.ksize,
@@ -339,7 +353,8 @@ def main():
         # q, k, v, dout and writes dq, dk, dv (11 tensor passes of B*C*H*W bf16 elements)
         alg5 = 11 * wl5.B * wl5.C * wl5.H * wl5.W * 2
         ach5 = alg5 / (tms * 1e-3) / 1e9
-        result["training"] = {"workload": "stage1_bf16_train: B=128 H=W=56 C=64 heads=2 ksize=3, fwd+bwd",
+        result["training"] = {"workload": "%s: B=%d H=W=%d C=%d heads=%d ksize=%d, fwd+bwd"
+                                          % (wl5.name, wl5.B, wl5.H, wl5.C, wl5.heads, wl5.ksize),
                               "ms_per_step": tms, "steps": n_train,
                               "value": pxh5 / (tms * 1e-3) / 1e9, "unit": "Gpixel*head/s",
                               "launch": ("hip graph of 2 steps, replayed" if train_graph is not None
