@@ -80,10 +80,10 @@ struct RingArgs {
 // MODE: heads of 64 channels run as two half heads of 32 (the arguments then describe twice as
 // many heads; bias and lse are indexed by the pair) in two launches.  The logit of Eq. 2 is a
 // sum over the channels of the head, so MODE 1 only forms each half head's share of the nine
-// logits (key side; nothing else is computed or stored) and writes it to `part`; MODE 2 is the
-// whole kernel, which adds the other half's share to its own before the softmax: both halves
-// get the same attention weights, each applies them to its own 32 value channels.  MODE 0:
-// heads of DH channels, one launch.
+// logits (key side; nothing else is computed or stored, no value rows are staged) and writes it
+// to `part`; MODE 2 is the rest of the kernel (no q, no key rows, no key-side products): a pass
+// adds the two halves' shares, so both halves get the same attention weights, and applies them
+// to its own 32 value channels.  MODE 0: heads of DH channels, one launch.
 constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
 
 template <int RPG, bool LSE, bool PLAIN, int DH, int MODE = 0>
@@ -186,7 +186,9 @@ fwd16_ring_kernel(const RingArgs a)
         if (PLAIN) { if (lane < S) bias_early = a.bias[mb * S + lane]; }
         else if (tid < IMG_DWORDS - IMG_BIAS && shift_of_row(tid) >= 0) bias_early = a.bias[mb * S + shift_of_row(tid)];
     }
-    constexpr int NJ = MODE == 1 ? 1 : 2;                               // tensors a mover stages: K, and V unless only logits are formed
+    // tensors a mover stages: K (j = 0) unless the logits come in whole, V (j = 1) unless only logits are formed
+    constexpr int J0 = MODE == 2 ? 1 : 0, J1 = MODE == 1 ? 1 : 2, NJ = J1 - J0;
+    constexpr bool HAS_Q = MODE != 2;                                  // q is loaded (the key side is computed)
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;                                                // mover: loads issued after group 0
     if (!PLAIN && !mover) {
@@ -208,17 +210,19 @@ fwd16_ring_kernel(const RingArgs a)
         for (int k = 0; k <= v0; ++k) {                                // group 0 (at most RPG + 2 rows)
             const int gy = y0 - 1 + k;
             if (gy >= 0 && gy < H)
-                for (int j = 0; j < NJ; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+                for (int j = J0; j < J1; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
         }
-        for (int i = 0; i < 2; ++i) {
-            load_q(2 * mv + i, 16 * (2 * mv + i), 0);
-            load_q(2 * mv + i, 16 * (2 * mv + i) + PX_EPOCH, SLOT);
+        if (HAS_Q) {
+            for (int i = 0; i < 2; ++i) {
+                load_q(2 * mv + i, 16 * (2 * mv + i), 0);
+                load_q(2 * mv + i, 16 * (2 * mv + i) + PX_EPOCH, SLOT);
+            }
+            n_after_g0 = 4;
         }
-        n_after_g0 = 4;
         for (int k = 0; k < v1 - v0; ++k) {                            // group 1 into set 1
             const int gy = y0 + v0 + k;
             if (gy >= 0 && gy < H) {
-                for (int j = 0; j < NJ; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
+                for (int j = J0; j < J1; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
                 n_after_g0 += NJ;
             }
         }
@@ -257,13 +261,13 @@ fwd16_ring_kernel(const RingArgs a)
         }
     };
     if (DH < D) zero_q_rows(tid, 2 * WAVES, THREADS12, 0, 2);
-    constexpr int NL = NJ * RPG + 2;                                   // loads of a mover per epoch
+    constexpr int NL = NJ * RPG + (HAS_Q ? 2 : 0);                     // loads of a mover per epoch
     if (mover) {
         wait_vmem(n_after_g0);                                         // group 0 has landed
         for (int k = 0; k <= v0; ++k) {                                // group 0 -> ring rows 0 .. v0
             RawRow r0[2];
-            for (int j = 0; j < NJ; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
-            for (int j = 0; j < NJ; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
+            for (int j = J0; j < J1; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+            for (int j = J0; j < J1; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
         if (DH < D) {                                                 // third q slots of pass waves 2 mv, 2 mv + 1
@@ -278,11 +282,13 @@ fwd16_ring_kernel(const RingArgs a)
         for (int k = 0; k < RPG; ++k) {
             const int gy = y0 + v1 + k;
             const bool real = k < v2 - v1 && gy >= 0 && gy < H;
-            for (int j = 0; j < NJ; ++j)
+            for (int j = J0; j < J1; ++j)
                 load_row(j, (uint32_t)min(max(gy, 0), H - 1) * w2, real ? slot_off(j, k) : a.off_dummy);
         }
-        load_q(0, npix, 0);
-        load_q(0, npix, 0);                                            // (two dump loads complete the round)
+        if (HAS_Q) {
+            load_q(0, npix, 0);
+            load_q(0, npix, 0);                                        // (two dump loads complete the round)
+        }
         wait_vmem(NL);                                                 // everything but that round: group 1, q of epochs 0 and 1
     }
     block_barrier();
@@ -351,7 +357,7 @@ fwd16_ring_kernel(const RingArgs a)
             // group e + 1 has landed (waited for at the end of the previous epoch): fetch it
             RawRow raw[2][RPG];
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
+            for (int j = J0; j < J1; ++j)
 #pragma unroll
                 for (int k = 0; k < RPG; ++k) raw[j][k] = read_row(slot_off(j, 0) + set_rd + k * SLOT);
             if (MODE != 1 && e > 0) store_results(PX_EPOCH * (e - 1), out2_rd);   // (contains the wait for its LDS reads)
@@ -361,11 +367,13 @@ fwd16_ring_kernel(const RingArgs a)
             for (int k = 0; k < RPG; ++k) {
                 const bool real = (cvB >> (17 + k)) & 1u;
 #pragma unroll
-                for (int j = 0; j < NJ; ++j)
+                for (int j = J0; j < J1; ++j)
                     load_row(j, real ? ldo + (uint32_t)k * w2 : ldo, real ? slot_off(j, 0) + set_rd + k * SLOT : a.off_dummy);
             }
+            if (HAS_Q) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) load_q(2 * mv + i, PX_EPOCH * (e + 2) + 16 * (2 * mv + i), qo_2);
+                for (int i = 0; i < 2; ++i) load_q(2 * mv + i, PX_EPOCH * (e + 2) + 16 * (2 * mv + i), qo_2);
+            }
             // conversion of group e + 1 into the ring
             const int cnt = (cvB >> 10) & 7;
             if (((cvB >> 13) & 15u) == 0 && !oct_empty) {              // every row inside the map: the usual case
@@ -374,7 +382,7 @@ fwd16_ring_kernel(const RingArgs a)
                     const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
                     if (k < cnt) {
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) write_row_in_map(j, pos, raw[j][k]);
+                        for (int j = J0; j < J1; ++j) write_row_in_map(j, pos, raw[j][k]);
                     }
                 }
             } else {
@@ -383,14 +391,16 @@ fwd16_ring_kernel(const RingArgs a)
                     const uint32_t pos = (k < 3 ? (cvA >> (10 * k)) & 1023u : cvB & 1023u) * 16;
                     if (k < cnt) {
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) write_row(j, pos, !((cvB >> (13 + k)) & 1u), raw[j][k]);
+                        for (int j = J0; j < J1; ++j) write_row(j, pos, !((cvB >> (13 + k)) & 1u), raw[j][k]);
                     }
                 }
             }
             set_rd = RPG * SLOT - set_rd;
             { const int t = out2_wr; out2_wr = out2_rd; out2_rd = t; }
             { const int t = qo_cur; qo_cur = qo_1; qo_1 = qo_2; qo_2 = t; }
-            if (NL == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            if (NL == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else if (NL == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            else if (NL == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
             else if (NL == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
             else if (NL == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             else if (NL == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
@@ -413,14 +423,18 @@ fwd16_ring_kernel(const RingArgs a)
     // MODE 1: this half head's share of the logits goes out; MODE 2: the other half's comes in,
     // fetched one epoch ahead (lane (p, g) holds the shifts g, 4 + g, 8 + g of pixel p)
     float* part_out = MODE == 1 ? a.part + (long)plane * S * HW + (long)y0 * W : nullptr;
+    const float* part_own = MODE == 2 ? a.part + (long)plane * S * HW + (long)y0 * W : nullptr;
     const float* part_in = MODE == 2 ? a.part + (long)(plane ^ 1) * S * HW + (long)y0 * W : nullptr;
-    float oth[3] = {0.0f, 0.0f, 0.0f};
-    auto fetch_other = [&](int n_first) {
+    float oth[3] = {0.0f, 0.0f, 0.0f};                                 // the two halves' shares, added
+    auto fetch_shares = [&](int n_first) {
 #pragma unroll
-        for (int r = 0; r < 3; ++r)
-            oth[r] = (n_first + p < npix && (r < 2 || g == 0)) ? part_in[(long)(4 * r + g) * HW + n_first + p] : 0.0f;
+        for (int r = 0; r < 3; ++r) {
+            const bool has = n_first + p < npix && (r < 2 || g == 0);
+            const long at = (long)(4 * r + g) * HW + n_first + p;
+            oth[r] = has ? part_own[at] + part_in[at] : 0.0f;
+        }
     };
-    if (MODE == 2) fetch_other(nb);
+    if (MODE == 2) fetch_shares(nb);
     for (int e = 0; e < E; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
         if (p2 & 256u) {
@@ -433,12 +447,15 @@ fwd16_ring_kernel(const RingArgs a)
 #pragma unroll
             for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
             const unsigned char* qsrc = smem + q_slots + qo_cur + (8 * g + (p >> 2)) * 32 + (p & 3) * 8;
-            const uint2_t q0 = lds_read_tr(qsrc), q1 = lds_read_tr(qsrc + 4 * 32);
+            uint2_t q0 = {0u, 0u}, q1 = {0u, 0u};
             uint4_t kd[S];
+            if (HAS_Q) {
+                q0 = lds_read_tr(qsrc); q1 = lds_read_tr(qsrc + 4 * 32);
 #pragma unroll
-            for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
+                for (int t = 0; t < S; ++t) kd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
+            }
             half2_t qs[4];
-            {
+            if (HAS_Q) {
                 const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
                 qs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; qs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
                 qs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; qs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
@@ -479,6 +496,7 @@ fwd16_ring_kernel(const RingArgs a)
             } else {
                 // (two accumulation chains, even and odd taps: a product does not wait for the one before it)
                 float4_t acc1 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1b = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (HAS_Q) {
 #pragma unroll
                 for (int t = 0; t < S; ++t) {
                     uint4_t bb;
@@ -488,6 +506,7 @@ fwd16_ring_kernel(const RingArgs a)
                     else       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1[t], __builtin_bit_cast(half8_t, bb), acc1, 0, 0, 0);
                 }
                 acc1 += acc1b;
+                }
                 if (MODE == 1) {
                     if (nb + p < npix) {
 #pragma unroll
@@ -500,12 +519,8 @@ fwd16_ring_kernel(const RingArgs a)
                 for (int t = 0; t < S; ++t) vd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
                 float l[3];
 #pragma unroll
-                for (int r = 0; r < 3; ++r) l[r] = fmaf(acc1[r], a.scale_log2e, bias2[r]);
-                if (MODE == 2) {
-#pragma unroll
-                    for (int r = 0; r < 3; ++r) l[r] += oth[r];
-                    fetch_other(nb + PX_EPOCH);
-                }
+                for (int r = 0; r < 3; ++r) l[r] = MODE == 2 ? oth[r] + bias2[r] : fmaf(acc1[r], a.scale_log2e, bias2[r]);
+                if (MODE == 2) fetch_shares(nb + PX_EPOCH);
                 const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
                 float pr[3];
 #pragma unroll
