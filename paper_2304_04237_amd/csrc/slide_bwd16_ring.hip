@@ -506,10 +506,11 @@ struct PixelArgs {
 
 // MODE: heads of 64 channels run as two half heads of 32 (the arguments describe twice as many
 // heads).  Logits and da are sums over the channels of the whole head: MODE 1 forms each half's
-// share of both and writes them to `part`, nothing else; MODE 2 is the whole kernel with the
-// other half's shares added in, so both halves arrive at the same a and dl (each writes its
-// copy, which the other two backward kernels read per half head) and each forms dq of its own
-// 32 channels.  MODE 0: heads of 32 channels, one launch.
+// share of both and writes them to `part`, nothing else; MODE 2 is the rest: it adds the two
+// halves' shares (no q, dO or value rows are staged, no products formed for them), so both
+// halves arrive at the same a and dl (each writes its copy, which the other two backward kernels
+// read per half head), and each forms dq of its own 32 channels from its key rows.  MODE 0:
+// heads of 32 channels, one launch.
 template <int RPG, int MODE = 0>
 __global__ void __launch_bounds__(THREADS)
 bwd16_ring_pixel_kernel(const PixelArgs a)
@@ -591,6 +592,9 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
     };
 
     // ---- start-up
+    // MODE 2 takes logits and da whole from the workspace: no q, dO or value rows, only key rows for dq
+    constexpr int J1 = MODE == 2 ? 1 : 2;                              // tensors a mover stages: K (j = 0), V (j = 1)
+    constexpr bool HAS_QD = MODE != 2;
     const int v0 = srn(0), v1 = srn(1), v2 = srn(2);
     int n_after_g0 = 0;
     half8_t A1k[S];
@@ -601,16 +605,18 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
         for (int k = 0; k <= v0; ++k) {                                // group 0 (at most RPG + 2 rows)
             const int gy = y0 - 1 + k;
             if (gy >= 0 && gy < H)
-                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+                for (int j = 0; j < J1; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
         }
-        for (int i = 0; i < 2; ++i)
-            for (int x = 0; x < 2; ++x) load_qd(x, 2 * mv + i, 16 * (2 * mv + i), 0);
-        n_after_g0 = 4;
+        if (HAS_QD) {
+            for (int i = 0; i < 2; ++i)
+                for (int x = 0; x < 2; ++x) load_qd(x, 2 * mv + i, 16 * (2 * mv + i), 0);
+            n_after_g0 = 4;
+        }
         for (int k = 0; k < v1 - v0; ++k) {                            // group 1 into set 1
             const int gy = y0 + v0 + k;
             if (gy >= 0 && gy < H) {
-                for (int j = 0; j < 2; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
-                n_after_g0 += 2;
+                for (int j = 0; j < J1; ++j) load_row(j, (uint32_t)gy * w2, slot_off(j, RPG + k));
+                n_after_g0 += J1;
             }
         }
     } else {
@@ -654,22 +660,25 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
     if (mover) {
         // only the row loads of the epoch are still in flight (they follow its q and dO loads)
         auto wait_rows = [&]() {
-            if (RPG == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else if (RPG == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            constexpr int NR = J1 * RPG;                                // row loads per epoch
+            if (NR == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+            else if (NR == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            else if (NR == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else if (NR == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         };
         wait_vmem(n_after_g0);                                         // group 0 has landed
         for (int k = 0; k <= v0; ++k) {                                // group 0 -> ring rows 0 .. v0
             RawRow r0[2];
-            for (int j = 0; j < 2; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
-            for (int j = 0; j < 2; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
+            for (int j = 0; j < J1; ++j) r0[j] = read_row(slot_off(j, k < RPG ? k : 2 * RPG + (k - RPG)));
+            for (int j = 0; j < J1; ++j) write_row(j, (uint32_t)(k * RS), y0 - 1 + k >= 0 && y0 - 1 + k < H, r0[j]);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");             // set 0 has been read before it is loaded again
 #pragma unroll
         for (int k = 0; k < RPG; ++k) {                                // group 2 into set 0, as a full round of row loads
             const int gy = y0 + v1 + k;
             const bool real = k < v2 - v1 && gy >= 0 && gy < H;
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < J1; ++j)
                 load_row(j, (uint32_t)min(max(gy, 0), H - 1) * w2, real ? slot_off(j, k) : a.off_dummy);
         }
         wait_rows();                                                   // group 1, q and dO of epoch 0 have landed
@@ -682,21 +691,23 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             const uint32_t ldo = __builtin_amdgcn_readlane(t_ld, e);
             RawRow raw[2][RPG];
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < J1; ++j)
 #pragma unroll
                 for (int k = 0; k < RPG; ++k) raw[j][k] = read_row(slot_off(j, 0) + set_rd + k * SLOT);
             // q and dO of the next epoch, into the slots that the epoch before this one read
+            if (HAS_QD) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int x = 0; x < 2; ++x) load_qd(x, 2 * mv + i, PX_EPOCH * (e + 1) + 16 * (2 * mv + i), (e + 1) & 1);
+            }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             // group e + 3 into the slots just read
 #pragma unroll
             for (int k = 0; k < RPG; ++k) {
                 const bool real = (cvB >> (17 + k)) & 1u;
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < J1; ++j)
                     load_row(j, real ? ldo + (uint32_t)k * w2 : ldo, real ? slot_off(j, 0) + set_rd + k * SLOT : a.off_dummy);
             }
             const int cnt = (cvB >> 10) & 7;
@@ -706,7 +717,7 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
                 if (k < cnt) {
                     const bool in_map = !((cvB >> (13 + k)) & 1u);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) write_row(j, pos, in_map, raw[j][k]);
+                    for (int j = 0; j < J1; ++j) write_row(j, pos, in_map, raw[j][k]);
                 }
             }
             set_rd = RPG * SLOT - set_rd;
@@ -731,16 +742,21 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     // lane (p, g) holds the shifts g, 4 + g, 8 + g of pixel p
     float* part_out = MODE == 1 ? a.part + (long)plane * 2 * S * HW + (long)y0 * W : nullptr;
+    const float* part_own = MODE == 2 ? a.part + (long)plane * 2 * S * HW + (long)y0 * W : nullptr;
     const float* part_in = MODE == 2 ? a.part + (long)(plane ^ 1) * 2 * S * HW + (long)y0 * W : nullptr;
     int nb = 16 * wave;
     for (int e = 0; e < E; ++e) {
         const uint32_t p2 = __builtin_amdgcn_readlane(t_p2, e);
         if (p2 & 256u) {
-            float oth_l[3] = {0.0f, 0.0f, 0.0f}, oth_da[3] = {0.0f, 0.0f, 0.0f};
-            if (MODE == 2) {                                            // (used after the first chain of products)
+            float sh_l[3] = {0.0f, 0.0f, 0.0f}, sh_da[3] = {0.0f, 0.0f, 0.0f};   // MODE 2: the two halves' shares, added
+            if (MODE == 2) {
 #pragma unroll
-                for (int r = 0; r < 3; ++r)
-                    oth_l[r] = (nb + p < npix && (r < 2 || g == 0)) ? part_in[(long)(4 * r + g) * HW + nb + p] : 0.0f;
+                for (int r = 0; r < 3; ++r) {
+                    const bool has = nb + p < npix && (r < 2 || g == 0);
+                    const long at = (long)(4 * r + g) * HW + nb + p;
+                    sh_l[r] = has ? part_own[at] + part_in[at] : 0.0f;
+                    sh_da[r] = has ? part_own[at + (long)S * HW] + part_in[at + (long)S * HW] : 0.0f;
+                }
             }
             const uint32_t p0 = __builtin_amdgcn_readlane(t_p0, e), p1 = __builtin_amdgcn_readlane(t_p1, e);
             const int cx0 = (int)(p2 & 255u) + p;
@@ -751,17 +767,19 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
 #pragma unroll
             for (int ty = 0; ty < KS; ++ty) kb[ty] = tap_base + ((((rows >> (10 * ty)) & 1023u) + cx) << 4);
             const int slot = wave * (2 * SLOT) + (e & 1) * SLOT + q_rd;
-            const uint2_t q0 = lds_read_tr(smem + a.off_q + slot), q1 = lds_read_tr(smem + a.off_q + slot + 4 * 32);
-            const uint2_t d0 = lds_read_tr(smem + a.off_do + slot), d1 = lds_read_tr(smem + a.off_do + slot + 4 * 32);
+            uint2_t q0 = {0u, 0u}, q1 = {0u, 0u}, d0 = {0u, 0u}, d1 = {0u, 0u};
             uint4_t xd[S];
-#pragma unroll
-            for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
             const half2_t sc = {(_Float16)G_SCALE, (_Float16)G_SCALE};
             half2_t xs[4];
+            float4_t acc = zero4, accb = zero4;
+            if (MODE != 2) {
+            q0 = lds_read_tr(smem + a.off_q + slot); q1 = lds_read_tr(smem + a.off_q + slot + 4 * 32);
+            d0 = lds_read_tr(smem + a.off_do + slot); d1 = lds_read_tr(smem + a.off_do + slot + 4 * 32);
+#pragma unroll
+            for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kb[t / KS] + (t % KS) * 16);
             xs[0] = as_half2(bf16x2_to_half2(q0[0])) * sc; xs[1] = as_half2(bf16x2_to_half2(q0[1])) * sc;
             xs[2] = as_half2(bf16x2_to_half2(q1[0])) * sc; xs[3] = as_half2(bf16x2_to_half2(q1[1])) * sc;
             // ---- attention weights (as in the forward)
-            float4_t acc = zero4, accb = zero4;
 #pragma unroll
             for (int t = 0; t < S; ++t) {
                 uint4_t bb;
@@ -776,13 +794,10 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < S; ++t) xd[t] = *(const uint4_t*)(kb[t / KS] + VD + (t % KS) * 16);
+            }
             float l[3], pr[3];
 #pragma unroll
-            for (int r = 0; r < 3; ++r) l[r] = fmaf(acc[r], a.scale_log2e, bias2[r]);
-            if (MODE == 2) {
-#pragma unroll
-                for (int r = 0; r < 3; ++r) l[r] += oth_l[r];
-            }
+            for (int r = 0; r < 3; ++r) l[r] = MODE == 2 ? sh_l[r] + bias2[r] : fmaf(acc[r], a.scale_log2e, bias2[r]);
             const float lg_own[3] = {acc[0] * a.scale_log2e, acc[1] * a.scale_log2e, acc[2] * a.scale_log2e};
             const float mx = allmax_groups(fmaxf(fmaxf(l[0], l[1]), l[2]));
 #pragma unroll
@@ -790,12 +805,8 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             const float inv = __builtin_amdgcn_rcpf(allsum_groups(pr[0] + pr[1] + pr[2]));
 #pragma unroll
             for (int r = 0; r < 3; ++r) pr[r] *= inv;
-            if (MODE == 2) {                                            // (used after the second chain; fetched here: no registers to hold it earlier)
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-                    oth_da[r] = (nb + p < npix && (r < 2 || g == 0)) ? part_in[(long)(S + 4 * r + g) * HW + nb + p] : 0.0f;
-            }
             // ---- da[s] = dO . Vs[s], then dl
+            if (MODE != 2) {
             xs[0] = as_half2(bf16x2_to_half2(d0[0])) * sc; xs[1] = as_half2(bf16x2_to_half2(d0[1])) * sc;
             xs[2] = as_half2(bf16x2_to_half2(d1[0])) * sc; xs[3] = as_half2(bf16x2_to_half2(d1[1])) * sc;
             acc = zero4; accb = zero4;
@@ -809,6 +820,7 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
                 else       acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(A1v, __builtin_bit_cast(half8_t, bb), acc, 0, 0, 0);
             }
             acc += accb;
+            }
             if (MODE == 1) {
                 if (nb + p < npix) {
 #pragma unroll
@@ -822,7 +834,7 @@ bwd16_ring_pixel_kernel(const PixelArgs a)
             } else {
             if (MODE == 2) {
 #pragma unroll
-                for (int r = 0; r < 3; ++r) acc[r] += oth_da[r];
+                for (int r = 0; r < 3; ++r) acc[r] = sh_da[r];
             }
             // k taps again for the dq step
             __builtin_amdgcn_sched_barrier(0);
