@@ -68,7 +68,12 @@ int slide_reparam(const float* w_learned, float* w_merged, int C, int ksize, voi
 /*
  * Bytes of device scratch that slide_attn_fwd (backward == 0) or slide_attn_bwd
  * (backward != 0) needs for this problem.  Returns 0 if the arguments are
- * invalid or no scratch is needed.  Host-only; makes no HIP call.
+ * invalid or no scratch is needed.  Makes no HIP call that touches a stream.
+ * For bf16 problems with ksize 3 whose heads have 64 channels or fewer than 32 the figure
+ * includes what the matrix-core kernels need to serve that head size (partial sums exchanged
+ * between half heads; copies padded to 32 channels per head: several times the size of an
+ * activation tensor).  slide_attn_bwd requires it; a forward call that brings less scratch than
+ * this (but enough for the general path: none) is served by the general kernel instead.
  */
 size_t slide_attn_workspace_bytes(int B, int H, int W, int C, int heads, int ksize,
                                   int dtype, int backward);
