@@ -68,7 +68,8 @@ int slide_reparam(const float* w_learned, float* w_merged, int C, int ksize, voi
 /*
  * Bytes of device scratch that slide_attn_fwd (backward == 0) or slide_attn_bwd
  * (backward != 0) needs for this problem.  Returns 0 if the arguments are
- * invalid or no scratch is needed.  Makes no HIP call that touches a stream.
+ * invalid or no scratch is needed.  Launches nothing; reads the compute-unit count of the
+ * current device (256 if there is none).
  * For bf16 problems with ksize 3 whose heads have 64 channels or fewer than 32 the figure
  * includes what the matrix-core kernels need to serve that head size (partial sums exchanged
  * between half heads; copies padded to 32 channels per head: several times the size of an
