@@ -559,6 +559,7 @@ int fwd_mfma_variant(const Problem& p, bool aligned16)
 {
     using namespace f16path;
     if (fwd_ring_enabled() && fwd_ring_supported(p, aligned16)) return 24;
+    if (fwd_ring_enabled() && fwd_ring_strip_supported(p, aligned16)) return 26;
     TilePlan t;
     if (!choose_pipelined(p, aligned16, t)) return 20;
     return t.tw == 64 ? 23 : 21;
@@ -573,6 +574,8 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
                            (uintptr_t)wk | (uintptr_t)wv) % 16 == 0);
     if (fwd_ring_enabled() && fwd_ring_supported(p, aligned))
         return launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, false, st);
+    if (fwd_ring_enabled() && fwd_ring_strip_supported(p, aligned))
+        return launch_fwd_ring_strip(p, q, k, v, wk, wv, bias, out, lse, st);
     TilePlan t;
     const bool pipelined = choose_pipelined(p, aligned, t);
     uint32_t* image = (uint32_t*)workspace;

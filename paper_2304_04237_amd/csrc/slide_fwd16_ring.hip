@@ -57,6 +57,7 @@ struct RingArgs {
     uint32_t magic_w, magic_r;                 // ceil(2^32 / W), ceil(2^32 / R): x / W == umulhi(x, magic_w) for x < 2^26
     float scale_log2e, idw;
     float* part;                               // heads of 64 channels (MODE 1, 2): partial logits of every half head, [B, 2 heads, 9, H, W], times scale_log2e
+    int Wf, n_strips;                          // STRIP: columns of the whole map (W is the strip's width), strips per plane
 };
 
 // RPG: most rows a group of new K/V rows can have (rows that one epoch is the first to read).
@@ -86,7 +87,7 @@ struct RingArgs {
 // to its own 32 value channels.  MODE 0: heads of DH channels, one launch.
 constexpr int MOVERS = 4, WAVES12 = WAVES + MOVERS, THREADS12 = WAVES12 * 64;
 
-template <int RPG, bool LSE, bool PLAIN, int DH, int MODE = 0>
+template <int RPG, bool LSE, bool PLAIN, int DH, int MODE = 0, bool STRIP = false>
 __global__ void __launch_bounds__(THREADS12)
 fwd16_ring_kernel(const RingArgs a)
 {
@@ -97,10 +98,12 @@ fwd16_ring_kernel(const RingArgs a)
     const bool mover = wave >= WAVES;
     const int mv = wave - WAVES;                                       // mover index 0 .. 3
     const int p = lane & 15, g = lane >> 4;
+    // W: columns a block works on, the whole row, or (STRIP) a strip of a wider map of Wf columns
     const int W = a.W, H = a.H, R = a.R;
+    const int Wf = STRIP ? a.Wf : W;
     const int RS = a.RS, PS = a.PS;
-    const uint32_t hw2 = (uint32_t)H * (uint32_t)W * 2u;             // bytes of one channel plane
-    const uint32_t w2 = (uint32_t)W * 2u;
+    const uint32_t hw2 = (uint32_t)H * (uint32_t)Wf * 2u;            // bytes of one channel plane
+    const uint32_t w2 = (uint32_t)Wf * 2u;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
     // ---- block -> band of rows of one plane.  Consecutive block indices are dealt round-robin to
@@ -111,11 +114,15 @@ fwd16_ring_kernel(const RingArgs a)
         const int per = a.n_blocks >> 3;
         if (u < 8 * per) u = (u & 7) * per + (u >> 3);
     }
-    const int plane = u / a.nbp, part = u - plane * a.nbp;
+    const int plane_s = u / a.nbp, part = u - plane_s * a.nbp;        // (plane, strip) and band
+    const int plane = STRIP ? plane_s / a.n_strips : plane_s;
+    // first column of the strip; the last strip is moved left so that it ends with the map (the
+    // columns it shares with the strip before it are computed twice, with identical results)
+    const int x0 = STRIP ? min((plane_s - plane * a.n_strips) * W, Wf - W) : 0;
     const int b = plane / a.heads, m = plane - b * a.heads;
     const int y0 = part * a.rows_pb;
     const int nr = min(a.rows_pb, H - y0);
-    const long HW = (long)H * W;
+    const long HW = (long)H * Wf;
     const long head_base = ((long)b * a.C + (long)m * DH) * HW;   // element offset of channel 0 of the head
     const bool oct_empty = DH < D && mover && 8 * mv >= DH;         // this mover's octet does not exist
     const int npix = nr * W, npass = (npix + 15) >> 4, E = (npass + WAVES - 1) / WAVES;
@@ -131,9 +138,18 @@ fwd16_ring_kernel(const RingArgs a)
     const int oct = mover ? mv : 0;
     const int src_oct = oct_empty ? 0 : oct;
     const bf16_bits* kv_src[2] = {a.k + head_base + (long)(8 * src_oct) * HW, a.v + head_base + (long)(8 * src_oct) * HW};
-    const int NXC = W >> 3;
+    // a row of a unit lands as [8 channels][WL pixels]; STRIP: the strip and the 8 pixels either
+    // side of it (WL = W + 16 <= 64), of which the ring takes one column left and right
+    const int WL = STRIP ? W + 16 : W;
+    const int NXC = WL >> 3;
     const int kv_cc = lane / NXC, kv_x = lane - kv_cc * NXC;
-    const uint32_t kv_lane_off = (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
+    const int kv_col = x0 - 8 + 8 * kv_x;                            // STRIP: first map column of the lane's 16 bytes
+    const bool kv_lane = STRIP ? (lane < 8 * NXC && kv_col >= 0 && kv_col < Wf) : lane < W;
+    const uint32_t kv_lane_off = STRIP ? (uint32_t)kv_cc * hw2 + (uint32_t)max(kv_col, 0) * 2u
+                                       : (uint32_t)kv_cc * hw2 + (uint32_t)kv_x * 16u;
+    // ring column that the lane's landed pixel goes to: lane + 1, or (STRIP) lane - 7
+    const bool ring_lane = STRIP ? (lane >= 7 && lane <= W + 8) : lane < W;
+    const bool ring_zero = STRIP && (x0 - 8 + lane < 0 || x0 - 8 + lane >= Wf);   // a column outside the map
     // landing slots of unit j: two sets of RPG; at start-up also the third q slot and the result
     // slot of pass wave 2 mv + j
     auto slot_off = [&](int j, int s) {
@@ -143,15 +159,15 @@ fwd16_ring_kernel(const RingArgs a)
     };
     // (an empty octet reads channel 0 of the head's first octet into the dump slot)
     auto load_row = [&](int j, uint32_t row_off, int off) {
-        if (lane < W) load_to_lds(kv_src[j], kv_lane_off + row_off, lds0 + (oct_empty ? a.off_dummy : off));
+        if (kv_lane) load_to_lds(kv_src[j], kv_lane_off + row_off, lds0 + (oct_empty ? a.off_dummy : off));
     };
-    const int cv_src_off = ((lane & 15) >> 2) * (W * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
+    const int cv_src_off = ((lane & 15) >> 2) * (WL * 2) + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
     struct RawRow { uint2_t lo, hi; };
     auto read_row = [&](int off) {
         RawRow r;
         const unsigned char* src = smem + off + cv_src_off;
         r.lo = lds_read_tr(src);
-        r.hi = lds_read_tr(src + 4 * (W * 2));
+        r.hi = lds_read_tr(src + 4 * (WL * 2));
         return r;
     };
     auto write_row = [&](int j, uint32_t ring_off, bool in_map, const RawRow& r) {
@@ -159,23 +175,34 @@ fwd16_ring_kernel(const RingArgs a)
         h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
         h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
 #pragma unroll
-        for (int y = 0; y < 4; ++y) h4[y] = (in_map && !oct_empty) ? h4[y] : 0u;
-        if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
+        for (int y = 0; y < 4; ++y) h4[y] = (in_map && !oct_empty && !ring_zero) ? h4[y] : 0u;
+        if (ring_lane) *(uint4_t*)(smem + (4 * j + oct) * PS + (STRIP ? lane - 7 : lane + 1) * 16 + ring_off) = h4;
     };
     auto write_row_in_map = [&](int j, uint32_t ring_off, const RawRow& r) {
         uint4_t h4;
         h4[0] = bf16x2_to_half2(r.lo[0]); h4[1] = bf16x2_to_half2(r.lo[1]);
         h4[2] = bf16x2_to_half2(r.hi[0]); h4[3] = bf16x2_to_half2(r.hi[1]);
-        if (lane < W) *(uint4_t*)(smem + (4 * j + oct) * PS + (lane + 1) * 16 + ring_off) = h4;
+        if (STRIP) {
+#pragma unroll
+            for (int y = 0; y < 4; ++y) h4[y] = ring_zero ? 0u : h4[y];
+        }
+        if (ring_lane) *(uint4_t*)(smem + (4 * j + oct) * PS + (STRIP ? lane - 7 : lane + 1) * 16 + ring_off) = h4;
     };
     // q of pass wave pw, pass starting at band pixel n_first, into slot offset qo of that wave
-    const bf16_bits* q_src = a.q + head_base + (long)y0 * W;
-    const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (uint32_t)(lane & 1) * 16u;
+    // band pixel n (a multiple of 8) -> byte offset inside a channel plane, from the band's first row
+    auto px_off = [&](int n) {
+        if (!STRIP) return (uint32_t)n * 2u;
+        const int r = div_w(n);
+        return (uint32_t)(r * Wf + x0 + (n - r * W)) * 2u;
+    };
+    const bf16_bits* q_src = a.q + head_base + (long)y0 * Wf;
+    const uint32_t q_lane_off = (uint32_t)(lane >> 1) * hw2 + (STRIP ? 0u : (uint32_t)(lane & 1) * 16u);
     auto load_q = [&](int pw, int n_first, int qo) {
         const bool real = n_first < npix;
         const int nf = real ? n_first : 0;
         const int off = real ? a.off_q + pw * (3 * SLOT) + qo : a.off_dummy;
-        if (nf + 8 * (lane & 1) < npix && (lane >> 1) < DH) load_to_lds(q_src, q_lane_off + (uint32_t)nf * 2u, lds0 + off);
+        if (nf + 8 * (lane & 1) < npix && (lane >> 1) < DH)
+            load_to_lds(q_src, q_lane_off + (STRIP ? px_off(nf + 8 * (lane & 1)) : (uint32_t)nf * 2u), lds0 + off);
     };
 
     // ---- start-up.  The first access to a tensor takes microseconds (cold translation): the
@@ -317,7 +344,7 @@ fwd16_ring_kernel(const RingArgs a)
             ldm |= (k < s3 - s2 && gl >= 0 && gl < H) ? 1u << k : 0u;
         }
         t_cvB = ring_of(s0 + 4) | (uint32_t)(s1 - s0) << 10 | outside << 13 | ldm << 17;
-        t_ld = (uint32_t)(min(max(y0 + s2, 0), H - 1) * W) * 2u;
+        t_ld = (uint32_t)(min(max(y0 + s2, 0), H - 1) * Wf) * 2u;
         const int nbe = PX_EPOCH * e + 16 * (mover ? 0 : wave);
         const int ra = div_w(nbe), c0 = nbe - ra * W;
         t_p0 = ring_of(ra) | ring_of(ra + 1) << 10 | ring_of(ra + 2) << 20;
@@ -326,7 +353,7 @@ fwd16_ring_kernel(const RingArgs a)
     }
 
     constexpr int OUT_ROW = 2 * PX_EPOCH + 16;
-    char* out_base = (char*)(a.out + head_base + (long)y0 * W);
+    char* out_base = (char*)(a.out + head_base + (long)y0 * Wf);
     int out2_wr = a.off_out2, out2_rd = a.off_out2 + 32 * OUT_ROW;     // buffer written this epoch / stored this epoch
     int qo_cur = 0, qo_1 = SLOT, qo_2 = 2 * SLOT;                      // slot offsets of q(e), q(e+1), q(e+2)
     // mover: store channels 8 mv .. 8 mv + 7 of the epoch whose first pixel is e0 from buffer rd
@@ -341,7 +368,7 @@ fwd16_ring_kernel(const RingArgs a)
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int c = 8 * mv + 4 * i + (lane >> 4);
-            if (n0 < npix && (DH == D || c < DH)) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + (uint32_t)n0 * 2u)) = val[i];
+            if (n0 < npix && (DH == D || c < DH)) *(uint4_t*)(out_base + ((uint32_t)c * hw2 + px_off(n0))) = val[i];
         }
     };
 
@@ -419,7 +446,12 @@ fwd16_ring_kernel(const RingArgs a)
     const unsigned char* tap_base = smem + g * PS;
     const int st_c = 16 * ((lane >> 4) & 1) + (lane & 15), st_hh = lane >> 5;
     int nb = 16 * wave;
-    float* lse_ptr = LSE ? a.lse + ((long)(MODE ? plane >> 1 : plane) * H + y0) * W : nullptr;
+    float* lse_ptr = LSE ? a.lse + ((long)(MODE ? plane >> 1 : plane) * H + y0) * Wf : nullptr;
+    auto lse_at = [&](int n) {                                         // band pixel -> index from the band's first row
+        if (!STRIP) return n;
+        const int r = div_w(n);
+        return r * Wf + x0 + (n - r * W);
+    };
     // MODE 1: this half head's share of the logits goes out; MODE 2: the other half's comes in,
     // fetched one epoch ahead (lane (p, g) holds the shifts g, 4 + g, 8 + g of pixel p)
     float* part_out = MODE == 1 ? a.part + (long)plane * S * HW + (long)y0 * W : nullptr;
@@ -486,7 +518,7 @@ fwd16_ring_kernel(const RingArgs a)
 #pragma unroll
                 for (int t = 0; t < S; ++t) { l[t] = __builtin_amdgcn_exp2f(l[t] - mx); den += l[t]; }
                 const float inv = __builtin_amdgcn_rcpf(den);
-                if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+                if (LSE) { if (g == 0 && nb + p < npix) lse_ptr[lse_at(nb + p)] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
 #pragma unroll
                 for (int t = 0; t < S; ++t)
 #pragma unroll
@@ -527,7 +559,7 @@ fwd16_ring_kernel(const RingArgs a)
                 for (int r = 0; r < 3; ++r) pr[r] = __builtin_amdgcn_exp2f(l[r] - mx);
                 const float den = allsum_groups(pr[0] + pr[1] + pr[2]);
                 const float inv = __builtin_amdgcn_rcpf(den);
-                if (LSE) { if (g == 0 && nb + p < npix && (MODE != 2 || (m & 1) == 0)) lse_ptr[nb + p] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
+                if (LSE) { if (g == 0 && nb + p < npix && (MODE != 2 || (m & 1) == 0)) lse_ptr[lse_at(nb + p)] = LN2 * (mx + __builtin_amdgcn_logf(den)); }
                 uint2_t b2;
                 b2[0] = pack_half(pr[0] * inv, pr[1] * inv);
                 b2[1] = pack_half(pr[2] * inv, 0.0f);
@@ -1090,7 +1122,7 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f * p.logit_scale();
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    a.part = nullptr;
+    a.part = nullptr; a.Wf = p.W; a.n_strips = 1;
     static LdsOptIn opt_in;
 #define SLIDE_RING_KERNELS2(RPGV, DHV)                                                                              \
     (const void*)fwd16_ring_kernel<RPGV, false, false, DHV>, (const void*)fwd16_ring_kernel<RPGV, true, false, DHV>, \
@@ -1127,6 +1159,70 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
 #undef SLIDE_RING_LAUNCH3
 #undef SLIDE_RING_LAUNCH4
 #undef SLIDE_RING_LAUNCH
+    return hipGetLastError();
+}
+
+// ---- maps wider than 64 columns: column strips of 48 (the last one moved left to end with the map)
+constexpr int STRIP_W = 48;
+static Problem strip_problem(const Problem& p, int& n_strips)
+{
+    n_strips = (p.W + STRIP_W - 1) / STRIP_W;
+    Problem s = p;
+    s.W = STRIP_W;
+    s.B = p.B * n_strips;                       // (plane, strip) pairs take the place of planes
+    return s;
+}
+
+bool fwd_ring_strip_supported(const Problem& p, bool aligned16)
+{
+    if (!aligned16 || p.dtype != 1 || p.ksize != 3 || p.C != p.heads * f16ring::D) return false;
+    if (p.W <= f16ring::MAX_W || p.W % 8 != 0) return false;
+    if ((long)p.H * p.W * 2 * f16ring::D >= (1L << 31)) return false;
+    int n_strips;
+    const Problem s = strip_problem(p, n_strips);
+    if ((long)s.B * p.heads >= (1L << 24)) return false;
+    // (strips that overlap by much, or too few blocks to fill the chip, are left to the tile kernels)
+    if ((long)n_strips * STRIP_W * 100 > (long)p.W * 125) return false;
+    return f16ring::plan_ring(s).ok;
+}
+
+hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k, const void* v,
+                                 const float* wk, const float* wv, const float* bias, void* out,
+                                 float* lse, hipStream_t st)
+{
+    using namespace f16ring;
+    int n_strips;
+    const Problem s = strip_problem(p, n_strips);
+    const RingPlan r = plan_ring(s);
+    if (!r.ok) return hipErrorInvalidValue;
+    RingArgs a;
+    a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
+    a.out = (bf16_bits*)out; a.lse = lse;
+    a.wk = wk; a.wv = wv; a.bias = bias;
+    a.B = p.B; a.H = p.H; a.W = STRIP_W; a.C = p.C; a.heads = p.heads; a.d = D;
+    a.Wf = p.W; a.n_strips = n_strips;
+    a.nbp = r.nbp; a.rows_pb = r.rows_pb; a.n_blocks = r.n_blocks;
+    a.R = r.R; a.RS = r.RS; a.PS = r.PS; a.off_raw = r.off_raw; a.off_dummy = r.off_dummy; a.off_q = r.off_q; a.off_out = r.off_out; a.off_out2 = r.off_out2;
+    a.magic_w = (uint32_t)(((1ULL << 32) + STRIP_W - 1) / STRIP_W);
+    a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
+    a.scale_log2e = 1.44269504088896341f * p.logit_scale();
+    a.idw = p.two_branch ? 1.0f : 0.0f;
+    a.part = nullptr;
+    static LdsOptIn opt_in;
+#define SLIDE_STRIP_KERNELS(RPGV) (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 0, true>, (const void*)fwd16_ring_kernel<RPGV, true, false, 32, 0, true>
+    hipError_t e = opt_in.ensure({SLIDE_STRIP_KERNELS(2), SLIDE_STRIP_KERNELS(3), SLIDE_STRIP_KERNELS(4)}, LDS_LIMIT);
+#undef SLIDE_STRIP_KERNELS
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
+#define SLIDE_STRIP_LAUNCH(RPGV)                                                                                      \
+    do {                                                                                                              \
+        if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true, false, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a);  \
+        else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false, false, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a); \
+    } while (0)
+    if (r.rpg == 2) SLIDE_STRIP_LAUNCH(2);
+    else if (r.rpg == 3) SLIDE_STRIP_LAUNCH(3);
+    else SLIDE_STRIP_LAUNCH(4);
+#undef SLIDE_STRIP_LAUNCH
     return hipGetLastError();
 }
 
@@ -1170,7 +1266,7 @@ hipError_t launch_fwd_ring_wide(const Problem& p, const void* q, const void* k, 
     a.magic_r = (uint32_t)(((1ULL << 32) + r.R - 1) / r.R);
     a.scale_log2e = 1.44269504088896341f / sqrtf(64.0f);               // (the head has 64 channels)
     a.idw = p.two_branch ? 1.0f : 0.0f;
-    a.part = (float*)workspace;
+    a.part = (float*)workspace; a.Wf = h.W; a.n_strips = 1;
     static LdsOptIn opt_in;
 #define SLIDE_WIDE_KERNELS(RPGV)                                                                                    \
     (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 1>, (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 2>, \

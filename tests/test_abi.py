@@ -177,12 +177,14 @@ def test_forward_variant_selection(lib):
     assert v(64, 28, 28, 128, 4, 5, 1, 1) == 30                    # 5x5
     assert v(64, 56, 56, 64, 2, 3, 1, 1) == 24                     # stage 1: streaming kernel
     assert v(64, 56, 56, 64, 2, 3, 1, 0) == 20                     # unaligned pointers: one tile per block
-    assert v(2, 200, 304, 96, 3, 3, 1, 1) == 23                    # 200x304: pipelined tiles, width 64
+    assert v(2, 200, 304, 96, 3, 3, 1, 1) == 26                    # 200x304: streaming kernel on column strips
+    assert v(12, 64, 72, 64, 2, 3, 1, 1) == 23                     # 72 columns: two strips would overlap by a third: pipelined tiles, width 64
     assert v(96, 48, 48, 64, 2, 3, 1, 1) == 24                     # streaming kernel, 48 columns
     assert v(96, 40, 40, 64, 2, 3, 1, 1) == 21                     # 40 columns need too much LDS there: pipelined tiles
     assert v(300, 24, 24, 64, 2, 3, 1, 1) == 21                    # narrower than 32: pipelined tiles, width from the arguments
     assert v(2, 9, 21, 64, 2, 3, 1, 1) == 20                       # W % 8 != 0
-    assert v(8, 100, 128, 32, 1, 3, 1, 1) == 20                    # wider than 64 and too few tiles to pipeline
+    assert v(8, 100, 128, 32, 1, 3, 1, 1) == 26                    # 128 columns: three strips
+    assert v(8, 100, 128, 32, 1, 3, 1, 0) == 20                    # ... not from unaligned pointers: one tile per block
     # many small planes: enough tiles, but a tile buffer too small to build the operand image in
     assert v(128, 8, 8, 128, 4, 3, 1, 1) == 20
     assert v(256, 2, 64, 64, 2, 3, 1, 1) == 24                     # two-row planes: streaming kernel

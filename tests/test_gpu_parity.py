@@ -434,6 +434,16 @@ PIPELINED_SHAPES = [
     (256, 2, 64, 64, 2, 24),             # two-row planes: a band shorter than the window's reach
     (1, 1, 56, 32, 1, 24),               # a single row
     (12, 64, 72, 64, 2, 23),             # pipelined tiles of width 64, ragged second column tile
+    # maps wider than 64 columns on the streaming kernel: column strips of 48, the last one moved
+    # left to end with the map (columns computed twice), edge columns from the neighbouring strips
+    (2, 9, 304, 96, 3, 26),
+    (1, 20, 96, 32, 1, 26),              # two strips, no overlap
+    (3, 5, 144, 64, 2, 26),
+    (1, 33, 240, 32, 1, 26),
+    (1, 1, 192, 32, 1, 26),              # a single row
+    (2, 7, 432, 64, 2, 26),
+    (4, 12, 200, 64, 2, 26),             # the last strip overlaps by 40 columns
+    (2, 70, 128, 64, 2, 26),             # several bands per strip
     (300, 24, 24, 64, 2, 21),            # pipelined tiles, width from the arguments
     (700, 16, 16, 32, 1, 21),
     # enough tiles for the pipelined kernel, but tile buffers too small to build a head's
@@ -583,7 +593,7 @@ def test_kernel_selection():
     """Which forward kernel serves which problem (host-side query of the C ABI)."""
     assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, True) == 24
     assert sa.slide_attn_fwd_variant(64, 56, 56, 64, 2, 3, torch.bfloat16, False) == 20
-    assert sa.slide_attn_fwd_variant(2, 200, 304, 96, 3, 3, torch.bfloat16, True) == 23
+    assert sa.slide_attn_fwd_variant(2, 200, 304, 96, 3, 3, torch.bfloat16, True) == 26
     assert sa.slide_attn_fwd_path(64, 56, 56, 64, 2, 3, torch.bfloat16) == 2
     assert sa.slide_attn_fwd_path(64, 28, 28, 128, 4, 5, torch.bfloat16) == 3
     assert sa.slide_attn_fwd_path(1, 14, 14, 64, 2, 3, torch.float32) == 1
