@@ -1,6 +1,7 @@
 // Streaming matrix-core forward of Slide Attention for gfx950: bf16 activations, head size
 // 32, 3x3 window, maps of 32..64 columns (a multiple of 8) whose rows and pointers are
-// 16-byte aligned.  Same arithmetic as the tiled kernels (operator of Sec. 4.1-4.3 with the
+// 16-byte aligned; wider maps as column strips of 48 (template argument STRIP), heads of 24
+// channels with an empty fourth octet (DH), heads of 64 as two half heads (MODE).  Same arithmetic as the tiled kernels (operator of Sec. 4.1-4.3 with the
 // merged kernel W~ of Sec. 4.3 / Fig. 4 as matrix-core operands, see slide_fwd16_ops.h); what
 // differs is how data moves:
 //
