@@ -213,8 +213,8 @@ int slide_attn_fwd_path(int B, int H, int W, int C, int heads, int ksize, int dt
  * during the passes of the current one) with the tile width taken from its arguments / fixed
  * at 64, 24 = streaming ksize-3 kernel (a block walks down a band of rows, K/V rows in an LDS
  * ring; maps 32..64 columns wide; head size 32, or 24 with the fourth channel octet of every
- * head left empty), 26 = the streaming kernel on column strips of 48 (maps wider than 64 columns,
- * W % 8 == 0, strips covering at most 1.25 W), 25 = two launches of the streaming kernel for heads of 64 channels (each
+ * head left empty), 26 = the streaming kernel on column strips of 48, 40 or 32 (maps wider than 64
+ * columns, W % 8 == 0, strips covering at most 1.25 W), 25 = two launches of the streaming kernel for heads of 64 channels (each
  * head as two halves of 32 whose shares of the logits cross the workspace; a call that brings
  * less workspace than slide_attn_workspace_bytes says runs on the general kernel), 30 = ksize-5
  * matrix-core kernel, 100 + v = heads narrower than 32 channels (bf16, ksize 3, H * W % 8 == 0)

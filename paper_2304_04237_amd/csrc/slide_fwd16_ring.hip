@@ -1,6 +1,6 @@
 // Streaming matrix-core forward of Slide Attention for gfx950: bf16 activations, head size
 // 32, 3x3 window, maps of 32..64 columns (a multiple of 8) whose rows and pointers are
-// 16-byte aligned; wider maps as column strips of 48 (template argument STRIP), heads of 24
+// 16-byte aligned; wider maps as column strips of up to 48 (template argument STRIP), heads of 24
 // channels with an empty fourth octet (DH), heads of 64 as two half heads (MODE).  Same arithmetic as the tiled kernels (operator of Sec. 4.1-4.3 with the
 // merged kernel W~ of Sec. 4.3 / Fig. 4 as matrix-core operands, see slide_fwd16_ops.h); what
 // differs is how data moves:
@@ -1163,15 +1163,28 @@ hipError_t launch_fwd_ring(const Problem& p, const void* q, const void* k, const
     return hipGetLastError();
 }
 
-// ---- maps wider than 64 columns: column strips of 48 (the last one moved left to end with the map)
-constexpr int STRIP_W = 48;
-static Problem strip_problem(const Problem& p, int& n_strips)
+// ---- maps wider than 64 columns: column strips (the last one moved left to end with the map)
+// A strip of Ws columns is loaded as Ws + 16 (at most 64: one landing slot), so Ws is 48, 40 or
+// 32; the width that moves the fewest bytes per map column is taken (strips that together cover
+// more than 1.25 x the map, or whose ring does not fit, are left to the tile kernels).
+static bool strip_problem(const Problem& p, Problem& s, int& n_strips)
 {
-    n_strips = (p.W + STRIP_W - 1) / STRIP_W;
-    Problem s = p;
-    s.W = STRIP_W;
-    s.B = p.B * n_strips;                       // (plane, strip) pairs take the place of planes
-    return s;
+    double best = 1e300;
+    bool found = false;
+    for (int ws = 48; ws >= 32; ws -= 8) {
+        if (p.W < ws) continue;
+        const int n = (p.W + ws - 1) / ws;
+        if ((long)n * ws * 100 > (long)p.W * 125) continue;
+        const double cost = (double)(ws + 16) / ws * ((double)n * ws / p.W);
+        if (cost >= best - 1e-9) continue;
+        Problem c = p;
+        c.W = ws;
+        if ((long)p.B * n * p.heads >= (1L << 24)) continue;
+        c.B = p.B * n;                          // (plane, strip) pairs take the place of planes
+        if (!f16ring::plan_ring(c).ok) continue;
+        best = cost; s = c; n_strips = n; found = true;
+    }
+    return found;
 }
 
 bool fwd_ring_strip_supported(const Problem& p, bool aligned16)
@@ -1180,11 +1193,8 @@ bool fwd_ring_strip_supported(const Problem& p, bool aligned16)
     if (p.W <= f16ring::MAX_W || p.W % 8 != 0) return false;
     if ((long)p.H * p.W * 2 * f16ring::D >= (1L << 31)) return false;
     int n_strips;
-    const Problem s = strip_problem(p, n_strips);
-    if ((long)s.B * p.heads >= (1L << 24)) return false;
-    // (strips that overlap by much, or too few blocks to fill the chip, are left to the tile kernels)
-    if ((long)n_strips * STRIP_W * 100 > (long)p.W * 125) return false;
-    return f16ring::plan_ring(s).ok;
+    Problem s;
+    return strip_problem(p, s, n_strips);
 }
 
 hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k, const void* v,
@@ -1193,9 +1203,11 @@ hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k,
 {
     using namespace f16ring;
     int n_strips;
-    const Problem s = strip_problem(p, n_strips);
+    Problem s;
+    if (!strip_problem(p, s, n_strips)) return hipErrorInvalidValue;
     const RingPlan r = plan_ring(s);
     if (!r.ok) return hipErrorInvalidValue;
+    const int STRIP_W = s.W;
     RingArgs a;
     a.q = (const bf16_bits*)q; a.k = (const bf16_bits*)k; a.v = (const bf16_bits*)v;
     a.out = (bf16_bits*)out; a.lse = lse;

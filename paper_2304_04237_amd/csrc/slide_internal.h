@@ -171,7 +171,7 @@ struct RingRows { int nbp, rows_pb, n_blocks, R, rpg; bool ok; };
 RingRows plan_ring_rows(const Problem& p, int nw, int per_cu);
 
 // the streaming forward on maps wider than 64 columns (bf16, d == 32, ksize 3, W % 8 == 0): column
-// strips of 48, each with its neighbours' edge columns; needs no workspace
+// strips of 48, 40 or 32, each with its neighbours' edge columns; needs no workspace
 bool fwd_ring_strip_supported(const Problem& p, bool aligned16);
 hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k, const void* v,
                                  const float* wk, const float* wv, const float* bias, void* out,

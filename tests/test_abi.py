@@ -77,7 +77,7 @@ def test_variant_query_knows_head_size_24():
     # through the other matrix-core kernels, else on the general kernel
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, True) == 24
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 1, False) == 10
-    assert sa.slide_attn_fwd_variant(2, 56, 72, 48, 2, 3, 1, True) == 120     # wider than the ring takes: padded to 32 channels per head, tile kernel
+    assert sa.slide_attn_fwd_variant(2, 56, 72, 48, 2, 3, 1, True) == 126     # wider than the ring takes: padded to 32 channels per head, streaming kernel on column strips
     assert sa.slide_attn_fwd_variant(2, 9, 21, 48, 2, 3, 1, True) == 10       # H * W % 8 != 0: general kernel
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 5, 1, True) == 10      # 5x5 window
     assert sa.slide_attn_fwd_variant(2, 56, 56, 48, 2, 3, 0, True) == 10      # float32
@@ -178,7 +178,8 @@ def test_forward_variant_selection(lib):
     assert v(64, 56, 56, 64, 2, 3, 1, 1) == 24                     # stage 1: streaming kernel
     assert v(64, 56, 56, 64, 2, 3, 1, 0) == 20                     # unaligned pointers: one tile per block
     assert v(2, 200, 304, 96, 3, 3, 1, 1) == 26                    # 200x304: streaming kernel on column strips
-    assert v(12, 64, 72, 64, 2, 3, 1, 1) == 23                     # 72 columns: two strips would overlap by a third: pipelined tiles, width 64
+    assert v(12, 64, 72, 64, 2, 3, 1, 1) == 23                     # 72 columns in bands of 64 rows: strips of 40 need too deep a ring, strips of 48 overlap by a third: pipelined tiles, width 64
+    assert v(12, 20, 72, 64, 2, 3, 1, 1) == 26                     # 72 columns, short bands: two strips of 40
     assert v(96, 48, 48, 64, 2, 3, 1, 1) == 24                     # streaming kernel, 48 columns
     assert v(96, 40, 40, 64, 2, 3, 1, 1) == 21                     # 40 columns need too much LDS there: pipelined tiles
     assert v(300, 24, 24, 64, 2, 3, 1, 1) == 21                    # narrower than 32: pipelined tiles, width from the arguments

@@ -444,6 +444,9 @@ PIPELINED_SHAPES = [
     (2, 7, 432, 64, 2, 26),
     (4, 12, 200, 64, 2, 26),             # the last strip overlaps by 40 columns
     (2, 70, 128, 64, 2, 26),             # several bands per strip
+    (3, 17, 80, 64, 2, 26),              # strips of 40
+    (2, 9, 72, 64, 2, 26),               # two strips of 40 that overlap by 8 columns
+    (4, 50, 104, 64, 2, 26),
     (300, 24, 24, 64, 2, 21),            # pipelined tiles, width from the arguments
     (700, 16, 16, 32, 1, 21),
     # enough tiles for the pipelined kernel, but tile buffers too small to build a head's
@@ -518,7 +521,8 @@ def test_forward_heads_of_64_channels(shape):
 NARROW_HEAD_FWD_SHAPES = [
     (2, 8, 40, 32, 2, 124),              # 16 channels per head
     (3, 20, 56, 24, 3, 124),             # 8
-    (2, 12, 72, 48, 2, 120),             # 24 on a map wider than the streaming kernel takes
+    (2, 12, 72, 48, 2, 126),             # 24 on a map wider than 64 columns: padded, then column strips
+    (2, 12, 172, 48, 2, 120),            # ... W % 8 != 0: padded, then one tile per block
     (2, 56, 56, 48, 2, 24),              # 24 on the streaming kernel itself
     (2, 9, 21, 48, 2, 10),               # H * W % 8 != 0: general kernel
 ]
