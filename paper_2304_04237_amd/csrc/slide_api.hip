@@ -250,6 +250,8 @@ extern "C" int slide_attn_fwd_shift(const void* q, const void* k, const void* v,
     hipError_t e;
     if ((slide::fwd_mfma_supported(p) || C == heads * 24) && slide::fwd_ring_enabled() && slide::fwd_ring_supported(p, aligned16))
         e = slide::launch_fwd_ring(p, q, k, v, nullptr, nullptr, bias, out, lse, true, (hipStream_t)stream);
+    else if (slide::fwd_mfma_supported(p) && slide::fwd_ring_enabled() && slide::fwd_ring_strip_supported(p, aligned16))
+        e = slide::launch_fwd_ring_strip(p, q, k, v, nullptr, nullptr, bias, out, lse, true, (hipStream_t)stream);
     else
         e = slide::launch_fwd_generic(p, q, k, v, nullptr, nullptr, bias, out, lse, (hipStream_t)stream);
     return e == hipSuccess ? SLIDE_OK : SLIDE_ERR_HIP;

@@ -575,7 +575,7 @@ hipError_t launch_fwd_mfma(const Problem& p, const void* q, const void* k, const
     if (fwd_ring_enabled() && fwd_ring_supported(p, aligned))
         return launch_fwd_ring(p, q, k, v, wk, wv, bias, out, lse, false, st);
     if (fwd_ring_enabled() && fwd_ring_strip_supported(p, aligned))
-        return launch_fwd_ring_strip(p, q, k, v, wk, wv, bias, out, lse, st);
+        return launch_fwd_ring_strip(p, q, k, v, wk, wv, bias, out, lse, false, st);
     TilePlan t;
     const bool pipelined = choose_pipelined(p, aligned, t);
     uint32_t* image = (uint32_t*)workspace;

@@ -1199,7 +1199,7 @@ bool fwd_ring_strip_supported(const Problem& p, bool aligned16)
 
 hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k, const void* v,
                                  const float* wk, const float* wv, const float* bias, void* out,
-                                 float* lse, hipStream_t st)
+                                 float* lse, bool plain, hipStream_t st)
 {
     using namespace f16ring;
     int n_strips;
@@ -1222,14 +1222,18 @@ hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k,
     a.idw = p.two_branch ? 1.0f : 0.0f;
     a.part = nullptr;
     static LdsOptIn opt_in;
-#define SLIDE_STRIP_KERNELS(RPGV) (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 0, true>, (const void*)fwd16_ring_kernel<RPGV, true, false, 32, 0, true>
+#define SLIDE_STRIP_KERNELS(RPGV) (const void*)fwd16_ring_kernel<RPGV, false, false, 32, 0, true>, (const void*)fwd16_ring_kernel<RPGV, true, false, 32, 0, true>, \
+                                  (const void*)fwd16_ring_kernel<RPGV, false, true, 32, 0, true>, (const void*)fwd16_ring_kernel<RPGV, true, true, 32, 0, true>
     hipError_t e = opt_in.ensure({SLIDE_STRIP_KERNELS(2), SLIDE_STRIP_KERNELS(3), SLIDE_STRIP_KERNELS(4)}, LDS_LIMIT);
 #undef SLIDE_STRIP_KERNELS
     if (e != hipSuccess) return e;
     const dim3 grid((unsigned)r.n_blocks), block12(THREADS12);
 #define SLIDE_STRIP_LAUNCH(RPGV)                                                                                      \
     do {                                                                                                              \
-        if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true, false, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a);  \
+        if (plain) {                                                                                                  \
+            if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true, true, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a);  \
+            else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false, true, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a); \
+        } else if (lse) hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, true, false, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a);  \
         else     hipLaunchKernelGGL((fwd16_ring_kernel<RPGV, false, false, 32, 0, true>), grid, block12, (size_t)r.lds_bytes, st, a); \
     } while (0)
     if (r.rpg == 2) SLIDE_STRIP_LAUNCH(2);

@@ -175,7 +175,7 @@ RingRows plan_ring_rows(const Problem& p, int nw, int per_cu);
 bool fwd_ring_strip_supported(const Problem& p, bool aligned16);
 hipError_t launch_fwd_ring_strip(const Problem& p, const void* q, const void* k, const void* v,
                                  const float* wk, const float* wv, const float* bias, void* out,
-                                 float* lse, hipStream_t st);
+                                 float* lse, bool plain, hipStream_t st);
 
 // heads of 64 channels on the streaming forward (bf16, ksize 3, maps the streaming kernel
 // takes): two launches over half heads, the halves' shares of the logits exchanged through the

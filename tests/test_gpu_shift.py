@@ -24,6 +24,9 @@ SHIFT_SHAPES = [
     (1, 33, 64, 32, 1, 3, "bf16", 24),      # widest map of the streaming kernel, odd height
     (5, 31, 32, 96, 3, 3, "bf16", 24),      # narrowest, three heads
     (4, 21, 48, 64, 2, 3, "bf16", 24),
+    (2, 9, 304, 96, 3, 3, "bf16", 26),      # wide maps: column strips
+    (3, 17, 80, 64, 2, 3, "bf16", 26),
+    (1, 40, 144, 32, 1, 3, "bf16", 26),
     (2, 9, 40, 64, 2, 3, "bf16", None),     # general kernel from here on
     (1, 14, 14, 64, 2, 3, "f32", None),
     (2, 9, 21, 64, 2, 3, "bf16", None),
